@@ -1,0 +1,202 @@
+/*
+ * relayhip -- C ABI for declaring, type-checking, grouping and running fused
+ * tensor-operator groups on one MI355X (gfx950).
+ *
+ * The interface follows the paper's statement of the problem:
+ *   - a program is a list of operator declarations and calls whose types are
+ *     tensor types with constant shapes      (grammar figure: Operator, Type,
+ *                                             BaseType, Shape);
+ *   - Tensor(bt, sh) is formed from one base type and one shape
+ *                                            (kinding rules BaseType-T, Shape-T, Tensor-T);
+ *   - unary operators keep Tensor(b, s); + - * / need both operands of the same
+ *     b and s and return it                  (Type-UnaryOp, Type-Noncomp-BinaryOp);
+ *   - a call is well typed only if every argument has the operator's parameter
+ *     type; its type is the arrow's result   (Type-Call);
+ *   - operators are primitives implemented outside the language and run as
+ *     type-specialised kernels               (sections "Frontend", "Runtime System");
+ *   - fusion and layout change are optimisations below the typed graph
+ *                                            (sections "Background", "Optimizations").
+ *
+ * Conventions for every entry point
+ *   - Handles (rl_ctx, rl_graph, rl_plan) are owned by the library and freed by
+ *     their destroy call; destroying a ctx does not free graphs/plans made from it.
+ *   - The caller owns all device memory and the stream.  The library never
+ *     allocates device memory, never synchronises and never changes the current
+ *     device.  Run calls only enqueue work on the given stream.
+ *   - "dev" pointers are device pointers, 16-byte aligned; everything else is
+ *     host memory.  hip_stream is a hipStream_t passed as void* (NULL = default
+ *     stream).
+ *   - No exception crosses the ABI and nothing aborts: every call returns
+ *     rl_status (0 = RL_OK, negative = error class); the text of the last error
+ *     on a ctx is available from rl_last_error.  A failed rl_graph_* call leaves
+ *     the graph unchanged.
+ *   - Tensors at the boundary are dense row-major in the order of their Shape
+ *     (so rank-4 activations are NCHW, conv weights OIHW, dense weights
+ *     [out, in]).  Kernel-native layouts are private to a plan.
+ *   - A ctx/graph is single-threaded.  A finished plan may be run from several
+ *     threads on different streams with different workspaces.
+ */
+#ifndef RELAYHIP_H
+#define RELAYHIP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct rl_ctx rl_ctx;
+typedef struct rl_graph rl_graph;
+typedef struct rl_plan rl_plan;
+typedef int32_t rl_status;
+
+enum {
+    RL_OK = 0,
+    RL_ERR_NULL = -1,        /* a required pointer argument is NULL */
+    RL_ERR_KIND = -2,        /* unknown base type / op kind, rank > RL_MAX_RANK, malformed attributes */
+    RL_ERR_SHAPE = -3,       /* a dimension is not a positive constant, or a window exceeds its input */
+    RL_ERR_TYPE = -4,        /* ill-typed: operand types or declared result type violate the typing rules */
+    RL_ERR_GROUP = -5,       /* the declared fusion group is not legal */
+    RL_ERR_BINDING = -6,     /* run: a needed value has no pointer, or an id is bound twice / unknown */
+    RL_ERR_WORKSPACE = -7,   /* run: workspace missing or too small */
+    RL_ERR_ALIGN = -8,       /* run: a device pointer is not 16-byte aligned */
+    RL_ERR_UNSUPPORTED = -9, /* well typed, but no kernel implements it */
+    RL_ERR_HIP = -10         /* a HIP runtime call failed (text has hipGetErrorString) */
+};
+
+/* BaseType.  The paper's FloatType(width) cannot tell bfloat16 from IEEE half,
+ * so bfloat16 has a tag of its own. */
+enum { RL_F32 = 0, RL_BF16 = 1 };
+
+#define RL_MAX_RANK 6
+
+/* Tensor(dtype, Shape(dims[0..rank-1])); rank 0 is a scalar. */
+typedef struct rl_type {
+    int32_t dtype;
+    int32_t rank;
+    int64_t dims[RL_MAX_RANK];
+} rl_type;
+
+/* Operator kinds.  The binary and unary arithmetic kinds are the grammar's
+ * BinOp / UnaryOp; the rest are declared operators (conv2d, linear, max_pool,
+ * flatten_layer, tanh appear in the paper's decorator example). */
+enum {
+    RL_OP_DENSE = 0,          /* (x[M,K], W[N,K]) -> [M,N]; attrs rl_attr_contract (may be NULL) */
+    RL_OP_CONV2D = 1,         /* (x[N,C,H,W], w[O,C,KH,KW]) -> [N,O,OH,OW]; attrs rl_attr_conv2d */
+    RL_OP_BIAS_ADD = 2,       /* (x, b[C]) -> x's type, b added along attrs rl_attr_axis.axis; b has x's dtype, or f32 when x is bf16 */
+    RL_OP_ADD = 3, RL_OP_SUB = 4, RL_OP_MUL = 5, RL_OP_DIV = 6,   /* (a, b) of one identical type */
+    RL_OP_NEG = 7, RL_OP_SQ = 8,                                     /* grammar's unary operators */
+    RL_OP_RELU = 9, RL_OP_SIGMOID = 10, RL_OP_TANH = 11,
+    RL_OP_MAXPOOL2D = 12,     /* attrs rl_attr_pool2d; taps outside the input are ignored */
+    RL_OP_GLOBAL_AVGPOOL = 13,/* [N,C,H,W] -> [N,C,1,1] */
+    RL_OP_FLATTEN = 14,       /* [N, d1, ...] -> [N, d1*...] */
+    RL_OP_LSTM_GATES = 15,    /* (z f32[B,4H] as i|f|g|o blocks, c f32[B,H]) -> (c' f32[B,H], h' f32|bf16[B,H]) */
+    RL_OP_CAST = 16,          /* explicit (Type) Expr; attrs rl_attr_cast */
+    RL_OP_CONCAT = 17,        /* (a[B,K1], b[B,K2]) -> [B,K1+K2]; only as the operand of a dense in the same group */
+    RL_OP_KIND_COUNT = 18
+};
+
+typedef struct rl_attr_contract { int32_t out_dtype; /* operand dtype, or RL_F32 */ } rl_attr_contract;
+typedef struct rl_attr_conv2d {
+    int32_t stride_h, stride_w, pad_h, pad_w;   /* zero padding, symmetric */
+    int32_t dilation_h, dilation_w, groups;     /* must be 1 (else RL_ERR_UNSUPPORTED) */
+    int32_t out_dtype;
+} rl_attr_conv2d;
+typedef struct rl_attr_axis { int32_t axis; } rl_attr_axis;
+typedef struct rl_attr_pool2d { int32_t kernel_h, kernel_w, stride_h, stride_w, pad_h, pad_w; } rl_attr_pool2d;
+typedef struct rl_attr_cast { int32_t to; } rl_attr_cast;
+
+typedef struct rl_binding { int32_t value_id; void *dev_ptr; } rl_binding;
+
+/* ---- context ------------------------------------------------------------ */
+rl_status rl_ctx_create(rl_ctx **out);
+void rl_ctx_destroy(rl_ctx *ctx);
+/* Text of the most recent error on ctx ("" if none); valid until the next call on ctx. */
+const char *rl_last_error(const rl_ctx *ctx);
+
+/* ---- graph: typed values and operator calls ------------------------------
+ * rl_graph_input / rl_graph_param introduce a value of the given tensor type
+ * (Tensor-T: dtype known, rank <= RL_MAX_RANK, every dim >= 1).  A param is a
+ * constant the plan may ask to have re-laid-out once (rl_plan_prepack).
+ * rl_graph_op appends a call.  The caller must state the result type(s)
+ * (declared_outs, n_out = 1 except RL_OP_LSTM_GATES which has 2); the library
+ * infers the result type from the argument types and attributes and rejects
+ * the call with RL_ERR_TYPE when they differ (Type-Call), or when the
+ * arguments break the operator's rule (Type-UnaryOp, Type-Noncomp-BinaryOp:
+ * no implicit broadcast or promotion).  attrs points to the kind's POD struct
+ * (attrs_size = its sizeof) or is NULL for kinds without attributes. */
+rl_status rl_graph_create(rl_ctx *ctx, rl_graph **out);
+void rl_graph_destroy(rl_graph *g);
+rl_status rl_graph_input(rl_graph *g, const rl_type *t, int32_t *value_id);
+rl_status rl_graph_param(rl_graph *g, const rl_type *t, int32_t *value_id);
+rl_status rl_graph_op(rl_graph *g, int32_t op_kind, const int32_t *in_ids, int32_t n_in,
+                      const void *attrs, size_t attrs_size,
+                      const rl_type *declared_outs, int32_t n_out,
+                      int32_t *op_id, int32_t *out_value_ids);
+/* Declare a fusion group: a connected set of calls with at most one
+ * contraction (dense / conv2d, which must come first; a concat feeding that
+ * dense may precede it), every other member injective on the group's output
+ * shape (elementwise, bias_add, cast; lstm_gates only as the last member), and
+ * no intermediate used outside the group.  Checked here as far as the calls
+ * are known and again by rl_plan_create.  Calls left ungrouped run alone. */
+rl_status rl_graph_group(rl_graph *g, const int32_t *op_ids, int32_t n, int32_t *group_id);
+rl_status rl_graph_output(rl_graph *g, int32_t value_id);
+
+/* ---- plan ---------------------------------------------------------------
+ * rl_plan_create re-checks the whole graph (types, groups, outputs reachable),
+ * picks kernels, tiles and private layouts and sizes the workspace.  It needs
+ * no GPU.  The graph may be destroyed afterwards. */
+rl_status rl_plan_create(rl_graph *g, rl_plan **out);
+void rl_plan_destroy(rl_plan *plan);
+/* JSON text describing the steps (kernel, tile, flops, algorithmic bytes).
+ * Writes at most cap bytes including the terminator; *needed gets the full size. */
+rl_status rl_plan_describe(const rl_plan *plan, char *buf, size_t cap, size_t *needed);
+rl_status rl_plan_workspace_bytes(const rl_plan *plan, size_t *bytes);
+/* Bytes of the kernel-native copy of a param, or 0 when the param is bound as is. */
+rl_status rl_plan_packed_bytes(const rl_plan *plan, int32_t param_value_id, size_t *bytes);
+/* Enqueue the re-layout of one param: src_dev holds it in boundary layout,
+ * dst_dev (rl_plan_packed_bytes bytes) receives the kernel-native copy, which
+ * is what rl_plan_run must then be given for that value id. */
+rl_status rl_plan_prepack(const rl_plan *plan, int32_t param_value_id, const void *src_dev, void *dst_dev,
+                          void *hip_stream);
+/* Enqueue every step of the plan.  bindings must cover every input, param
+ * (packed copy where rl_plan_packed_bytes > 0) and output value id exactly
+ * once; intermediates live in workspace_dev (>= rl_plan_workspace_bytes).
+ * Inputs and params are read only; outputs and workspace are overwritten.
+ * An output may alias an input only for lstm_gates' cell state (c' over c). */
+rl_status rl_plan_run(const rl_plan *plan, const rl_binding *bindings, int32_t n_bindings,
+                      void *workspace_dev, size_t workspace_bytes, void *hip_stream);
+
+/* Recurrent execution of a one-step cell plan for `steps` steps: at step t the
+ * cell's x input is x_seq_dev + t*x_step_bytes, its h input is h0_dev (t = 0)
+ * or the previous step's h output, its c input/output is c_dev (updated in
+ * place; the caller initialises it), and its h output is written to
+ * h_seq_dev + t*h_step_bytes.  `bindings` supplies the params.  The value ids
+ * name the cell graph's values playing each role. */
+typedef struct rl_recurrent {
+    int32_t x_id, h_in_id, c_in_id, h_out_id, c_out_id;
+    const void *x_seq_dev; size_t x_step_bytes;
+    const void *h0_dev;
+    void *c_dev;
+    void *h_seq_dev; size_t h_step_bytes;
+} rl_recurrent;
+rl_status rl_plan_run_recurrent(const rl_plan *cell, int32_t steps, const rl_recurrent *io,
+                                const rl_binding *param_bindings, int32_t n_bindings,
+                                void *workspace_dev, size_t workspace_bytes, void *hip_stream);
+
+/* ---- one-time weight preparation (device side, asynchronous) ------------- */
+/* Fold an inference batch-norm into the preceding convolution:
+ * scale[o] = gamma[o]/sqrt(var[o]+eps); w_out[o,:] = w[o,:]*scale[o];
+ * b_out[o] = beta[o] - mean[o]*scale[o], evaluated in float64 and rounded to
+ * f32 (then to out_dtype for w_out).  w: f32 [O, per_o]; gamma..var, b_out:
+ * f32 [O]; w_out: out_dtype [O, per_o].  All device pointers. */
+rl_status rl_prep_fold_batchnorm(rl_ctx *ctx, const void *w_dev, const void *gamma_dev, const void *beta_dev,
+                                 const void *mean_dev, const void *var_dev, double eps,
+                                 void *w_out_dev, int32_t out_dtype, void *b_out_dev,
+                                 int64_t O, int64_t per_o, void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RELAYHIP_H */

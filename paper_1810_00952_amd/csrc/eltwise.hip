@@ -1,0 +1,400 @@
+// HBM-bound kernels for gfx950: the single-pass fused elementwise group, the
+// stand-alone LSTM gate group, window reductions, layout change, weight
+// packing and batch-norm folding.  All move 16-byte vectors per lane where the
+// tensor's geometry allows and touch every input and output exactly once.
+#include "device_utils.h"
+
+namespace rl {
+
+// ---------------------------------------------------------------------------
+// fused elementwise chain: y = chain(x, operands...), 8 elements per thread
+// per iteration (one 16-byte load for bf16, two for f32).
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ void load8(const void *p, int dtype, int64_t i, float v[8])
+{
+    if (dtype == DT_BF16) {
+        u32x4 r = *(const u32x4 *)((const uint16_t *)p + i);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            v[2 * k] = __uint_as_float(r[k] << 16);
+            v[2 * k + 1] = __uint_as_float(r[k] & 0xffff0000u);
+        }
+    } else {
+        f32x4 a = *(const f32x4 *)((const float *)p + i);
+        f32x4 b = *(const f32x4 *)((const float *)p + i + 4);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) { v[k] = a[k]; v[4 + k] = b[k]; }
+    }
+}
+
+__device__ __forceinline__ void store8(void *p, int dtype, int64_t i, const float v[8])
+{
+    if (dtype == DT_BF16) {
+        u32x4 r;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) r[k] = f32_to_bf16_bits(v[2 * k]) | (f32_to_bf16_bits(v[2 * k + 1]) << 16);
+        *(u32x4 *)((uint16_t *)p + i) = r;
+    } else {
+        f32x4 a, b;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) { a[k] = v[k]; b[k] = v[4 + k]; }
+        *(f32x4 *)((float *)p + i) = a;
+        *(f32x4 *)((float *)p + i + 4) = b;
+    }
+}
+
+__device__ __forceinline__ float binop(int op, float v, float t)
+{
+    switch (op) {
+    case E_ADD: return v + t;
+    case E_SUB: return v - t;
+    case E_RSUB: return t - v;
+    case E_MUL: return v * t;
+    case E_DIV: return v / t;
+    default: return t / v;   // E_RDIV
+    }
+}
+
+__global__ __launch_bounds__(256) void eltwise_kernel(const EltwiseParams p)
+{
+    const Epilogue &e = p.epi;
+    const int64_t nvec = p.n >> 3;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t vi = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; vi < nvec; vi += stride) {
+        const int64_t i0 = vi << 3;
+        float v[8];
+        load8(p.x, p.x_dtype, i0, v);
+        for (int s = 0; s < e.n_ops; ++s) {
+            const int op = e.op[s], a = e.arg[s];
+            if (op == E_BIAS) {
+                // channel of element i: (i / ch_inner) % ch_count
+                if (p.ch_inner == 1 && (p.ch_count & 7) == 0) {
+                    int ch = (int)(i0 % p.ch_count);
+                    float b[8];
+                    load8(e.ptr[a], e.ptr_dtype[a], ch, b);
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) v[k] += b[k];
+                } else if ((p.ch_inner & 7) == 0) {
+                    int ch = (int)((i0 / p.ch_inner) % p.ch_count);
+                    float b = load_as_f32(e.ptr[a], e.ptr_dtype[a], ch);
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) v[k] += b;
+                } else {
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) {
+                        int ch = (int)(((i0 + k) / p.ch_inner) % p.ch_count);
+                        v[k] += load_as_f32(e.ptr[a], e.ptr_dtype[a], ch);
+                    }
+                }
+            } else if (op >= E_ADD && op <= E_RDIV) {
+                float tt[8];
+                load8(e.ptr[a], e.ptr_dtype[a], i0, tt);
+#pragma unroll
+                for (int k = 0; k < 8; ++k) v[k] = binop(op, v[k], tt[k]);
+            } else {
+#pragma unroll
+                for (int k = 0; k < 8; ++k) v[k] = epi_step(e, s, v[k], 0, 0);
+            }
+        }
+        store8(p.y, p.y_dtype, i0, v);
+    }
+    // ragged tail (< 8 elements), one thread each
+    const int64_t tail0 = nvec << 3;
+    const int64_t ti = tail0 + (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (ti < p.n) {
+        float v = load_as_f32(p.x, p.x_dtype, ti);
+        int ch = (int)((ti / p.ch_inner) % p.ch_count);
+        for (int s = 0; s < e.n_ops; ++s) v = epi_step(e, s, v, ti, ch);
+        store_from_f32(p.y, p.y_dtype, ti, v);
+    }
+}
+
+hipError_t launch_eltwise(const EltwiseParams &p, hipStream_t s)
+{
+    int64_t nvec = p.n >> 3;
+    int64_t blocks = (nvec + 255) / 256;
+    const int64_t cap = 256 * 16;               // 16 workgroups per CU, grid-stride beyond that
+    if (blocks > cap) blocks = cap;
+    if (blocks < 1) blocks = 1;
+    hipLaunchKernelGGL(eltwise_kernel, dim3((unsigned)blocks), dim3(256), 0, s, p);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// stand-alone LSTM gate group: z[B, 4H] in (i | f | g | o) blocks
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void lstm_gates_kernel(const GatesParams p)
+{
+    const int64_t total = (int64_t)p.B * p.H;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    if ((p.H & 3) == 0) {
+        for (int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; q < (total >> 2); q += stride) {
+            int64_t idx = q << 2;
+            int b = (int)(idx / p.H), u = (int)(idx - (int64_t)b * p.H);
+            const float *zr = p.z + (int64_t)b * 4 * p.H + u;
+            f32x4 zi = *(const f32x4 *)zr, zf = *(const f32x4 *)(zr + p.H);
+            f32x4 zg = *(const f32x4 *)(zr + 2 * p.H), zo = *(const f32x4 *)(zr + 3 * p.H);
+            f32x4 c = *(const f32x4 *)(p.c_in + idx), cn;
+            float hn[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                cn[k] = sigmoidf_(zf[k]) * c[k] + sigmoidf_(zi[k]) * tanhf_(zg[k]);
+                hn[k] = sigmoidf_(zo[k]) * tanhf_(cn[k]);
+            }
+            *(f32x4 *)(p.c_out + idx) = cn;
+            if (p.h_dtype == DT_BF16) {
+                u32x2 r;
+                r[0] = f32_to_bf16_bits(hn[0]) | (f32_to_bf16_bits(hn[1]) << 16);
+                r[1] = f32_to_bf16_bits(hn[2]) | (f32_to_bf16_bits(hn[3]) << 16);
+                *(u32x2 *)((uint16_t *)p.h_out + idx) = r;
+            } else {
+                f32x4 hv = {hn[0], hn[1], hn[2], hn[3]};
+                *(f32x4 *)((float *)p.h_out + idx) = hv;
+            }
+        }
+    } else {
+        for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += stride) {
+            int b = (int)(idx / p.H), u = (int)(idx - (int64_t)b * p.H);
+            const float *zr = p.z + (int64_t)b * 4 * p.H + u;
+            float cn = sigmoidf_(zr[p.H]) * p.c_in[idx] + sigmoidf_(zr[0]) * tanhf_(zr[2 * p.H]);
+            p.c_out[idx] = cn;
+            store_from_f32(p.h_out, p.h_dtype, idx, sigmoidf_(zr[3 * p.H]) * tanhf_(cn));
+        }
+    }
+}
+
+hipError_t launch_lstm_gates(const GatesParams &p, hipStream_t s)
+{
+    int64_t work = ((int64_t)p.B * p.H + 3) / 4;
+    int64_t blocks = (work + 255) / 256;
+    if (blocks > 4096) blocks = 4096;
+    if (blocks < 1) blocks = 1;
+    hipLaunchKernelGGL(lstm_gates_kernel, dim3((unsigned)blocks), dim3(256), 0, s, p);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// window reductions on channel-last tensors; VEC channels per thread
+// ---------------------------------------------------------------------------
+template <typename T, int VEC> struct VecIO;
+template <> struct VecIO<uint16_t, 8> {
+    static __device__ void load(const uint16_t *p, float v[8]) { load8(p, DT_BF16, 0, v); }
+    static __device__ void store(uint16_t *p, const float v[8]) { store8(p, DT_BF16, 0, v); }
+};
+template <> struct VecIO<float, 4> {
+    static __device__ void load(const float *p, float v[4]) { f32x4 a = *(const f32x4 *)p; for (int k = 0; k < 4; ++k) v[k] = a[k]; }
+    static __device__ void store(float *p, const float v[4]) { f32x4 a = {v[0], v[1], v[2], v[3]}; *(f32x4 *)p = a; }
+};
+template <> struct VecIO<uint16_t, 1> {
+    static __device__ void load(const uint16_t *p, float v[1]) { v[0] = bf16_bits_to_f32(*p); }
+    static __device__ void store(uint16_t *p, const float v[1]) { *p = (uint16_t)f32_to_bf16_bits(v[0]); }
+};
+template <> struct VecIO<float, 1> {
+    static __device__ void load(const float *p, float v[1]) { v[0] = *p; }
+    static __device__ void store(float *p, const float v[1]) { *p = v[0]; }
+};
+
+template <typename T, int VEC>
+__global__ __launch_bounds__(256) void maxpool_nhwc_kernel(const PoolParams p)
+{
+    const int cv = p.C / VEC;
+    const int64_t total = (int64_t)p.N * p.OH * p.OW * cv;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    const T *x = (const T *)p.x;
+    T *y = (T *)p.y;
+    for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += stride) {
+        int c = (int)(idx % cv) * VEC;
+        int64_t q = idx / cv;
+        int ow = (int)(q % p.OW); q /= p.OW;
+        int oh = (int)(q % p.OH);
+        int n = (int)(q / p.OH);
+        float best[VEC];
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) best[k] = -INFINITY;
+        for (int a = 0; a < p.KH; ++a) {
+            int ih = oh * p.sh - p.ph + a;
+            if ((unsigned)ih >= (unsigned)p.H) continue;
+            for (int b = 0; b < p.KW; ++b) {
+                int iw = ow * p.sw - p.pw + b;
+                if ((unsigned)iw >= (unsigned)p.W) continue;
+                float v[VEC];
+                VecIO<T, VEC>::load(x + (((int64_t)n * p.H + ih) * p.W + iw) * p.C + c, v);
+#pragma unroll
+                for (int k = 0; k < VEC; ++k) best[k] = v[k] > best[k] ? v[k] : best[k];
+            }
+        }
+        VecIO<T, VEC>::store(y + (((int64_t)n * p.OH + oh) * p.OW + ow) * p.C + c, best);
+    }
+}
+
+template <typename T, int VEC>
+__global__ __launch_bounds__(256) void gavgpool_nhwc_kernel(const PoolParams p)
+{
+    const int cv = p.C / VEC;
+    const int64_t total = (int64_t)p.N * cv;
+    const T *x = (const T *)p.x;
+    T *y = (T *)p.y;
+    const int HW = p.H * p.W;
+    for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += (int64_t)gridDim.x * blockDim.x) {
+        int c = (int)(idx % cv) * VEC;
+        int n = (int)(idx / cv);
+        float acc[VEC];
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) acc[k] = 0.0f;
+        for (int q = 0; q < HW; ++q) {
+            float v[VEC];
+            VecIO<T, VEC>::load(x + ((int64_t)n * HW + q) * p.C + c, v);
+#pragma unroll
+            for (int k = 0; k < VEC; ++k) acc[k] += v[k];
+        }
+        const float inv = 1.0f / (float)HW;
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) acc[k] *= inv;
+        VecIO<T, VEC>::store(y + (int64_t)n * p.C + c, acc);
+    }
+}
+
+template <template <typename, int> class K>
+struct PoolDispatch;
+
+static inline unsigned grid_for(int64_t total)
+{
+    int64_t blocks = (total + 255) / 256;
+    if (blocks > 256 * 32) blocks = 256 * 32;
+    if (blocks < 1) blocks = 1;
+    return (unsigned)blocks;
+}
+
+hipError_t launch_maxpool_nhwc(const PoolParams &p, hipStream_t s)
+{
+    if (p.dtype == DT_BF16) {
+        if (p.C % 8 == 0) hipLaunchKernelGGL((maxpool_nhwc_kernel<uint16_t, 8>), dim3(grid_for((int64_t)p.N * p.OH * p.OW * (p.C / 8))), dim3(256), 0, s, p);
+        else hipLaunchKernelGGL((maxpool_nhwc_kernel<uint16_t, 1>), dim3(grid_for((int64_t)p.N * p.OH * p.OW * p.C)), dim3(256), 0, s, p);
+    } else {
+        if (p.C % 4 == 0) hipLaunchKernelGGL((maxpool_nhwc_kernel<float, 4>), dim3(grid_for((int64_t)p.N * p.OH * p.OW * (p.C / 4))), dim3(256), 0, s, p);
+        else hipLaunchKernelGGL((maxpool_nhwc_kernel<float, 1>), dim3(grid_for((int64_t)p.N * p.OH * p.OW * p.C)), dim3(256), 0, s, p);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_gavgpool_nhwc(const PoolParams &p, hipStream_t s)
+{
+    if (p.dtype == DT_BF16) {
+        if (p.C % 8 == 0) hipLaunchKernelGGL((gavgpool_nhwc_kernel<uint16_t, 8>), dim3(grid_for((int64_t)p.N * (p.C / 8))), dim3(256), 0, s, p);
+        else hipLaunchKernelGGL((gavgpool_nhwc_kernel<uint16_t, 1>), dim3(grid_for((int64_t)p.N * p.C)), dim3(256), 0, s, p);
+    } else {
+        if (p.C % 4 == 0) hipLaunchKernelGGL((gavgpool_nhwc_kernel<float, 4>), dim3(grid_for((int64_t)p.N * (p.C / 4))), dim3(256), 0, s, p);
+        else hipLaunchKernelGGL((gavgpool_nhwc_kernel<float, 1>), dim3(grid_for((int64_t)p.N * p.C)), dim3(256), 0, s, p);
+    }
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// layout change through a 32 x 32 LDS tile: src[n][r][q] -> dst[n][q][r]
+// (R rows of Q contiguous elements become Q rows of R contiguous elements)
+// ---------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void transpose_kernel(const T *__restrict__ src, T *__restrict__ dst, int R, int Q)
+{
+    __shared__ T tile[32][33];
+    const int n = blockIdx.z;
+    const int q0 = blockIdx.x * 32, r0 = blockIdx.y * 32;
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;     // 32 x 8
+    const T *s = src + (int64_t)n * R * Q;
+    T *d = dst + (int64_t)n * R * Q;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        int r = r0 + ty + 8 * k, q = q0 + tx;
+        if (r < R && q < Q) tile[ty + 8 * k][tx] = s[(int64_t)r * Q + q];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        int q = q0 + ty + 8 * k, r = r0 + tx;
+        if (r < R && q < Q) d[(int64_t)q * R + r] = tile[tx][ty + 8 * k];
+    }
+}
+
+static hipError_t launch_transpose(const void *src, void *dst, int dtype, int N, int R, int Q, hipStream_t s)
+{
+    dim3 grid((Q + 31) / 32, (R + 31) / 32, N);
+    if (grid.y > 65535 || grid.z > 65535) return hipErrorInvalidValue;
+    if (dtype == DT_BF16) hipLaunchKernelGGL(transpose_kernel<uint16_t>, grid, dim3(256), 0, s, (const uint16_t *)src, (uint16_t *)dst, R, Q);
+    else hipLaunchKernelGGL(transpose_kernel<float>, grid, dim3(256), 0, s, (const float *)src, (float *)dst, R, Q);
+    return hipGetLastError();
+}
+
+hipError_t launch_nchw_to_nhwc(const void *src, void *dst, int32_t dtype, int32_t N, int32_t C, int32_t P, hipStream_t s)
+{
+    return launch_transpose(src, dst, dtype, N, C, P, s);
+}
+
+hipError_t launch_nhwc_to_nchw(const void *src, void *dst, int32_t dtype, int32_t N, int32_t C, int32_t P, hipStream_t s)
+{
+    return launch_transpose(src, dst, dtype, N, P, C, s);
+}
+
+// ---------------------------------------------------------------------------
+// weight packing: src[O][C][T] -> dst[O'][T][C] with rows padded to Kp and
+// optionally permuted (gate interleave)
+// ---------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void pack_weight_kernel(const T *__restrict__ src, T *__restrict__ dst, int O, int C, int Tt,
+                                                          int Kp, int perm_block)
+{
+    const int64_t total = (int64_t)O * Kp;
+    for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += (int64_t)gridDim.x * blockDim.x) {
+        int k = (int)(idx % Kp);
+        int j = (int)(idx / Kp);
+        int o = j;
+        if (perm_block > 0) {
+            int U = perm_block / 4;
+            int blk = j / perm_block, r = j - blk * perm_block;
+            int gate = r / U, u = r - gate * U;
+            o = gate * (O / 4) + blk * U + u;
+        }
+        T v = 0;
+        if (k < C * Tt) {
+            int tap = k / C, c = k - tap * C;
+            v = src[((int64_t)o * C + c) * Tt + tap];
+        }
+        dst[idx] = v;
+    }
+}
+
+hipError_t launch_pack_weight(const void *src, void *dst, int32_t dtype, int32_t O, int32_t C, int32_t T, int32_t Kp,
+                              int32_t perm_block, hipStream_t s)
+{
+    unsigned grid = grid_for((int64_t)O * Kp);
+    if (dtype == DT_BF16) hipLaunchKernelGGL(pack_weight_kernel<uint16_t>, dim3(grid), dim3(256), 0, s, (const uint16_t *)src, (uint16_t *)dst, O, C, T, Kp, perm_block);
+    else hipLaunchKernelGGL(pack_weight_kernel<float>, dim3(grid), dim3(256), 0, s, (const float *)src, (float *)dst, O, C, T, Kp, perm_block);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// batch-norm folding, float64 arithmetic
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void fold_bn_kernel(const float *__restrict__ w, const float *__restrict__ gamma,
+                                                      const float *__restrict__ beta, const float *__restrict__ mean,
+                                                      const float *__restrict__ var, double eps, void *w_out, int out_dtype,
+                                                      float *b_out, int64_t O, int64_t per_o)
+{
+    const int64_t total = O * per_o;
+    for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += (int64_t)gridDim.x * blockDim.x) {
+        int64_t o = idx / per_o;
+        double scale = (double)gamma[o] / sqrt((double)var[o] + eps);
+        float r = (float)((double)w[idx] * scale);
+        store_from_f32(w_out, out_dtype, idx, r);
+        if (idx == o * per_o) b_out[o] = (float)((double)beta[o] - (double)mean[o] * scale);
+    }
+}
+
+hipError_t launch_fold_bn(const float *w, const float *gamma, const float *beta, const float *mean, const float *var,
+                          double eps, void *w_out, int32_t out_dtype, float *b_out, int64_t O, int64_t per_o, hipStream_t s)
+{
+    hipLaunchKernelGGL(fold_bn_kernel, dim3(grid_for(O * per_o)), dim3(256), 0, s, w, gamma, beta, mean, var, eps, w_out,
+                       out_dtype, b_out, O, per_o);
+    return hipGetLastError();
+}
+
+}  // namespace rl

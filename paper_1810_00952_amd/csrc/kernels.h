@@ -1,0 +1,101 @@
+// Launch descriptors shared by the planner/executor (host) and the gfx950
+// kernels.  Plain structs passed by value as kernel arguments.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace rl {
+
+enum { DT_F32 = 0, DT_BF16 = 1 };
+
+// ---- injective epilogue program ------------------------------------------
+// A fused group's injective operators form a chain over one running value v
+// (the contraction's accumulator, or the first operand of an anchor-less
+// group).  Each step is one op code and, for ops with a second operand, the
+// index of that operand in the pointer table.
+enum EpiOp : uint8_t {
+    E_BIAS = 0,   // v += vec[channel]
+    E_ADD, E_SUB, E_RSUB, E_MUL, E_DIV, E_RDIV,   // v = v op t[idx]   (R*: t[idx] op v)
+    E_NEG, E_SQ, E_RELU, E_SIGMOID, E_TANH,
+    E_ADD_VV, E_SUB_VV, E_DIV_VV,                 // both operands are the running value
+    E_ROUND_BF16,                                 // cast to bf16 (value stays in a float register)
+    E_NOP
+};
+#define RL_EPI_MAX_OPS 12
+#define RL_EPI_MAX_PTRS 6
+
+struct Epilogue {
+    int32_t n_ops;
+    uint8_t op[RL_EPI_MAX_OPS];
+    uint8_t arg[RL_EPI_MAX_OPS];
+    const void *ptr[RL_EPI_MAX_PTRS];
+    uint8_t ptr_dtype[RL_EPI_MAX_PTRS];
+};
+
+// ---- implicit-GEMM contraction (conv2d and dense) ------------------------
+// C[m, n] = sum_k A[m, k] * Wp[n, k], m = (image, oh, ow), n = output channel,
+// k = (kh, kw, c).  A is gathered from x with element strides; Wp is the
+// packed weight [N][Kp] (K contiguous, Kp a multiple of the 16-byte vector).
+struct IgemmParams {
+    const void *x;
+    const void *x2;          // second operand of a row concatenation (dense): k >= K1 reads x2[m, k-K1]
+    const void *w;
+    void *y;
+    int32_t M, N, K, Kp, K1;
+    int32_t C, H, W, KH, KW, OH, OW, OHW, sh, sw, ph, pw;
+    int64_t xs_n, xs_c, xs_h, xs_w;     // element strides of x
+    int64_t x2s_n;                      // row stride of x2
+    int64_t ys_n, ys_p, ys_c;           // element strides of y: image, pixel (oh*OW+ow), channel
+    int32_t y_dtype;                    // DT_*
+    int32_t in_dtype;
+    Epilogue epi;
+    // LSTM gate epilogue (mode GATES): packed column j of block tile holds gate j/(BN/4), unit j%(BN/4)
+    const float *c_in; float *c_out; void *h_out; int32_t h_dtype; int32_t hidden;
+    int32_t nblk_m, nblk_n;
+};
+
+enum IgemmTile { TILE_128x128 = 0, TILE_128x64 = 1, TILE_64x64 = 2, TILE_COUNT };
+struct IgemmLaunch {
+    int32_t tile;       // IgemmTile
+    int32_t avec;       // 1: A rows are 16-byte-vector loadable (channel-contiguous, aligned)
+    int32_t gates;      // 1: LSTM gate epilogue (tile must be TILE_64x64)
+};
+hipError_t launch_igemm(const IgemmParams &p, const IgemmLaunch &l, hipStream_t s);
+
+// ---- purely elementwise fused group ---------------------------------------
+struct EltwiseParams {
+    const void *x; int32_t x_dtype;     // first operand: initial running value
+    void *y; int32_t y_dtype;
+    int64_t n;                          // elements
+    int64_t ch_inner; int32_t ch_count; // channel of flat index i = (i / ch_inner) % ch_count (for E_BIAS)
+    Epilogue epi;
+};
+hipError_t launch_eltwise(const EltwiseParams &p, hipStream_t s);
+
+struct GatesParams {
+    const float *z; const float *c_in; float *c_out; void *h_out; int32_t h_dtype; int32_t B, H;
+};
+hipError_t launch_lstm_gates(const GatesParams &p, hipStream_t s);
+
+// ---- window reductions (channel-last tensors [N, H, W, C]) ------------------
+struct PoolParams {
+    const void *x; void *y; int32_t dtype;
+    int32_t N, C, H, W, OH, OW, KH, KW, sh, sw, ph, pw;
+};
+hipError_t launch_maxpool_nhwc(const PoolParams &p, hipStream_t s);
+hipError_t launch_gavgpool_nhwc(const PoolParams &p, hipStream_t s);   // y: [N, C]
+
+// ---- layout change and weight packing -------------------------------------
+// dst[n, p, c] (pixel-major, channel-last) <-> src[n, c, p]
+hipError_t launch_nchw_to_nhwc(const void *src, void *dst, int32_t dtype, int32_t N, int32_t C, int32_t P, hipStream_t s);
+hipError_t launch_nhwc_to_nchw(const void *src, void *dst, int32_t dtype, int32_t N, int32_t C, int32_t P, hipStream_t s);
+// conv weight [O, C, KH*KW] -> [O, KH*KW, C] padded with zeros to Kp per row.
+// perm_block > 0: output row j holds source row gate*(O/4) + blk*(perm_block/4) + u
+// for j = blk*perm_block + gate*(perm_block/4) + u (LSTM gate interleave).
+hipError_t launch_pack_weight(const void *src, void *dst, int32_t dtype, int32_t O, int32_t C, int32_t T,
+                              int32_t Kp, int32_t perm_block, hipStream_t s);
+hipError_t launch_fold_bn(const float *w, const float *gamma, const float *beta, const float *mean, const float *var,
+                          double eps, void *w_out, int32_t out_dtype, float *b_out, int64_t O, int64_t per_o,
+                          hipStream_t s);
+
+}  // namespace rl

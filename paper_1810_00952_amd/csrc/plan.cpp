@@ -1,0 +1,662 @@
+// Fusion-group planner and executor (host).
+//
+// For every caller-declared group the planner re-checks legality, picks the
+// kernel (implicit-GEMM contraction with epilogue, single-pass elementwise
+// chain, window reduction, gate kernel), the tile, and the private layout of
+// each intermediate: rank-4 activations between contractions live
+// channel-last so that a K slice of the implicit GEMM is a run of channels;
+// tensors at the boundary keep the order of their Shape.  Layout changes are
+// inserted only where a consumer cannot read what its producer wrote.
+#include "plan.h"
+
+#include <algorithm>
+#include <set>
+#include <sstream>
+
+namespace rl {
+
+namespace {
+
+enum { L_NATIVE = 0, L_NHWC = 1 };
+
+inline int64_t round_up(int64_t a, int64_t b) { return (a + b - 1) / b * b; }
+inline int kv_of(int dtype) { return dtype == RL_BF16 ? 8 : 4; }
+
+struct Planner {
+    const Graph &g;
+    Plan &plan;
+    std::string &msg;
+    std::vector<int> phys[2];              // [layout][value] -> buffer index or -1
+    std::set<int> out_set;
+    std::vector<std::vector<int>> consumers;
+
+    Planner(const Graph &g_, Plan &p_, std::string &m_) : g(g_), plan(p_), msg(m_) {}
+
+    rl_status fail(rl_status st, const std::string &m) { msg = m; return st; }
+
+    const rl_type &T(int v) const { return g.values[v].type; }
+    bool hw1(int v) const { return T(v).rank == 4 && T(v).dims[2] * T(v).dims[3] == 1; }
+    bool layout_free(int v) const { return T(v).rank != 4 || hw1(v) || T(v).dims[1] == 1; }
+    size_t bytes_of(int v) const { return (size_t)numel(T(v)) * dtype_size(T(v).dtype); }
+
+    int bound(int v)
+    {
+        if (plan.bound_buf[v] < 0) {
+            BufDesc b;
+            b.bound_value = v;
+            b.bytes = bytes_of(v);
+            plan.bufs.push_back(b);
+            plan.bound_buf[v] = (int)plan.bufs.size() - 1;
+        }
+        return plan.bound_buf[v];
+    }
+    int new_ws(size_t bytes)
+    {
+        BufDesc b;
+        b.bytes = round_up((int64_t)bytes, 256);
+        plan.bufs.push_back(b);
+        return (int)plan.bufs.size() - 1;
+    }
+    void set_phys(int v, int layout, int buf)
+    {
+        phys[layout][v] = buf;
+        if (layout_free(v)) phys[1 - layout][v] = buf;
+    }
+    // buffer a step writes value v into, in `layout`
+    int out_buf(int v, int layout)
+    {
+        int b;
+        if (out_set.count(v) && (layout == L_NATIVE || layout_free(v))) b = bound(v);
+        else b = new_ws(bytes_of(v));
+        set_phys(v, layout, b);
+        return b;
+    }
+    Step &add_step(int kind, const std::string &name, const std::string &kernel)
+    {
+        plan.steps.emplace_back();
+        Step &s = plan.steps.back();
+        s.kind = kind;
+        s.name = name;
+        s.kernel = kernel;
+        return s;
+    }
+    // make value v available in `layout`; returns the buffer
+    rl_status need(int v, int layout, int &buf)
+    {
+        if (phys[layout][v] >= 0) { buf = phys[layout][v]; return RL_OK; }
+        int other = phys[1 - layout][v];
+        if (other < 0) return fail(RL_ERR_UNSUPPORTED, "internal: value has no storage yet");
+        const rl_type &t = T(v);
+        int dst = out_buf(v, layout);
+        Step &s = add_step(layout == L_NHWC ? S_TO_NHWC : S_TO_NCHW, "layout", layout == L_NHWC ? "nchw_to_nhwc" : "nhwc_to_nchw");
+        s.t_dtype = t.dtype; s.t_N = (int)t.dims[0]; s.t_C = (int)t.dims[1]; s.t_P = (int)(t.dims[2] * t.dims[3]);
+        s.slot[SL_X] = other; s.slot[SL_Y] = dst;
+        s.bytes = 2.0 * bytes_of(v);
+        buf = dst;
+        return RL_OK;
+    }
+
+    // ---- injective chain -------------------------------------------------
+    struct Chain {
+        Epilogue epi{};
+        std::vector<int> operand;        // value id per pointer slot
+        std::vector<bool> is_vec;        // bias vector (1-D) or full-shape tensor
+        int bias_axis = -1;
+        int last_value = -1;
+    };
+    rl_status push_op(Chain &c, uint8_t op, int operand, bool vec)
+    {
+        if (c.epi.n_ops >= RL_EPI_MAX_OPS) return fail(RL_ERR_UNSUPPORTED, "fused chain longer than the kernel's program");
+        int a = 0;
+        if (operand >= 0) {
+            a = -1;
+            for (size_t i = 0; i < c.operand.size(); ++i)
+                if (c.operand[i] == operand) a = (int)i;
+            if (a < 0) {
+                if ((int)c.operand.size() >= RL_EPI_MAX_PTRS) return fail(RL_ERR_UNSUPPORTED, "fused chain has too many operands");
+                c.operand.push_back(operand);
+                c.is_vec.push_back(vec);
+                a = (int)c.operand.size() - 1;
+                c.epi.ptr_dtype[a] = (uint8_t)T(operand).dtype;
+            }
+        }
+        c.epi.op[c.epi.n_ops] = op;
+        c.epi.arg[c.epi.n_ops] = (uint8_t)a;
+        c.epi.n_ops++;
+        return RL_OK;
+    }
+    // ops[from..to) applied to running value `cur`
+    rl_status build_chain(const std::vector<int> &ops, size_t from, size_t to, int cur, const std::set<int> &gset, Chain &c)
+    {
+        for (size_t i = from; i < to; ++i) {
+            const OpNode &o = g.ops[ops[i]];
+            auto external = [&](int v) { return g.values[v].producer < 0 || !gset.count(g.values[v].producer); };
+            rl_status st = RL_OK;
+            switch (o.kind) {
+            case RL_OP_NEG: case RL_OP_SQ: case RL_OP_RELU: case RL_OP_SIGMOID: case RL_OP_TANH: case RL_OP_CAST: {
+                if (o.in[0] != cur) return fail(RL_ERR_UNSUPPORTED, "fused group is not a single chain");
+                uint8_t code = o.kind == RL_OP_NEG ? E_NEG : o.kind == RL_OP_SQ ? E_SQ : o.kind == RL_OP_RELU ? E_RELU
+                             : o.kind == RL_OP_SIGMOID ? E_SIGMOID : o.kind == RL_OP_TANH ? E_TANH
+                             : (o.attrs.to == RL_BF16 ? E_ROUND_BF16 : E_NOP);
+                st = push_op(c, code, -1, false);
+                break;
+            }
+            case RL_OP_BIAS_ADD:
+                if (o.in[0] != cur || !external(o.in[1])) return fail(RL_ERR_UNSUPPORTED, "fused group is not a single chain");
+                if (c.bias_axis >= 0 && c.bias_axis != o.attrs.axis) return fail(RL_ERR_UNSUPPORTED, "bias_add along two axes in one group");
+                c.bias_axis = o.attrs.axis;
+                st = push_op(c, E_BIAS, o.in[1], true);
+                break;
+            case RL_OP_ADD: case RL_OP_SUB: case RL_OP_MUL: case RL_OP_DIV: {
+                int a = o.in[0], b = o.in[1];
+                if (a == cur && b == cur) {
+                    uint8_t code = o.kind == RL_OP_ADD ? E_ADD_VV : o.kind == RL_OP_SUB ? E_SUB_VV : o.kind == RL_OP_MUL ? E_SQ : E_DIV_VV;
+                    st = push_op(c, code, -1, false);
+                } else if (a == cur && external(b)) {
+                    uint8_t code = o.kind == RL_OP_ADD ? E_ADD : o.kind == RL_OP_SUB ? E_SUB : o.kind == RL_OP_MUL ? E_MUL : E_DIV;
+                    st = push_op(c, code, b, false);
+                } else if (b == cur && external(a)) {
+                    uint8_t code = o.kind == RL_OP_ADD ? E_ADD : o.kind == RL_OP_SUB ? E_RSUB : o.kind == RL_OP_MUL ? E_MUL : E_RDIV;
+                    st = push_op(c, code, a, false);
+                } else {
+                    return fail(RL_ERR_UNSUPPORTED, "fused group is not a single chain");
+                }
+                break;
+            }
+            default:
+                return fail(RL_ERR_UNSUPPORTED, std::string(op_name(o.kind)) + " inside a chain");
+            }
+            if (st != RL_OK) return st;
+            cur = o.out[0];
+        }
+        c.last_value = cur;
+        return RL_OK;
+    }
+    // bind the chain's operands to step slots; full-shape operands in `layout`
+    rl_status bind_chain(Chain &c, Step &s, int layout, double &bytes)
+    {
+        for (size_t i = 0; i < c.operand.size(); ++i) {
+            int buf;
+            rl_status st = need(c.operand[i], c.is_vec[i] ? L_NATIVE : layout, buf);
+            if (st != RL_OK) return st;
+            // `need` may have appended a layout step: s is re-fetched by the caller, so only indices are kept here
+            s.slot[SL_E0 + i] = buf;
+            bytes += (double)bytes_of(c.operand[i]);
+        }
+        return RL_OK;
+    }
+
+    // ---- contraction groups ------------------------------------------------
+    rl_status plan_anchor(int gi, const std::vector<int> &ops)
+    {
+        std::set<int> gset(ops.begin(), ops.end());
+        size_t ai = 0;
+        int x = -1, x2 = -1;
+        if (g.ops[ops[0]].kind == RL_OP_CONCAT) {
+            ai = 1;
+            const OpNode &cc = g.ops[ops[0]];
+            if (g.ops[ops[1]].in[0] != cc.out[0]) return fail(RL_ERR_UNSUPPORTED, "concat must feed the dense's first operand");
+            x = cc.in[0];
+            x2 = cc.in[1];
+        }
+        const OpNode &an = g.ops[ops[ai]];
+        if (x < 0) x = an.in[0];
+        const int wv = an.in[1];
+        if (g.values[wv].role != ROLE_PARAM) return fail(RL_ERR_UNSUPPORTED, "contraction weights must be a param");
+        const int in_dt = T(x).dtype;
+        const int KV = kv_of(in_dt);
+        const bool gates = g.ops[ops.back()].kind == RL_OP_LSTM_GATES && ops.size() > ai + 1;
+        Chain chain;
+        rl_status st = build_chain(ops, ai + 1, gates ? ops.size() - 1 : ops.size(), an.out[0], gset, chain);
+        if (st != RL_OK) return st;
+        if (chain.bias_axis >= 0 && chain.bias_axis != 1) return fail(RL_ERR_UNSUPPORTED, "bias_add fused into a contraction must be along axis 1");
+        if (gates)
+            for (int i = 0; i < chain.epi.n_ops; ++i)
+                if (chain.epi.op[i] != E_BIAS) return fail(RL_ERR_UNSUPPORTED, "only bias_add may sit between the contraction and lstm_gates");
+
+        IgemmParams p{};
+        IgemmLaunch il{};
+        PackSpec pack;
+        bool need_pack = false;
+        int xbuf = -1, x2buf = -1;
+        const rl_type &ot = T(an.out[0]);
+        p.in_dtype = in_dt;
+        int out_layout = L_NATIVE;
+        const int vout = gates ? -1 : chain.last_value;
+
+        if (an.kind == RL_OP_CONV2D) {
+            const rl_type &xt = T(x), &wt = T(wv);
+            p.C = (int)xt.dims[1]; p.H = (int)xt.dims[2]; p.W = (int)xt.dims[3];
+            p.KH = (int)wt.dims[2]; p.KW = (int)wt.dims[3];
+            p.OH = (int)ot.dims[2]; p.OW = (int)ot.dims[3]; p.OHW = p.OH * p.OW;
+            p.sh = an.attrs.stride[0]; p.sw = an.attrs.stride[1]; p.ph = an.attrs.pad[0]; p.pw = an.attrs.pad[1];
+            if (xt.dims[0] * (int64_t)p.OHW > 0x7fffffff) return fail(RL_ERR_UNSUPPORTED, "conv2d too large");
+            p.M = (int)(xt.dims[0] * p.OHW); p.N = (int)wt.dims[0]; p.K = p.C * p.KH * p.KW; p.K1 = p.K;
+            p.Kp = (int)round_up(p.K, KV);
+            il.avec = (p.C % KV == 0);
+            int xl;
+            if (il.avec) xl = L_NHWC;
+            else xl = phys[L_NATIVE][x] >= 0 ? L_NATIVE : L_NHWC;
+            st = need(x, xl, xbuf);
+            if (st != RL_OK) return st;
+            if (xl == L_NHWC) { p.xs_n = (int64_t)p.H * p.W * p.C; p.xs_h = (int64_t)p.W * p.C; p.xs_w = p.C; p.xs_c = 1; }
+            else { p.xs_n = (int64_t)p.C * p.H * p.W; p.xs_c = (int64_t)p.H * p.W; p.xs_h = p.W; p.xs_w = 1; }
+            need_pack = !(p.KH * p.KW == 1 && p.C % KV == 0);
+            pack.dtype = in_dt; pack.O = p.N; pack.C = p.C; pack.T = p.KH * p.KW; pack.Kp = p.Kp; pack.perm_block = 0;
+            out_layout = (vout >= 0 && out_set.count(vout)) ? L_NATIVE : L_NHWC;
+            if (out_layout == L_NHWC) { p.ys_n = (int64_t)p.OHW * p.N; p.ys_p = p.N; p.ys_c = 1; }
+            else { p.ys_n = (int64_t)p.N * p.OHW; p.ys_p = 1; p.ys_c = p.OHW; }
+        } else {
+            const rl_type &wt = T(wv);
+            const int64_t K = wt.dims[1];
+            if (ot.dims[0] > 0x7fffffff || K > 0x7ffffff0 || wt.dims[0] > 0x7fffffff) return fail(RL_ERR_UNSUPPORTED, "dense too large");
+            p.M = (int)ot.dims[0]; p.N = (int)wt.dims[0]; p.K = (int)K; p.Kp = (int)round_up(K, KV);
+            p.C = p.K; p.H = p.W = p.KH = p.KW = p.OH = p.OW = p.OHW = 1; p.sh = p.sw = 1;
+            p.K1 = x2 >= 0 ? (int)T(x).dims[1] : p.K;
+            const int K2 = p.K - p.K1;
+            il.avec = (p.K1 % KV == 0) && (K2 % KV == 0);
+            st = need(x, L_NATIVE, xbuf);
+            if (st != RL_OK) return st;
+            if (x2 >= 0) { st = need(x2, L_NATIVE, x2buf); if (st != RL_OK) return st; }
+            p.xs_n = p.K1; p.xs_c = 1; p.xs_h = 0; p.xs_w = 0; p.x2s_n = K2;
+            need_pack = (p.K % KV != 0) || gates;
+            pack.dtype = in_dt; pack.O = p.N; pack.C = p.K; pack.T = 1; pack.Kp = p.Kp; pack.perm_block = gates ? 64 : 0;
+            p.ys_n = p.N; p.ys_p = p.N; p.ys_c = 1;
+        }
+        pack.bytes = (size_t)pack.O * pack.Kp * dtype_size(in_dt);
+        if (need_pack) {
+            auto it = plan.packs.find(wv);
+            if (it != plan.packs.end() && (it->second.perm_block != pack.perm_block || it->second.Kp != pack.Kp))
+                return fail(RL_ERR_UNSUPPORTED, "one param needs two different kernel-native layouts");
+            plan.packs[wv] = pack;
+        } else if (plan.packs.count(wv)) {
+            return fail(RL_ERR_UNSUPPORTED, "one param needs two different kernel-native layouts");
+        }
+
+        // tile: the largest that still yields enough workgroups for 256 CUs
+        auto nblk = [&](int bm, int bn) { return (int64_t)((p.M + bm - 1) / bm) * ((p.N + bn - 1) / bn); };
+        if (gates) {
+            il.tile = TILE_64x64;
+            il.gates = 1;
+            int64_t Hd = T(g.ops[ops.back()].in[1]).dims[1];
+            if (Hd % 16 != 0) return fail(RL_ERR_UNSUPPORTED, "fused gate epilogue needs hidden size divisible by 16");
+            p.hidden = (int)Hd;
+            p.h_dtype = T(g.ops[ops.back()].out[1]).dtype;
+        } else if (!il.avec) {
+            il.tile = TILE_64x64;
+        } else if (p.N > 64 && nblk(128, 128) >= 192) {
+            il.tile = TILE_128x128;
+        } else if (nblk(128, 64) >= 192) {
+            il.tile = TILE_128x64;
+        } else {
+            il.tile = TILE_64x64;
+        }
+
+        double bytes = (double)bytes_of(x) + (x2 >= 0 ? (double)bytes_of(x2) : 0.0) + (double)bytes_of(wv);
+        std::vector<int> eslots(RL_EPI_MAX_PTRS, -1);
+        {
+            Step tmp;
+            st = bind_chain(chain, tmp, out_layout, bytes);
+            if (st != RL_OK) return st;
+            for (int i = 0; i < RL_EPI_MAX_PTRS; ++i) eslots[i] = tmp.slot[SL_E0 + i];
+        }
+        int cin_buf = -1, cout_buf = -1, hout_buf = -1, ybuf = -1;
+        if (gates) {
+            const OpNode &go = g.ops[ops.back()];
+            st = need(go.in[1], L_NATIVE, cin_buf);
+            if (st != RL_OK) return st;
+            cout_buf = out_buf(go.out[0], L_NATIVE);
+            hout_buf = out_buf(go.out[1], L_NATIVE);
+            bytes += 2.0 * bytes_of(go.in[1]) + bytes_of(go.out[1]);
+        } else {
+            p.y_dtype = T(vout).dtype;
+            ybuf = out_buf(vout, out_layout);
+            bytes += (double)bytes_of(vout);
+        }
+        p.epi = chain.epi;
+        static const char *tile_names[] = {"128x128", "128x64", "64x64"};
+        std::string kname = std::string(an.kind == RL_OP_CONV2D ? "igemm_conv2d_" : "igemm_dense_") + (in_dt == RL_BF16 ? "bf16_" : "f32_") +
+                            tile_names[il.tile] + (il.avec ? "" : "_gather") + (gates ? "_gates" : "");
+        Step &s = add_step(S_IGEMM, std::string(op_name(an.kind)) + "#" + std::to_string(ops[ai]), kname);
+        s.group = gi;
+        s.ig = p; s.il = il;
+        s.slot[SL_X] = xbuf; s.slot[SL_X2] = x2buf; s.slot[SL_W] = bound(wv); s.slot[SL_Y] = ybuf;
+        for (int i = 0; i < RL_EPI_MAX_PTRS; ++i) s.slot[SL_E0 + i] = eslots[i];
+        s.slot[SL_CIN] = cin_buf; s.slot[SL_COUT] = cout_buf; s.slot[SL_HOUT] = hout_buf;
+        s.flops = 2.0 * p.M * (double)p.N * p.K;
+        s.bytes = bytes;
+        return RL_OK;
+    }
+
+    // ---- anchor-less injective groups ---------------------------------------
+    rl_status plan_eltwise(int gi, const std::vector<int> &ops)
+    {
+        std::set<int> gset(ops.begin(), ops.end());
+        const OpNode &first = g.ops[ops[0]];
+        const int start = first.in[0];
+        Chain chain;
+        rl_status st = build_chain(ops, 0, ops.size(), start, gset, chain);
+        if (st != RL_OK) return st;
+        const int vout = chain.last_value;
+        const rl_type &ot = T(vout);
+        int layout = L_NATIVE;
+        if (ot.rank == 4 && !layout_free(vout) && (chain.bias_axis < 0 || chain.bias_axis == 1) && phys[L_NATIVE][start] < 0 &&
+            !out_set.count(vout))
+            layout = L_NHWC;
+        int xbuf;
+        st = need(start, layout, xbuf);
+        if (st != RL_OK) return st;
+        EltwiseParams e{};
+        e.x_dtype = T(start).dtype;
+        e.y_dtype = ot.dtype;
+        e.n = numel(ot);
+        e.ch_inner = 1; e.ch_count = 1;
+        if (chain.bias_axis >= 0) {
+            if (layout == L_NHWC) { e.ch_inner = 1; e.ch_count = (int)ot.dims[1]; }
+            else {
+                int64_t inner = 1;
+                for (int d = chain.bias_axis + 1; d < ot.rank; ++d) inner *= ot.dims[d];
+                e.ch_inner = inner; e.ch_count = (int)ot.dims[chain.bias_axis];
+            }
+        }
+        double bytes = (double)bytes_of(start) + (double)bytes_of(vout);
+        Step tmp;
+        st = bind_chain(chain, tmp, layout, bytes);
+        if (st != RL_OK) return st;
+        int ybuf = out_buf(vout, layout);
+        e.epi = chain.epi;
+        Step &s = add_step(S_ELTWISE, "eltwise#" + std::to_string(ops[0]), "eltwise_chain");
+        s.group = gi;
+        s.el = e;
+        s.slot[SL_X] = xbuf; s.slot[SL_Y] = ybuf;
+        for (int i = 0; i < RL_EPI_MAX_PTRS; ++i) s.slot[SL_E0 + i] = tmp.slot[SL_E0 + i];
+        s.flops = (double)e.n * chain.epi.n_ops;
+        s.bytes = bytes;
+        return RL_OK;
+    }
+
+    rl_status plan_pool(int gi, int oi)
+    {
+        const OpNode &o = g.ops[oi];
+        const rl_type &xt = T(o.in[0]), &ot = T(o.out[0]);
+        int xbuf;
+        rl_status st = need(o.in[0], L_NHWC, xbuf);
+        if (st != RL_OK) return st;
+        PoolParams p{};
+        p.dtype = xt.dtype;
+        p.N = (int)xt.dims[0]; p.C = (int)xt.dims[1]; p.H = (int)xt.dims[2]; p.W = (int)xt.dims[3];
+        p.OH = (int)ot.dims[2]; p.OW = (int)ot.dims[3];
+        bool mx = o.kind == RL_OP_MAXPOOL2D;
+        if (mx) {
+            p.KH = o.attrs.kernel[0]; p.KW = o.attrs.kernel[1]; p.sh = o.attrs.stride[0]; p.sw = o.attrs.stride[1];
+            p.ph = o.attrs.pad[0]; p.pw = o.attrs.pad[1];
+        }
+        int ybuf = out_buf(o.out[0], L_NHWC);
+        Step &s = add_step(mx ? S_MAXPOOL : S_GAVG, std::string(op_name(o.kind)) + "#" + std::to_string(oi), mx ? "maxpool_nhwc" : "gavgpool_nhwc");
+        s.group = gi;
+        s.po = p;
+        s.slot[SL_X] = xbuf; s.slot[SL_Y] = ybuf;
+        s.bytes = (double)bytes_of(o.in[0]) + (double)bytes_of(o.out[0]);
+        s.flops = (double)numel(ot) * (mx ? p.KH * p.KW : p.H * p.W);
+        return RL_OK;
+    }
+
+    rl_status plan_flatten(int oi)
+    {
+        const OpNode &o = g.ops[oi];
+        int buf;
+        rl_status st = need(o.in[0], L_NATIVE, buf);      // row-major order of the Shape is what flatten keeps
+        if (st != RL_OK) return st;
+        set_phys(o.out[0], L_NATIVE, buf);                // zero-copy alias
+        return RL_OK;
+    }
+
+    rl_status plan_gates(int gi, int oi)
+    {
+        const OpNode &o = g.ops[oi];
+        int zbuf, cbuf;
+        rl_status st = need(o.in[0], L_NATIVE, zbuf);
+        if (st != RL_OK) return st;
+        st = need(o.in[1], L_NATIVE, cbuf);
+        if (st != RL_OK) return st;
+        GatesParams p{};
+        p.B = (int)T(o.in[1]).dims[0]; p.H = (int)T(o.in[1]).dims[1];
+        p.h_dtype = T(o.out[1]).dtype;
+        int cob = out_buf(o.out[0], L_NATIVE), hob = out_buf(o.out[1], L_NATIVE);
+        Step &s = add_step(S_GATES, "lstm_gates#" + std::to_string(oi), "lstm_gates");
+        s.group = gi;
+        s.ga = p;
+        s.slot[SL_X] = zbuf; s.slot[SL_CIN] = cbuf; s.slot[SL_COUT] = cob; s.slot[SL_HOUT] = hob;
+        s.bytes = (double)bytes_of(o.in[0]) + 2.0 * bytes_of(o.in[1]) + bytes_of(o.out[1]);
+        s.flops = 30.0 * p.B * p.H;
+        return RL_OK;
+    }
+
+    rl_status plan_group(int gi, std::vector<int> ops)
+    {
+        std::sort(ops.begin(), ops.end());
+        rl_status st = check_group(g, ops, msg);
+        if (st != RL_OK) return st;
+        bool has_anchor = false;
+        for (int o : ops) has_anchor |= is_anchor(g.ops[o].kind);
+        if (has_anchor) return plan_anchor(gi, ops);
+        int k0 = g.ops[ops[0]].kind;
+        if (ops.size() == 1) {
+            if (k0 == RL_OP_MAXPOOL2D || k0 == RL_OP_GLOBAL_AVGPOOL) return plan_pool(gi, ops[0]);
+            if (k0 == RL_OP_FLATTEN) return plan_flatten(ops[0]);
+            if (k0 == RL_OP_LSTM_GATES) return plan_gates(gi, ops[0]);
+            if (k0 == RL_OP_CONCAT) return fail(RL_ERR_UNSUPPORTED, "concat is only implemented as the operand of a dense in its group");
+        }
+        return plan_eltwise(gi, ops);
+    }
+
+    rl_status run()
+    {
+        const int nv = (int)g.values.size();
+        plan.values = g.values;
+        plan.outputs = g.outputs;
+        plan.err = g.err;
+        plan.bound_buf.assign(nv, -1);
+        phys[0].assign(nv, -1);
+        phys[1].assign(nv, -1);
+        out_set.insert(g.outputs.begin(), g.outputs.end());
+        if (g.outputs.empty()) return fail(RL_ERR_TYPE, "graph has no output");
+        for (int v = 0; v < nv; ++v)
+            if (g.values[v].role != ROLE_OP) set_phys(v, L_NATIVE, bound(v));
+
+        // groups: declared ones plus a singleton for every ungrouped call
+        std::vector<std::vector<int>> groups = g.groups;
+        std::vector<int> group_of(g.ops.size(), -1);
+        for (size_t gi = 0; gi < groups.size(); ++gi)
+            for (int o : groups[gi]) {
+                if (o < 0 || o >= (int)g.ops.size() || group_of[o] >= 0) return fail(RL_ERR_GROUP, "an op is missing or in two groups");
+                group_of[o] = (int)gi;
+            }
+        for (size_t o = 0; o < g.ops.size(); ++o)
+            if (group_of[o] < 0) { group_of[o] = (int)groups.size(); groups.push_back({(int)o}); }
+
+        // order groups so that producers run first; a cycle between groups is illegal
+        const int ng = (int)groups.size();
+        std::vector<std::set<int>> deps(ng);
+        for (size_t o = 0; o < g.ops.size(); ++o)
+            for (int v : g.ops[o].in) {
+                int pr = g.values[v].producer;
+                if (pr >= 0 && group_of[pr] != group_of[o]) deps[group_of[o]].insert(group_of[pr]);
+            }
+        std::vector<int> order, state(ng, 0);
+        std::vector<int> key(ng);
+        for (int i = 0; i < ng; ++i) key[i] = *std::min_element(groups[i].begin(), groups[i].end());
+        std::vector<int> by_key(ng);
+        for (int i = 0; i < ng; ++i) by_key[i] = i;
+        std::sort(by_key.begin(), by_key.end(), [&](int a, int b) { return key[a] < key[b]; });
+        bool cyc = false;
+        std::vector<std::pair<int, std::set<int>::iterator>> stack;
+        for (int root : by_key) {
+            if (state[root]) continue;
+            stack.push_back({root, deps[root].begin()});
+            state[root] = 1;
+            while (!stack.empty()) {
+                auto &top = stack.back();
+                if (top.second == deps[top.first].end()) {
+                    state[top.first] = 2;
+                    order.push_back(top.first);
+                    stack.pop_back();
+                } else {
+                    int d = *top.second;
+                    ++top.second;
+                    if (state[d] == 1) { cyc = true; break; }
+                    if (state[d] == 0) { state[d] = 1; stack.push_back({d, deps[d].begin()}); }
+                }
+            }
+            if (cyc) return fail(RL_ERR_GROUP, "fusion groups depend on each other cyclically");
+        }
+        for (int gi : order) {
+            rl_status st = plan_group(gi, groups[gi]);
+            if (st != RL_OK) return st;
+        }
+        // every output must end up in its bound buffer in boundary order
+        for (int v : g.outputs) {
+            int b = bound(v);
+            if (phys[L_NATIVE][v] == b) continue;
+            if (phys[L_NATIVE][v] >= 0) {
+                EltwiseParams e{};
+                e.x_dtype = e.y_dtype = T(v).dtype;
+                e.n = numel(T(v));
+                e.ch_inner = 1; e.ch_count = 1;
+                int src = phys[L_NATIVE][v];
+                Step &s = add_step(S_ELTWISE, "copy_out", "eltwise_chain");
+                s.el = e;
+                s.slot[SL_X] = src; s.slot[SL_Y] = b;
+                s.bytes = 2.0 * bytes_of(v);
+            } else if (phys[L_NHWC][v] >= 0) {
+                const rl_type &t = T(v);
+                int src = phys[L_NHWC][v];
+                Step &s = add_step(S_TO_NCHW, "layout_out", "nhwc_to_nchw");
+                s.t_dtype = t.dtype; s.t_N = (int)t.dims[0]; s.t_C = (int)t.dims[1]; s.t_P = (int)(t.dims[2] * t.dims[3]);
+                s.slot[SL_X] = src; s.slot[SL_Y] = b;
+                s.bytes = 2.0 * bytes_of(v);
+            } else {
+                return fail(RL_ERR_TYPE, "an output is never computed");
+            }
+        }
+        assign_workspace();
+        return RL_OK;
+    }
+
+    // liveness-based first-fit packing of workspace buffers
+    void assign_workspace()
+    {
+        for (size_t si = 0; si < plan.steps.size(); ++si)
+            for (int b : plan.steps[si].slot)
+                if (b >= 0) {
+                    BufDesc &d = plan.bufs[b];
+                    if (d.first < 0) d.first = (int)si;
+                    d.last = (int)si;
+                }
+        std::vector<int> ws;
+        for (size_t b = 0; b < plan.bufs.size(); ++b)
+            if (plan.bufs[b].bound_value < 0 && plan.bufs[b].first >= 0) ws.push_back((int)b);
+        std::sort(ws.begin(), ws.end(), [&](int a, int b) { return plan.bufs[a].first < plan.bufs[b].first; });
+        std::vector<int> placed;
+        size_t total = 0;
+        for (int b : ws) {
+            BufDesc &d = plan.bufs[b];
+            std::vector<std::pair<size_t, size_t>> busy;
+            for (int q : placed) {
+                const BufDesc &o = plan.bufs[q];
+                if (o.last >= d.first && o.first <= d.last) busy.push_back({o.offset, o.offset + o.bytes});
+            }
+            std::sort(busy.begin(), busy.end());
+            size_t off = 0;
+            for (auto &iv : busy) {
+                if (off + d.bytes <= iv.first) break;
+                if (iv.second > off) off = iv.second;
+            }
+            d.offset = off;
+            total = std::max(total, off + d.bytes);
+            placed.push_back(b);
+        }
+        plan.workspace_bytes = total;
+    }
+};
+
+}  // namespace
+
+rl_status build_plan(const Graph &g, Plan &plan, std::string &msg)
+{
+    Planner pl(g, plan, msg);
+    return pl.run();
+}
+
+std::string describe_plan(const Plan &p)
+{
+    std::ostringstream o;
+    o << "{\"workspace_bytes\": " << p.workspace_bytes << ", \"steps\": [";
+    for (size_t i = 0; i < p.steps.size(); ++i) {
+        const Step &s = p.steps[i];
+        o << (i ? ", " : "") << "{\"name\": \"" << s.name << "\", \"kernel\": \"" << s.kernel << "\", \"group\": " << s.group
+          << ", \"flops\": " << (long long)s.flops << ", \"bytes\": " << (long long)s.bytes;
+        if (s.kind == S_IGEMM)
+            o << ", \"M\": " << s.ig.M << ", \"N\": " << s.ig.N << ", \"K\": " << s.ig.K << ", \"epilogue_ops\": " << s.ig.epi.n_ops;
+        if (s.kind == S_ELTWISE) o << ", \"n\": " << (long long)s.el.n << ", \"chain_ops\": " << s.el.epi.n_ops;
+        o << "}";
+    }
+    o << "], \"packed_params\": [";
+    bool firstp = true;
+    for (auto &kv : p.packs) {
+        o << (firstp ? "" : ", ") << "{\"value\": " << kv.first << ", \"bytes\": " << kv.second.bytes << "}";
+        firstp = false;
+    }
+    o << "]}";
+    return o.str();
+}
+
+rl_status run_steps(const Plan &plan, void *const *ptrs, hipStream_t stream, std::string &msg)
+{
+    auto P = [&](const Step &s, int slot) -> void * { return s.slot[slot] >= 0 ? ptrs[s.slot[slot]] : nullptr; };
+    for (const Step &s : plan.steps) {
+        hipError_t er = hipSuccess;
+        switch (s.kind) {
+        case S_IGEMM: {
+            IgemmParams p = s.ig;
+            p.x = P(s, SL_X); p.x2 = P(s, SL_X2); p.w = P(s, SL_W); p.y = P(s, SL_Y);
+            for (int i = 0; i < RL_EPI_MAX_PTRS; ++i) p.epi.ptr[i] = P(s, SL_E0 + i);
+            p.c_in = (const float *)P(s, SL_CIN); p.c_out = (float *)P(s, SL_COUT); p.h_out = P(s, SL_HOUT);
+            er = launch_igemm(p, s.il, stream);
+            break;
+        }
+        case S_ELTWISE: {
+            EltwiseParams p = s.el;
+            p.x = P(s, SL_X); p.y = P(s, SL_Y);
+            for (int i = 0; i < RL_EPI_MAX_PTRS; ++i) p.epi.ptr[i] = P(s, SL_E0 + i);
+            er = launch_eltwise(p, stream);
+            break;
+        }
+        case S_GATES: {
+            GatesParams p = s.ga;
+            p.z = (const float *)P(s, SL_X); p.c_in = (const float *)P(s, SL_CIN); p.c_out = (float *)P(s, SL_COUT); p.h_out = P(s, SL_HOUT);
+            er = launch_lstm_gates(p, stream);
+            break;
+        }
+        case S_MAXPOOL: case S_GAVG: {
+            PoolParams p = s.po;
+            p.x = P(s, SL_X); p.y = P(s, SL_Y);
+            er = s.kind == S_MAXPOOL ? launch_maxpool_nhwc(p, stream) : launch_gavgpool_nhwc(p, stream);
+            break;
+        }
+        case S_TO_NHWC:
+            er = launch_nchw_to_nhwc(P(s, SL_X), P(s, SL_Y), s.t_dtype, s.t_N, s.t_C, s.t_P, stream);
+            break;
+        case S_TO_NCHW:
+            er = launch_nhwc_to_nchw(P(s, SL_X), P(s, SL_Y), s.t_dtype, s.t_N, s.t_C, s.t_P, stream);
+            break;
+        }
+        if (er != hipSuccess) {
+            msg = "launch of " + s.kernel + " (" + s.name + ") failed: " + hipGetErrorString(er);
+            return RL_ERR_HIP;
+        }
+    }
+    return RL_OK;
+}
+
+}  // namespace rl

@@ -1,0 +1,60 @@
+// Execution plan: one kernel launch per fusion group (plus layout changes the
+// planner inserts), buffers for intermediates carved from one workspace.
+#pragma once
+#include <map>
+#include <string>
+#include <vector>
+
+#include "graph.h"
+#include "kernels.h"
+
+namespace rl {
+
+enum StepKind { S_IGEMM = 0, S_ELTWISE, S_GATES, S_MAXPOOL, S_GAVG, S_TO_NHWC, S_TO_NCHW };
+enum Slot { SL_X = 0, SL_X2, SL_W, SL_Y, SL_E0, SL_E1, SL_E2, SL_E3, SL_E4, SL_E5, SL_CIN, SL_COUT, SL_HOUT, SL_COUNT };
+
+struct BufDesc {
+    int bound_value = -1;     // >= 0: caller-bound pointer of that value id; -1: workspace
+    size_t bytes = 0;
+    size_t offset = 0;        // workspace offset
+    int first = -1, last = -1;
+};
+
+struct Step {
+    int kind = 0;
+    int group = -1;
+    std::string name, kernel;
+    IgemmParams ig{};
+    IgemmLaunch il{};
+    EltwiseParams el{};
+    GatesParams ga{};
+    PoolParams po{};
+    int t_dtype = 0, t_N = 0, t_C = 0, t_P = 0;
+    int slot[SL_COUNT];
+    double flops = 0, bytes = 0;
+    Step() { for (int &s : slot) s = -1; }
+};
+
+struct PackSpec {
+    int dtype = 0, O = 0, C = 0, T = 0, Kp = 0, perm_block = 0;
+    size_t bytes = 0;
+};
+
+struct Plan {
+    std::shared_ptr<ErrBox> err;
+    std::vector<Value> values;
+    std::vector<int> outputs;
+    std::vector<BufDesc> bufs;
+    std::vector<Step> steps;
+    std::vector<int> bound_buf;          // value id -> buffer index of its bound pointer, or -1
+    std::map<int, PackSpec> packs;       // param value id -> packing
+    size_t workspace_bytes = 0;
+};
+
+rl_status build_plan(const Graph &g, Plan &plan, std::string &msg);
+std::string describe_plan(const Plan &p);
+
+// ptrs[buffer index] must be resolved; launches every step.
+rl_status run_steps(const Plan &p, void *const *ptrs, hipStream_t s, std::string &msg);
+
+}  // namespace rl

@@ -1,0 +1,308 @@
+"""Parity of the HIP library against the CPU oracle, element by element, on
+seeded synthetic inputs -- needs an MI355X.  Every call goes through the C ABI."""
+import numpy as np
+import pytest
+
+import oracle as O
+from oracle import graph as OG
+import workloads as W
+from helpers import assert_close, extract_group, fold_resnet_hip, fold_resnet_oracle, run_hip, store_as
+
+pytestmark = pytest.mark.gpu
+
+
+def check_graph(spec, data, what, atol_scale=1.0):
+    ref = OG.run(spec, data)
+    got, _ = run_hip(spec, data)
+    for vid in spec.outputs:
+        assert_close(got[vid], ref[vid], spec.values[vid].type.dtype, f"{what} value {vid}", atol_scale)
+    return got, ref
+
+
+# ------------------------------------------------------------------ dense / MLP
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("batch,d_in,d_hidden,d_out", [(32, 784, 128, 10), (1, 8, 8, 8), (70, 200, 136, 24), (5, 30, 7, 3), (300, 512, 256, 72)])
+def test_mlp(dtype, batch, d_in, d_hidden, d_out):
+    if dtype == "bf16" and d_hidden % 8:
+        d_hidden += 8 - d_hidden % 8
+    spec, data = W.mlp(batch, d_in, d_hidden, d_out, dtype)
+    check_graph(spec, data, f"mlp {dtype} {batch}x{d_in}x{d_hidden}x{d_out}")
+
+
+def test_dense_gather_path_odd_k():
+    # K not a multiple of the 16-byte vector: weights are re-laid-out with zero padding, A rows are gathered
+    for dtype, k in (("f32", 30), ("bf16", 30), ("f32", 5), ("bf16", 77)):
+        spec, data = W.mlp(9, k, 16, 6, dtype)
+        check_graph(spec, data, f"mlp odd K {dtype} {k}")
+
+
+# ------------------------------------------------------------------ conv groups
+CONV_CASES = [
+    # batch cin cout h  w  k s p residual relu
+    (1, 64, 64, 56, 56, 3, 1, 1, False, True),      # the single-group configuration
+    (2, 8, 24, 13, 11, 3, 1, 1, True, True),        # ragged M and N tails
+    (3, 16, 40, 15, 15, 3, 2, 1, False, True),      # stride 2
+    (2, 32, 64, 14, 14, 1, 2, 0, False, False),     # 1x1 stride-2 projection, no ReLU
+    (1, 3, 16, 33, 33, 7, 2, 3, False, True),       # 3 input channels: gather path straight from NCHW
+    (2, 5, 7, 9, 10, 3, 1, 0, True, False),         # odd everything
+    (1, 128, 128, 28, 28, 3, 1, 1, True, True),     # 128-wide tiles
+    (2, 64, 130, 20, 20, 3, 1, 1, False, True),     # N tail on a 128 tile
+    (1, 8, 8, 3, 3, 3, 1, 1, False, False),         # input as small as the kernel
+]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("case", CONV_CASES, ids=[f"c{i}" for i in range(len(CONV_CASES))])
+def test_conv_group(dtype, case):
+    b, ci, co, h, w, k, s, p, res, relu = case
+    spec, data = W.conv_group(b, ci, co, h, w, k, s, p, dtype, residual=res, relu=relu)
+    check_graph(spec, data, f"conv {dtype} {case}")
+
+
+def test_conv_large_tiles_many_blocks():
+    # enough rows that the planner picks its largest tile (several tiles + ragged tail)
+    for dtype in ("f32", "bf16"):
+        spec, data = W.conv_group(8, 64, 128, 57, 57, 3, 1, 1, dtype, residual=True)
+        check_graph(spec, data, f"conv big {dtype}")
+
+
+def test_fused_equals_unfused_on_device():
+    spec, data = W.conv_group(2, 16, 32, 12, 12, 3, 1, 1, "f32", residual=True)
+    fused, _ = run_hip(spec, data)
+    unf, _ = run_hip(spec.ungrouped(), data)
+    assert_close(fused[spec.outputs[0]], unf[spec.outputs[0]], "f32", "fused vs unfused")
+    # and the unfused plan itself matches the oracle's unfused run
+    check_graph(spec.ungrouped(), data, "unfused conv group")
+
+
+def test_conv1x1_equals_dense_on_device():
+    b, c, o, h, w = 2, 32, 48, 6, 5
+    spec, data = W.conv_group(b, c, o, h, w, 1, 1, 0, "f32", relu=False)
+    y, _ = run_hip(spec, data)
+    y = y[spec.outputs[0]]
+    g = W.GraphSpec("dense_view")
+    x2 = g.input("x", "f32", (b * h * w, c)); w2 = g.param("w", "f32", (o, c)); b2 = g.param("b", "f32", (o,))
+    o0, (t,) = g.op("dense", [x2, w2], [("f32", (b * h * w, o))])
+    o1, (t,) = g.op("bias_add", [t, b2], [("f32", (b * h * w, o))], axis=1)
+    g.group([o0, o1]); g.output(t)
+    d2 = {"x": np.ascontiguousarray(data["x"].transpose(0, 2, 3, 1).reshape(-1, c)), "w": data["w"].reshape(o, c), "b": data["b"]}
+    z, _ = run_hip(g, d2)
+    z = z[g.outputs[0]].reshape(b, h, w, o).transpose(0, 3, 1, 2)
+    assert_close(y, z, "f32", "1x1 conv vs dense")
+
+
+def test_run_twice_is_bitwise_identical():
+    spec, data = W.conv_group(4, 64, 64, 28, 28, 3, 1, 1, "bf16", residual=True)
+    a, s = run_hip(spec, data)
+    first = a[spec.outputs[0]].copy()
+    s.run()
+    import torch
+    from paper_1810_00952_amd import harness
+    torch.cuda.synchronize()
+    second = O.widen(harness.to_host(s.output()), "bf16")
+    np.testing.assert_array_equal(first, second)
+
+
+# ------------------------------------------------------------------ elementwise groups
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("shape", [(7, 5, 33), (4096,), (3, 1000, 9), (1,), (2, 3, 4, 5, 6)])
+def test_eltwise_chain_all_ops(dtype, shape):
+    spec, data = W.eltwise_chain(shape, dtype)
+    check_graph(spec, data, f"eltwise chain {dtype} {shape}")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("shape", [(2, 16, 8, 8), (3, 5, 7, 9), (1, 64, 56, 56), (2, 3, 1, 1), (4, 8, 2, 4)])
+def test_eltwise_bias_residual_relu(dtype, shape):
+    spec, make = W.eltwise_bias_res_relu(shape, dtype)
+    check_graph(spec, make(), f"bias+res+relu {dtype} {shape}")
+
+
+def test_eltwise_operand_order_and_self_operands():
+    for dtype in ("f32", "bf16"):
+        g = W.GraphSpec("order")
+        t = (dtype, (5, 13))
+        a = g.input("a", dtype, t[1]); b = g.input("b", dtype, t[1]); c = g.input("c", dtype, t[1])
+        ops = []
+        o, (y,) = g.op("sub", [b, a], [t]); ops.append(o)       # start value is b
+        o, (y,) = g.op("sub", [c, y], [t]); ops.append(o)       # running value on the right
+        o, (y,) = g.op("div", [a, y], [t]); ops.append(o)
+        o, (y,) = g.op("add", [y, y], [t]); ops.append(o)       # both operands the running value
+        o, (y,) = g.op("mul", [y, y], [t]); ops.append(o)
+        g.group(ops); g.output(y)
+        rng = W.rng_for(8)
+        data = {"a": W.as_dtype(rng.uniform(1, 2, t[1]), dtype), "b": W.as_dtype(rng.uniform(3, 4, t[1]), dtype),
+                "c": W.as_dtype(rng.uniform(-1, 0, t[1]), dtype)}
+        check_graph(g, data, f"operand order {dtype}")
+
+
+def test_cast_group():
+    g = W.GraphSpec("cast")
+    x = g.input("x", "f32", (3, 50))
+    o0, (y,) = g.op("cast", [x], [("bf16", (3, 50))], to="bf16")
+    o1, (y,) = g.op("tanh", [y], [("bf16", (3, 50))])
+    o2, (y,) = g.op("cast", [y], [("f32", (3, 50))], to="f32")
+    g.group([o0, o1, o2]); g.output(y)
+    data = {"x": W.as_dtype(W.rng_for(9).standard_normal((3, 50)), "f32")}
+    got, ref = check_graph(g, data, "cast chain")
+
+
+# ------------------------------------------------------------------ window reductions
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("shape,k,s,p", [((2, 16, 15, 14), 3, 2, 1), ((1, 5, 9, 9), 3, 2, 1), ((2, 8, 8, 8), 2, 2, 0), ((1, 64, 112, 112), 3, 2, 1)])
+def test_maxpool_signed_inputs(dtype, shape, k, s, p):
+    g = W.GraphSpec("pool")
+    x = g.input("x", dtype, shape)
+    oh, ow = W.conv_out(shape[2], k, s, p), W.conv_out(shape[3], k, s, p)
+    o, (y,) = g.op("maxpool2d", [x], [(dtype, (shape[0], shape[1], oh, ow))], kernel=(k, k), stride=(s, s), pad=(p, p))
+    g.output(y)
+    data = {"x": W.as_dtype(W.rng_for(10).standard_normal(shape) - 2.0, dtype)}      # mostly negative: padding must not win
+    got, ref = check_graph(g, data, f"maxpool {dtype} {shape}")
+    np.testing.assert_array_equal(got[y], ref[y])                                      # selection is exact
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_global_avgpool_flatten_dense(dtype):
+    g = W.GraphSpec("head")
+    x = g.input("x", dtype, (3, 24, 7, 7))
+    w = g.param("w", dtype, (10, 24)); b = g.param("b", "f32", (10,))
+    o, (y,) = g.op("global_avgpool", [x], [(dtype, (3, 24, 1, 1))])
+    o, (y,) = g.op("flatten", [y], [(dtype, (3, 24))])
+    o0, (y,) = g.op("dense", [y, w], [(dtype, (3, 10))])
+    o1, (y,) = g.op("bias_add", [y, b], [(dtype, (3, 10))], axis=1)
+    g.group([o0, o1]); g.output(y)
+    rng = W.rng_for(11)
+    data = {"x": W.as_dtype(rng.standard_normal((3, 24, 7, 7)), dtype), "w": W.as_dtype(rng.standard_normal((10, 24)) * 0.2, dtype),
+            "b": W.as_dtype(rng.uniform(-.1, .1, 10), "f32")}
+    check_graph(g, data, f"head {dtype}")
+
+
+# ------------------------------------------------------------------ weight preparation
+def test_fold_batchnorm_matches_oracle_bitwise():
+    import torch
+    from paper_1810_00952_amd import harness, binding
+    rng = W.rng_for(12)
+    O_, per = 37, 3 * 7 * 7
+    w = W.as_dtype(rng.standard_normal((O_, per)), "f32")
+    st = [W.as_dtype(a, "f32") for a in (rng.uniform(.5, 1.5, O_), rng.uniform(-.1, .1, O_), rng.standard_normal(O_) * .1, rng.uniform(.5, 1.5, O_))]
+    wf64, bf64 = O.fold_batchnorm(w, *st, W.BN_EPS)
+    ctx = binding.Context()
+    dw = harness.to_device(w, "f32"); ds = [harness.to_device(a, "f32") for a in st]
+    for dtype in ("f32", "bf16"):
+        out = torch.empty((O_, per), dtype=torch.bfloat16 if dtype == "bf16" else torch.float32, device="cuda:0")
+        bo = torch.empty(O_, dtype=torch.float32, device="cuda:0")
+        ctx.fold_batchnorm(dw.data_ptr(), *[d.data_ptr() for d in ds], W.BN_EPS, out.data_ptr(), dtype, bo.data_ptr(), O_, per)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(harness.to_host(out), store_as(O.round_to(wf64, "f32"), dtype))
+        np.testing.assert_array_equal(harness.to_host(bo), bf64.astype(np.float32))
+
+
+# ------------------------------------------------------------------ ResNet-18-shaped graphs
+def _resnet_hip(spec, raw, bn, dtype):
+    import torch
+    from paper_1810_00952_amd import harness
+    s = harness.Session(spec)
+    fold_resnet_hip(s, raw, bn, dtype)
+    s.alloc(); s.run(); torch.cuda.synchronize()
+    return O.widen(harness.to_host(s.output()), dtype), s
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_resnet_small_end_to_end_and_per_group(dtype):
+    spec, raw, bn = W.resnet18(batch=2, dtype=dtype, image=64, width=16, classes=24)
+    data = fold_resnet_oracle(raw, bn, dtype)
+    allv = OG.run(spec, data, keep_all=True)
+    got, _ = _resnet_hip(spec, raw, bn, dtype)
+    assert_close(got, allv[spec.outputs[0]], dtype, f"resnet small {dtype} end to end", atol_scale=4.0)
+    # every group on its own, fed the oracle's values at its boundary
+    for gi in range(len(spec.groups)):
+        sub, vmap = extract_group(spec, gi)
+        if not sub.outputs:
+            continue
+        sd = {}
+        for old, new in vmap.items():
+            if sub.values[new].role in ("input", "param"):
+                sd[sub.values[new].name] = store_as(allv[old], sub.values[new].type.dtype)
+        out, _ = run_hip(sub, sd)
+        inv = {n: o for o, n in vmap.items()}
+        for vid in sub.outputs:
+            assert_close(out[vid], allv[inv[vid]], sub.values[vid].type.dtype, f"resnet small {dtype} group {gi} ({spec.ops[spec.groups[gi][0]].kind})")
+
+
+def test_resnet18_f32_batch1():
+    spec, raw, bn = W.resnet18(batch=1, dtype="f32")
+    ref = OG.run(spec, fold_resnet_oracle(raw, bn, "f32"))[spec.outputs[0]]
+    got, _ = _resnet_hip(spec, raw, bn, "f32")
+    # 20 chained contractions: the fp32 bound is applied with its absolute term scaled to the logits' size
+    assert_close(got, ref, "f32", "resnet18 f32 b1", atol_scale=max(1.0, float(np.sqrt(np.mean(ref ** 2)))))
+
+
+def test_resnet18_bf16_batch64_sampled_images():
+    # full benchmark configuration on the device; the oracle computes images 0 and 63 (inference is independent per image)
+    spec, raw, bn = W.resnet18(batch=64, dtype="bf16")
+    got, _ = _resnet_hip(spec, raw, bn, "bf16")
+    assert got.shape == (64, 1000) and np.all(np.isfinite(got))
+    for n in (0, 63):
+        s1, raw1, bn1 = W.resnet18(batch=1, dtype="bf16")
+        raw1 = dict(raw1); raw1["x"] = raw["x"][n:n + 1]
+        ref = OG.run(s1, fold_resnet_oracle(raw1, bn, "bf16"))[s1.outputs[0]]
+        assert_close(got[n:n + 1], ref, "bf16", f"resnet18 bf16 b64 image {n}")
+    # images differ, so must the logits (guards against a batch-index bug that repeats one image)
+    assert np.abs(got[0] - got[63]).max() > 1e-3
+
+
+# ------------------------------------------------------------------ LSTM
+def _lstm_hip(T, B, I, H, dtype, fused, d):
+    import torch
+    from paper_1810_00952_amd import harness
+    spec = W.lstm_cell_graph(B, I, H, dtype, fused)
+    s = harness.Session(spec)
+    s.load({"w": d["w"], "b": d["b"]})
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    x = harness.to_device(d["x"], dtype)
+    h0 = torch.zeros((B, H), dtype=tdt, device="cuda:0")
+    c = torch.zeros((B, H), dtype=torch.float32, device="cuda:0")
+    hs = torch.empty((T, B, H), dtype=tdt, device="cuda:0")
+    ws = torch.empty(max(256, s.plan.workspace_bytes()), dtype=torch.uint8, device="cuda:0")
+    n = s.by_name
+    roles = {"x": n["x"], "h_in": n["h"], "c_in": n["c"], "c_out": spec.outputs[0], "h_out": spec.outputs[1]}
+    esz = 2 if dtype == "bf16" else 4
+    s.plan.run_recurrent(T, roles, x.data_ptr(), B * I * esz, h0.data_ptr(), c.data_ptr(), hs.data_ptr(), B * H * esz,
+                         {n["w"]: s.tensors[n["w"]].data_ptr(), n["b"]: s.tensors[n["b"]].data_ptr()}, ws.data_ptr(), ws.numel(),
+                         harness.stream_handle())
+    torch.cuda.synchronize()
+    return O.widen(harness.to_host(hs), dtype), O.widen(harness.to_host(c), "f32")
+
+
+@pytest.mark.parametrize("fused", [True, False])
+@pytest.mark.parametrize("dtype,T,B,I,H", [("bf16", 6, 8, 32, 32), ("f32", 5, 3, 24, 16), ("bf16", 4, 70, 64, 48), ("bf16", 3, 64, 256, 128)])
+def test_lstm_recurrent(fused, dtype, T, B, I, H):
+    d = W.lstm_data(T, B, I, H, dtype)
+    hs_ref, c_ref = O.lstm_sequence(O.widen(d["x"], dtype), O.widen(d["w"], dtype), O.widen(d["b"], "f32"),
+                                    np.zeros((B, H)), np.zeros((B, H)), h_dtype=dtype)
+    hs, c = _lstm_hip(T, B, I, H, dtype, fused, d)
+    assert_close(hs, hs_ref, dtype, f"lstm h {dtype} fused={fused}")
+    assert_close(c, c_ref, dtype if dtype == "bf16" else "f32", f"lstm c {dtype} fused={fused}")
+
+
+def test_lstm_unrolled_graph_equals_recurrent_call():
+    T, B, I, H = 3, 16, 32, 32
+    d = W.lstm_data(T, B, I, H, "bf16")
+    hs, c = _lstm_hip(T, B, I, H, "bf16", True, d)
+    spec = W.lstm_unrolled_graph(T, B, I, H, "bf16", fused=True)
+    data = {f"x{t}": d["x"][t] for t in range(T)}
+    data.update(h0=np.zeros((B, H), np.uint16), c0=np.zeros((B, H), np.float32), w=d["w"], b=d["b"])
+    out, _ = run_hip(spec, data)
+    for t in range(T):
+        np.testing.assert_array_equal(out[spec.outputs[t]], hs[t])
+    np.testing.assert_array_equal(out[spec.outputs[T]], c)
+
+
+def test_lstm_full_configuration():
+    T, B, I, H = 128, 64, 1024, 1024
+    d = W.lstm_data(T, B, I, H, "bf16")
+    hs, c = _lstm_hip(T, B, I, H, "bf16", True, d)
+    hs_ref, c_ref = O.lstm_sequence(O.widen(d["x"], "bf16"), O.widen(d["w"], "bf16"), O.widen(d["b"], "f32"),
+                                    np.zeros((B, H)), np.zeros((B, H)), h_dtype="bf16")
+    assert_close(hs, hs_ref, "bf16", "lstm full h")
+    assert_close(c, c_ref, "bf16", "lstm full c")

@@ -186,7 +186,7 @@ def _flatten_wrong():
 
 
 def _lstm_ok():
-    return W.lstm_cell_graph(batch=2, d_in=8, hidden=8, dtype="bf16", fused=True)
+    return W.lstm_cell_graph(batch=2, d_in=8, hidden=16, dtype="bf16", fused=True)
 
 
 def _lstm_unfused_ok():
