@@ -168,6 +168,16 @@ rl_status rl_plan_prepack(const rl_plan *plan, int32_t param_value_id, const voi
 rl_status rl_plan_run(const rl_plan *plan, const rl_binding *bindings, int32_t n_bindings,
                       void *workspace_dev, size_t workspace_bytes, void *hip_stream);
 
+/* Measurement aid (not part of the hot path): enqueue the plan `reps` times
+ * with a HIP event recorded on hip_stream before and after every step, then
+ * wait for the stream -- the only entry point that synchronises.  step_ms[i]
+ * receives the mean milliseconds between the events around step i (i follows
+ * the "steps" array of rl_plan_describe); at most cap entries are written and
+ * *n_steps gets the plan's step count. */
+rl_status rl_plan_profile(const rl_plan *plan, const rl_binding *bindings, int32_t n_bindings,
+                          void *workspace_dev, size_t workspace_bytes, void *hip_stream,
+                          int32_t reps, float *step_ms, int32_t cap, int32_t *n_steps);
+
 /* Recurrent execution of a one-step cell plan for `steps` steps: at step t the
  * cell's x input is x_seq_dev + t*x_step_bytes, its h input is h0_dev (t = 0)
  * or the previous step's h output, its c input/output is c_dev (updated in

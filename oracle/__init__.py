@@ -194,3 +194,7 @@ def lstm_sequence(x_seq, w, b, h0, c0, h_dtype="bf16"):
         h = round_to(h2, h_dtype)
         hs.append(h)
     return np.stack(hs), c
+
+
+def num_threads() -> int:
+    return int(lib().oracle_num_threads())

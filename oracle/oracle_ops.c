@@ -210,3 +210,11 @@ void oracle_round_bf16(const double *x, double *y, int64_t n)
         y[i] = v < 0 ? -out : out;
     }
 }
+
+/* Threads the parallel loops above will use (for reporting). */
+#ifdef _OPENMP
+#include <omp.h>
+int oracle_num_threads(void) { return omp_get_max_threads(); }
+#else
+int oracle_num_threads(void) { return 1; }
+#endif

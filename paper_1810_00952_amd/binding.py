@@ -72,7 +72,7 @@ _lib = None
 SYMBOLS = ["rl_ctx_create", "rl_ctx_destroy", "rl_last_error", "rl_graph_create", "rl_graph_destroy", "rl_graph_input",
            "rl_graph_param", "rl_graph_op", "rl_graph_group", "rl_graph_output", "rl_plan_create", "rl_plan_destroy",
            "rl_plan_describe", "rl_plan_workspace_bytes", "rl_plan_packed_bytes", "rl_plan_prepack", "rl_plan_run",
-           "rl_plan_run_recurrent", "rl_prep_fold_batchnorm"]
+           "rl_plan_run_recurrent", "rl_prep_fold_batchnorm", "rl_plan_profile"]
 
 
 def lib():
@@ -101,6 +101,8 @@ def lib():
         L.rl_plan_packed_bytes.argtypes = [c_void_p, c_int32, POINTER(c_size_t)]
         L.rl_plan_prepack.argtypes = [c_void_p, c_int32, c_void_p, c_void_p, c_void_p]
         L.rl_plan_run.argtypes = [c_void_p, POINTER(rl_binding), c_int32, c_void_p, c_size_t, c_void_p]
+        L.rl_plan_profile.argtypes = [c_void_p, POINTER(rl_binding), c_int32, c_void_p, c_size_t, c_void_p, c_int32,
+                                      POINTER(ctypes.c_float), c_int32, POINTER(c_int32)]
         L.rl_plan_run_recurrent.argtypes = [c_void_p, c_int32, POINTER(rl_recurrent), POINTER(rl_binding), c_int32, c_void_p,
                                             c_size_t, c_void_p]
         L.rl_prep_fold_batchnorm.argtypes = [c_void_p] + [c_void_p] * 5 + [c_double, c_void_p, c_int32, c_void_p, c_int64, c_int64, c_void_p]
@@ -275,6 +277,15 @@ class Plan:
     def run(self, bindings: Dict[int, int], workspace_ptr: int = 0, workspace_bytes: int = 0, stream: int = 0) -> None:
         self.ctx.check(lib().rl_plan_run(self._h, self._bindings(bindings), len(bindings), c_void_p(workspace_ptr),
                                          c_size_t(workspace_bytes), c_void_p(stream)))
+
+    def profile(self, bindings: Dict[int, int], workspace_ptr: int, workspace_bytes: int, stream: int, reps: int) -> List[float]:
+        """Mean milliseconds per plan step over `reps` runs (synchronises)."""
+        n = c_int32()
+        cap = 4096
+        buf = (ctypes.c_float * cap)()
+        self.ctx.check(lib().rl_plan_profile(self._h, self._bindings(bindings), len(bindings), c_void_p(workspace_ptr),
+                                             c_size_t(workspace_bytes), c_void_p(stream), reps, buf, cap, byref(n)))
+        return list(buf[:n.value])
 
     def run_recurrent(self, steps: int, roles: Dict[str, int], x_seq: int, x_step_bytes: int, h0: int, c: int, h_seq: int,
                       h_step_bytes: int, param_bindings: Dict[int, int], workspace_ptr: int = 0, workspace_bytes: int = 0,

@@ -296,6 +296,43 @@ rl_status rl_plan_run(const rl_plan *plan, const rl_binding *bindings, int32_t n
     });
 }
 
+rl_status rl_plan_profile(const rl_plan *plan, const rl_binding *bindings, int32_t n_bindings, void *ws, size_t ws_bytes, void *stream,
+                          int32_t reps, float *step_ms, int32_t cap, int32_t *n_steps)
+{
+    if (!plan) return RL_ERR_NULL;
+    auto &err = plan->p.err;
+    return guarded(err, [&]() -> rl_status {
+        if (!step_ms || !n_steps) return fail(err, RL_ERR_NULL, "null argument");
+        if (reps < 1 || reps > 10000) return fail(err, RL_ERR_BINDING, "reps out of range");
+        const int ns = (int)plan->p.steps.size();
+        *n_steps = ns;
+        std::vector<void *> ptrs;
+        std::string msg;
+        rl_status st = resolve(plan->p, bindings, n_bindings, ws, ws_bytes, ptrs, msg);
+        if (st != RL_OK) return fail(err, st, msg);
+        std::vector<hipEvent_t> ev((size_t)reps * (ns + 1), nullptr);
+        auto cleanup = [&]() { for (hipEvent_t e : ev) if (e) (void)hipEventDestroy(e); };
+        for (auto &e : ev)
+            if (hipEventCreate(&e) != hipSuccess) { cleanup(); return fail(err, RL_ERR_HIP, "hipEventCreate failed"); }
+        for (int r = 0; r < reps && st == RL_OK; ++r) st = run_steps(plan->p, ptrs.data(), (hipStream_t)stream, msg, ev.data() + (size_t)r * (ns + 1));
+        hipError_t er = hipStreamSynchronize((hipStream_t)stream);
+        if (st == RL_OK && er != hipSuccess) { st = RL_ERR_HIP; msg = std::string("hipStreamSynchronize: ") + hipGetErrorString(er); }
+        if (st == RL_OK) {
+            std::vector<double> acc(ns, 0.0);
+            for (int r = 0; r < reps; ++r)
+                for (int i = 0; i < ns; ++i) {
+                    float ms = 0.f;
+                    if (hipEventElapsedTime(&ms, ev[(size_t)r * (ns + 1) + i], ev[(size_t)r * (ns + 1) + i + 1]) != hipSuccess) { st = RL_ERR_HIP; msg = "hipEventElapsedTime failed"; }
+                    acc[i] += ms;
+                }
+            for (int i = 0; i < ns && i < cap; ++i) step_ms[i] = (float)(acc[i] / reps);
+        }
+        cleanup();
+        if (st != RL_OK) return fail(err, st, msg);
+        return RL_OK;
+    });
+}
+
 rl_status rl_plan_run_recurrent(const rl_plan *cell, int32_t steps, const rl_recurrent *io, const rl_binding *pb, int32_t npb,
                                 void *ws, size_t ws_bytes, void *stream)
 {

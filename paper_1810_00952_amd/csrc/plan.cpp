@@ -611,12 +611,15 @@ std::string describe_plan(const Plan &p)
     return o.str();
 }
 
-rl_status run_steps(const Plan &plan, void *const *ptrs, hipStream_t stream, std::string &msg)
+rl_status run_steps(const Plan &plan, void *const *ptrs, hipStream_t stream, std::string &msg, hipEvent_t *events)
 {
+    size_t si = 0;
     auto P = [&](const Step &s, int slot) -> void * { return s.slot[slot] >= 0 ? ptrs[s.slot[slot]] : nullptr; };
     for (const Step &s : plan.steps) {
         hipError_t er = hipSuccess;
-        switch (s.kind) {
+        if (events) er = hipEventRecord(events[si], stream);
+        ++si;
+        if (er == hipSuccess) switch (s.kind) {
         case S_IGEMM: {
             IgemmParams p = s.ig;
             p.x = P(s, SL_X); p.x2 = P(s, SL_X2); p.w = P(s, SL_W); p.y = P(s, SL_Y);
@@ -656,6 +659,7 @@ rl_status run_steps(const Plan &plan, void *const *ptrs, hipStream_t stream, std
             return RL_ERR_HIP;
         }
     }
+    if (events && hipEventRecord(events[si], stream) != hipSuccess) { msg = "hipEventRecord failed"; return RL_ERR_HIP; }
     return RL_OK;
 }
 

@@ -55,6 +55,7 @@ rl_status build_plan(const Graph &g, Plan &plan, std::string &msg);
 std::string describe_plan(const Plan &p);
 
 // ptrs[buffer index] must be resolved; launches every step.
-rl_status run_steps(const Plan &p, void *const *ptrs, hipStream_t s, std::string &msg);
+// events (optional): steps+1 events, events[i] recorded before step i, events[steps] after the last
+rl_status run_steps(const Plan &p, void *const *ptrs, hipStream_t s, std::string &msg, hipEvent_t *events = nullptr);
 
 }  // namespace rl
