@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "librelayhip.so")
-SOURCES = ["api.cpp", "graph.cpp", "plan.cpp", "igemm.hip", "eltwise.hip"]
+SOURCES = ["api.cpp", "graph.cpp", "plan.cpp", "igemm.hip", "igemm_fast.hip", "igemm_dma.hip", "eltwise.hip"]
 HEADERS = ["graph.h", "plan.h", "kernels.h", "device_utils.h", os.path.join("..", "..", "include", "relayhip.h")]
 FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -56,6 +56,9 @@ def build(force: bool = True, verbose: bool = False) -> str:
         raise RuntimeError("hipcc failed")
     tmp = LIB + f".tmp{os.getpid()}"
     subprocess.check_call([_hipcc(), "-shared", "-fPIC", "--offload-arch=gfx950", "-o", tmp] + objs)
+    # every symbol must resolve: load the freshly linked file before it replaces the old one
+    import ctypes
+    ctypes.CDLL(tmp)
     os.replace(tmp, LIB)
     return LIB
 

@@ -10,51 +10,6 @@ namespace rl {
 // fused elementwise chain: y = chain(x, operands...), 8 elements per thread
 // per iteration (one 16-byte load for bf16, two for f32).
 // ---------------------------------------------------------------------------
-__device__ __forceinline__ void load8(const void *p, int dtype, int64_t i, float v[8])
-{
-    if (dtype == DT_BF16) {
-        u32x4 r = *(const u32x4 *)((const uint16_t *)p + i);
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            v[2 * k] = __uint_as_float(r[k] << 16);
-            v[2 * k + 1] = __uint_as_float(r[k] & 0xffff0000u);
-        }
-    } else {
-        f32x4 a = *(const f32x4 *)((const float *)p + i);
-        f32x4 b = *(const f32x4 *)((const float *)p + i + 4);
-#pragma unroll
-        for (int k = 0; k < 4; ++k) { v[k] = a[k]; v[4 + k] = b[k]; }
-    }
-}
-
-__device__ __forceinline__ void store8(void *p, int dtype, int64_t i, const float v[8])
-{
-    if (dtype == DT_BF16) {
-        u32x4 r;
-#pragma unroll
-        for (int k = 0; k < 4; ++k) r[k] = f32_to_bf16_bits(v[2 * k]) | (f32_to_bf16_bits(v[2 * k + 1]) << 16);
-        *(u32x4 *)((uint16_t *)p + i) = r;
-    } else {
-        f32x4 a, b;
-#pragma unroll
-        for (int k = 0; k < 4; ++k) { a[k] = v[k]; b[k] = v[4 + k]; }
-        *(f32x4 *)((float *)p + i) = a;
-        *(f32x4 *)((float *)p + i + 4) = b;
-    }
-}
-
-__device__ __forceinline__ float binop(int op, float v, float t)
-{
-    switch (op) {
-    case E_ADD: return v + t;
-    case E_SUB: return v - t;
-    case E_RSUB: return t - v;
-    case E_MUL: return v * t;
-    case E_DIV: return v / t;
-    default: return t / v;   // E_RDIV
-    }
-}
-
 __global__ __launch_bounds__(256) void eltwise_kernel(const EltwiseParams p)
 {
     const Epilogue &e = p.epi;
@@ -64,38 +19,7 @@ __global__ __launch_bounds__(256) void eltwise_kernel(const EltwiseParams p)
         const int64_t i0 = vi << 3;
         float v[8];
         load8(p.x, p.x_dtype, i0, v);
-        for (int s = 0; s < e.n_ops; ++s) {
-            const int op = e.op[s], a = e.arg[s];
-            if (op == E_BIAS) {
-                // channel of element i: (i / ch_inner) % ch_count
-                if (p.ch_inner == 1 && (p.ch_count & 7) == 0) {
-                    int ch = (int)(i0 % p.ch_count);
-                    float b[8];
-                    load8(e.ptr[a], e.ptr_dtype[a], ch, b);
-#pragma unroll
-                    for (int k = 0; k < 8; ++k) v[k] += b[k];
-                } else if ((p.ch_inner & 7) == 0) {
-                    int ch = (int)((i0 / p.ch_inner) % p.ch_count);
-                    float b = load_as_f32(e.ptr[a], e.ptr_dtype[a], ch);
-#pragma unroll
-                    for (int k = 0; k < 8; ++k) v[k] += b;
-                } else {
-#pragma unroll
-                    for (int k = 0; k < 8; ++k) {
-                        int ch = (int)(((i0 + k) / p.ch_inner) % p.ch_count);
-                        v[k] += load_as_f32(e.ptr[a], e.ptr_dtype[a], ch);
-                    }
-                }
-            } else if (op >= E_ADD && op <= E_RDIV) {
-                float tt[8];
-                load8(e.ptr[a], e.ptr_dtype[a], i0, tt);
-#pragma unroll
-                for (int k = 0; k < 8; ++k) v[k] = binop(op, v[k], tt[k]);
-            } else {
-#pragma unroll
-                for (int k = 0; k < 8; ++k) v[k] = epi_step(e, s, v[k], 0, 0);
-            }
-        }
+        chain8(e, v, i0, i0, p.ch_inner, p.ch_count);
         store8(p.y, p.y_dtype, i0, v);
     }
     // ragged tail (< 8 elements), one thread each

@@ -1,5 +1,8 @@
 // Implicit-GEMM contraction kernels for gfx950 (conv2d and dense anchors of a
 // fusion group) with the group's injective epilogue applied in registers.
+// This file holds the gather variant (any element strides, any channel count:
+// A elements are fetched one by one) and the dispatcher; the vector-load
+// variant lives in igemm_fast.hip.
 //
 //   C[m, n] = sum_k A[m, k] * Wp[n, k]
 //   m = (image, oh, ow)   n = output channel   k = (kh, kw, c)
@@ -332,20 +335,17 @@ static hipError_t launch_one(const IgemmParams &p0, hipStream_t s)
 template <typename T>
 static hipError_t launch_typed(const IgemmParams &p, const IgemmLaunch &l, hipStream_t s)
 {
-    if (l.gates) {
-        if (l.tile != TILE_64x64) return hipErrorInvalidValue;
-        return l.avec ? launch_one<T, 64, 64, true, true>(p, s) : launch_one<T, 64, 64, false, true>(p, s);
-    }
-    if (!l.avec) return launch_one<T, 64, 64, false, false>(p, s);
-    switch (l.tile) {
-    case TILE_128x128: return launch_one<T, 128, 128, true, false>(p, s);
-    case TILE_128x64: return launch_one<T, 128, 64, true, false>(p, s);
-    default: return launch_one<T, 64, 64, true, false>(p, s);
-    }
+    if (l.tile != TILE_64x64) return hipErrorInvalidValue;
+    return l.gates ? launch_one<T, 64, 64, false, true>(p, s) : launch_one<T, 64, 64, false, false>(p, s);
 }
+
+hipError_t launch_igemm_fast(const IgemmParams &p, const IgemmLaunch &l, hipStream_t s);
+hipError_t launch_igemm_dma(const IgemmParams &p, const IgemmLaunch &l, hipStream_t s);
 
 hipError_t launch_igemm(const IgemmParams &p, const IgemmLaunch &l, hipStream_t s)
 {
+    if (l.avec && l.dma) return launch_igemm_dma(p, l, s);
+    if (l.avec) return launch_igemm_fast(p, l, s);
     if (p.in_dtype == DT_BF16) return launch_typed<uint16_t>(p, l, s);
     return launch_typed<float>(p, l, s);
 }

@@ -52,6 +52,7 @@ struct IgemmParams {
     // LSTM gate epilogue (mode GATES): packed column j of block tile holds gate j/(BN/4), unit j%(BN/4)
     const float *c_in; float *c_out; void *h_out; int32_t h_dtype; int32_t hidden;
     int32_t nblk_m, nblk_n;
+    uint32_t x_bytes, x2_bytes, w_bytes;   // extents for range-checked buffer loads (vector-load variant)
 };
 
 enum IgemmTile { TILE_128x128 = 0, TILE_128x64 = 1, TILE_64x64 = 2, TILE_COUNT };
@@ -59,6 +60,7 @@ struct IgemmLaunch {
     int32_t tile;       // IgemmTile
     int32_t avec;       // 1: A rows are 16-byte-vector loadable (channel-contiguous, aligned)
     int32_t gates;      // 1: LSTM gate epilogue (tile must be TILE_64x64)
+    int32_t dma;        // 1: K tiles go global -> LDS directly (needs avec, C and K multiples of the K tile, >= 2 tiles)
 };
 hipError_t launch_igemm(const IgemmParams &p, const IgemmLaunch &l, hipStream_t s);
 

@@ -10,6 +10,7 @@
 #include "plan.h"
 
 #include <algorithm>
+#include <cstdlib>
 #include <set>
 #include <sstream>
 
@@ -264,6 +265,21 @@ struct Planner {
             p.ys_n = p.N; p.ys_p = p.N; p.ys_c = 1;
         }
         pack.bytes = (size_t)pack.O * pack.Kp * dtype_size(in_dt);
+        // the vector-load kernel addresses its operands with 32-bit byte offsets and wants a K tile
+        // (128 bytes per row) to lie inside one operand of a concatenation
+        {
+            const size_t lim = (size_t)1 << 31;
+            if (bytes_of(x) >= lim || pack.bytes >= lim || (x2 >= 0 && bytes_of(x2) >= lim)) il.avec = 0;
+            if (x2 >= 0 && p.K1 % (8 * KV) != 0) il.avec = 0;
+            p.x_bytes = (uint32_t)std::min(bytes_of(x), lim - 1);
+            p.x2_bytes = x2 >= 0 ? (uint32_t)std::min(bytes_of(x2), lim - 1) : 0;
+            p.w_bytes = (uint32_t)std::min(pack.bytes, lim - 1);
+            // LDS-DMA variant: a K tile must lie inside one filter tap (and one concat operand)
+            const int bke = 8 * KV;
+            const size_t halo = (size_t)((int64_t)p.ph * p.xs_h + (int64_t)p.pw * p.xs_w) * dtype_size(in_dt);
+            il.dma = il.avec && p.C % bke == 0 && p.K % bke == 0 && p.K / bke >= 2 && p.KH * p.KW <= 32 &&
+                     (x2 < 0 || p.K1 % bke == 0) && bytes_of(x) + halo < lim && !getenv("RELAYHIP_NO_DMA");
+        }
         if (need_pack) {
             auto it = plan.packs.find(wv);
             if (it != plan.packs.end() && (it->second.perm_block != pack.perm_block || it->second.Kp != pack.Kp))
@@ -316,7 +332,7 @@ struct Planner {
         p.epi = chain.epi;
         static const char *tile_names[] = {"128x128", "128x64", "64x64"};
         std::string kname = std::string(an.kind == RL_OP_CONV2D ? "igemm_conv2d_" : "igemm_dense_") + (in_dt == RL_BF16 ? "bf16_" : "f32_") +
-                            tile_names[il.tile] + (il.avec ? "" : "_gather") + (gates ? "_gates" : "");
+                            tile_names[il.tile] + (il.avec ? (il.dma ? "_dma" : "") : "_gather") + (gates ? "_gates" : "");
         Step &s = add_step(S_IGEMM, std::string(op_name(an.kind)) + "#" + std::to_string(ops[ai]), kname);
         s.group = gi;
         s.ig = p; s.il = il;
