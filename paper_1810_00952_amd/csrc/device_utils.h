@@ -47,21 +47,10 @@ __device__ __forceinline__ float tanhf_(float x)
     return copysignf(t, x);
 }
 
-// One step of the epilogue chain on one element.
-//   idx : flat offset of the element in the group's output tensor (operands
-//         of the group's shape share its layout)
-//   ch  : channel index for E_BIAS
-__device__ __forceinline__ float epi_step(const Epilogue &e, int s, float v, int64_t idx, int ch)
+// operand-free steps
+__device__ __forceinline__ float unary_step(int op, float v)
 {
-    const int a = e.arg[s];
-    switch (e.op[s]) {
-    case E_BIAS: return v + load_as_f32(e.ptr[a], e.ptr_dtype[a], ch);
-    case E_ADD: return v + load_as_f32(e.ptr[a], e.ptr_dtype[a], idx);
-    case E_SUB: return v - load_as_f32(e.ptr[a], e.ptr_dtype[a], idx);
-    case E_RSUB: return load_as_f32(e.ptr[a], e.ptr_dtype[a], idx) - v;
-    case E_MUL: return v * load_as_f32(e.ptr[a], e.ptr_dtype[a], idx);
-    case E_DIV: return v / load_as_f32(e.ptr[a], e.ptr_dtype[a], idx);
-    case E_RDIV: return load_as_f32(e.ptr[a], e.ptr_dtype[a], idx) / v;
+    switch (op) {
     case E_NEG: return -v;
     case E_SQ: return v * v;
     case E_RELU: return v > 0.0f ? v : 0.0f;
@@ -74,6 +63,56 @@ __device__ __forceinline__ float epi_step(const Epilogue &e, int s, float v, int
     default: return v;
     }
 }
+
+// Table lookups with compile-time indices only: the tables live in the kernel-argument segment,
+// and a run-time index would turn every lookup into a dependent memory load.
+__device__ __forceinline__ int epi_op(const Epilogue &e, int s)
+{
+    uint32_t w = e.opw[0];
+#pragma unroll
+    for (int i = 1; i < RL_EPI_MAX_OPS / 4; ++i) w = (i == (s >> 2)) ? e.opw[i] : w;
+    return (int)((w >> (8 * (s & 3))) & 0xffu);
+}
+__device__ __forceinline__ int epi_arg(const Epilogue &e, int s)
+{
+    uint32_t w = e.argw[0];
+#pragma unroll
+    for (int i = 1; i < RL_EPI_MAX_OPS / 4; ++i) w = (i == (s >> 2)) ? e.argw[i] : w;
+    return (int)((w >> (8 * (s & 3))) & 0xffu);
+}
+__device__ __forceinline__ const void *epi_ptr(const Epilogue &e, int a)
+{
+    const void *r = e.ptr[0];
+#pragma unroll
+    for (int i = 1; i < RL_EPI_MAX_PTRS; ++i) r = (i == a) ? e.ptr[i] : r;
+    return r;
+}
+__device__ __forceinline__ int epi_ptr_dtype(const Epilogue &e, int a) { return (int)((e.dtw >> (4 * a)) & 0xfu); }
+
+// One step of the epilogue chain on one element.
+//   idx : flat offset of the element in the group's output tensor (operands
+//         of the group's shape share its layout)
+//   ch  : channel index for E_BIAS
+__device__ __forceinline__ float epi_step(const Epilogue &e, int s, float v, int64_t idx, int ch)
+{
+    const int a = epi_arg(e, s);
+    const int op = epi_op(e, s);
+    if (op <= E_RDIV) {
+        const void *ptr = epi_ptr(e, a);
+        const int dt = epi_ptr_dtype(e, a);
+        const float o = load_as_f32(ptr, dt, op == E_BIAS ? (int64_t)ch : idx);
+        switch (op) {
+        case E_BIAS: case E_ADD: return v + o;
+        case E_SUB: return v - o;
+        case E_RSUB: return o - v;
+        case E_MUL: return v * o;
+        case E_DIV: return v / o;
+        default: return o / v;   // E_RDIV
+        }
+    }
+    return unary_step(op, v);
+}
+
 
 // ---- 8-element vector forms (one 16-byte access for bf16, two for f32) -----
 __device__ __forceinline__ void load8(const void *p, int dtype, int64_t i, float v[8])
@@ -130,29 +169,31 @@ __device__ __forceinline__ float binop(int op, float v, float t)
 __device__ __forceinline__ void chain8(const Epilogue &e, float v[8], int64_t idx0, int64_t ci0, int64_t ch_inner, int ch_count)
 {
     for (int s = 0; s < e.n_ops; ++s) {
-        const int op = e.op[s], a = e.arg[s];
+        const int op = epi_op(e, s), a = epi_arg(e, s);
+        const void *optr = epi_ptr(e, a);
+        const int odt = epi_ptr_dtype(e, a);
         if (op == E_BIAS) {
             if (ch_inner == 1 && (ch_count & 7) == 0) {
                 int ch = (int)(ci0 % ch_count);
                 float b[8];
-                load8(e.ptr[a], e.ptr_dtype[a], ch, b);
+                load8(optr, odt, ch, b);
 #pragma unroll
                 for (int k = 0; k < 8; ++k) v[k] += b[k];
             } else if ((ch_inner & 7) == 0) {
                 int ch = (int)((ci0 / ch_inner) % ch_count);
-                float b = load_as_f32(e.ptr[a], e.ptr_dtype[a], ch);
+                float b = load_as_f32(optr, odt, ch);
 #pragma unroll
                 for (int k = 0; k < 8; ++k) v[k] += b;
             } else {
 #pragma unroll
                 for (int k = 0; k < 8; ++k) {
                     int ch = (int)(((ci0 + k) / ch_inner) % ch_count);
-                    v[k] += load_as_f32(e.ptr[a], e.ptr_dtype[a], ch);
+                    v[k] += load_as_f32(optr, odt, ch);
                 }
             }
         } else if (op >= E_ADD && op <= E_RDIV) {
             float tt[8];
-            load8(e.ptr[a], e.ptr_dtype[a], idx0, tt);
+            load8(optr, odt, idx0, tt);
 #pragma unroll
             for (int k = 0; k < 8; ++k) v[k] = binop(op, v[k], tt[k]);
         } else if (op == E_RELU) {
@@ -160,7 +201,7 @@ __device__ __forceinline__ void chain8(const Epilogue &e, float v[8], int64_t id
             for (int k = 0; k < 8; ++k) v[k] = v[k] > 0.0f ? v[k] : 0.0f;
         } else {
 #pragma unroll
-            for (int k = 0; k < 8; ++k) v[k] = epi_step(e, s, v[k], 0, 0);
+            for (int k = 0; k < 8; ++k) v[k] = unary_step(op, v[k]);
         }
     }
 }

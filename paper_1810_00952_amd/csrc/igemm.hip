@@ -229,13 +229,13 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmParams p)
     };
 
     for (int s = 0; s < e.n_ops; ++s) {
-        const int op = e.op[s];
+        const int op = epi_op(e, s);
         if (op == E_BIAS) {
-            const int a = e.arg[s];
+            const int a = epi_arg(e, s);
 #pragma unroll
             for (int j = 0; j < TN; ++j) {
                 int n = col_of(j);
-                float b = (n < p.N) ? load_as_f32(e.ptr[a], e.ptr_dtype[a], chan_of(n)) : 0.0f;
+                float b = (n < p.N) ? load_as_f32(epi_ptr(e, a), epi_ptr_dtype(e, a), chan_of(n)) : 0.0f;
 #pragma unroll
                 for (int i = 0; i < TM; ++i)
 #pragma unroll

@@ -27,7 +27,7 @@
 //     wait(my DMAs of tile t) ; barrier ; issue DMA of tile t+2 ; MFMAs on tile t
 // After the barrier every wave's part of tile t has landed and every wave has
 // left tile t-1, whose stage the new DMA overwrites.
-#include "device_utils.h"
+#include "igemm_epilogue.h"
 
 namespace rl {
 
@@ -242,16 +242,24 @@ __global__ __launch_bounds__(256) void igemm_dma_kernel(const IgemmParams p)
 #undef RL_COMPUTE
 #undef RL_ISSUE
 
-    // ---- epilogue: 32 rows at a time through LDS (stage 0's array), then 8 channels per thread
-    const Epilogue &e = p.epi;
+    // ---- epilogue: 32 rows at a time through LDS (stage 0's array), then 8 channels per thread;
+    // the residual rows of the next pass are fetched while this pass is staged and stored
+    using TE = TileEpilogue<BN>;
     float *sC = (float *)st0;
     const bool rowmajor = (p.ys_n == (int64_t)p.OHW * p.ys_p) && p.ys_c == 1;
-    const bool vec_ok = rowmajor && (p.N & 7) == 0 && (p.ys_p & 7) == 0;
+    const bool vec_ok = !GATES && rowmajor && (p.N & 7) == 0 && (p.ys_p & 7) == 0;
+    const bool pre = vec_ok && p.epi.simple;
+    float bias8[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    OperandRegs<TE::NV> cur = {}, nxt = {};
+    if (pre) {
+        TE::load_bias(p, t, n0, bias8);
+        TE::prefetch(p, t, m0, n0, cur);
+    }
 #pragma unroll
     for (int q = 0; q < BM / 32; ++q) {
+        if (pre && q + 1 < BM / 32) TE::prefetch(p, t, m0 + (q + 1) * 32, n0, nxt);
         wg_barrier();                           // previous pass read out / last K tile consumed
         if (wm == q / TM) {
-            constexpr int dummy = 0; (void)dummy;
 #pragma unroll
             for (int j = 0; j < TN; ++j)
 #pragma unroll
@@ -263,57 +271,10 @@ __global__ __launch_bounds__(256) void igemm_dma_kernel(const IgemmParams p)
         }
         __syncthreads();
         const int mq = m0 + q * 32;
-        if (GATES) {
-            // packed column g*(BN/4)+u of the tile holds gate g of hidden unit bn*(BN/4)+u
-            constexpr int U = BN / 4;
-            for (int idx = t; idx < 32 * U; idx += 256) {
-                int row = idx / U, u = idx - row * U;
-                int m = mq + row, unit = bn * U + u;
-                if (m < p.M && unit < p.hidden) {
-                    float z[4];
-#pragma unroll
-                    for (int g = 0; g < 4; ++g) {
-                        z[g] = sC[row * LDC + g * U + u];
-                        for (int s = 0; s < e.n_ops; ++s)      // only E_BIAS steps reach a gate epilogue
-                            z[g] += load_as_f32(e.ptr[e.arg[s]], e.ptr_dtype[e.arg[s]], g * p.hidden + unit);
-                    }
-                    float c_old = p.c_in[(int64_t)m * p.hidden + unit];
-                    float cn = sigmoidf_(z[1]) * c_old + sigmoidf_(z[0]) * tanhf_(z[2]);
-                    float hn = sigmoidf_(z[3]) * tanhf_(cn);
-                    p.c_out[(int64_t)m * p.hidden + unit] = cn;
-                    store_from_f32(p.h_out, p.h_dtype, (int64_t)m * p.hidden + unit, hn);
-                }
-            }
-        } else if (vec_ok) {
-            constexpr int VPR = BN / 8;
-            for (int v = t; v < 32 * VPR; v += 256) {
-                int row = v / VPR, cv = v - row * VPR;
-                int m = mq + row, n = n0 + cv * 8;
-                if (m < p.M && n < p.N) {
-                    float val[8];
-                    f32x4 lo = *(const f32x4 *)(sC + row * LDC + cv * 8);
-                    f32x4 hi = *(const f32x4 *)(sC + row * LDC + cv * 8 + 4);
-#pragma unroll
-                    for (int k = 0; k < 4; ++k) { val[k] = lo[k]; val[4 + k] = hi[k]; }
-                    int64_t off = (int64_t)m * p.ys_p + n;
-                    chain8(e, val, off, n, 1, p.N);
-                    store8(p.y, p.y_dtype, off, val);
-                }
-            }
-        } else {
-            for (int idx = t; idx < 32 * BN; idx += 256) {
-                int col = idx / 32, row = idx - col * 32;
-                int m = mq + row, n = n0 + col;
-                if (m < p.M && n < p.N) {
-                    int img = m / p.OHW;
-                    int pix = m - img * p.OHW;
-                    int64_t off = (int64_t)img * p.ys_n + (int64_t)pix * p.ys_p + (int64_t)n * p.ys_c;
-                    float val = sC[row * LDC + col];
-                    for (int s = 0; s < e.n_ops; ++s) val = epi_step(e, s, val, off, n);
-                    store_from_f32(p.y, p.y_dtype, off, val);
-                }
-            }
-        }
+        if (GATES) TE::gates_pass(p, sC, LDC, t, mq, bn);
+        else if (vec_ok) TE::store_pass(p, sC, LDC, t, mq, n0, bias8, cur);
+        else TE::store_pass_scalar(p, sC, LDC, t, mq, n0);
+        cur = nxt;
     }
 #endif
 }

@@ -14,7 +14,7 @@
 // output channels per thread with 16-byte operand loads and 16-byte stores.
 // Workgroup ids are remapped so that the tiles sharing activation rows run on
 // one XCD (one L2).
-#include "device_utils.h"
+#include "igemm_epilogue.h"
 
 namespace rl {
 
@@ -231,64 +231,27 @@ __global__ __launch_bounds__(256) void igemm_fast_kernel(const IgemmParams p)
             }
     __syncthreads();
 
-    const Epilogue &e = p.epi;
-    if (GATES) {
-        // packed column g*(BN/4)+u of the tile holds gate g of hidden unit bn*(BN/4)+u
-        constexpr int U = BN / 4;
-        for (int idx = t; idx < BM * U; idx += 256) {
-            int row = idx / U, u = idx - row * U;
-            int m = m0 + row, unit = bn * U + u;
-            if (m < p.M && unit < p.hidden) {
-                float z[4];
-#pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    z[g] = sC[row * LDC + g * U + u];
-                    for (int s = 0; s < e.n_ops; ++s)      // only E_BIAS steps reach a gate epilogue
-                        z[g] += load_as_f32(e.ptr[e.arg[s]], e.ptr_dtype[e.arg[s]], g * p.hidden + unit);
-                }
-                float c_old = p.c_in[(int64_t)m * p.hidden + unit];
-                float cn = sigmoidf_(z[1]) * c_old + sigmoidf_(z[0]) * tanhf_(z[2]);
-                float hn = sigmoidf_(z[3]) * tanhf_(cn);
-                p.c_out[(int64_t)m * p.hidden + unit] = cn;
-                store_from_f32(p.h_out, p.h_dtype, (int64_t)m * p.hidden + unit, hn);
-            }
-        }
-        return;
-    }
-
+    // ---- 32-row passes over the staged tile; the residual rows of the next pass are in flight
+    // while this pass is stored
+    using TE = TileEpilogue<BN>;
     const bool rowmajor = (p.ys_n == (int64_t)p.OHW * p.ys_p) && p.ys_c == 1;
-    if (rowmajor && (p.N & 7) == 0 && (p.ys_p & 7) == 0) {
-        // 8 consecutive channels per thread: vector operand loads, one 16-byte (bf16) or two (f32) stores
-        constexpr int VPR = BN / 8;
-        for (int v = t; v < BM * VPR; v += 256) {
-            int row = v / VPR, cv = v - row * VPR;
-            int m = m0 + row, n = n0 + cv * 8;
-            if (m < p.M && n < p.N) {
-                float val[8];
-                f32x4 lo = *(const f32x4 *)(sC + row * LDC + cv * 8);
-                f32x4 hi = *(const f32x4 *)(sC + row * LDC + cv * 8 + 4);
+    const bool vec_ok = !GATES && rowmajor && (p.N & 7) == 0 && (p.ys_p & 7) == 0;
+    const bool pre = vec_ok && p.epi.simple;
+    float bias8[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    OperandRegs<TE::NV> cur = {}, nxt = {};
+    if (pre) {
+        TE::load_bias(p, t, n0, bias8);
+        TE::prefetch(p, t, m0, n0, cur);
+    }
 #pragma unroll
-                for (int k = 0; k < 4; ++k) { val[k] = lo[k]; val[4 + k] = hi[k]; }
-                int64_t off = (int64_t)m * p.ys_p + n;
-                chain8(e, val, off, n, 1, p.N);
-                store8(p.y, p.y_dtype, off, val);
-            }
-        }
-    } else {
-        // any output strides (e.g. NCHW at the graph boundary), ragged N: one element at a time,
-        // consecutive threads on consecutive rows (pixels)
-        for (int idx = t; idx < BM * BN; idx += 256) {
-            int col = idx / BM, row = idx - col * BM;
-            int m = m0 + row, n = n0 + col;
-            if (m < p.M && n < p.N) {
-                int img = m / p.OHW;
-                int pix = m - img * p.OHW;
-                int64_t off = (int64_t)img * p.ys_n + (int64_t)pix * p.ys_p + (int64_t)n * p.ys_c;
-                float val = sC[row * LDC + col];
-                for (int s = 0; s < e.n_ops; ++s) val = epi_step(e, s, val, off, n);
-                store_from_f32(p.y, p.y_dtype, off, val);
-            }
-        }
+    for (int q = 0; q < BM / 32; ++q) {
+        if (pre && q + 1 < BM / 32) TE::prefetch(p, t, m0 + (q + 1) * 32, n0, nxt);
+        const int mq = m0 + q * 32;
+        const float *sq = sC + q * 32 * LDC;
+        if (GATES) TE::gates_pass(p, sq, LDC, t, mq, bn);
+        else if (vec_ok) TE::store_pass(p, sq, LDC, t, mq, n0, bias8, cur);
+        else TE::store_pass_scalar(p, sq, LDC, t, mq, n0);
+        cur = nxt;
     }
 }
 

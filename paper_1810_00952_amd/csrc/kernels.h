@@ -24,13 +24,37 @@ enum EpiOp : uint8_t {
 #define RL_EPI_MAX_OPS 12
 #define RL_EPI_MAX_PTRS 6
 
+// Every field is 32 or 64 bits wide: the struct travels in the kernel-argument segment, where
+// dword fields are fetched by scalar loads once per wave, while byte fields would be fetched by
+// vector loads from that (host-visible) segment at microseconds apiece.
 struct Epilogue {
     int32_t n_ops;
-    uint8_t op[RL_EPI_MAX_OPS];
-    uint8_t arg[RL_EPI_MAX_OPS];
+    uint32_t opw[RL_EPI_MAX_OPS / 4];     // op codes, 8 bits each
+    uint32_t argw[RL_EPI_MAX_OPS / 4];    // pointer-table slots, 8 bits each
+    uint32_t dtw;                         // dtype of pointer slot i in bits 4i .. 4i+3
     const void *ptr[RL_EPI_MAX_PTRS];
-    uint8_t ptr_dtype[RL_EPI_MAX_PTRS];
+    // Host-side classification of the common form  [bias] [one full-shape operand step] operand-free*
+    // (filled by finalize_epilogue; lets the kernels read fixed fields instead of walking the tables)
+    int32_t simple;        // 1: the chain has that form and at most 8 trailing steps
+    int32_t has_bias;
+    int32_t t_op;          // EpiOp of the full-shape operand step, or -1
+    int32_t bias_dtype, t_dtype;
+    int32_t rest_n;        // trailing operand-free steps
+    uint64_t rest_ops;     // their op codes, 8 bits each, first step in the low byte
+    const void *bias_ptr;
+    const void *t_ptr;
 };
+inline void epi_set_op(Epilogue &e, int s, int op, int arg)
+{
+    e.opw[s >> 2] = (e.opw[s >> 2] & ~(0xffu << (8 * (s & 3)))) | ((uint32_t)op << (8 * (s & 3)));
+    e.argw[s >> 2] = (e.argw[s >> 2] & ~(0xffu << (8 * (s & 3)))) | ((uint32_t)arg << (8 * (s & 3)));
+}
+inline int epi_host_op(const Epilogue &e, int s) { return (e.opw[s >> 2] >> (8 * (s & 3))) & 0xff; }
+inline int epi_host_arg(const Epilogue &e, int s) { return (e.argw[s >> 2] >> (8 * (s & 3))) & 0xff; }
+inline void epi_set_dtype(Epilogue &e, int slot, int dt) { e.dtw = (e.dtw & ~(0xfu << (4 * slot))) | ((uint32_t)dt << (4 * slot)); }
+inline int epi_host_dtype(const Epilogue &e, int slot) { return (e.dtw >> (4 * slot)) & 0xf; }
+// Derives the classification fields and the resolved pointers from the tables (call after ptr[] is final).
+void finalize_epilogue(Epilogue &e);
 
 // ---- implicit-GEMM contraction (conv2d and dense) ------------------------
 // C[m, n] = sum_k A[m, k] * Wp[n, k], m = (image, oh, ow), n = output channel,

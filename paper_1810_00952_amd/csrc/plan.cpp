@@ -118,11 +118,10 @@ struct Planner {
                 c.operand.push_back(operand);
                 c.is_vec.push_back(vec);
                 a = (int)c.operand.size() - 1;
-                c.epi.ptr_dtype[a] = (uint8_t)T(operand).dtype;
+                epi_set_dtype(c.epi, a, T(operand).dtype);
             }
         }
-        c.epi.op[c.epi.n_ops] = op;
-        c.epi.arg[c.epi.n_ops] = (uint8_t)a;
+        epi_set_op(c.epi, c.epi.n_ops, op, a);
         c.epi.n_ops++;
         return RL_OK;
     }
@@ -213,7 +212,7 @@ struct Planner {
         if (chain.bias_axis >= 0 && chain.bias_axis != 1) return fail(RL_ERR_UNSUPPORTED, "bias_add fused into a contraction must be along axis 1");
         if (gates)
             for (int i = 0; i < chain.epi.n_ops; ++i)
-                if (chain.epi.op[i] != E_BIAS) return fail(RL_ERR_UNSUPPORTED, "only bias_add may sit between the contraction and lstm_gates");
+                if (epi_host_op(chain.epi, i) != E_BIAS) return fail(RL_ERR_UNSUPPORTED, "only bias_add may sit between the contraction and lstm_gates");
 
         IgemmParams p{};
         IgemmLaunch il{};
@@ -627,6 +626,29 @@ std::string describe_plan(const Plan &p)
     return o.str();
 }
 
+void finalize_epilogue(Epilogue &e)
+{
+    int s = 0;
+    e.has_bias = 0; e.t_op = -1; e.bias_ptr = nullptr; e.t_ptr = nullptr; e.bias_dtype = 0; e.t_dtype = 0;
+    if (s < e.n_ops && epi_host_op(e, s) == E_BIAS) {
+        const int a = epi_host_arg(e, s);
+        e.has_bias = 1; e.bias_ptr = e.ptr[a]; e.bias_dtype = epi_host_dtype(e, a); ++s;
+    }
+    if (s < e.n_ops && epi_host_op(e, s) >= E_ADD && epi_host_op(e, s) <= E_RDIV) {
+        const int a = epi_host_arg(e, s);
+        e.t_op = epi_host_op(e, s); e.t_ptr = e.ptr[a]; e.t_dtype = epi_host_dtype(e, a); ++s;
+    }
+    e.simple = 1;
+    e.rest_n = 0;
+    e.rest_ops = 0;
+    for (; s < e.n_ops; ++s) {
+        const int op = epi_host_op(e, s);
+        if (op <= E_RDIV || e.rest_n >= 8) { e.simple = 0; break; }      // E_BIAS .. E_RDIV take operands
+        e.rest_ops |= (uint64_t)op << (8 * e.rest_n);
+        e.rest_n++;
+    }
+}
+
 rl_status run_steps(const Plan &plan, void *const *ptrs, hipStream_t stream, std::string &msg, hipEvent_t *events)
 {
     size_t si = 0;
@@ -640,6 +662,7 @@ rl_status run_steps(const Plan &plan, void *const *ptrs, hipStream_t stream, std
             IgemmParams p = s.ig;
             p.x = P(s, SL_X); p.x2 = P(s, SL_X2); p.w = P(s, SL_W); p.y = P(s, SL_Y);
             for (int i = 0; i < RL_EPI_MAX_PTRS; ++i) p.epi.ptr[i] = P(s, SL_E0 + i);
+            finalize_epilogue(p.epi);
             p.c_in = (const float *)P(s, SL_CIN); p.c_out = (float *)P(s, SL_COUT); p.h_out = P(s, SL_HOUT);
             er = launch_igemm(p, s.il, stream);
             break;
@@ -648,6 +671,7 @@ rl_status run_steps(const Plan &plan, void *const *ptrs, hipStream_t stream, std
             EltwiseParams p = s.el;
             p.x = P(s, SL_X); p.y = P(s, SL_Y);
             for (int i = 0; i < RL_EPI_MAX_PTRS; ++i) p.epi.ptr[i] = P(s, SL_E0 + i);
+            finalize_epilogue(p.epi);
             er = launch_eltwise(p, stream);
             break;
         }
