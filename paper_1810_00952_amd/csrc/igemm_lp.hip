@@ -1,0 +1,368 @@
+// Implicit-GEMM contraction for gfx950, bf16 in / fp32 accumulate, with the
+// output pixel on the lane axis of the MFMA result so that the fused epilogue
+// (bias, one residual operand, ReLU) runs on the accumulators where they are
+// and every lane stores runs of consecutive output channels of its own pixel.
+//
+//   C[m, n] = sum_k A[m, k] * Wp[n, k],  m = (image, oh, ow), n = out channel,
+//   k = (kh, kw, c)
+//
+// MFMA operand roles: the 32x32x16 instruction computes D[i][j] with lane l
+// holding column j = l % 32 and rows i = 8*(r/4) + 4*(l/32) + r%4 in its 16
+// result registers r.  Weights are fed as the row operand (i = channel) and
+// activations as the column operand (j = pixel): a lane then owns one pixel
+// and, per group of four registers, four consecutive channels -- 8 bytes of
+// bf16 output, stored directly.  No LDS round trip and no barrier after the
+// K loop.
+//
+// Operand tiles travel global -> LDS by direct loads (16 bytes per lane, one
+// instruction fills 8 rows of 128 bytes), STAGES tiles deep.  Rows are 128
+// bytes (one K tile of 64 bf16), unpadded; bank conflicts are avoided by
+// choosing which global chunk a lane fetches: position q of row r holds chunk
+// q ^ ((r >> 1) & 7).  Padding taps and rows past M get a buffer offset outside
+// the descriptor's range, for which the hardware writes zeros into LDS without
+// touching memory.
+//
+// K loop, one barrier per K tile.  With four stages, at the barrier of tile t
+// the tiles t and t+1 have landed, t+2 is in flight and t+3 is issued into the
+// stage tile t-1 just left; fragments of k-step s+1 are read from LDS into a
+// second register set before the MFMAs of k-step s are issued, and the first
+// fragments of tile t+1 are read before the barrier of t+1, so the matrix
+// pipeline does not drain at the barrier.  With three stages (smaller LDS
+// footprint, two workgroups per CU) tile t+2 is issued at the barrier of t and
+// fragment prefetch stays inside a tile.  Each stage is its own LDS array so
+// that the compiler's wait-count insertion can tell direct loads into one
+// stage from fragment reads of another; the waits on the direct loads
+// themselves are explicit (s_waitcnt vmcnt), which is why every K-loop body
+// issues the same number of them (issues past the last tile are sent out of
+// range and cost no memory traffic).
+//
+// Preconditions (checked by the planner): bf16 operands and output; channel-
+// last activations with C a multiple of 64 so that a K tile lies inside one
+// filter tap; K a multiple of 64; KH*KW <= 32; output rows contiguous in n with
+// N a multiple of 4; epilogue of the form [f32 bias] [+ bf16 residual] [relu]; every
+// tensor below 2 GiB.
+#include "device_utils.h"
+
+namespace rl {
+
+namespace {
+
+typedef __amdgpu_buffer_rsrc_t rsrc_t;
+#define RL_LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
+
+__device__ __forceinline__ rsrc_t make_rsrc(const void *ptr, uint32_t bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc((void *)ptr, 0, bytes, 0x00020000);   // raw buffer, untyped dwords
+}
+
+// s_waitcnt with only the vector-memory counter constrained (gfx9 encoding:
+// vmcnt = bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8)
+template <int N> __device__ __forceinline__ void wait_vmcnt()
+{
+    static_assert(N >= 0 && N < 64, "vmcnt is six bits");
+    __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
+}
+
+__device__ __forceinline__ void wg_barrier()
+{
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+}
+
+// n / d for n < 2^31 with the host-computed multiplier (d >= 2) or d == 1
+__device__ __forceinline__ uint32_t fast_div(uint32_t n, uint32_t d, uint32_t mul, uint32_t sh)
+{
+    return d == 1 ? n : (__umulhi(n, mul) >> sh);
+}
+
+constexpr int NUM_XCD = 8;
+constexpr uint32_t OOB = 0x80000000u;
+
+}  // namespace
+
+template <int BM, int BN, int WGM, int WGN, int STAGES>
+__global__ __launch_bounds__(256) void igemm_lp_kernel(const IgemmParams p)
+{
+#if defined(__HIP_DEVICE_COMPILE__)   // the host pass only needs the launch stub; the body uses gfx950-only builtins
+    static_assert(WGM * WGN == 4, "four waves");
+    static_assert(STAGES == 3 || STAGES == 4, "three or four stages");
+    constexpr int BKE = 64;                         // K elements per tile (128 bytes per row)
+    constexpr int WTM = BM / WGM, WTN = BN / WGN;   // wave tile: pixels x channels
+    constexpr int TM = WTM / 32, TN = WTN / 32;
+    constexpr int AG = BM / 32, BG = BN / 32;       // 8-row direct-load groups per wave
+    constexpr int LPT = AG + BG;                    // direct loads per wave per tile
+    constexpr int A_BYTES = BM * 128, B_BYTES = BN * 128, STAGE = A_BYTES + B_BYTES;
+
+    __shared__ __attribute__((aligned(1024))) unsigned char st0[STAGE];
+    __shared__ __attribute__((aligned(1024))) unsigned char st1[STAGE];
+    __shared__ __attribute__((aligned(1024))) unsigned char st2[STAGE];
+    __shared__ __attribute__((aligned(1024))) unsigned char st3[STAGES == 4 ? STAGE : 1024];
+
+    const int t = threadIdx.x;
+    const int lane = t & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(t >> 6);   // wave-uniform by construction; keep it in an SGPR
+    const int wm = wave / WGN, wn = wave % WGN;
+
+    // consecutive workgroup ids go to different XCDs; give each XCD a contiguous run of tiles
+    const int nblk = p.nblk_m * p.nblk_n;
+    int bid = blockIdx.x;
+    {
+        const int per = nblk / NUM_XCD, main = per * NUM_XCD;
+        if (bid < main) bid = (bid % NUM_XCD) * per + bid / NUM_XCD;
+    }
+    const int bm = bid / p.nblk_n, bn = bid - bm * p.nblk_n;
+    const int m0 = bm * BM, n0 = bn * BN;
+
+    // The activation descriptor starts `halo` bytes before x so that the per-lane offset of a
+    // row's tap (0,0) -- which lies above/left of the image for border pixels -- is never negative.
+    const uint32_t halo = (uint32_t)(((int64_t)p.ph * p.xs_h + (int64_t)p.pw * p.xs_w) * 2);
+    const rsrc_t rx = make_rsrc((const char *)p.x - halo, p.x_bytes + halo);
+    const rsrc_t rw = make_rsrc(p.w, p.w_bytes);
+
+    // ---- epilogue operands, fetched first so that they are the oldest vector-memory operations
+    // in flight and the K loop's counted waits never depend on them
+    const int epix = lane & 31, ehalf = lane >> 5;
+    const Epilogue &e = p.epi;
+    const bool has_res = e.t_op >= 0;
+    f32x4 bias_r[TN][4];
+    u32x2 res_r[TM][TN][4];
+    uint32_t y_off[TM];                            // byte offset of channel n0 + wn*WTN + 4*ehalf of the lane's pixel
+    const uint32_t y_bytes = p.y_bytes;
+    {
+        const rsrc_t rb = make_rsrc(e.bias_ptr ? e.bias_ptr : p.w, e.has_bias ? (uint32_t)p.N * 4u : 0u);
+        const rsrc_t rr = make_rsrc(has_res ? e.t_ptr : p.w, has_res ? y_bytes : 0u);
+        const int nb = n0 + wn * WTN + 4 * ehalf;
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int n = nb + j * 32 + 8 * g;
+                // no bias: the descriptor is empty and every load returns zeros without touching memory
+                bias_r[j][g] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rb, n < p.N ? (uint32_t)n * 4u : OOB, 0, 0));
+            }
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int m = m0 + wm * WTM + i * 32 + epix;
+            y_off[i] = m < p.M ? (uint32_t)(((int64_t)m * p.ys_p + nb) * 2) : OOB;
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const int n = nb + j * 32 + 8 * g;
+                    res_r[i][j][g] = __builtin_bit_cast(u32x2, __builtin_amdgcn_raw_buffer_load_b64(rr, (m < p.M && n < p.N) ? y_off[i] + (uint32_t)(j * 64 + g * 16) : OOB, 0, 0));
+                }
+        }
+    }
+
+    // ---- per-lane direct-load state.  Lane l of a group writes LDS row (l >> 3), position (l & 7).
+    const int r8 = lane >> 3, pos = lane & 7;
+    uint32_t a_voff[AG], a_mask[AG], b_voff[BG];
+#pragma unroll
+    for (int i = 0; i < AG; ++i) {
+        const int row = wave * 8 * AG + 8 * i + r8;
+        const int chunk = pos ^ ((row >> 1) & 7);
+        const int m = m0 + row;
+        uint32_t mask = 0;
+        int64_t off = 0;
+        if (m < p.M) {
+            const int img = (int)fast_div((uint32_t)m, (uint32_t)p.OHW, p.div_ohw_mul, p.div_ohw_sh);
+            const int pix = m - img * p.OHW;
+            const int oh = (int)fast_div((uint32_t)pix, (uint32_t)p.OW, p.div_ow_mul, p.div_ow_sh);
+            const int ow = pix - oh * p.OW;
+            const int ih0 = oh * p.sh - p.ph, iw0 = ow * p.sw - p.pw;
+            uint32_t hm = 0, wmk = 0;
+            for (int kh = 0; kh < p.KH; ++kh) hm |= ((unsigned)(ih0 + kh) < (unsigned)p.H ? 1u : 0u) << kh;
+            for (int kw = 0; kw < p.KW; ++kw) wmk |= ((unsigned)(iw0 + kw) < (unsigned)p.W ? 1u : 0u) << kw;
+            for (int kh = 0; kh < p.KH; ++kh) mask |= ((hm >> kh) & 1u) ? (wmk << (kh * p.KW)) : 0u;
+            off = ((int64_t)img * p.xs_n + (int64_t)ih0 * p.xs_h + (int64_t)iw0 * p.xs_w) * 2;
+        }
+        a_mask[i] = mask;
+        // a K tile is two segments of 64 bytes, seg_stride bytes apart (64: one contiguous 128-byte run)
+        a_voff[i] = (uint32_t)(off + halo) + (uint32_t)(chunk >> 2) * p.seg_stride + (uint32_t)(chunk & 3) * 16u;
+    }
+#pragma unroll
+    for (int j = 0; j < BG; ++j) {
+        const int row = wave * 8 * BG + 8 * j + r8;
+        const int chunk = pos ^ ((row >> 1) & 7);
+        int n = n0 + row;
+        if (n > p.N - 1) n = p.N - 1;          // rows past N are computed on valid memory and never stored
+        b_voff[j] = (uint32_t)((int64_t)n * p.Kp * 2) + chunk * 16;
+    }
+
+    // ---- wave-uniform K state of the tile to be issued next
+    const int nk = p.K / BKE;
+    int f_kt = 0, f_c0 = 0, f_tap = 0, f_kh = 0, f_kw = 0;
+#define RL_ISSUE(ST)                                                                                                  \
+    {                                                                                                                 \
+        const bool live = f_kt < nk;                                                                                  \
+        const uint32_t soff_b = live ? (uint32_t)(f_kt * BKE) * 2u : 0u;                                              \
+        const uint32_t tapbit = live ? (1u << f_tap) : 0u;                                                            \
+        const uint32_t soff_a = live ? (uint32_t)(((int64_t)f_kh * p.xs_h + (int64_t)f_kw * p.xs_w + f_c0) * 2) : 0u; \
+        _Pragma("unroll") for (int i = 0; i < AG; ++i)                                                                \
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rx, RL_LDS_PTR(ST + (wave * AG + i) * 1024), 16,                 \
+                                                     (a_mask[i] & tapbit) ? a_voff[i] : OOB, soff_a, 0, 0);           \
+        _Pragma("unroll") for (int j = 0; j < BG; ++j)                                                                \
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rw, RL_LDS_PTR(ST + A_BYTES + (wave * BG + j) * 1024), 16,       \
+                                                     live ? b_voff[j] : OOB, soff_b, 0, 0);                           \
+        ++f_kt;                                                                                                       \
+        f_c0 += BKE;                                                                                                  \
+        if (f_c0 >= p.C) {                                                                                            \
+            f_c0 = 0;                                                                                                 \
+            ++f_tap;                                                                                                  \
+            if (++f_kw == p.KW) { f_kw = 0; ++f_kh; }                                                                 \
+        }                                                                                                             \
+    }
+
+    f32x16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int q = 0; q < 16; ++q) acc[i][j][q] = 0.0f;
+
+    // ---- fragment addresses: row frow of a 32-row MFMA tile, chunk 2*ks + fhalf, swizzled
+    const int frow = lane & 31, fhalf = lane >> 5;
+    int f_off[4];
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) f_off[ks] = frow * 128 + (((2 * ks + fhalf) ^ ((frow >> 1) & 7)) << 4);
+
+    u32x4 fw[2][TN], fx[2][TM];
+#define RL_LOADF(ST, KS, SET)                                                                                         \
+    {                                                                                                                 \
+        _Pragma("unroll") for (int j = 0; j < TN; ++j)                                                                \
+            fw[SET][j] = *(const u32x4 *)(ST + A_BYTES + (wn * WTN + j * 32) * 128 + f_off[KS]);                      \
+        _Pragma("unroll") for (int i = 0; i < TM; ++i)                                                                \
+            fx[SET][i] = *(const u32x4 *)(ST + (wm * WTM + i * 32) * 128 + f_off[KS]);                                \
+        __builtin_amdgcn_sched_barrier(0);   /* keep the reads ahead of the MFMAs that follow in program order */    \
+    }
+#define RL_MMA(SET)                                                                                                   \
+    {                                                                                                                 \
+        _Pragma("unroll") for (int i = 0; i < TM; ++i)                                                                \
+            _Pragma("unroll") for (int j = 0; j < TN; ++j)                                                            \
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fw[SET][j]),           \
+                                                                    __builtin_bit_cast(bf16x8, fx[SET][i]), acc[i][j], 0, 0, 0); \
+        __builtin_amdgcn_sched_barrier(0);                                                                            \
+    }
+
+    int kt = 0;
+    if (STAGES == 4) {
+        // tile kt lives in stage kt % 4
+#define RL_BODY(CUR, NXT, ISS)                                                                                        \
+    {                                                                                                                 \
+        wait_vmcnt<LPT>();                                                                                            \
+        wg_barrier();                                                                                                 \
+        RL_ISSUE(ISS)                                                                                                 \
+        RL_LOADF(CUR, 1, 1) RL_MMA(0)                                                                                 \
+        RL_LOADF(CUR, 2, 0) RL_MMA(1)                                                                                 \
+        RL_LOADF(CUR, 3, 1) RL_MMA(0)                                                                                 \
+        RL_LOADF(NXT, 0, 0) RL_MMA(1)                                                                                 \
+    }
+        RL_ISSUE(st0)
+        RL_ISSUE(st1)
+        RL_ISSUE(st2)
+        wait_vmcnt<2 * LPT>();
+        wg_barrier();
+        RL_LOADF(st0, 0, 0)
+#pragma unroll 1
+        for (; kt + 4 <= nk; kt += 4) {
+            RL_BODY(st0, st1, st3)
+            RL_BODY(st1, st2, st0)
+            RL_BODY(st2, st3, st1)
+            RL_BODY(st3, st0, st2)
+        }
+        if (kt < nk) {
+            RL_BODY(st0, st1, st3)
+            if (kt + 1 < nk) {
+                RL_BODY(st1, st2, st0)
+                if (kt + 2 < nk) RL_BODY(st2, st3, st1)
+            }
+        }
+#undef RL_BODY
+    } else {
+        // tile kt lives in stage kt % 3
+#define RL_BODY(CUR, ISS)                                                                                             \
+    {                                                                                                                 \
+        wait_vmcnt<LPT>();                                                                                            \
+        wg_barrier();                                                                                                 \
+        RL_ISSUE(ISS)                                                                                                 \
+        RL_LOADF(CUR, 0, 0)                                                                                           \
+        RL_LOADF(CUR, 1, 1) RL_MMA(0)                                                                                 \
+        RL_LOADF(CUR, 2, 0) RL_MMA(1)                                                                                 \
+        RL_LOADF(CUR, 3, 1) RL_MMA(0)                                                                                 \
+        RL_MMA(1)                                                                                                     \
+    }
+        RL_ISSUE(st0)
+        RL_ISSUE(st1)
+#pragma unroll 1
+        for (; kt + 3 <= nk; kt += 3) {
+            RL_BODY(st0, st2)
+            RL_BODY(st1, st0)
+            RL_BODY(st2, st1)
+        }
+        if (kt < nk) {
+            RL_BODY(st0, st2)
+            if (kt + 1 < nk) RL_BODY(st1, st0)
+        }
+#undef RL_BODY
+    }
+    wait_vmcnt<0>();           // the trailing out-of-range issues
+#undef RL_MMA
+#undef RL_LOADF
+#undef RL_ISSUE
+
+    // ---- epilogue on the accumulators: lane = pixel, four consecutive channels per register group
+    const rsrc_t ry = make_rsrc(p.y, y_bytes);
+    const float lo = e.relu_last ? 0.0f : -INFINITY;
+    const int nb = n0 + wn * WTN + 4 * ehalf;
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int n = nb + j * 32 + 8 * g;
+                float v[4];
+#pragma unroll
+                for (int k = 0; k < 4; ++k) v[k] = acc[i][j][4 * g + k] + bias_r[j][g][k];
+                const u32x2 r = res_r[i][j][g];
+                v[0] += __uint_as_float(r[0] << 16); v[1] += __uint_as_float(r[0] & 0xffff0000u);
+                v[2] += __uint_as_float(r[1] << 16); v[3] += __uint_as_float(r[1] & 0xffff0000u);
+#pragma unroll
+                for (int k = 0; k < 4; ++k) v[k] = fmaxf(v[k], lo);
+                u32x2 o;
+                o[0] = f32_to_bf16_bits(v[0]) | (f32_to_bf16_bits(v[1]) << 16);
+                o[1] = f32_to_bf16_bits(v[2]) | (f32_to_bf16_bits(v[3]) << 16);
+                __builtin_amdgcn_raw_buffer_store_b64(o, ry, n < p.N ? y_off[i] + (uint32_t)(j * 64 + g * 16) : OOB, 0, 0);
+            }
+#endif
+}
+
+#define RL_INST(BM, BN, WGM, WGN, ST) template __global__ void igemm_lp_kernel<BM, BN, WGM, WGN, ST>(const IgemmParams);
+RL_INST(128, 128, 2, 2, 4) RL_INST(128, 64, 4, 1, 3) RL_INST(64, 64, 2, 2, 4)
+#undef RL_INST
+
+template <int BM, int BN, int WGM, int WGN, int STAGES>
+static hipError_t launch_lp(const IgemmParams &p0, hipStream_t s)
+{
+    IgemmParams p = p0;
+    p.nblk_m = (p.M + BM - 1) / BM;
+    p.nblk_n = (p.N + BN - 1) / BN;
+    int64_t nblk = (int64_t)p.nblk_m * p.nblk_n;
+    if (nblk <= 0 || nblk > 0x7fffffff) return hipErrorInvalidValue;
+    hipLaunchKernelGGL((igemm_lp_kernel<BM, BN, WGM, WGN, STAGES>), dim3((unsigned)nblk), dim3(256), 0, s, p);
+    return hipGetLastError();
+}
+
+hipError_t launch_igemm_lp(const IgemmParams &p, const IgemmLaunch &l, hipStream_t s)
+{
+    if (p.in_dtype != DT_BF16 || p.y_dtype != DT_BF16 || l.gates || p.x2) return hipErrorInvalidValue;
+    switch (l.tile) {
+    case TILE_128x128: return launch_lp<128, 128, 2, 2, 4>(p, s);
+    case TILE_128x64: return launch_lp<128, 64, 4, 1, 3>(p, s);
+    default: return launch_lp<64, 64, 2, 2, 4>(p, s);
+    }
+}
+
+}  // namespace rl

@@ -40,6 +40,7 @@ struct Epilogue {
     int32_t t_op;          // EpiOp of the full-shape operand step, or -1
     int32_t bias_dtype, t_dtype;
     int32_t rest_n;        // trailing operand-free steps
+    int32_t relu_last;     // 1: the trailing steps are exactly one ReLU
     uint64_t rest_ops;     // their op codes, 8 bits each, first step in the low byte
     const void *bias_ptr;
     const void *t_ptr;
@@ -77,7 +78,12 @@ struct IgemmParams {
     const float *c_in; float *c_out; void *h_out; int32_t h_dtype; int32_t hidden;
     int32_t nblk_m, nblk_n;
     uint32_t x_bytes, x2_bytes, w_bytes;   // extents for range-checked buffer loads (vector-load variant)
+    uint32_t y_bytes;                      // extent of y (and of a full-shape epilogue operand)
+    uint32_t seg_stride;                   // bytes between the two 64-byte halves of an A row's K tile (64: contiguous)
+    uint32_t div_ohw_mul, div_ohw_sh, div_ow_mul, div_ow_sh;   // m / OHW and pix / OW by multiply-high (make_fast_div)
 };
+// q = n / d for n < 2^31:  d == 1 ? n : (mulhi(n, mul) >> sh)
+void make_fast_div(uint32_t d, uint32_t &mul, uint32_t &sh);
 
 enum IgemmTile { TILE_128x128 = 0, TILE_128x64 = 1, TILE_64x64 = 2, TILE_COUNT };
 struct IgemmLaunch {
@@ -85,6 +91,7 @@ struct IgemmLaunch {
     int32_t avec;       // 1: A rows are 16-byte-vector loadable (channel-contiguous, aligned)
     int32_t gates;      // 1: LSTM gate epilogue (tile must be TILE_64x64)
     int32_t dma;        // 1: K tiles go global -> LDS directly (needs avec, C and K multiples of the K tile, >= 2 tiles)
+    int32_t lp;         // 1: pixel-on-lane variant with the register epilogue (bf16, [bias] [+residual] [relu])
 };
 hipError_t launch_igemm(const IgemmParams &p, const IgemmLaunch &l, hipStream_t s);
 

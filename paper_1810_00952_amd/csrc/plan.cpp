@@ -278,6 +278,18 @@ struct Planner {
             const size_t halo = (size_t)((int64_t)p.ph * p.xs_h + (int64_t)p.pw * p.xs_w) * dtype_size(in_dt);
             il.dma = il.avec && p.C % bke == 0 && p.K % bke == 0 && p.K / bke >= 2 && p.KH * p.KW <= 32 &&
                      (x2 < 0 || p.K1 % bke == 0) && bytes_of(x) + halo < lim && !getenv("RELAYHIP_NO_DMA");
+            // pixel-on-lane variant: bf16 throughout, output rows contiguous in n, epilogue [bias] [+residual] [relu]
+            Epilogue cls = chain.epi;
+            finalize_epilogue(cls);
+            bool epi_ok = cls.simple && (!cls.has_bias || cls.bias_dtype == DT_F32) && (cls.t_op < 0 || (cls.t_op == E_ADD && cls.t_dtype == DT_BF16)) && (cls.rest_n == 0 || cls.relu_last);
+            bool y_ok = vout >= 0 && T(vout).dtype == RL_BF16 && p.ys_c == 1 && p.ys_n == (int64_t)p.OHW * p.ys_p && p.N % 4 == 0 &&
+                        bytes_of(vout) < lim;
+            il.lp = il.avec && in_dt == RL_BF16 && p.C % bke == 0 && p.K % bke == 0 && p.KH * p.KW <= 32 && x2 < 0 && !gates &&
+                    bytes_of(x) + halo < lim && epi_ok && y_ok && !getenv("RELAYHIP_NO_LP");
+            p.y_bytes = vout >= 0 ? (uint32_t)std::min(bytes_of(vout), lim - 1) : 0;
+            p.seg_stride = 64;
+            make_fast_div((uint32_t)p.OHW, p.div_ohw_mul, p.div_ohw_sh);
+            make_fast_div((uint32_t)p.OW, p.div_ow_mul, p.div_ow_sh);
         }
         if (need_pack) {
             auto it = plan.packs.find(wv);
@@ -331,7 +343,7 @@ struct Planner {
         p.epi = chain.epi;
         static const char *tile_names[] = {"128x128", "128x64", "64x64"};
         std::string kname = std::string(an.kind == RL_OP_CONV2D ? "igemm_conv2d_" : "igemm_dense_") + (in_dt == RL_BF16 ? "bf16_" : "f32_") +
-                            tile_names[il.tile] + (il.avec ? (il.dma ? "_dma" : "") : "_gather") + (gates ? "_gates" : "");
+                            tile_names[il.tile] + (il.lp ? "_lp" : il.avec ? (il.dma ? "_dma" : "") : "_gather") + (gates ? "_gates" : "");
         Step &s = add_step(S_IGEMM, std::string(op_name(an.kind)) + "#" + std::to_string(ops[ai]), kname);
         s.group = gi;
         s.ig = p; s.il = il;
@@ -647,6 +659,18 @@ void finalize_epilogue(Epilogue &e)
         e.rest_ops |= (uint64_t)op << (8 * e.rest_n);
         e.rest_n++;
     }
+    e.relu_last = (e.simple && e.rest_n == 1 && e.rest_ops == (uint64_t)E_RELU) ? 1 : 0;
+}
+
+void make_fast_div(uint32_t d, uint32_t &mul, uint32_t &sh)
+{
+    mul = 0; sh = 0;
+    if (d < 2) return;
+    uint32_t l = 0;
+    while (((uint64_t)1 << l) < d) ++l;                  // ceil(log2 d) >= 1
+    const uint64_t pw = (uint64_t)1 << (31 + l);         // 2^31 <= pw / d < 2^32; exact quotients for n < 2^31
+    mul = (uint32_t)((pw + d - 1) / d);
+    sh = l - 1;
 }
 
 rl_status run_steps(const Plan &plan, void *const *ptrs, hipStream_t stream, std::string &msg, hipEvent_t *events)
