@@ -296,6 +296,60 @@ hipError_t launch_pack_weight(const void *src, void *dst, int32_t dtype, int32_t
 }
 
 // ---------------------------------------------------------------------------
+// stem convolutions: zero-padded 4-channel channel-last frame and matching weights (bf16)
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void stem_pad_kernel(const uint16_t *__restrict__ src, uint16_t *__restrict__ dst, int N, int C, int H,
+                                                       int W, int Hp, int Wp, int ph, int pw)
+{
+    const int64_t total = (int64_t)N * Hp * Wp;
+    for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += (int64_t)gridDim.x * blockDim.x) {
+        const int wp = (int)(idx % Wp);
+        const int64_t q = idx / Wp;
+        const int hp = (int)(q % Hp);
+        const int n = (int)(q / Hp);
+        const int h = hp - ph, w = wp - pw;
+        uint32_t v[4] = {0u, 0u, 0u, 0u};
+        if ((unsigned)h < (unsigned)H && (unsigned)w < (unsigned)W) {
+            const uint16_t *sp = src + (((int64_t)n * C) * H + h) * W + w;
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+                if (c < C) v[c] = sp[(int64_t)c * H * W];
+        }
+        u32x2 o = {v[0] | (v[1] << 16), v[2] | (v[3] << 16)};
+        *(u32x2 *)(dst + idx * 4) = o;
+    }
+}
+
+hipError_t launch_stem_pad(const void *src, void *dst, int32_t N, int32_t C, int32_t H, int32_t W, int32_t Hp, int32_t Wp,
+                           int32_t ph, int32_t pw, hipStream_t s)
+{
+    if (C < 1 || C > 4) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(stem_pad_kernel, dim3(grid_for((int64_t)N * Hp * Wp)), dim3(256), 0, s, (const uint16_t *)src, (uint16_t *)dst, N, C,
+                       H, W, Hp, Wp, ph, pw);
+    return hipGetLastError();
+}
+
+__global__ __launch_bounds__(256) void pack_weight_stem_kernel(const uint16_t *__restrict__ src, uint16_t *__restrict__ dst, int O, int C,
+                                                               int KH, int KW, int Kp)
+{
+    const int64_t total = (int64_t)O * Kp;
+    for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += (int64_t)gridDim.x * blockDim.x) {
+        const int k = (int)(idx % Kp), o = (int)(idx / Kp);
+        const int c = k & 3, px = (k >> 2) & 7, kh = k >> 5;      // kh = 2t + seg
+        uint16_t v = 0;
+        if (c < C && px < KW && kh < KH) v = src[(((int64_t)o * C + c) * KH + kh) * KW + px];
+        dst[idx] = v;
+    }
+}
+
+hipError_t launch_pack_weight_stem(const void *src, void *dst, int32_t O, int32_t C, int32_t KH, int32_t KW, int32_t Kp, hipStream_t s)
+{
+    hipLaunchKernelGGL(pack_weight_stem_kernel, dim3(grid_for((int64_t)O * Kp)), dim3(256), 0, s, (const uint16_t *)src, (uint16_t *)dst,
+                       O, C, KH, KW, Kp);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
 // batch-norm folding, float64 arithmetic
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void fold_bn_kernel(const float *__restrict__ w, const float *__restrict__ gamma,

@@ -198,7 +198,7 @@ __global__ __launch_bounds__(256) void igemm_lp_kernel(const IgemmParams p)
         const bool live = f_kt < nk;                                                                                  \
         const uint32_t soff_b = live ? (uint32_t)(f_kt * BKE) * 2u : 0u;                                              \
         const uint32_t tapbit = live ? (1u << f_tap) : 0u;                                                            \
-        const uint32_t soff_a = live ? (uint32_t)(((int64_t)f_kh * p.xs_h + (int64_t)f_kw * p.xs_w + f_c0) * 2) : 0u; \
+        const uint32_t soff_a = live ? (uint32_t)(((int64_t)f_kh * p.ts_h + (int64_t)f_kw * p.ts_w + f_c0) * 2) : 0u; \
         _Pragma("unroll") for (int i = 0; i < AG; ++i)                                                                \
             __builtin_amdgcn_raw_ptr_buffer_load_lds(rx, RL_LDS_PTR(ST + (wave * AG + i) * 1024), 16,                 \
                                                      (a_mask[i] & tapbit) ? a_voff[i] : OOB, soff_a, 0, 0);           \

@@ -80,6 +80,7 @@ struct IgemmParams {
     uint32_t x_bytes, x2_bytes, w_bytes;   // extents for range-checked buffer loads (vector-load variant)
     uint32_t y_bytes;                      // extent of y (and of a full-shape epilogue operand)
     uint32_t seg_stride;                   // bytes between the two 64-byte halves of an A row's K tile (64: contiguous)
+    int64_t ts_h, ts_w;                    // element strides of one filter-tap step (xs_h, xs_w unless the taps are regrouped)
     uint32_t div_ohw_mul, div_ohw_sh, div_ow_mul, div_ow_sh;   // m / OHW and pix / OW by multiply-high (make_fast_div)
 };
 // q = n / d for n < 2^31:  d == 1 ? n : (mulhi(n, mul) >> sh)
@@ -127,6 +128,14 @@ hipError_t launch_nhwc_to_nchw(const void *src, void *dst, int32_t dtype, int32_
 // for j = blk*perm_block + gate*(perm_block/4) + u (LSTM gate interleave).
 hipError_t launch_pack_weight(const void *src, void *dst, int32_t dtype, int32_t O, int32_t C, int32_t T,
                               int32_t Kp, int32_t perm_block, hipStream_t s);
+// Few-channel stem convolutions (C <= 4, KW <= 8): the input is copied once into a zero-padded
+// channel-last frame with 4 channels per pixel, dst[n][hp][wp][4] with image pixel (h, w) at
+// (h + ph, w + pw); a run of 8 pixels then is 64 contiguous bytes and a K tile holds filter rows
+// 2t and 2t+1 (8 pixels x 4 channels each).  The weights are packed to match:
+// dst[o][((t*2 + seg)*8 + px)*4 + c] = src[o][c][2t+seg][px], zero outside the filter.
+hipError_t launch_stem_pad(const void *src, void *dst, int32_t N, int32_t C, int32_t H, int32_t W, int32_t Hp, int32_t Wp,
+                           int32_t ph, int32_t pw, hipStream_t s);
+hipError_t launch_pack_weight_stem(const void *src, void *dst, int32_t O, int32_t C, int32_t KH, int32_t KW, int32_t Kp, hipStream_t s);
 hipError_t launch_fold_bn(const float *w, const float *gamma, const float *beta, const float *mean, const float *var,
                           double eps, void *w_out, int32_t out_dtype, float *b_out, int64_t O, int64_t per_o,
                           hipStream_t s);

@@ -219,10 +219,20 @@ struct Planner {
         PackSpec pack;
         bool need_pack = false;
         int xbuf = -1, x2buf = -1;
+        double flops = 0.0;
+        size_t x_extent = 0;                 // bytes of the tensor the kernel reads as x
         const rl_type &ot = T(an.out[0]);
         p.in_dtype = in_dt;
         int out_layout = L_NATIVE;
         const int vout = gates ? -1 : chain.last_value;
+
+        // form of the injective chain, needed before the kernel variant is chosen
+        Epilogue cls = chain.epi;
+        finalize_epilogue(cls);
+        const bool epi_lp = cls.simple && (!cls.has_bias || cls.bias_dtype == DT_F32) && (cls.t_op < 0 || (cls.t_op == E_ADD && cls.t_dtype == DT_BF16)) &&
+                            (cls.rest_n == 0 || cls.relu_last);
+        bool stem = false;
+        const size_t lim = (size_t)1 << 31;
 
         if (an.kind == RL_OP_CONV2D) {
             const rl_type &xt = T(x), &wt = T(wv);
@@ -233,19 +243,52 @@ struct Planner {
             if (xt.dims[0] * (int64_t)p.OHW > 0x7fffffff) return fail(RL_ERR_UNSUPPORTED, "conv2d too large");
             p.M = (int)(xt.dims[0] * p.OHW); p.N = (int)wt.dims[0]; p.K = p.C * p.KH * p.KW; p.K1 = p.K;
             p.Kp = (int)round_up(p.K, KV);
-            il.avec = (p.C % KV == 0);
-            int xl;
-            if (il.avec) xl = L_NHWC;
-            else xl = phys[L_NATIVE][x] >= 0 ? L_NATIVE : L_NHWC;
-            st = need(x, xl, xbuf);
-            if (st != RL_OK) return st;
-            if (xl == L_NHWC) { p.xs_n = (int64_t)p.H * p.W * p.C; p.xs_h = (int64_t)p.W * p.C; p.xs_w = p.C; p.xs_c = 1; }
-            else { p.xs_n = (int64_t)p.C * p.H * p.W; p.xs_c = (int64_t)p.H * p.W; p.xs_h = p.W; p.xs_w = 1; }
-            need_pack = !(p.KH * p.KW == 1 && p.C % KV == 0);
-            pack.dtype = in_dt; pack.O = p.N; pack.C = p.C; pack.T = p.KH * p.KW; pack.Kp = p.Kp; pack.perm_block = 0;
             out_layout = (vout >= 0 && out_set.count(vout)) ? L_NATIVE : L_NHWC;
             if (out_layout == L_NHWC) { p.ys_n = (int64_t)p.OHW * p.N; p.ys_p = p.N; p.ys_c = 1; }
             else { p.ys_n = (int64_t)p.N * p.OHW; p.ys_p = 1; p.ys_c = p.OHW; }
+            flops = 2.0 * p.M * (double)p.N * p.K;
+            // Few-channel stem (e.g. 3 -> 64, 7x7, stride 2): gathering single elements starves the MFMAs.  Copy the
+            // input into a zero-padded 4-channel channel-last frame instead; a K tile then holds two filter rows of
+            // 8 pixels x 4 channels and travels by direct loads like any other (see launch_stem_pad).
+            const int KH2 = (p.KH + 1) / 2;
+            const int64_t Hp = (int64_t)(p.OH - 1) * p.sh + 2 * KH2, Wp = (int64_t)(p.OW - 1) * p.sw + 8;
+            const size_t frame = (size_t)xt.dims[0] * Hp * Wp * 8;
+            stem = in_dt == RL_BF16 && p.C <= 4 && p.KW <= 8 && p.sw % 2 == 0 && KH2 <= 32 && epi_lp && vout >= 0 && T(vout).dtype == RL_BF16 &&
+                   out_layout == L_NHWC && p.N % 4 == 0 && bytes_of(vout) < lim && frame < lim && phys[L_NATIVE][x] >= 0 && !getenv("RELAYHIP_NO_STEM");
+            if (stem) {
+                int xnat;
+                st = need(x, L_NATIVE, xnat);
+                if (st != RL_OK) return st;
+                xbuf = new_ws(frame);
+                Step &ps = add_step(S_STEM_PAD, "stem_pad", "stem_pad_nhwc4");
+                ps.t_N = (int)xt.dims[0]; ps.t_C = p.C; ps.st_H = p.H; ps.st_W = p.W; ps.st_Hp = (int)Hp; ps.st_Wp = (int)Wp;
+                ps.st_ph = p.ph; ps.st_pw = p.pw;
+                ps.slot[SL_X] = xnat; ps.slot[SL_Y] = xbuf;
+                ps.bytes = (double)bytes_of(x) + (double)frame;
+                pack.dtype = in_dt; pack.O = p.N; pack.C = p.C; pack.KH = p.KH; pack.KW = p.KW; pack.stem = 1; pack.T = p.KH * p.KW;
+                // the contraction as the kernel sees it: 64 "channels" per tap, KH2 taps, taps two frame rows apart
+                p.C = 64; p.KH = KH2; p.KW = 1; p.H = (int)Hp; p.W = (int)Wp; p.ph = 0; p.pw = 0;
+                p.xs_n = Hp * Wp * 4; p.xs_h = Wp * 4; p.xs_w = 4; p.xs_c = 1;
+                p.ts_h = 2 * Wp * 4; p.ts_w = 0; p.seg_stride = (uint32_t)(Wp * 8);
+                p.K = KH2 * 64; p.K1 = p.K; p.Kp = p.K;
+                pack.Kp = p.Kp; pack.perm_block = 0;
+                il.avec = 1;
+                need_pack = true;
+                x_extent = frame;
+            } else {
+                il.avec = (p.C % KV == 0);
+                int xl;
+                if (il.avec) xl = L_NHWC;
+                else xl = phys[L_NATIVE][x] >= 0 ? L_NATIVE : L_NHWC;
+                st = need(x, xl, xbuf);
+                if (st != RL_OK) return st;
+                if (xl == L_NHWC) { p.xs_n = (int64_t)p.H * p.W * p.C; p.xs_h = (int64_t)p.W * p.C; p.xs_w = p.C; p.xs_c = 1; }
+                else { p.xs_n = (int64_t)p.C * p.H * p.W; p.xs_c = (int64_t)p.H * p.W; p.xs_h = p.W; p.xs_w = 1; }
+                p.ts_h = p.xs_h; p.ts_w = p.xs_w; p.seg_stride = 64;
+                need_pack = !(p.KH * p.KW == 1 && p.C % KV == 0);
+                pack.dtype = in_dt; pack.O = p.N; pack.C = p.C; pack.T = p.KH * p.KW; pack.Kp = p.Kp; pack.perm_block = 0;
+                x_extent = bytes_of(x);
+            }
         } else {
             const rl_type &wt = T(wv);
             const int64_t K = wt.dims[1];
@@ -259,6 +302,9 @@ struct Planner {
             if (st != RL_OK) return st;
             if (x2 >= 0) { st = need(x2, L_NATIVE, x2buf); if (st != RL_OK) return st; }
             p.xs_n = p.K1; p.xs_c = 1; p.xs_h = 0; p.xs_w = 0; p.x2s_n = K2;
+            p.ts_h = 0; p.ts_w = 0; p.seg_stride = 64;
+            flops = 2.0 * p.M * (double)p.N * p.K;
+            x_extent = bytes_of(x);
             need_pack = (p.K % KV != 0) || gates;
             pack.dtype = in_dt; pack.O = p.N; pack.C = p.K; pack.T = 1; pack.Kp = p.Kp; pack.perm_block = gates ? 64 : 0;
             p.ys_n = p.N; p.ys_p = p.N; p.ys_c = 1;
@@ -267,27 +313,22 @@ struct Planner {
         // the vector-load kernel addresses its operands with 32-bit byte offsets and wants a K tile
         // (128 bytes per row) to lie inside one operand of a concatenation
         {
-            const size_t lim = (size_t)1 << 31;
-            if (bytes_of(x) >= lim || pack.bytes >= lim || (x2 >= 0 && bytes_of(x2) >= lim)) il.avec = 0;
+            if (x_extent >= lim || pack.bytes >= lim || (x2 >= 0 && bytes_of(x2) >= lim)) il.avec = 0;
             if (x2 >= 0 && p.K1 % (8 * KV) != 0) il.avec = 0;
-            p.x_bytes = (uint32_t)std::min(bytes_of(x), lim - 1);
+            p.x_bytes = (uint32_t)std::min(x_extent, lim - 1);
             p.x2_bytes = x2 >= 0 ? (uint32_t)std::min(bytes_of(x2), lim - 1) : 0;
             p.w_bytes = (uint32_t)std::min(pack.bytes, lim - 1);
             // LDS-DMA variant: a K tile must lie inside one filter tap (and one concat operand)
             const int bke = 8 * KV;
             const size_t halo = (size_t)((int64_t)p.ph * p.xs_h + (int64_t)p.pw * p.xs_w) * dtype_size(in_dt);
-            il.dma = il.avec && p.C % bke == 0 && p.K % bke == 0 && p.K / bke >= 2 && p.KH * p.KW <= 32 &&
-                     (x2 < 0 || p.K1 % bke == 0) && bytes_of(x) + halo < lim && !getenv("RELAYHIP_NO_DMA");
+            il.dma = !stem && il.avec && p.C % bke == 0 && p.K % bke == 0 && p.K / bke >= 2 && p.KH * p.KW <= 32 &&
+                     (x2 < 0 || p.K1 % bke == 0) && x_extent + halo < lim && !getenv("RELAYHIP_NO_DMA");
             // pixel-on-lane variant: bf16 throughout, output rows contiguous in n, epilogue [bias] [+residual] [relu]
-            Epilogue cls = chain.epi;
-            finalize_epilogue(cls);
-            bool epi_ok = cls.simple && (!cls.has_bias || cls.bias_dtype == DT_F32) && (cls.t_op < 0 || (cls.t_op == E_ADD && cls.t_dtype == DT_BF16)) && (cls.rest_n == 0 || cls.relu_last);
             bool y_ok = vout >= 0 && T(vout).dtype == RL_BF16 && p.ys_c == 1 && p.ys_n == (int64_t)p.OHW * p.ys_p && p.N % 4 == 0 &&
                         bytes_of(vout) < lim;
-            il.lp = il.avec && in_dt == RL_BF16 && p.C % bke == 0 && p.K % bke == 0 && p.KH * p.KW <= 32 && x2 < 0 && !gates &&
-                    bytes_of(x) + halo < lim && epi_ok && y_ok && !getenv("RELAYHIP_NO_LP");
+            il.lp = stem || (il.avec && in_dt == RL_BF16 && p.C % bke == 0 && p.K % bke == 0 && p.KH * p.KW <= 32 && x2 < 0 && !gates &&
+                             x_extent + halo < lim && epi_lp && y_ok && !getenv("RELAYHIP_NO_LP"));
             p.y_bytes = vout >= 0 ? (uint32_t)std::min(bytes_of(vout), lim - 1) : 0;
-            p.seg_stride = 64;
             make_fast_div((uint32_t)p.OHW, p.div_ohw_mul, p.div_ohw_sh);
             make_fast_div((uint32_t)p.OW, p.div_ow_mul, p.div_ow_sh);
         }
@@ -350,7 +391,7 @@ struct Planner {
         s.slot[SL_X] = xbuf; s.slot[SL_X2] = x2buf; s.slot[SL_W] = bound(wv); s.slot[SL_Y] = ybuf;
         for (int i = 0; i < RL_EPI_MAX_PTRS; ++i) s.slot[SL_E0 + i] = eslots[i];
         s.slot[SL_CIN] = cin_buf; s.slot[SL_COUT] = cout_buf; s.slot[SL_HOUT] = hout_buf;
-        s.flops = 2.0 * p.M * (double)p.N * p.K;
+        s.flops = flops;
         s.bytes = bytes;
         return RL_OK;
     }
@@ -716,6 +757,9 @@ rl_status run_steps(const Plan &plan, void *const *ptrs, hipStream_t stream, std
             break;
         case S_TO_NCHW:
             er = launch_nhwc_to_nchw(P(s, SL_X), P(s, SL_Y), s.t_dtype, s.t_N, s.t_C, s.t_P, stream);
+            break;
+        case S_STEM_PAD:
+            er = launch_stem_pad(P(s, SL_X), P(s, SL_Y), s.t_N, s.t_C, s.st_H, s.st_W, s.st_Hp, s.st_Wp, s.st_ph, s.st_pw, stream);
             break;
         }
         if (er != hipSuccess) {

@@ -59,6 +59,55 @@ def test_conv_group(dtype, case):
     check_graph(spec, data, f"conv {dtype} {case}")
 
 
+# The conv group's result stays an intermediate (channel-last inside the plan), which is what selects the
+# pixel-on-lane bf16 kernel: every tile shape, stride-2 and 1x1 taps, K tiles spanning several taps,
+# ragged M tails inside and across tiles, N tails on 4-channel granularity, and epilogues with and
+# without residual / ReLU.
+LP_CASES = [
+    # batch cin cout h  w  k s p residual relu
+    (2, 64, 64, 14, 14, 3, 1, 1, True, True),        # 64x64 tile, M = 392
+    (3, 64, 128, 29, 29, 3, 1, 1, True, True),       # M = 2523: ragged last tile
+    (16, 64, 64, 56, 56, 3, 1, 1, True, True),       # 128x64 tile, two workgroups per CU
+    (16, 128, 128, 28, 28, 3, 1, 1, False, True),    # 128x128 tile, 18 K tiles
+    (4, 64, 128, 57, 57, 3, 2, 1, False, True),      # stride 2, odd image
+    (4, 64, 132, 28, 28, 1, 2, 0, False, False),     # 1x1 stride-2 projection: a single K tile, N tail of 4
+    (2, 128, 72, 9, 7, 3, 1, 1, True, False),        # N = 72, no ReLU
+    (1, 192, 64, 5, 5, 5, 1, 2, False, True),        # 25 taps, 3 K tiles per tap
+    (2, 256, 512, 7, 7, 3, 1, 1, True, True),        # image smaller than a tile row block
+    (40, 64, 64, 30, 30, 1, 1, 0, True, True),       # 1x1, M = 36000: many tiles, K = one tile
+]
+
+
+@pytest.mark.parametrize("case", LP_CASES, ids=[f"lp{i}" for i in range(len(LP_CASES))])
+def test_conv_group_internal_layout_bf16(case):
+    b, ci, co, h, w, k, s, p, res, relu = case
+    spec, data = W.conv_group(b, ci, co, h, w, k, s, p, "bf16", residual=res, relu=relu, tail=True)
+    from paper_1810_00952_amd import binding
+    desc = binding.Plan(binding.graph_from_spec(binding.Context(), spec)).describe()
+    assert any(st["kernel"].endswith("_lp") for st in desc["steps"]), [st["kernel"] for st in desc["steps"]]
+    check_graph(spec, data, f"conv lp {case}")
+
+
+STEM_CASES = [
+    # batch cin cout h   w   k s p relu
+    (2, 3, 64, 224, 224, 7, 2, 3, True),     # the ResNet stem
+    (3, 3, 16, 33, 35, 7, 2, 3, True),       # odd sizes, ragged M
+    (2, 1, 8, 20, 20, 5, 2, 2, False),       # one channel, 5x5
+    (2, 4, 32, 17, 18, 3, 2, 1, True),       # four channels, 3x3
+    (1, 2, 12, 12, 40, 8, 4, 0, True),       # 8-wide filter, stride 4
+]
+
+
+@pytest.mark.parametrize("case", STEM_CASES, ids=[f"stem{i}" for i in range(len(STEM_CASES))])
+def test_conv_stem_few_channels_bf16(case):
+    b, ci, co, h, w, k, s, p, relu = case
+    spec, data = W.conv_group(b, ci, co, h, w, k, s, p, "bf16", relu=relu, tail=True)
+    from paper_1810_00952_amd import binding
+    desc = binding.Plan(binding.graph_from_spec(binding.Context(), spec)).describe()
+    assert any(st["kernel"] == "stem_pad_nhwc4" for st in desc["steps"]), [st["kernel"] for st in desc["steps"]]
+    check_graph(spec, data, f"conv stem {case}")
+
+
 def test_conv_large_tiles_many_blocks():
     # enough rows that the planner picks its largest tile (several tiles + ragged tail)
     for dtype in ("f32", "bf16"):

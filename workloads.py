@@ -178,7 +178,9 @@ def mlp(batch=32, d_in=784, d_hidden=128, d_out=10, dtype="f32", config=1):
 # config 2: one fused conv2d group
 # --------------------------------------------------------------------------
 def conv_group(batch=1, cin=64, cout=64, h=56, w=56, k=3, stride=1, pad=1, dtype="f32",
-               residual=False, relu=True, config=2):
+               residual=False, relu=True, config=2, tail=False):
+    """One fused conv2d group.  tail=True appends a second group (neg) so that the
+    conv group's result is an intermediate the plan keeps in its private layout."""
     rng = rng_for(config)
     g = GraphSpec("conv_group")
     data = {}
@@ -200,6 +202,9 @@ def conv_group(batch=1, cin=64, cout=64, h=56, w=56, k=3, stride=1, pad=1, dtype
     if relu:
         o, (y,) = g.op("relu", [y], [ot]); ids.append(o)
     g.group(ids)
+    if tail:
+        o, (y,) = g.op("neg", [y], [ot])
+        g.group([o])
     g.output(y)
     return g, data
 
