@@ -20,6 +20,20 @@ __device__ __forceinline__ uint32_t f32_to_bf16_bits(float f)
     return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
 }
 
+// two floats to a packed pair of bf16 (low half = a), round to nearest even, by the hardware
+// conversion of gfx950 (v_cvt_pk_bf16_f32)
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t pack_bf16x2(float a, float b)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    f32x2 v = {a, b};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+#else
+    return 0;
+#endif
+}
+
 __device__ __forceinline__ float round_bf16(float f) { return bf16_bits_to_f32(f32_to_bf16_bits(f)); }
 
 __device__ __forceinline__ float load_as_f32(const void *p, int dtype, int64_t i)

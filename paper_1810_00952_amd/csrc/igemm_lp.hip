@@ -1,7 +1,5 @@
 // Implicit-GEMM contraction for gfx950, bf16 in / fp32 accumulate, with the
-// output pixel on the lane axis of the MFMA result so that the fused epilogue
-// (bias, one residual operand, ReLU) runs on the accumulators where they are
-// and every lane stores runs of consecutive output channels of its own pixel.
+// output pixel on the lane axis of the MFMA result and a wave-private epilogue.
 //
 //   C[m, n] = sum_k A[m, k] * Wp[n, k],  m = (image, oh, ow), n = out channel,
 //   k = (kh, kw, c)
@@ -10,9 +8,7 @@
 // holding column j = l % 32 and rows i = 8*(r/4) + 4*(l/32) + r%4 in its 16
 // result registers r.  Weights are fed as the row operand (i = channel) and
 // activations as the column operand (j = pixel): a lane then owns one pixel
-// and, per group of four registers, four consecutive channels -- 8 bytes of
-// bf16 output, stored directly.  No LDS round trip and no barrier after the
-// K loop.
+// and, per group of four registers, four consecutive channels.
 //
 // Operand tiles travel global -> LDS by direct loads (16 bytes per lane, one
 // instruction fills 8 rows of 128 bytes), STAGES tiles deep.  Rows are 128
@@ -34,13 +30,25 @@
 // stage from fragment reads of another; the waits on the direct loads
 // themselves are explicit (s_waitcnt vmcnt), which is why every K-loop body
 // issues the same number of them (issues past the last tile are sent out of
-// range and cost no memory traffic).
+// range and cost no memory traffic).  The epilogue's operands (bias, residual)
+// are requested right behind the first tiles, so their latency hides under
+// the K loop; the first two waits count them in.
+//
+// Epilogue: after one barrier the stages are free and every wave owns a
+// private piece of them.  It adds the bias to its accumulators and parks them
+// there as fp32, 16 bytes (4 channels of one pixel) per lane and store, chunk
+// positions XOR-swizzled by the row so that both the stores and the reads
+// below are bank-conflict free.  It then reads them back row-wise -- a lane
+// gets 8 consecutive channels of one pixel, the lanes of a row cover the row
+// -- adds the residual (fetched with the same row-wise 16-byte accesses),
+// applies ReLU, rounds once to bf16 and stores 16 bytes: whole output rows
+// per instruction instead of 8-byte fragments scattered over 32 rows.
 //
 // Preconditions (checked by the planner): bf16 operands and output; channel-
 // last activations with C a multiple of 64 so that a K tile lies inside one
 // filter tap; K a multiple of 64; KH*KW <= 32; output rows contiguous in n with
-// N a multiple of 4; epilogue of the form [f32 bias] [+ bf16 residual] [relu]; every
-// tensor below 2 GiB.
+// N a multiple of 8; epilogue of the form [f32 bias] [+ bf16 residual] [relu];
+// every tensor below 2 GiB.
 #include "device_utils.h"
 
 namespace rl {
@@ -120,41 +128,6 @@ __global__ __launch_bounds__(256) void igemm_lp_kernel(const IgemmParams p)
     const rsrc_t rx = make_rsrc((const char *)p.x - halo, p.x_bytes + halo);
     const rsrc_t rw = make_rsrc(p.w, p.w_bytes);
 
-    // ---- epilogue operands, fetched first so that they are the oldest vector-memory operations
-    // in flight and the K loop's counted waits never depend on them
-    const int epix = lane & 31, ehalf = lane >> 5;
-    const Epilogue &e = p.epi;
-    const bool has_res = e.t_op >= 0;
-    f32x4 bias_r[TN][4];
-    u32x2 res_r[TM][TN][4];
-    uint32_t y_off[TM];                            // byte offset of channel n0 + wn*WTN + 4*ehalf of the lane's pixel
-    const uint32_t y_bytes = p.y_bytes;
-    {
-        const rsrc_t rb = make_rsrc(e.bias_ptr ? e.bias_ptr : p.w, e.has_bias ? (uint32_t)p.N * 4u : 0u);
-        const rsrc_t rr = make_rsrc(has_res ? e.t_ptr : p.w, has_res ? y_bytes : 0u);
-        const int nb = n0 + wn * WTN + 4 * ehalf;
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const int n = nb + j * 32 + 8 * g;
-                // no bias: the descriptor is empty and every load returns zeros without touching memory
-                bias_r[j][g] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rb, n < p.N ? (uint32_t)n * 4u : OOB, 0, 0));
-            }
-#pragma unroll
-        for (int i = 0; i < TM; ++i) {
-            const int m = m0 + wm * WTM + i * 32 + epix;
-            y_off[i] = m < p.M ? (uint32_t)(((int64_t)m * p.ys_p + nb) * 2) : OOB;
-#pragma unroll
-            for (int j = 0; j < TN; ++j)
-#pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    const int n = nb + j * 32 + 8 * g;
-                    res_r[i][j][g] = __builtin_bit_cast(u32x2, __builtin_amdgcn_raw_buffer_load_b64(rr, (m < p.M && n < p.N) ? y_off[i] + (uint32_t)(j * 64 + g * 16) : OOB, 0, 0));
-                }
-        }
-    }
-
     // ---- per-lane direct-load state.  Lane l of a group writes LDS row (l >> 3), position (l & 7).
     const int r8 = lane >> 3, pos = lane & 7;
     uint32_t a_voff[AG], a_mask[AG], b_voff[BG];
@@ -171,10 +144,12 @@ __global__ __launch_bounds__(256) void igemm_lp_kernel(const IgemmParams p)
             const int oh = (int)fast_div((uint32_t)pix, (uint32_t)p.OW, p.div_ow_mul, p.div_ow_sh);
             const int ow = pix - oh * p.OW;
             const int ih0 = oh * p.sh - p.ph, iw0 = ow * p.sw - p.pw;
-            uint32_t hm = 0, wmk = 0;
-            for (int kh = 0; kh < p.KH; ++kh) hm |= ((unsigned)(ih0 + kh) < (unsigned)p.H ? 1u : 0u) << kh;
-            for (int kw = 0; kw < p.KW; ++kw) wmk |= ((unsigned)(iw0 + kw) < (unsigned)p.W ? 1u : 0u) << kw;
-            for (int kh = 0; kh < p.KH; ++kh) mask |= ((hm >> kh) & 1u) ? (wmk << (kh * p.KW)) : 0u;
+            // taps inside the image form a contiguous range of kh and of kw
+            const int lo_h = max(0, -ih0), hi_h = max(lo_h, min(p.KH, p.H - ih0));
+            const int lo_w = max(0, -iw0), hi_w = max(lo_w, min(p.KW, p.W - iw0));
+            const uint32_t wmk = (uint32_t)(((1ull << hi_w) - 1) & ~((1ull << lo_w) - 1));
+            const uint32_t rows = (uint32_t)(((1ull << (hi_h * p.KW)) - 1) & ~((1ull << (lo_h * p.KW)) - 1));
+            mask = (wmk * p.tap_rep) & rows;      // tap_rep has bit kh*KW set for every kh: no carries, wmk < 2^KW
             off = ((int64_t)img * p.xs_n + (int64_t)ih0 * p.xs_h + (int64_t)iw0 * p.xs_w) * 2;
         }
         a_mask[i] = mask;
@@ -246,12 +221,50 @@ __global__ __launch_bounds__(256) void igemm_lp_kernel(const IgemmParams p)
         __builtin_amdgcn_sched_barrier(0);                                                                            \
     }
 
+    // ---- epilogue operands: requested behind the first tiles (see RL_EPI_LOADS below)
+    const int epix = lane & 31, ehalf = lane >> 5;
+    const Epilogue &e = p.epi;
+    constexpr int LPR = WTN / 8;                   // lanes per output row of the wave tile (16 bytes of bf16 each)
+    constexpr int RPP = 64 / LPR;                  // rows per row-wise pass
+    constexpr int NPASS = WTM / RPP;
+    constexpr int NEPI = TN * 4 + NPASS;           // vector-memory operations RL_EPI_LOADS issues
+    constexpr int POSN = WTN / 4;                  // 16-byte fp32 positions per parked row
+    constexpr int RP = 16 / POSN > 0 ? 16 / POSN : 1;   // parked rows per 256 bytes (all 64 banks)
+    const int rr = lane / LPR, pp = lane % LPR;
+    f32x4 bias_r[TN][4];
+    u32x4 res_r[NPASS];
+    uint32_t y_off[NPASS];                         // byte offset of the lane's 8 channels in pass q, or out of range
+    int pA[NPASS];                                 // parked position read first in pass q
+    const uint32_t y_bytes = p.y_bytes;
+#define RL_EPI_LOADS                                                                                                  \
+    {                                                                                                                 \
+        const bool has_res = e.t_op >= 0;                                                                             \
+        /* absent operands get an empty descriptor: every load then returns zeros without touching memory */         \
+        const rsrc_t rb = make_rsrc(e.has_bias ? e.bias_ptr : p.w, e.has_bias ? (uint32_t)p.N * 4u : 0u);             \
+        const rsrc_t rres = make_rsrc(has_res ? e.t_ptr : p.w, has_res ? y_bytes : 0u);                               \
+        const int nb = n0 + wn * WTN + 4 * ehalf;                                                                     \
+        _Pragma("unroll") for (int j = 0; j < TN; ++j)                                                                \
+            _Pragma("unroll") for (int g = 0; g < 4; ++g) {                                                           \
+                const int n = nb + j * 32 + 8 * g;                                                                    \
+                bias_r[j][g] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rb, n < p.N ? (uint32_t)n * 4u : OOB, 0, 0)); \
+            }                                                                                                         \
+        _Pragma("unroll") for (int q = 0; q < NPASS; ++q) {                                                           \
+            const int row = q * RPP + rr;                                                                             \
+            const int key = (row / RP) & (POSN - 1);                                                                  \
+            pA[q] = 2 * pp + (key & 1);                                                                               \
+            const int cc = pp ^ (key >> 1);                  /* 8-channel chunk this lane finishes in pass q */      \
+            const int m = m0 + wm * WTM + row, n = n0 + wn * WTN + cc * 8;                                            \
+            y_off[q] = (m < p.M && n < p.N) ? (uint32_t)(((int64_t)m * p.ys_p + n) * 2) : OOB;                        \
+            res_r[q] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(rres, y_off[q], 0, 0));        \
+        }                                                                                                             \
+    }
+
     int kt = 0;
     if (STAGES == 4) {
         // tile kt lives in stage kt % 4
-#define RL_BODY(CUR, NXT, ISS)                                                                                        \
+#define RL_BODY(CUR, NXT, ISS, INFLIGHT)                                                                              \
     {                                                                                                                 \
-        wait_vmcnt<LPT>();                                                                                            \
+        wait_vmcnt<INFLIGHT>();                                                                                       \
         wg_barrier();                                                                                                 \
         RL_ISSUE(ISS)                                                                                                 \
         RL_LOADF(CUR, 1, 1) RL_MMA(0)                                                                                 \
@@ -262,29 +275,33 @@ __global__ __launch_bounds__(256) void igemm_lp_kernel(const IgemmParams p)
         RL_ISSUE(st0)
         RL_ISSUE(st1)
         RL_ISSUE(st2)
-        wait_vmcnt<2 * LPT>();
+        RL_EPI_LOADS
+        wait_vmcnt<2 * LPT + NEPI>();
         wg_barrier();
         RL_LOADF(st0, 0, 0)
+        // first tile peeled: the epilogue operands are still in flight behind tile 2
+        RL_BODY(st0, st1, st3, LPT + NEPI)
+        kt = 1;
 #pragma unroll 1
         for (; kt + 4 <= nk; kt += 4) {
-            RL_BODY(st0, st1, st3)
-            RL_BODY(st1, st2, st0)
-            RL_BODY(st2, st3, st1)
-            RL_BODY(st3, st0, st2)
+            RL_BODY(st1, st2, st0, LPT)
+            RL_BODY(st2, st3, st1, LPT)
+            RL_BODY(st3, st0, st2, LPT)
+            RL_BODY(st0, st1, st3, LPT)
         }
         if (kt < nk) {
-            RL_BODY(st0, st1, st3)
+            RL_BODY(st1, st2, st0, LPT)
             if (kt + 1 < nk) {
-                RL_BODY(st1, st2, st0)
-                if (kt + 2 < nk) RL_BODY(st2, st3, st1)
+                RL_BODY(st2, st3, st1, LPT)
+                if (kt + 2 < nk) RL_BODY(st3, st0, st2, LPT)
             }
         }
 #undef RL_BODY
     } else {
         // tile kt lives in stage kt % 3
-#define RL_BODY(CUR, ISS)                                                                                             \
+#define RL_BODY(CUR, ISS, INFLIGHT)                                                                                   \
     {                                                                                                                 \
-        wait_vmcnt<LPT>();                                                                                            \
+        wait_vmcnt<INFLIGHT>();                                                                                       \
         wg_barrier();                                                                                                 \
         RL_ISSUE(ISS)                                                                                                 \
         RL_LOADF(CUR, 0, 0)                                                                                           \
@@ -295,47 +312,70 @@ __global__ __launch_bounds__(256) void igemm_lp_kernel(const IgemmParams p)
     }
         RL_ISSUE(st0)
         RL_ISSUE(st1)
+        RL_EPI_LOADS
+        RL_BODY(st0, st2, LPT + NEPI)
+        kt = 1;
 #pragma unroll 1
         for (; kt + 3 <= nk; kt += 3) {
-            RL_BODY(st0, st2)
-            RL_BODY(st1, st0)
-            RL_BODY(st2, st1)
+            RL_BODY(st1, st0, LPT)
+            RL_BODY(st2, st1, LPT)
+            RL_BODY(st0, st2, LPT)
         }
         if (kt < nk) {
-            RL_BODY(st0, st2)
-            if (kt + 1 < nk) RL_BODY(st1, st0)
+            RL_BODY(st1, st0, LPT)
+            if (kt + 1 < nk) RL_BODY(st2, st1, LPT)
         }
 #undef RL_BODY
     }
+#undef RL_EPI_LOADS
     wait_vmcnt<0>();           // the trailing out-of-range issues
 #undef RL_MMA
 #undef RL_LOADF
 #undef RL_ISSUE
 
-    // ---- epilogue on the accumulators: lane = pixel, four consecutive channels per register group
-    const rsrc_t ry = make_rsrc(p.y, y_bytes);
-    const float lo = e.relu_last ? 0.0f : -INFINITY;
-    const int nb = n0 + wn * WTN + 4 * ehalf;
+    // ---- epilogue.  All waves are past their last fragment read and every direct load has landed once
+    // the barrier is crossed; from there on each wave works alone in its own piece of the stages.
+    wg_barrier();
+    constexpr int WBYTES = WTM * WTN * 4, ROWB = WTN * 4;
+    static_assert((4 + STAGES - 1) / STAGES * WBYTES <= STAGE, "a stage must hold its waves' parked tiles");
+    const int wsel = wave % STAGES;
+    unsigned char *park = (wsel == 0 ? st0 : wsel == 1 ? st1 : wsel == 2 ? st2 : st3) + (wave / STAGES) * WBYTES;
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j)
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
-                const int n = nb + j * 32 + 8 * g;
-                float v[4];
+                const int row = i * 32 + epix;
+                const int c = j * 8 + 2 * g + ehalf;                    // 4-channel chunk of the row
+                const int pos = c ^ ((row / RP) & (POSN - 1));
+                f32x4 v;
 #pragma unroll
                 for (int k = 0; k < 4; ++k) v[k] = acc[i][j][4 * g + k] + bias_r[j][g][k];
-                const u32x2 r = res_r[i][j][g];
-                v[0] += __uint_as_float(r[0] << 16); v[1] += __uint_as_float(r[0] & 0xffff0000u);
-                v[2] += __uint_as_float(r[1] << 16); v[3] += __uint_as_float(r[1] & 0xffff0000u);
-#pragma unroll
-                for (int k = 0; k < 4; ++k) v[k] = fmaxf(v[k], lo);
-                u32x2 o;
-                o[0] = f32_to_bf16_bits(v[0]) | (f32_to_bf16_bits(v[1]) << 16);
-                o[1] = f32_to_bf16_bits(v[2]) | (f32_to_bf16_bits(v[3]) << 16);
-                __builtin_amdgcn_raw_buffer_store_b64(o, ry, n < p.N ? y_off[i] + (uint32_t)(j * 64 + g * 16) : OOB, 0, 0);
+                *(f32x4 *)(park + row * ROWB + pos * 16) = v;
             }
+    const rsrc_t ry = make_rsrc(p.y, y_bytes);
+    const float lo = e.relu_last ? 0.0f : -INFINITY;
+#pragma unroll
+    for (int q = 0; q < NPASS; ++q) {
+        const int row = q * RPP + rr;
+        const f32x4 a = *(const f32x4 *)(park + row * ROWB + pA[q] * 16);
+        const f32x4 b = *(const f32x4 *)(park + row * ROWB + (pA[q] ^ 1) * 16);
+        const u32x4 r = res_r[q];
+        float v[8];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) { v[k] = a[k]; v[4 + k] = b[k]; }
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            v[2 * k] += __uint_as_float(r[k] << 16);
+            v[2 * k + 1] += __uint_as_float(r[k] & 0xffff0000u);
+        }
+        u32x4 o;
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+            o[k] = pack_bf16x2(fmaxf(v[2 * k], lo), fmaxf(v[2 * k + 1], lo));
+        __builtin_amdgcn_raw_buffer_store_b128(o, ry, y_off[q], 0, 0);
+    }
 #endif
 }
 

@@ -82,6 +82,7 @@ struct IgemmParams {
     uint32_t seg_stride;                   // bytes between the two 64-byte halves of an A row's K tile (64: contiguous)
     int64_t ts_h, ts_w;                    // element strides of one filter-tap step (xs_h, xs_w unless the taps are regrouped)
     uint32_t div_ohw_mul, div_ohw_sh, div_ow_mul, div_ow_sh;   // m / OHW and pix / OW by multiply-high (make_fast_div)
+    uint32_t tap_rep;                      // bit kh*KW set for every kh < KH (KH*KW <= 32)
 };
 // q = n / d for n < 2^31:  d == 1 ? n : (mulhi(n, mul) >> sh)
 void make_fast_div(uint32_t d, uint32_t &mul, uint32_t &sh);

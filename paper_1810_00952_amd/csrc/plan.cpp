@@ -254,7 +254,7 @@ struct Planner {
             const int64_t Hp = (int64_t)(p.OH - 1) * p.sh + 2 * KH2, Wp = (int64_t)(p.OW - 1) * p.sw + 8;
             const size_t frame = (size_t)xt.dims[0] * Hp * Wp * 8;
             stem = in_dt == RL_BF16 && p.C <= 4 && p.KW <= 8 && p.sw % 2 == 0 && KH2 <= 32 && epi_lp && vout >= 0 && T(vout).dtype == RL_BF16 &&
-                   out_layout == L_NHWC && p.N % 4 == 0 && bytes_of(vout) < lim && frame < lim && phys[L_NATIVE][x] >= 0 && !getenv("RELAYHIP_NO_STEM");
+                   out_layout == L_NHWC && p.N % 8 == 0 && bytes_of(vout) < lim && frame < lim && phys[L_NATIVE][x] >= 0 && !getenv("RELAYHIP_NO_STEM");
             if (stem) {
                 int xnat;
                 st = need(x, L_NATIVE, xnat);
@@ -324,13 +324,16 @@ struct Planner {
             il.dma = !stem && il.avec && p.C % bke == 0 && p.K % bke == 0 && p.K / bke >= 2 && p.KH * p.KW <= 32 &&
                      (x2 < 0 || p.K1 % bke == 0) && x_extent + halo < lim && !getenv("RELAYHIP_NO_DMA");
             // pixel-on-lane variant: bf16 throughout, output rows contiguous in n, epilogue [bias] [+residual] [relu]
-            bool y_ok = vout >= 0 && T(vout).dtype == RL_BF16 && p.ys_c == 1 && p.ys_n == (int64_t)p.OHW * p.ys_p && p.N % 4 == 0 &&
+            bool y_ok = vout >= 0 && T(vout).dtype == RL_BF16 && p.ys_c == 1 && p.ys_n == (int64_t)p.OHW * p.ys_p && p.N % 8 == 0 &&
                         bytes_of(vout) < lim;
             il.lp = stem || (il.avec && in_dt == RL_BF16 && p.C % bke == 0 && p.K % bke == 0 && p.KH * p.KW <= 32 && x2 < 0 && !gates &&
                              x_extent + halo < lim && epi_lp && y_ok && !getenv("RELAYHIP_NO_LP"));
             p.y_bytes = vout >= 0 ? (uint32_t)std::min(bytes_of(vout), lim - 1) : 0;
             make_fast_div((uint32_t)p.OHW, p.div_ohw_mul, p.div_ohw_sh);
             make_fast_div((uint32_t)p.OW, p.div_ow_mul, p.div_ow_sh);
+            p.tap_rep = 0;
+            if (p.KH * p.KW <= 32)
+                for (int kh = 0; kh < p.KH; ++kh) p.tap_rep |= 1u << (kh * p.KW);
         }
         if (need_pack) {
             auto it = plan.packs.find(wv);

@@ -61,7 +61,7 @@ def test_conv_group(dtype, case):
 
 # The conv group's result stays an intermediate (channel-last inside the plan), which is what selects the
 # pixel-on-lane bf16 kernel: every tile shape, stride-2 and 1x1 taps, K tiles spanning several taps,
-# ragged M tails inside and across tiles, N tails on 4-channel granularity, and epilogues with and
+# ragged M tails inside and across tiles, N tails on 8-channel granularity, and epilogues with and
 # without residual / ReLU.
 LP_CASES = [
     # batch cin cout h  w  k s p residual relu
@@ -70,7 +70,7 @@ LP_CASES = [
     (16, 64, 64, 56, 56, 3, 1, 1, True, True),       # 128x64 tile, two workgroups per CU
     (16, 128, 128, 28, 28, 3, 1, 1, False, True),    # 128x128 tile, 18 K tiles
     (4, 64, 128, 57, 57, 3, 2, 1, False, True),      # stride 2, odd image
-    (4, 64, 132, 28, 28, 1, 2, 0, False, False),     # 1x1 stride-2 projection: a single K tile, N tail of 4
+    (4, 64, 136, 28, 28, 1, 2, 0, False, False),     # 1x1 stride-2 projection: a single K tile, N tail of 8
     (2, 128, 72, 9, 7, 3, 1, 1, True, False),        # N = 72, no ReLU
     (1, 192, 64, 5, 5, 5, 1, 2, False, True),        # 25 taps, 3 K tiles per tap
     (2, 256, 512, 7, 7, 3, 1, 1, True, True),        # image smaller than a tile row block
@@ -94,7 +94,7 @@ STEM_CASES = [
     (3, 3, 16, 33, 35, 7, 2, 3, True),       # odd sizes, ragged M
     (2, 1, 8, 20, 20, 5, 2, 2, False),       # one channel, 5x5
     (2, 4, 32, 17, 18, 3, 2, 1, True),       # four channels, 3x3
-    (1, 2, 12, 12, 40, 8, 4, 0, True),       # 8-wide filter, stride 4
+    (1, 2, 24, 12, 40, 8, 4, 0, True),       # 8-wide filter, stride 4
 ]
 
 
