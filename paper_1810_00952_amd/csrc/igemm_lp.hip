@@ -23,7 +23,10 @@
 // stage tile t-1 just left; fragments of k-step s+1 are read from LDS into a
 // second register set before the MFMAs of k-step s are issued, and the first
 // fragments of tile t+1 are read before the barrier of t+1, so the matrix
-// pipeline does not drain at the barrier.  With three stages (smaller LDS
+// pipeline does not drain at the barrier.  The direct loads of a tile are not
+// issued in one burst but one at a time between the MFMAs: a wave whose
+// vector-memory queue is full stalls at the load, and the MFMAs behind it in
+// program order would wait with it.  With three stages (smaller LDS
 // footprint, two workgroups per CU) tile t+2 is issued at the barrier of t and
 // fragment prefetch stays inside a tile.  Each stage is its own LDS array so
 // that the compiler's wait-count insertion can tell direct loads into one
@@ -165,21 +168,19 @@ __global__ __launch_bounds__(256) void igemm_lp_kernel(const IgemmParams p)
         b_voff[j] = (uint32_t)((int64_t)n * p.Kp * 2) + chunk * 16;
     }
 
-    // ---- wave-uniform K state of the tile to be issued next
+    // ---- wave-uniform K state of the tile to be issued next.  RL_TILE_BEGIN latches the scalars of
+    // that tile and advances the state; RL_DMA(ST, d) then issues direct load d of the tile (A groups
+    // first, then B groups) wherever the K loop wants it.
     const int nk = p.K / BKE;
     int f_kt = 0, f_c0 = 0, f_tap = 0, f_kh = 0, f_kw = 0;
-#define RL_ISSUE(ST)                                                                                                  \
+    bool t_live;
+    uint32_t t_soff_a, t_soff_b, t_tapbit;
+#define RL_TILE_BEGIN                                                                                                 \
     {                                                                                                                 \
-        const bool live = f_kt < nk;                                                                                  \
-        const uint32_t soff_b = live ? (uint32_t)(f_kt * BKE) * 2u : 0u;                                              \
-        const uint32_t tapbit = live ? (1u << f_tap) : 0u;                                                            \
-        const uint32_t soff_a = live ? (uint32_t)(((int64_t)f_kh * p.ts_h + (int64_t)f_kw * p.ts_w + f_c0) * 2) : 0u; \
-        _Pragma("unroll") for (int i = 0; i < AG; ++i)                                                                \
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rx, RL_LDS_PTR(ST + (wave * AG + i) * 1024), 16,                 \
-                                                     (a_mask[i] & tapbit) ? a_voff[i] : OOB, soff_a, 0, 0);           \
-        _Pragma("unroll") for (int j = 0; j < BG; ++j)                                                                \
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rw, RL_LDS_PTR(ST + A_BYTES + (wave * BG + j) * 1024), 16,       \
-                                                     live ? b_voff[j] : OOB, soff_b, 0, 0);                           \
+        t_live = f_kt < nk;                                                                                           \
+        t_soff_b = t_live ? (uint32_t)(f_kt * BKE) * 2u : 0u;                                                         \
+        t_tapbit = t_live ? (1u << f_tap) : 0u;                                                                       \
+        t_soff_a = t_live ? (uint32_t)(((int64_t)f_kh * p.ts_h + (int64_t)f_kw * p.ts_w + f_c0) * 2) : 0u;            \
         ++f_kt;                                                                                                       \
         f_c0 += BKE;                                                                                                  \
         if (f_c0 >= p.C) {                                                                                            \
@@ -187,6 +188,20 @@ __global__ __launch_bounds__(256) void igemm_lp_kernel(const IgemmParams p)
             ++f_tap;                                                                                                  \
             if (++f_kw == p.KW) { f_kw = 0; ++f_kh; }                                                                 \
         }                                                                                                             \
+    }
+#define RL_DMA(ST, D)                                                                                                 \
+    {                                                                                                                 \
+        if ((D) < AG)                                                                                                 \
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rx, RL_LDS_PTR(ST + (wave * AG + (D)) * 1024), 16,               \
+                                                     (a_mask[(D) < AG ? (D) : 0] & t_tapbit) ? a_voff[(D) < AG ? (D) : 0] : OOB, t_soff_a, 0, 0); \
+        else                                                                                                          \
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rw, RL_LDS_PTR(ST + A_BYTES + (wave * BG + ((D) - AG)) * 1024), 16, \
+                                                     t_live ? b_voff[(D) >= AG ? (D) - AG : 0] : OOB, t_soff_b, 0, 0); \
+    }
+#define RL_ISSUE(ST)                                                                                                  \
+    {                                                                                                                 \
+        RL_TILE_BEGIN                                                                                                 \
+        _Pragma("unroll") for (int d = 0; d < LPT; ++d) RL_DMA(ST, d)                                                 \
     }
 
     f32x16 acc[TM][TN];
@@ -203,22 +218,38 @@ __global__ __launch_bounds__(256) void igemm_lp_kernel(const IgemmParams p)
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) f_off[ks] = frow * 128 + (((2 * ks + fhalf) ^ ((frow >> 1) & 7)) << 4);
 
-    u32x4 fw[2][TN], fx[2][TM];
-#define RL_LOADF(ST, KS, SET)                                                                                         \
+    // A K tile is worked off in phases of four MFMAs (KSP k-steps each).  The fragments of a phase are
+    // read into one of two register sets while the MFMAs of the phase before run from the other; the
+    // tile's direct loads are spread between the MFMAs, one at a time, so that a full vector-memory
+    // queue stalls the wave only while the matrix pipeline still has work.
+    constexpr int NMMA = 4 * TM * TN;              // MFMAs per wave per K tile
+    constexpr int KSP = 4 / (TM * TN);             // k-steps per phase
+    constexpr int NPH = 4 / KSP;                   // phases per K tile
+    static_assert(TM * TN == 1 || TM * TN == 2 || TM * TN == 4, "wave tile of one, two or four MFMA tiles");
+    u32x4 fw[2][KSP][TN], fx[2][KSP][TM];
+#define RL_LOADP(ST, PH, SET)                                                                                         \
     {                                                                                                                 \
-        _Pragma("unroll") for (int j = 0; j < TN; ++j)                                                                \
-            fw[SET][j] = *(const u32x4 *)(ST + A_BYTES + (wn * WTN + j * 32) * 128 + f_off[KS]);                      \
-        _Pragma("unroll") for (int i = 0; i < TM; ++i)                                                                \
-            fx[SET][i] = *(const u32x4 *)(ST + (wm * WTM + i * 32) * 128 + f_off[KS]);                                \
+        _Pragma("unroll") for (int s_ = 0; s_ < KSP; ++s_) {                                                          \
+            _Pragma("unroll") for (int j = 0; j < TN; ++j)                                                            \
+                fw[SET][s_][j] = *(const u32x4 *)(ST + A_BYTES + (wn * WTN + j * 32) * 128 + f_off[(PH) * KSP + s_]); \
+            _Pragma("unroll") for (int i = 0; i < TM; ++i)                                                            \
+                fx[SET][s_][i] = *(const u32x4 *)(ST + (wm * WTM + i * 32) * 128 + f_off[(PH) * KSP + s_]);           \
+        }                                                                                                             \
         __builtin_amdgcn_sched_barrier(0);   /* keep the reads ahead of the MFMAs that follow in program order */    \
     }
-#define RL_MMA(SET)                                                                                                   \
+    // the phase's MFMAs; direct load d of the tile being issued into ISS follows MFMA number d*NMMA/LPT of the tile
+#define RL_MMAP(SET, PH, ISS)                                                                                         \
     {                                                                                                                 \
-        _Pragma("unroll") for (int i = 0; i < TM; ++i)                                                                \
-            _Pragma("unroll") for (int j = 0; j < TN; ++j)                                                            \
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fw[SET][j]),           \
-                                                                    __builtin_bit_cast(bf16x8, fx[SET][i]), acc[i][j], 0, 0, 0); \
-        __builtin_amdgcn_sched_barrier(0);                                                                            \
+        _Pragma("unroll") for (int s_ = 0; s_ < KSP; ++s_)                                                            \
+            _Pragma("unroll") for (int i = 0; i < TM; ++i)                                                            \
+                _Pragma("unroll") for (int j = 0; j < TN; ++j) {                                                      \
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fw[SET][s_][j]),   \
+                                                                        __builtin_bit_cast(bf16x8, fx[SET][s_][i]), acc[i][j], 0, 0, 0); \
+                    const int q_ = (((PH) * KSP + s_) * TM + i) * TN + j;                                             \
+                    _Pragma("unroll") for (int d = 0; d < LPT; ++d)                                                   \
+                        if (d * NMMA / LPT == q_) RL_DMA(ISS, d)                                                      \
+                    __builtin_amdgcn_sched_barrier(0);                                                                \
+                }                                                                                                     \
     }
 
     // ---- epilogue operands: requested behind the first tiles (see RL_EPI_LOADS below)
@@ -261,39 +292,41 @@ __global__ __launch_bounds__(256) void igemm_lp_kernel(const IgemmParams p)
 
     int kt = 0;
     if (STAGES == 4) {
-        // tile kt lives in stage kt % 4
-#define RL_BODY(CUR, NXT, ISS, INFLIGHT)                                                                              \
+        // tile kt lives in stage kt % 4; S0 is the register set holding the tile's first phase
+#define RL_BODY(CUR, NXT, ISS, INFLIGHT, S0)                                                                          \
     {                                                                                                                 \
         wait_vmcnt<INFLIGHT>();                                                                                       \
         wg_barrier();                                                                                                 \
-        RL_ISSUE(ISS)                                                                                                 \
-        RL_LOADF(CUR, 1, 1) RL_MMA(0)                                                                                 \
-        RL_LOADF(CUR, 2, 0) RL_MMA(1)                                                                                 \
-        RL_LOADF(CUR, 3, 1) RL_MMA(0)                                                                                 \
-        RL_LOADF(NXT, 0, 0) RL_MMA(1)                                                                                 \
+        RL_TILE_BEGIN                                                                                                 \
+        _Pragma("unroll") for (int ph = 0; ph < NPH; ++ph) {                                                          \
+            if (ph + 1 < NPH) RL_LOADP(CUR, ph + 1 < NPH ? ph + 1 : 0, ((S0) + ph + 1) & 1)                           \
+            else RL_LOADP(NXT, 0, ((S0) + ph + 1) & 1)                                                                \
+            RL_MMAP(((S0) + ph) & 1, ph, ISS)                                                                         \
+        }                                                                                                             \
     }
+        constexpr int SODD = NPH & 1;              // one phase per tile: the register sets alternate from tile to tile
         RL_ISSUE(st0)
         RL_ISSUE(st1)
         RL_ISSUE(st2)
         RL_EPI_LOADS
         wait_vmcnt<2 * LPT + NEPI>();
         wg_barrier();
-        RL_LOADF(st0, 0, 0)
+        RL_LOADP(st0, 0, 0)
         // first tile peeled: the epilogue operands are still in flight behind tile 2
-        RL_BODY(st0, st1, st3, LPT + NEPI)
+        RL_BODY(st0, st1, st3, LPT + NEPI, 0)
         kt = 1;
 #pragma unroll 1
         for (; kt + 4 <= nk; kt += 4) {
-            RL_BODY(st1, st2, st0, LPT)
-            RL_BODY(st2, st3, st1, LPT)
-            RL_BODY(st3, st0, st2, LPT)
-            RL_BODY(st0, st1, st3, LPT)
+            RL_BODY(st1, st2, st0, LPT, SODD)
+            RL_BODY(st2, st3, st1, LPT, 0)
+            RL_BODY(st3, st0, st2, LPT, SODD)
+            RL_BODY(st0, st1, st3, LPT, 0)
         }
         if (kt < nk) {
-            RL_BODY(st1, st2, st0, LPT)
+            RL_BODY(st1, st2, st0, LPT, SODD)
             if (kt + 1 < nk) {
-                RL_BODY(st2, st3, st1, LPT)
-                if (kt + 2 < nk) RL_BODY(st3, st0, st2, LPT)
+                RL_BODY(st2, st3, st1, LPT, 0)
+                if (kt + 2 < nk) RL_BODY(st3, st0, st2, LPT, SODD)
             }
         }
 #undef RL_BODY
@@ -303,12 +336,12 @@ __global__ __launch_bounds__(256) void igemm_lp_kernel(const IgemmParams p)
     {                                                                                                                 \
         wait_vmcnt<INFLIGHT>();                                                                                       \
         wg_barrier();                                                                                                 \
-        RL_ISSUE(ISS)                                                                                                 \
-        RL_LOADF(CUR, 0, 0)                                                                                           \
-        RL_LOADF(CUR, 1, 1) RL_MMA(0)                                                                                 \
-        RL_LOADF(CUR, 2, 0) RL_MMA(1)                                                                                 \
-        RL_LOADF(CUR, 3, 1) RL_MMA(0)                                                                                 \
-        RL_MMA(1)                                                                                                     \
+        RL_TILE_BEGIN                                                                                                 \
+        RL_LOADP(CUR, 0, 0)                                                                                           \
+        _Pragma("unroll") for (int ph = 0; ph < NPH; ++ph) {                                                          \
+            if (ph + 1 < NPH) RL_LOADP(CUR, ph + 1 < NPH ? ph + 1 : 0, (ph + 1) & 1)                                  \
+            RL_MMAP(ph & 1, ph, ISS)                                                                                  \
+        }                                                                                                             \
     }
         RL_ISSUE(st0)
         RL_ISSUE(st1)
@@ -329,9 +362,11 @@ __global__ __launch_bounds__(256) void igemm_lp_kernel(const IgemmParams p)
     }
 #undef RL_EPI_LOADS
     wait_vmcnt<0>();           // the trailing out-of-range issues
-#undef RL_MMA
-#undef RL_LOADF
+#undef RL_MMAP
+#undef RL_LOADP
 #undef RL_ISSUE
+#undef RL_DMA
+#undef RL_TILE_BEGIN
 
     // ---- epilogue.  All waves are past their last fragment read and every direct load has landed once
     // the barrier is crossed; from there on each wave works alone in its own piece of the stages.
