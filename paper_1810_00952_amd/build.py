@@ -8,11 +8,15 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "librelayhip.so")
-SOURCES = ["api.cpp", "graph.cpp", "plan.cpp", "igemm.hip", "igemm_fast.hip", "igemm_dma.hip", "igemm_lp.hip", "eltwise.hip"]
+SOURCES = ["api.cpp", "graph.cpp", "plan.cpp", "igemm.hip", "igemm_fast.hip", "igemm_dma.hip", "igemm_lp.hip", "igemm_ws.hip", "eltwise.hip"]
 HEADERS = ["graph.h", "plan.h", "kernels.h", "device_utils.h", "igemm_epilogue.h", os.path.join("..", "..", "include", "relayhip.h")]
 FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wno-unused-function"]
+# Per-source additions.  igemm_ws.hip: its accumulators live across a loop that also holds the epilogue's
+# VALU code; with the accumulators in AGPRs the compiler copies all of them to VGPRs and back on every
+# trip, so keep MFMA results in VGPRs there (the kernel fits in 256).
+EXTRA_FLAGS = {"igemm_ws.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"]}
 
 
 def _hipcc() -> str:
@@ -39,7 +43,7 @@ def build(force: bool = True, verbose: bool = False) -> str:
     for src in SOURCES:
         obj = os.path.join(objdir, src + ".o")
         objs.append(obj)
-        cmd = [_hipcc()] + FLAGS + (["-x", "hip"] if src.endswith(".hip") else []) + ["-c", os.path.join(CSRC, src), "-o", obj]
+        cmd = [_hipcc()] + FLAGS + EXTRA_FLAGS.get(src, []) + (["-x", "hip"] if src.endswith(".hip") else []) + ["-c", os.path.join(CSRC, src), "-o", obj]
         if verbose:
             print(" ".join(cmd))
         procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))

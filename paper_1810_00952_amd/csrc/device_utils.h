@@ -10,6 +10,19 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
+// Lanes of one wave exchanging data through LDS without a workgroup barrier: the LDS executes a
+// wave's instructions in order, so no hardware wait is needed, but the compiler must not move or
+// reuse LDS accesses across the exchange point (to it, what other lanes wrote is invisible).
+__device__ __forceinline__ void wave_lds_exchange()
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    asm volatile("" ::: "memory");
+#endif
+}
+
 __device__ __forceinline__ float bf16_bits_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
 
 // round to nearest, ties to even; finite inputs (NaN maps to a quiet NaN)

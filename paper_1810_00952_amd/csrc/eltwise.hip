@@ -151,30 +151,38 @@ __global__ __launch_bounds__(256) void maxpool_nhwc_kernel(const PoolParams p)
     }
 }
 
+// One workgroup per (image, slab of 64 channel vectors): the 256 threads split the pixels four ways,
+// each sums its share in fp32, and the four partial sums meet in LDS (fixed order, so the result does
+// not depend on timing).
 template <typename T, int VEC>
 __global__ __launch_bounds__(256) void gavgpool_nhwc_kernel(const PoolParams p)
 {
+    __shared__ float part[4][64][VEC];
     const int cv = p.C / VEC;
-    const int64_t total = (int64_t)p.N * cv;
+    const int slabs = (cv + 63) / 64;
+    const int n = blockIdx.x / slabs, slab = blockIdx.x - n * slabs;
+    const int v = slab * 64 + (threadIdx.x & 63), g = threadIdx.x >> 6;
     const T *x = (const T *)p.x;
     T *y = (T *)p.y;
     const int HW = p.H * p.W;
-    for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += (int64_t)gridDim.x * blockDim.x) {
-        int c = (int)(idx % cv) * VEC;
-        int n = (int)(idx / cv);
-        float acc[VEC];
+    float acc[VEC];
 #pragma unroll
-        for (int k = 0; k < VEC; ++k) acc[k] = 0.0f;
-        for (int q = 0; q < HW; ++q) {
-            float v[VEC];
-            VecIO<T, VEC>::load(x + ((int64_t)n * HW + q) * p.C + c, v);
+    for (int k = 0; k < VEC; ++k) acc[k] = 0.0f;
+    if (v < cv)
+        for (int q = g; q < HW; q += 4) {
+            float t[VEC];
+            VecIO<T, VEC>::load(x + ((int64_t)n * HW + q) * p.C + v * VEC, t);
 #pragma unroll
-            for (int k = 0; k < VEC; ++k) acc[k] += v[k];
+            for (int k = 0; k < VEC; ++k) acc[k] += t[k];
         }
+#pragma unroll
+    for (int k = 0; k < VEC; ++k) part[g][threadIdx.x & 63][k] = acc[k];
+    __syncthreads();
+    if (g == 0 && v < cv) {
         const float inv = 1.0f / (float)HW;
 #pragma unroll
-        for (int k = 0; k < VEC; ++k) acc[k] *= inv;
-        VecIO<T, VEC>::store(y + (int64_t)n * p.C + c, acc);
+        for (int k = 0; k < VEC; ++k) acc[k] = (((part[0][threadIdx.x][k] + part[1][threadIdx.x][k]) + part[2][threadIdx.x][k]) + part[3][threadIdx.x][k]) * inv;
+        VecIO<T, VEC>::store(y + (int64_t)n * p.C + v * VEC, acc);
     }
 }
 
@@ -203,12 +211,16 @@ hipError_t launch_maxpool_nhwc(const PoolParams &p, hipStream_t s)
 
 hipError_t launch_gavgpool_nhwc(const PoolParams &p, hipStream_t s)
 {
+    auto blocks = [&](int vec) { return (int64_t)p.N * ((p.C / vec + 63) / 64); };
+    const bool wide = p.dtype == DT_BF16 ? p.C % 8 == 0 : p.C % 4 == 0;
+    const int64_t nb = blocks(wide ? (p.dtype == DT_BF16 ? 8 : 4) : 1);
+    if (nb <= 0 || nb > 0x7fffffff) return hipErrorInvalidValue;
     if (p.dtype == DT_BF16) {
-        if (p.C % 8 == 0) hipLaunchKernelGGL((gavgpool_nhwc_kernel<uint16_t, 8>), dim3(grid_for((int64_t)p.N * (p.C / 8))), dim3(256), 0, s, p);
-        else hipLaunchKernelGGL((gavgpool_nhwc_kernel<uint16_t, 1>), dim3(grid_for((int64_t)p.N * p.C)), dim3(256), 0, s, p);
+        if (wide) hipLaunchKernelGGL((gavgpool_nhwc_kernel<uint16_t, 8>), dim3((unsigned)nb), dim3(256), 0, s, p);
+        else hipLaunchKernelGGL((gavgpool_nhwc_kernel<uint16_t, 1>), dim3((unsigned)nb), dim3(256), 0, s, p);
     } else {
-        if (p.C % 4 == 0) hipLaunchKernelGGL((gavgpool_nhwc_kernel<float, 4>), dim3(grid_for((int64_t)p.N * (p.C / 4))), dim3(256), 0, s, p);
-        else hipLaunchKernelGGL((gavgpool_nhwc_kernel<float, 1>), dim3(grid_for((int64_t)p.N * p.C)), dim3(256), 0, s, p);
+        if (wide) hipLaunchKernelGGL((gavgpool_nhwc_kernel<float, 4>), dim3((unsigned)nb), dim3(256), 0, s, p);
+        else hipLaunchKernelGGL((gavgpool_nhwc_kernel<float, 1>), dim3((unsigned)nb), dim3(256), 0, s, p);
     }
     return hipGetLastError();
 }

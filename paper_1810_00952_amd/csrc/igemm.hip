@@ -342,9 +342,11 @@ static hipError_t launch_typed(const IgemmParams &p, const IgemmLaunch &l, hipSt
 hipError_t launch_igemm_fast(const IgemmParams &p, const IgemmLaunch &l, hipStream_t s);
 hipError_t launch_igemm_dma(const IgemmParams &p, const IgemmLaunch &l, hipStream_t s);
 hipError_t launch_igemm_lp(const IgemmParams &p, const IgemmLaunch &l, hipStream_t s);
+hipError_t launch_igemm_ws(const IgemmParams &p, hipStream_t s);
 
 hipError_t launch_igemm(const IgemmParams &p, const IgemmLaunch &l, hipStream_t s)
 {
+    if (l.lp && l.ws) return launch_igemm_ws(p, s);
     if (l.lp) return launch_igemm_lp(p, l, s);
     if (l.avec && l.dma) return launch_igemm_dma(p, l, s);
     if (l.avec) return launch_igemm_fast(p, l, s);

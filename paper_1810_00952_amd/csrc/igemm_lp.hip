@@ -389,6 +389,7 @@ __global__ __launch_bounds__(256) void igemm_lp_kernel(const IgemmParams p)
                 for (int k = 0; k < 4; ++k) v[k] = acc[i][j][4 * g + k] + bias_r[j][g][k];
                 *(f32x4 *)(park + row * ROWB + pos * 16) = v;
             }
+    wave_lds_exchange();
     const rsrc_t ry = make_rsrc(p.y, y_bytes);
     const float lo = e.relu_last ? 0.0f : -INFINITY;
 #pragma unroll

@@ -94,6 +94,7 @@ struct IgemmLaunch {
     int32_t gates;      // 1: LSTM gate epilogue (tile must be TILE_64x64)
     int32_t dma;        // 1: K tiles go global -> LDS directly (needs avec, C and K multiples of the K tile, >= 2 tiles)
     int32_t lp;         // 1: pixel-on-lane variant with the register epilogue (bf16, [bias] [+residual] [relu])
+    int32_t ws;         // 1 (with lp): weights-stationary persistent variant (N <= 64, K <= 576)
 };
 hipError_t launch_igemm(const IgemmParams &p, const IgemmLaunch &l, hipStream_t s);
 

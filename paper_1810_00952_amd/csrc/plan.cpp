@@ -328,6 +328,7 @@ struct Planner {
                         bytes_of(vout) < lim;
             il.lp = stem || (il.avec && in_dt == RL_BF16 && p.C % bke == 0 && p.K % bke == 0 && p.KH * p.KW <= 32 && x2 < 0 && !gates &&
                              x_extent + halo < lim && epi_lp && y_ok && !getenv("RELAYHIP_NO_LP"));
+            il.ws = il.lp && p.N <= 64 && p.K / bke <= 9 && getenv("RELAYHIP_WS") != nullptr;   // off by default until it beats the per-tile kernel
             p.y_bytes = vout >= 0 ? (uint32_t)std::min(bytes_of(vout), lim - 1) : 0;
             make_fast_div((uint32_t)p.OHW, p.div_ohw_mul, p.div_ohw_sh);
             make_fast_div((uint32_t)p.OW, p.div_ow_mul, p.div_ow_sh);
@@ -387,7 +388,7 @@ struct Planner {
         p.epi = chain.epi;
         static const char *tile_names[] = {"128x128", "128x64", "64x64"};
         std::string kname = std::string(an.kind == RL_OP_CONV2D ? "igemm_conv2d_" : "igemm_dense_") + (in_dt == RL_BF16 ? "bf16_" : "f32_") +
-                            tile_names[il.tile] + (il.lp ? "_lp" : il.avec ? (il.dma ? "_dma" : "") : "_gather") + (gates ? "_gates" : "");
+                            (il.ws ? "128x64_ws" : tile_names[il.tile]) + (il.ws ? "" : il.lp ? "_lp" : il.avec ? (il.dma ? "_dma" : "") : "_gather") + (gates ? "_gates" : "");
         Step &s = add_step(S_IGEMM, std::string(op_name(an.kind)) + "#" + std::to_string(ops[ai]), kname);
         s.group = gi;
         s.ig = p; s.il = il;
