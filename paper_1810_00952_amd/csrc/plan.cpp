@@ -328,7 +328,9 @@ struct Planner {
                         bytes_of(vout) < lim;
             il.lp = stem || (il.avec && in_dt == RL_BF16 && p.C % bke == 0 && p.K % bke == 0 && p.KH * p.KW <= 32 && x2 < 0 && !gates &&
                              x_extent + halo < lim && epi_lp && y_ok && !getenv("RELAYHIP_NO_LP"));
-            il.ws = il.lp && p.N <= 64 && p.K / bke <= 9 && getenv("RELAYHIP_WS") != nullptr;   // off by default until it beats the per-tile kernel
+            // weights-stationary persistent variant: pays off when the weights leave LDS for a deep ring (K <= 320);
+            // RELAYHIP_WS_ALL=1 also takes it up to K = 576, where its shallower ring is latency-bound
+            il.ws = il.lp && p.N <= 64 && (p.K / bke <= 5 || (p.K / bke <= 9 && getenv("RELAYHIP_WS_ALL"))) && !getenv("RELAYHIP_NO_WS");
             p.y_bytes = vout >= 0 ? (uint32_t)std::min(bytes_of(vout), lim - 1) : 0;
             make_fast_div((uint32_t)p.OHW, p.div_ohw_mul, p.div_ohw_sh);
             make_fast_div((uint32_t)p.OW, p.div_ow_mul, p.div_ow_sh);

@@ -88,6 +88,18 @@ def test_conv_group_internal_layout_bf16(case):
     check_graph(spec, data, f"conv lp {case}")
 
 
+def test_conv_weights_stationary_shallow_ring(monkeypatch):
+    # K = 576 (9 weight tiles, 5-stage ring, residual through the ring): opt-in, the planner prefers the per-tile kernel there
+    monkeypatch.setenv("RELAYHIP_WS_ALL", "1")
+    for case in [(16, 64, 64, 56, 56, 3, 1, 1, True, True), (3, 64, 48, 29, 31, 3, 1, 1, False, True)]:
+        b, ci, co, h, w, k, s, p, res, relu = case
+        spec, data = W.conv_group(b, ci, co, h, w, k, s, p, "bf16", residual=res, relu=relu, tail=True)
+        from paper_1810_00952_amd import binding
+        desc = binding.Plan(binding.graph_from_spec(binding.Context(), spec)).describe()
+        assert any(st["kernel"].endswith("_ws") for st in desc["steps"]), [st["kernel"] for st in desc["steps"]]
+        check_graph(spec, data, f"conv ws {case}")
+
+
 STEM_CASES = [
     # batch cin cout h   w   k s p relu
     (2, 3, 64, 224, 224, 7, 2, 3, True),     # the ResNet stem
