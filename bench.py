@@ -1,11 +1,21 @@
 """Benchmark of the fused-operator hot path on one MI355X.
 
-One step = one pass of the whole path (layout change of the input, 20 fused
-conv2d groups, max-pool, global average pool, dense head) over one batch of
-the ResNet-18-shaped graph: batch 64, bf16 activations and weights, fp32
-accumulation, seeded synthetic data, random-init weights with batch-norm
-folded in.  Prints ONE JSON line.  Paper figures for this metric: none (the
-paper reports no measurement).
+Default workload (the headline metric): one step = one pass of the whole path
+(stem frame copy, 20 fused conv2d groups, max-pool, global average pool, dense
+head) over one batch of the ResNet-18-shaped graph: batch 64, bf16 activations
+and weights, fp32 accumulation, seeded synthetic data, random-init weights with
+batch-norm folded in.  Prints ONE JSON line.  Paper figures for this metric:
+none (the paper reports no measurement).
+
+Other workloads (`--workload`), same JSON shape, for the remaining
+configurations and the HBM-bound groups:
+  eltwise   relu(bias_add(x) + r) on 256x64x112x112 bf16 (1.2 GB moved per step)
+  eltwise32 the same in f32 on 128x64x112x112
+  gates     stand-alone LSTM gate group on z 16384x4096 f32
+  lstm      unrolled LSTM, batch 64, 1024 -> 1024, 128 steps, bf16 weights
+  mlp       MLP 784 -> 128 -> 10, f32, batch 32
+  conv      single fused conv2d group 64 -> 64, 56x56, f32, batch 1
+  resnet18_f32_b1  the ResNet-18-shaped graph in f32 at batch 1
 """
 from __future__ import annotations
 
@@ -20,21 +30,11 @@ sys.path.insert(0, ROOT)
 sys.path.insert(0, os.path.join(ROOT, "tests"))
 
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
+PEAK_F32_TFLOPS = 157.3        # MI355X fp32 (MFMA and vector)
 PEAK_HBM_GBS = 8000.0
 
 
-def build_session(batch: int, dtype: str):
-    import workloads as W
-    from paper_1810_00952_amd import harness
-    from helpers import fold_resnet_hip
-    spec, raw, bn = W.resnet18(batch=batch, dtype=dtype)
-    s = harness.Session(spec)
-    fold_resnet_hip(s, raw, bn, dtype)
-    s.alloc()
-    return s, spec, raw, bn
-
-
-def cpu_baseline(n_images: int):
+def cpu_baseline_resnet(n_images: int):
     """The oracle, as it stands, on `n_images` images of the same workload."""
     import workloads as W
     import oracle as O
@@ -49,14 +49,174 @@ def cpu_baseline(n_images: int):
             "sample": f"{n_images} images of the batch-64 bf16 ResNet-18-shaped graph, one oracle run, {dt:.1f} s"}
 
 
+def cpu_baseline_graph(spec, data, unit_count: float, unit: str, what: str):
+    import oracle as O
+    from oracle import graph as OG
+    t0 = time.perf_counter()
+    OG.run(spec, data)
+    dt = time.perf_counter() - t0
+    return {"value": unit_count / dt, "unit": unit, "cores": O.num_threads(), "kind": "oracle", "sample": f"{what}, one oracle run, {dt:.1f} s"}
+
+
+def time_steps(run, steps, warmup):
+    import torch
+    stream = torch.cuda.current_stream()
+    for _ in range(warmup):
+        run()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record(stream)
+    for _ in range(steps):
+        run()
+    e1.record(stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms = e0.elapsed_time(e1) / steps
+    return max(ms, wall * 1e3 / steps)          # never report less than the host saw
+
+
+def kernel_table(session, reps):
+    """Per-kernel durations from HIP events recorded on the launch stream around every step of the plan."""
+    from paper_1810_00952_amd import harness
+    desc = session.plan.describe()
+    step_ms = session.plan.profile({vid: t.data_ptr() for vid, t in session.tensors.items()}, session.workspace.data_ptr(),
+                                   session.workspace.numel(), harness.stream_handle(), reps)
+    by_kernel = {}
+    for st, t in zip(desc["steps"], step_ms):
+        k = by_kernel.setdefault(st["kernel"], {"ms": 0.0, "flops": 0.0, "bytes": 0.0, "launches": 0})
+        k["ms"] += t; k["flops"] += st["flops"]; k["bytes"] += st["bytes"]; k["launches"] += 1
+    return desc, by_kernel
+
+
+def roofline_of(name, k, peak_tflops):
+    """Roofline entry of one kernel (all its launches in a step): MFMA-bound when its algorithmic
+    intensity is above the ridge of the peaks used, else HBM-bound."""
+    tflops = k["flops"] / (k["ms"] * 1e-3) / 1e12
+    gbs = k["bytes"] / (k["ms"] * 1e-3) / 1e9
+    ridge = peak_tflops * 1e12 / (PEAK_HBM_GBS * 1e9)
+    if name.startswith("igemm") and k["flops"] / max(k["bytes"], 1.0) >= ridge:
+        roof = {"bound": "mfma", "achieved": tflops, "peak": peak_tflops, "unit": "TFLOP/s", "frac": tflops / peak_tflops}
+    else:
+        roof = {"bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS}
+    roof.update({"traffic": None, "kernel": name, "launches_per_step": k["launches"], "avg_launch_us": k["ms"] * 1e3 / k["launches"],
+                 "algorithmic_flops_per_step": k["flops"], "algorithmic_bytes_per_step": k["bytes"]})
+    return roof
+
+
+def kernels_json(by_kernel):
+    return {k: {"ms_per_step": v["ms"], "launches": v["launches"], "tflops": v["flops"] / (v["ms"] * 1e-3) / 1e12,
+                "gbs": v["bytes"] / (v["ms"] * 1e-3) / 1e9} for k, v in sorted(by_kernel.items(), key=lambda kv: -kv[1]["ms"])}
+
+
+def base_json(metric, value, unit, args, ms, dtype, workload, extra_cfg=None):
+    cfg = {"workload": workload}
+    cfg.update(extra_cfg or {})
+    return {"metric": metric, "value": value, "unit": unit, "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
+            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": dtype, "data": "synthetic", "config": cfg,
+            "paper_figures": "none"}
+
+
+def bench_resnet(args, batch, dtype):
+    import workloads as W
+    from paper_1810_00952_amd import harness
+    from helpers import fold_resnet_hip
+    spec, raw, bn = W.resnet18(batch=batch, dtype=dtype)
+    s = harness.Session(spec)
+    fold_resnet_hip(s, raw, bn, dtype)
+    s.alloc()
+    ms = time_steps(s.run, args.steps, args.warmup)
+    desc, by_kernel = kernel_table(s, args.profile_reps)
+    peak = PEAK_BF16_TFLOPS if dtype == "bf16" else PEAK_F32_TFLOPS
+    dom_name, dom = max(by_kernel.items(), key=lambda kv: kv[1]["ms"])
+    total_flops = sum(st["flops"] for st in desc["steps"] if st["kernel"].startswith("igemm"))
+    name = "bf16 in / fp32 accumulate" if dtype == "bf16" else "f32"
+    out = base_json(f"images/sec ResNet-18-shape bs{batch} {dtype}", batch / (ms * 1e-3), "images/s", args, ms, dtype,
+                    f"ResNet-18-shaped inference graph, batch {batch}, {name}, folded batch-norm, 23 fused groups, 3x224x224 N(0,1) input",
+                    {"global_batch": batch})
+    out["tflops_whole_graph"] = total_flops / (ms * 1e-3) / 1e12
+    out["roofline"] = roofline_of(dom_name, dom, peak)
+    out["kernels"] = kernels_json(by_kernel)
+    if not args.no_cpu and dtype == "bf16" and batch == 64:
+        out["cpu_baseline"] = cpu_baseline_resnet(args.cpu_images)
+    return out
+
+
+def bench_graph(args, spec, data, metric, unit, units_per_step, dtype, workload, peak_tflops, cpu=None):
+    from paper_1810_00952_amd import harness
+    s = harness.Session(spec)
+    s.load(data)
+    s.alloc()
+    ms = time_steps(s.run, args.steps, args.warmup)
+    desc, by_kernel = kernel_table(s, args.profile_reps)
+    dom_name, dom = max(by_kernel.items(), key=lambda kv: kv[1]["ms"])
+    out = base_json(metric, units_per_step / (ms * 1e-3), unit, args, ms, dtype, workload)
+    out["roofline"] = roofline_of(dom_name, dom, peak_tflops)
+    out["kernels"] = kernels_json(by_kernel)
+    if cpu is not None and not args.no_cpu:
+        out["cpu_baseline"] = cpu()
+    return out
+
+
+def bench_lstm(args):
+    import numpy as np
+    import torch
+    import workloads as W
+    from paper_1810_00952_amd import harness
+    T, B, I, H = 128, 64, 1024, 1024
+    d = W.lstm_data(T, B, I, H, "bf16")
+    spec = W.lstm_cell_graph(B, I, H, "bf16", fused=not args.unfused)
+    s = harness.Session(spec)
+    s.load({"w": d["w"], "b": d["b"]})
+    x = harness.to_device(d["x"], "bf16")
+    h0 = torch.zeros((B, H), dtype=torch.bfloat16, device="cuda:0")
+    c = torch.zeros((B, H), dtype=torch.float32, device="cuda:0")
+    hs = torch.empty((T, B, H), dtype=torch.bfloat16, device="cuda:0")
+    ws = torch.empty(max(256, s.plan.workspace_bytes()), dtype=torch.uint8, device="cuda:0")
+    n = s.by_name
+    roles = {"x": n["x"], "h_in": n["h"], "c_in": n["c"], "c_out": spec.outputs[0], "h_out": spec.outputs[1]}
+    params = {n["w"]: s.tensors[n["w"]].data_ptr(), n["b"]: s.tensors[n["b"]].data_ptr()}
+
+    def run():
+        c.zero_()
+        s.plan.run_recurrent(T, roles, x.data_ptr(), B * I * 2, h0.data_ptr(), c.data_ptr(), hs.data_ptr(), B * H * 2, params,
+                             ws.data_ptr(), ws.numel(), harness.stream_handle())
+    ms = time_steps(run, args.steps, args.warmup)
+    desc = s.plan.describe()
+    flops = sum(st["flops"] for st in desc["steps"]) * T
+    nbytes = sum(st["bytes"] for st in desc["steps"]) * T
+    out = base_json("sequences/sec unrolled LSTM b64 1024x1024 T128 bf16", B / (ms * 1e-3), "sequences/s", args, ms, "bf16",
+                    "unrolled LSTM, batch 64, input and hidden 1024, 128 steps, bf16 weights, fp32 accumulate, "
+                    + ("gate math fused into the GEMM epilogue" if not args.unfused else "GEMM group and gate group"))
+    out["us_per_step_of_sequence"] = ms * 1e3 / T
+    tflops, gbs = flops / (ms * 1e-3) / 1e12, nbytes / (ms * 1e-3) / 1e9
+    # 59 flop/B per step (the 16.8 MB weight matrix is re-read every step): bound by memory traffic
+    out["roofline"] = {"bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS, "traffic": None,
+                       "kernel": "+".join(st["kernel"] for st in desc["steps"]), "launches_per_step": T * len(desc["steps"]),
+                       "avg_launch_us": ms * 1e3 / (T * len(desc["steps"])), "algorithmic_flops_per_step": flops,
+                       "algorithmic_bytes_per_step": nbytes, "tflops": tflops}
+    if not args.no_cpu:
+        import oracle as O
+        Ts = 8
+        t0 = time.perf_counter()
+        O.lstm_sequence(O.widen(d["x"][:Ts], "bf16"), O.widen(d["w"], "bf16"), O.widen(d["b"], "f32"), np.zeros((B, H)), np.zeros((B, H)), h_dtype="bf16")
+        dt = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": B / (dt * T / Ts), "unit": "sequences/s", "cores": O.num_threads(), "kind": "oracle",
+                               "sample": f"first {Ts} of the 128 steps, scaled to the full sequence, {dt:.1f} s"}
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="resnet18",
+                    choices=["resnet18", "resnet18_f32_b1", "eltwise", "eltwise32", "gates", "lstm", "mlp", "conv"])
     ap.add_argument("--batch", type=int, default=64)
     ap.add_argument("--cpu-images", type=int, default=128)
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--unfused", action="store_true", help="lstm: gate math as a group of its own")
     ap.add_argument("--profile-reps", type=int, default=20)
     args = ap.parse_args()
     if args.gpus != 1:
@@ -64,58 +224,42 @@ def main():
         sys.exit(2)
 
     import torch
-    from paper_1810_00952_amd import harness
+    import workloads as W
     assert torch.cuda.is_available(), "bench.py needs an MI355X"
-    s, spec, raw, bn = build_session(args.batch, "bf16")
-    stream = torch.cuda.current_stream()
-    for _ in range(args.warmup):
-        s.run()
-    torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    t0 = time.perf_counter()
-    e0.record(stream)
-    for _ in range(args.steps):
-        s.run()
-    e1.record(stream)
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-    ms = e0.elapsed_time(e1) / args.steps
-    ms = max(ms, wall * 1e3 / args.steps)          # never report less than the host saw
-
-    # per-kernel durations from HIP events around every step, same stream
-    desc = s.plan.describe()
-    step_ms = s.plan.profile({vid: t.data_ptr() for vid, t in s.tensors.items()}, s.workspace.data_ptr(), s.workspace.numel(),
-                             harness.stream_handle(), args.profile_reps)
-    by_kernel = {}
-    for st, t in zip(desc["steps"], step_ms):
-        k = by_kernel.setdefault(st["kernel"], {"ms": 0.0, "flops": 0.0, "bytes": 0.0, "launches": 0})
-        k["ms"] += t; k["flops"] += st["flops"]; k["bytes"] += st["bytes"]; k["launches"] += 1
-    dom_name, dom = max(by_kernel.items(), key=lambda kv: kv[1]["ms"])
-    tflops = dom["flops"] / (dom["ms"] * 1e-3) / 1e12
-    gbs = dom["bytes"] / (dom["ms"] * 1e-3) / 1e9
-    mfma_bound = dom_name.startswith("igemm") and (dom["flops"] / max(dom["bytes"], 1.0)) >= PEAK_BF16_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9)
-    if mfma_bound:
-        roof = {"bound": "mfma", "achieved": tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": tflops / PEAK_BF16_TFLOPS}
+    wl = args.workload
+    if wl == "resnet18":
+        out = bench_resnet(args, args.batch, "bf16")
+    elif wl == "resnet18_f32_b1":
+        out = bench_resnet(args, 1, "f32")
+    elif wl in ("eltwise", "eltwise32"):
+        dtype, shape = ("bf16", (256, 64, 112, 112)) if wl == "eltwise" else ("f32", (128, 64, 112, 112))
+        spec, make = W.eltwise_bias_res_relu(shape, dtype)
+        n = shape[0] * shape[1] * shape[2] * shape[3]
+        out = bench_graph(args, spec, make(), f"elements/sec fused bias+residual+relu {dtype}", "elements/s", n, dtype,
+                          f"relu(bias_add(x) + r) on {'x'.join(map(str, shape))} {dtype}, one fusion group, N(0,1) inputs", PEAK_F32_TFLOPS)
+    elif wl == "gates":
+        import numpy as np
+        B, H = 16384, 1024
+        g = W.GraphSpec("gates")
+        z = g.input("z", "f32", (B, 4 * H)); c = g.input("c", "f32", (B, H))
+        o, (c2, h2) = g.op("lstm_gates", [z, c], [("f32", (B, H)), ("bf16", (B, H))])
+        g.output(c2); g.output(h2)
+        rng = W.rng_for(6, salt=2)
+        data = {"z": W.as_dtype(W.normal(rng, (B, 4 * H)), "f32"), "c": W.as_dtype(W.normal(rng, (B, H)), "f32")}
+        out = bench_graph(args, g, data, "hidden units/sec LSTM gate group", "units/s", B * H, "f32",
+                          f"lstm_gates on z {B}x{4 * H} f32, c {B}x{H} f32 -> c' f32, h' bf16", PEAK_F32_TFLOPS)
+    elif wl == "lstm":
+        out = bench_lstm(args)
+    elif wl == "mlp":
+        spec, data = W.mlp(32, 784, 128, 10, "f32")
+        out = bench_graph(args, spec, data, "samples/sec MLP 784-128-10 f32 b32", "samples/s", 32, "f32",
+                          "MLP fusion graph, f32, batch 32: dense 784->128 + bias + ReLU, dense 128->10 + bias", PEAK_F32_TFLOPS,
+                          cpu=lambda: cpu_baseline_graph(spec, data, 32, "samples/s", "the same 32-sample batch"))
     else:
-        roof = {"bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS}
-    roof.update({"traffic": None, "kernel": dom_name, "launches_per_step": dom["launches"],
-                 "avg_launch_us": dom["ms"] * 1e3 / dom["launches"], "algorithmic_flops_per_step": dom["flops"],
-                 "algorithmic_bytes_per_step": dom["bytes"]})
-    total_flops = sum(st["flops"] for st in desc["steps"] if st["kernel"].startswith("igemm"))
-    out = {
-        "metric": "images/sec ResNet-18-shape bs64 bf16", "value": args.batch / (ms * 1e-3), "unit": "images/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True,
-        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": f"ResNet-18-shaped inference graph, batch {args.batch}, bf16 in / fp32 accumulate, folded batch-norm, "
-                               "23 fused groups, 3x224x224 N(0,1) input", "global_batch": args.batch},
-        "tflops_whole_graph": total_flops / (ms * 1e-3) / 1e12,
-        "roofline": roof,
-        "kernels": {k: {"ms_per_step": v["ms"], "launches": v["launches"], "tflops": v["flops"] / (v["ms"] * 1e-3) / 1e12,
-                        "gbs": v["bytes"] / (v["ms"] * 1e-3) / 1e9} for k, v in sorted(by_kernel.items(), key=lambda kv: -kv[1]["ms"])},
-        "paper_figures": "none",
-    }
-    if not args.no_cpu:
-        out["cpu_baseline"] = cpu_baseline(args.cpu_images)
+        spec, data = W.conv_group(1, 64, 64, 56, 56, 3, 1, 1, "f32")
+        out = bench_graph(args, spec, data, "images/sec single conv2d group 64->64 56x56 f32 b1", "images/s", 1, "f32",
+                          "single fused conv2d group, f32, NCHW, batch 1, 64->64 channels, 56x56, 3x3, + bias + ReLU", PEAK_F32_TFLOPS,
+                          cpu=lambda: cpu_baseline_graph(spec, data, 1, "images/s", "the same image"))
     print(json.dumps(out))
 
 

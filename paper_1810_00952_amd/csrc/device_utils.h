@@ -164,7 +164,7 @@ __device__ __forceinline__ void store8(void *p, int dtype, int64_t i, const floa
     if (dtype == DT_BF16) {
         u32x4 r;
 #pragma unroll
-        for (int k = 0; k < 4; ++k) r[k] = f32_to_bf16_bits(v[2 * k]) | (f32_to_bf16_bits(v[2 * k + 1]) << 16);
+        for (int k = 0; k < 4; ++k) r[k] = pack_bf16x2(v[2 * k], v[2 * k + 1]);
         *(u32x4 *)((uint16_t *)p + i) = r;
     } else {
         f32x4 a, b;
@@ -172,6 +172,41 @@ __device__ __forceinline__ void store8(void *p, int dtype, int64_t i, const floa
         for (int k = 0; k < 4; ++k) { a[k] = v[k]; b[k] = v[4 + k]; }
         *(f32x4 *)((float *)p + i) = a;
         *(f32x4 *)((float *)p + i + 4) = b;
+    }
+}
+
+// Streaming forms (nontemporal: the data is not expected to be re-read from cache soon), for tensors
+// far larger than the caches.
+__device__ __forceinline__ void load8_nt(const void *p, int dtype, int64_t i, float v[8])
+{
+    if (dtype == DT_BF16) {
+        u32x4 r = __builtin_nontemporal_load((const u32x4 *)((const uint16_t *)p + i));
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            v[2 * k] = __uint_as_float(r[k] << 16);
+            v[2 * k + 1] = __uint_as_float(r[k] & 0xffff0000u);
+        }
+    } else {
+        f32x4 a = __builtin_nontemporal_load((const f32x4 *)((const float *)p + i));
+        f32x4 b = __builtin_nontemporal_load((const f32x4 *)((const float *)p + i + 4));
+#pragma unroll
+        for (int k = 0; k < 4; ++k) { v[k] = a[k]; v[4 + k] = b[k]; }
+    }
+}
+
+__device__ __forceinline__ void store8_nt(void *p, int dtype, int64_t i, const float v[8])
+{
+    if (dtype == DT_BF16) {
+        u32x4 r;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) r[k] = pack_bf16x2(v[2 * k], v[2 * k + 1]);
+        __builtin_nontemporal_store(r, (u32x4 *)((uint16_t *)p + i));
+    } else {
+        f32x4 a, b;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) { a[k] = v[k]; b[k] = v[4 + k]; }
+        __builtin_nontemporal_store(a, (f32x4 *)((float *)p + i));
+        __builtin_nontemporal_store(b, (f32x4 *)((float *)p + i + 4));
     }
 }
 
@@ -193,7 +228,10 @@ __device__ __forceinline__ float binop(int op, float v, float t)
 //           operands share the output's layout)
 //   ci0   : flat index used to derive channels: channel of element k is
 //           ((ci0 + k) / ch_inner) % ch_count
-__device__ __forceinline__ void chain8(const Epilogue &e, float v[8], int64_t idx0, int64_t ci0, int64_t ch_inner, int ch_count)
+//   ch_hint: >= 0 when the caller already knows the one channel all 8 elements share (8 | ch_inner)
+//   nt    : full-shape operands are read with streaming loads
+__device__ __forceinline__ void chain8(const Epilogue &e, float v[8], int64_t idx0, int64_t ci0, int64_t ch_inner, int ch_count,
+                                       int ch_hint = -1, bool nt = false)
 {
     for (int s = 0; s < e.n_ops; ++s) {
         const int op = epi_op(e, s), a = epi_arg(e, s);
@@ -207,7 +245,7 @@ __device__ __forceinline__ void chain8(const Epilogue &e, float v[8], int64_t id
 #pragma unroll
                 for (int k = 0; k < 8; ++k) v[k] += b[k];
             } else if ((ch_inner & 7) == 0) {
-                int ch = (int)((ci0 / ch_inner) % ch_count);
+                int ch = ch_hint >= 0 ? ch_hint : (int)((ci0 / ch_inner) % ch_count);
                 float b = load_as_f32(optr, odt, ch);
 #pragma unroll
                 for (int k = 0; k < 8; ++k) v[k] += b;
@@ -220,7 +258,8 @@ __device__ __forceinline__ void chain8(const Epilogue &e, float v[8], int64_t id
             }
         } else if (op >= E_ADD && op <= E_RDIV) {
             float tt[8];
-            load8(optr, odt, idx0, tt);
+            if (nt) load8_nt(optr, odt, idx0, tt);
+            else load8(optr, odt, idx0, tt);
 #pragma unroll
             for (int k = 0; k < 8; ++k) v[k] = binop(op, v[k], tt[k]);
         } else if (op == E_RELU) {

@@ -2,44 +2,88 @@
 // stand-alone LSTM gate group, window reductions, layout change, weight
 // packing and batch-norm folding.  All move 16-byte vectors per lane where the
 // tensor's geometry allows and touch every input and output exactly once.
+#include <algorithm>
+
 #include "device_utils.h"
 
 namespace rl {
 
 // ---------------------------------------------------------------------------
-// fused elementwise chain: y = chain(x, operands...), 8 elements per thread
-// per iteration (one 16-byte load for bf16, two for f32).
+// fused elementwise chain: y = chain(x, operands...), one 8-element vector per
+// thread (one 16-byte access per bf16 tensor, two per f32 tensor), one pass, no
+// grid-stride loop: many short-lived workgroups with streaming accesses get
+// closest to the HBM rate on this part (four vectors per thread measured slower).
+// When a per-channel operand is constant over runs of >= 8 elements (e.g. NCHW
+// planes), a vector's channel comes from a multiply-high division by the run length.
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void eltwise_kernel(const EltwiseParams p)
 {
     const Epilogue &e = p.epi;
-    const int64_t nvec = p.n >> 3;
-    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    for (int64_t vi = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; vi < nvec; vi += stride) {
+    const int64_t vi = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const bool nt = p.nt != 0;
+    if (vi < (p.n >> 3)) {
         const int64_t i0 = vi << 3;
+        int ch_hint = -1;
+        if (p.runs > 0) {
+            const uint32_t run = p.vec_per_run == 1 ? (uint32_t)vi : (__umulhi((uint32_t)vi, p.run_mul) >> p.run_sh);
+            ch_hint = (int)(run % (uint32_t)p.ch_count);
+        }
         float v[8];
-        load8(p.x, p.x_dtype, i0, v);
-        chain8(e, v, i0, i0, p.ch_inner, p.ch_count);
-        store8(p.y, p.y_dtype, i0, v);
+        if (e.simple && e.t_op >= 0 && (p.runs > 0) == (e.has_bias != 0)) {
+            // the common form [per-run bias] one full-shape operand, operand-free steps: both tensors are
+            // requested before anything is computed
+            float tt[8];
+            if (nt) { load8_nt(p.x, p.x_dtype, i0, v); load8_nt(e.t_ptr, e.t_dtype, i0, tt); }
+            else { load8(p.x, p.x_dtype, i0, v); load8(e.t_ptr, e.t_dtype, i0, tt); }
+            const float b = e.has_bias ? load_as_f32(e.bias_ptr, e.bias_dtype, ch_hint) : 0.0f;
+#pragma unroll
+            for (int k = 0; k < 8; ++k) v[k] = binop(e.t_op, v[k] + b, tt[k]);
+            uint64_t codes = e.rest_ops;
+            for (int st = 0; st < e.rest_n; ++st, codes >>= 8) {
+                const int op = (int)(codes & 0xff);
+                if (op == E_RELU) {
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) v[k] = v[k] > 0.0f ? v[k] : 0.0f;
+                } else {
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) v[k] = unary_step(op, v[k]);
+                }
+            }
+        } else {
+            if (nt) load8_nt(p.x, p.x_dtype, i0, v);
+            else load8(p.x, p.x_dtype, i0, v);
+            chain8(e, v, i0, i0, p.ch_inner, p.ch_count, ch_hint, nt);
+        }
+        if (nt) store8_nt(p.y, p.y_dtype, i0, v);
+        else store8(p.y, p.y_dtype, i0, v);
     }
-    // ragged tail (< 8 elements), one thread each
-    const int64_t tail0 = nvec << 3;
-    const int64_t ti = tail0 + (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (ti < p.n) {
-        float v = load_as_f32(p.x, p.x_dtype, ti);
-        int ch = (int)((ti / p.ch_inner) % p.ch_count);
-        for (int s = 0; s < e.n_ops; ++s) v = epi_step(e, s, v, ti, ch);
-        store_from_f32(p.y, p.y_dtype, ti, v);
+    // ragged tail (< 8 elements), one thread each, first workgroup
+    if (blockIdx.x == 0) {
+        const int64_t ti = ((p.n >> 3) << 3) + threadIdx.x;
+        if (threadIdx.x < 8 && ti < p.n) {
+            float v = load_as_f32(p.x, p.x_dtype, ti);
+            int ch = (int)((ti / p.ch_inner) % p.ch_count);
+            for (int s = 0; s < e.n_ops; ++s) v = epi_step(e, s, v, ti, ch);
+            store_from_f32(p.y, p.y_dtype, ti, v);
+        }
     }
 }
 
-hipError_t launch_eltwise(const EltwiseParams &p, hipStream_t s)
+hipError_t launch_eltwise(const EltwiseParams &p0, hipStream_t s)
 {
-    int64_t nvec = p.n >> 3;
-    int64_t blocks = (nvec + 255) / 256;
-    const int64_t cap = 256 * 16;               // 16 workgroups per CU, grid-stride beyond that
-    if (blocks > cap) blocks = cap;
-    if (blocks < 1) blocks = 1;
+    EltwiseParams p = p0;
+    const int64_t nvec = p.n >> 3;
+    // per-channel runs: 8 | ch_inner, so a vector never straddles a channel and the tensor has no ragged tail
+    p.runs = 0; p.vec_per_run = 0; p.run_mul = 0; p.run_sh = 0;
+    if (p.ch_count > 1 && p.ch_inner >= 8 && (p.ch_inner & 7) == 0 && p.n % p.ch_inner == 0 && nvec < ((int64_t)1 << 31) &&
+        (p.ch_inner >> 3) < ((int64_t)1 << 31)) {
+        p.vec_per_run = p.ch_inner >> 3;
+        p.runs = 1;
+        make_fast_div((uint32_t)p.vec_per_run, p.run_mul, p.run_sh);
+    }
+    const int64_t blocks = std::max<int64_t>(1, (nvec + 255) / 256);
+    if (blocks > 0x7fffffff) return hipErrorInvalidValue;
+    p.nt = p.n >= ((int64_t)32 << 20);           // tens of MB per tensor: beyond what the caches would keep for a consumer
     hipLaunchKernelGGL(eltwise_kernel, dim3((unsigned)blocks), dim3(256), 0, s, p);
     return hipGetLastError();
 }
@@ -47,37 +91,43 @@ hipError_t launch_eltwise(const EltwiseParams &p, hipStream_t s)
 // ---------------------------------------------------------------------------
 // stand-alone LSTM gate group: z[B, 4H] in (i | f | g | o) blocks
 // ---------------------------------------------------------------------------
+template <typename V> __device__ __forceinline__ V ld_maybe_nt(const V *p, bool nt) { return nt ? __builtin_nontemporal_load(p) : *p; }
+template <typename V> __device__ __forceinline__ void st_maybe_nt(V *p, V v, bool nt) { if (nt) __builtin_nontemporal_store(v, p); else *p = v; }
+
+// one thread per four hidden units (16-byte accesses), one pass
 __global__ __launch_bounds__(256) void lstm_gates_kernel(const GatesParams p)
 {
     const int64_t total = (int64_t)p.B * p.H;
-    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    const bool nt = p.nt != 0;
     if ((p.H & 3) == 0) {
-        for (int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; q < (total >> 2); q += stride) {
+        const int64_t q = (int64_t)blockIdx.x * 256 + threadIdx.x;
+        if (q < (total >> 2)) {
             int64_t idx = q << 2;
             int b = (int)(idx / p.H), u = (int)(idx - (int64_t)b * p.H);
             const float *zr = p.z + (int64_t)b * 4 * p.H + u;
-            f32x4 zi = *(const f32x4 *)zr, zf = *(const f32x4 *)(zr + p.H);
-            f32x4 zg = *(const f32x4 *)(zr + 2 * p.H), zo = *(const f32x4 *)(zr + 3 * p.H);
-            f32x4 c = *(const f32x4 *)(p.c_in + idx), cn;
+            f32x4 zi = ld_maybe_nt((const f32x4 *)zr, nt), zf = ld_maybe_nt((const f32x4 *)(zr + p.H), nt);
+            f32x4 zg = ld_maybe_nt((const f32x4 *)(zr + 2 * p.H), nt), zo = ld_maybe_nt((const f32x4 *)(zr + 3 * p.H), nt);
+            f32x4 c = ld_maybe_nt((const f32x4 *)(p.c_in + idx), nt), cn;
             float hn[4];
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
                 cn[k] = sigmoidf_(zf[k]) * c[k] + sigmoidf_(zi[k]) * tanhf_(zg[k]);
                 hn[k] = sigmoidf_(zo[k]) * tanhf_(cn[k]);
             }
-            *(f32x4 *)(p.c_out + idx) = cn;
+            st_maybe_nt((f32x4 *)(p.c_out + idx), cn, nt);
             if (p.h_dtype == DT_BF16) {
                 u32x2 r;
                 r[0] = f32_to_bf16_bits(hn[0]) | (f32_to_bf16_bits(hn[1]) << 16);
                 r[1] = f32_to_bf16_bits(hn[2]) | (f32_to_bf16_bits(hn[3]) << 16);
-                *(u32x2 *)((uint16_t *)p.h_out + idx) = r;
+                st_maybe_nt((u32x2 *)((uint16_t *)p.h_out + idx), r, nt);
             } else {
                 f32x4 hv = {hn[0], hn[1], hn[2], hn[3]};
-                *(f32x4 *)((float *)p.h_out + idx) = hv;
+                st_maybe_nt((f32x4 *)((float *)p.h_out + idx), hv, nt);
             }
         }
     } else {
-        for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += stride) {
+        const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+        if (idx < total) {
             int b = (int)(idx / p.H), u = (int)(idx - (int64_t)b * p.H);
             const float *zr = p.z + (int64_t)b * 4 * p.H + u;
             float cn = sigmoidf_(zr[p.H]) * p.c_in[idx] + sigmoidf_(zr[0]) * tanhf_(zr[2 * p.H]);
@@ -87,12 +137,14 @@ __global__ __launch_bounds__(256) void lstm_gates_kernel(const GatesParams p)
     }
 }
 
-hipError_t launch_lstm_gates(const GatesParams &p, hipStream_t s)
+hipError_t launch_lstm_gates(const GatesParams &p0, hipStream_t s)
 {
-    int64_t work = ((int64_t)p.B * p.H + 3) / 4;
-    int64_t blocks = (work + 255) / 256;
-    if (blocks > 4096) blocks = 4096;
-    if (blocks < 1) blocks = 1;
+    GatesParams p = p0;
+    const int64_t total = (int64_t)p.B * p.H;
+    const int64_t work = (p.H & 3) == 0 ? (total + 3) / 4 : total;
+    const int64_t blocks = std::max<int64_t>(1, (work + 255) / 256);
+    if (blocks > 0x7fffffff) return hipErrorInvalidValue;
+    p.nt = total >= ((int64_t)8 << 20);
     hipLaunchKernelGGL(lstm_gates_kernel, dim3((unsigned)blocks), dim3(256), 0, s, p);
     return hipGetLastError();
 }

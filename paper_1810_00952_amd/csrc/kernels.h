@@ -105,11 +105,15 @@ struct EltwiseParams {
     int64_t n;                          // elements
     int64_t ch_inner; int32_t ch_count; // channel of flat index i = (i / ch_inner) % ch_count (for E_BIAS)
     Epilogue epi;
+    // filled by launch_eltwise.  runs > 0: a per-channel operand is constant over runs of vec_per_run
+    // 8-element vectors; the run of vector v is v / vec_per_run by multiply-high (make_fast_div)
+    int64_t vec_per_run; int32_t runs; uint32_t run_mul, run_sh; int32_t nt;   // nt: streaming accesses
 };
 hipError_t launch_eltwise(const EltwiseParams &p, hipStream_t s);
 
 struct GatesParams {
     const float *z; const float *c_in; float *c_out; void *h_out; int32_t h_dtype; int32_t B, H;
+    int32_t nt;                         // streaming accesses (filled by launch_lstm_gates)
 };
 hipError_t launch_lstm_gates(const GatesParams &p, hipStream_t s);
 
