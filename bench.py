@@ -16,6 +16,9 @@ configurations and the HBM-bound groups:
   mlp       MLP 784 -> 128 -> 10, f32, batch 32
   conv      single fused conv2d group 64 -> 64, 56x56, f32, batch 1
   resnet18_f32_b1  the ResNet-18-shaped graph in f32 at batch 1
+  copy      y = -x on 24 Mi f32 elements: a plain copy kernel of known size
+            (100.7 MB read, 100.7 MB written, ordinary loads and stores), the
+            yardstick for the HBM byte counters
 """
 from __future__ import annotations
 
@@ -89,6 +92,29 @@ def kernel_table(session, reps):
     return desc, by_kernel
 
 
+def measured_traffic(kernel_name, profile_file):
+    """HBM bytes per step of one kernel from the committed rocprofv3 counter summary, or None when the
+    summary is missing, lacks the kernel, or was taken on other kernel sources than the ones in the tree."""
+    import glob
+    import hashlib
+    path = os.path.join(ROOT, "profiles", profile_file)
+    if not os.path.exists(path):
+        return None
+    h = hashlib.sha256()
+    for f in sorted(glob.glob(os.path.join(ROOT, "paper_1810_00952_amd", "csrc", "*"))):
+        with open(f, "rb") as fh:
+            h.update(fh.read())
+    sha, found = h.hexdigest()[:16], None
+    sha_ok = False
+    for line in open(path):
+        if line.startswith("# source_sha"):
+            sha_ok = line.split()[2] == sha
+        elif not line.startswith("#") and line.split() and line.split()[0] == kernel_name:
+            _, _, fb, wb = line.split()
+            found = float(fb) + float(wb)
+    return found if sha_ok else None
+
+
 def roofline_of(name, k, peak_tflops):
     """Roofline entry of one kernel (all its launches in a step): MFMA-bound when its algorithmic
     intensity is above the ridge of the peaks used, else HBM-bound."""
@@ -136,6 +162,8 @@ def bench_resnet(args, batch, dtype):
                     {"global_batch": batch})
     out["tflops_whole_graph"] = total_flops / (ms * 1e-3) / 1e12
     out["roofline"] = roofline_of(dom_name, dom, peak)
+    if dtype == "bf16" and batch == 64:
+        out["roofline"]["traffic"] = measured_traffic(dom_name, "resnet18_b64_bf16_hbm_traffic.txt")
     out["kernels"] = kernels_json(by_kernel)
     if not args.no_cpu and dtype == "bf16" and batch == 64:
         out["cpu_baseline"] = cpu_baseline_resnet(args.cpu_images)
@@ -212,7 +240,7 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="resnet18",
-                    choices=["resnet18", "resnet18_f32_b1", "eltwise", "eltwise32", "gates", "lstm", "mlp", "conv"])
+                    choices=["resnet18", "resnet18_f32_b1", "eltwise", "eltwise32", "gates", "lstm", "mlp", "conv", "copy"])
     ap.add_argument("--batch", type=int, default=64)
     ap.add_argument("--cpu-images", type=int, default=128)
     ap.add_argument("--no-cpu", action="store_true")
@@ -248,6 +276,15 @@ def main():
         data = {"z": W.as_dtype(W.normal(rng, (B, 4 * H)), "f32"), "c": W.as_dtype(W.normal(rng, (B, H)), "f32")}
         out = bench_graph(args, g, data, "hidden units/sec LSTM gate group", "units/s", B * H, "f32",
                           f"lstm_gates on z {B}x{4 * H} f32, c {B}x{H} f32 -> c' f32, h' bf16", PEAK_F32_TFLOPS)
+    elif wl == "copy":
+        n = 24 << 20
+        g = W.GraphSpec("copy")
+        x = g.input("x", "f32", (n,))
+        o, (y,) = g.op("neg", [x], [("f32", (n,))])
+        g.group([o]); g.output(y)
+        data = {"x": W.as_dtype(W.normal(W.rng_for(6, salt=3), (n,)), "f32")}
+        out = bench_graph(args, g, data, "elements/sec y = -x f32", "elements/s", n, "f32",
+                          f"y = -x on {n} f32 elements (reads {4 * n} bytes, writes {4 * n} bytes)", PEAK_F32_TFLOPS)
     elif wl == "lstm":
         out = bench_lstm(args)
     elif wl == "mlp":
