@@ -416,7 +416,7 @@ __global__ __launch_bounds__(256) void igemm_lp_kernel(const IgemmParams p)
 }
 
 #define RL_INST(BM, BN, WGM, WGN, ST) template __global__ void igemm_lp_kernel<BM, BN, WGM, WGN, ST>(const IgemmParams);
-RL_INST(128, 128, 2, 2, 4) RL_INST(128, 64, 4, 1, 3) RL_INST(64, 64, 2, 2, 4)
+RL_INST(128, 128, 2, 2, 4) RL_INST(128, 64, 4, 1, 3) RL_INST(128, 64, 4, 1, 4) RL_INST(64, 64, 2, 2, 4)
 #undef RL_INST
 
 template <int BM, int BN, int WGM, int WGN, int STAGES>
@@ -436,7 +436,11 @@ hipError_t launch_igemm_lp(const IgemmParams &p, const IgemmLaunch &l, hipStream
     if (p.in_dtype != DT_BF16 || p.y_dtype != DT_BF16 || l.gates || p.x2) return hipErrorInvalidValue;
     switch (l.tile) {
     case TILE_128x128: return launch_lp<128, 128, 2, 2, 4>(p, s);
-    case TILE_128x64: return launch_lp<128, 64, 4, 1, 3>(p, s);
+    case TILE_128x64:
+        // few workgroups (at most one per CU anyway): four stages, so fragments are prefetched across the barrier;
+        // many: three stages, so two workgroups share a CU and cover each other's barriers and epilogues
+        if ((int64_t)((p.M + 127) / 128) * ((p.N + 63) / 64) <= 320) return launch_lp<128, 64, 4, 1, 4>(p, s);
+        return launch_lp<128, 64, 4, 1, 3>(p, s);
     default: return launch_lp<64, 64, 2, 2, 4>(p, s);
     }
 }
