@@ -82,6 +82,14 @@ def lib():
         if not os.path.exists(LIB_PATH):
             raise ImportError(f"{LIB_PATH} is not built: run `python -c 'import __graft_entry__ as g; g.build()'` "
                               "(or paper_1810_00952_amd/build.py)")
+        # One HIP runtime per process.  PyTorch (which the callers use for device memory) ships its own copy of
+        # libamdhip64 under the same SONAME and opens it by path; if this library pulled in the system copy first,
+        # the process would hold two runtimes and the second one to initialise finds no device.  With torch loaded
+        # first the dynamic linker resolves this library's dependency to the copy that is already there.
+        try:
+            import torch  # noqa: F401
+        except ImportError:
+            pass
         L = ctypes.CDLL(LIB_PATH)
         L.rl_ctx_create.argtypes = [POINTER(c_void_p)]
         L.rl_ctx_destroy.argtypes = [c_void_p]; L.rl_ctx_destroy.restype = None

@@ -366,3 +366,24 @@ def test_lstm_full_configuration():
                                     np.zeros((B, H)), np.zeros((B, H)), h_dtype="bf16")
     assert_close(hs, hs_ref, "bf16", "lstm full h")
     assert_close(c, c_ref, "bf16", "lstm full c")
+
+
+def test_library_loaded_before_torch_shares_one_hip_runtime():
+    # Planning needs no GPU, so a caller may well load the library (and build plans) before anything imports
+    # torch.  Both must then end up on one HIP runtime: with two copies in a process the second to
+    # initialise finds no device.  Fresh interpreter, library first, then a small group run through torch.
+    import os, subprocess, sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    code = (
+        "import sys; sys.path.insert(0, %r); sys.path.insert(0, %r)\n"
+        "from paper_1810_00952_amd import binding\n"
+        "binding.lib()\n"
+        "import workloads as W\n"
+        "spec, data = W.conv_group(2, 64, 64, 14, 14, 3, 1, 1, 'bf16', residual=True, relu=True, tail=True)\n"
+        "plan = binding.Plan(binding.graph_from_spec(binding.Context(), spec))\n"
+        "from helpers import run_hip\n"
+        "out = run_hip(spec, data)\n"
+        "print('ok', len(out))\n"
+    ) % (root, os.path.join(root, "tests"))
+    r = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, timeout=300)
+    assert r.returncode == 0 and "ok" in r.stdout, r.stdout + r.stderr
