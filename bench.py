@@ -200,7 +200,7 @@ def bench_lstm(args):
     h0 = torch.zeros((B, H), dtype=torch.bfloat16, device="cuda:0")
     c = torch.zeros((B, H), dtype=torch.float32, device="cuda:0")
     hs = torch.empty((T, B, H), dtype=torch.bfloat16, device="cuda:0")
-    ws = torch.empty(max(256, s.plan.workspace_bytes()), dtype=torch.uint8, device="cuda:0")
+    ws = torch.empty(max(256, s.plan.recurrent_workspace_bytes(T)), dtype=torch.uint8, device="cuda:0")
     n = s.by_name
     roles = {"x": n["x"], "h_in": n["h"], "c_in": n["c"], "c_out": spec.outputs[0], "h_out": spec.outputs[1]}
     params = {n["w"]: s.tensors[n["w"]].data_ptr(), n["b"]: s.tensors[n["b"]].data_ptr()}

@@ -191,6 +191,15 @@ typedef struct rl_recurrent {
     void *c_dev;
     void *h_seq_dev; size_t h_step_bytes;
 } rl_recurrent;
+/* Workspace that lets rl_plan_run_recurrent run `steps` steps of this cell at its best.  For a cell that is
+ * one fused [x, h] contraction + LSTM-gate group in bf16 this is rl_plan_workspace_bytes rounded up to 256 plus
+ * steps * batch * 4*hidden * 4 bytes: the input projection x_t . Wx^T of all steps is then computed by one
+ * contraction up front and each step only runs the recurrent part (h_{t-1} . Wh^T and the gates).  With less
+ * (but room for at least 8 steps' projections) the steps are processed in chunks; with only
+ * rl_plan_workspace_bytes the cell plan is replayed once per step.  For every other cell the value equals
+ * rl_plan_workspace_bytes.  Results of the forms agree to summation order.  Host call; errors: RL_ERR_NULL,
+ * RL_ERR_BINDING (negative steps). */
+rl_status rl_plan_recurrent_workspace_bytes(const rl_plan *cell, int32_t steps, size_t *bytes);
 rl_status rl_plan_run_recurrent(const rl_plan *cell, int32_t steps, const rl_recurrent *io,
                                 const rl_binding *param_bindings, int32_t n_bindings,
                                 void *workspace_dev, size_t workspace_bytes, void *hip_stream);

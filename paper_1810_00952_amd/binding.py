@@ -72,7 +72,7 @@ _lib = None
 SYMBOLS = ["rl_ctx_create", "rl_ctx_destroy", "rl_last_error", "rl_graph_create", "rl_graph_destroy", "rl_graph_input",
            "rl_graph_param", "rl_graph_op", "rl_graph_group", "rl_graph_output", "rl_plan_create", "rl_plan_destroy",
            "rl_plan_describe", "rl_plan_workspace_bytes", "rl_plan_packed_bytes", "rl_plan_prepack", "rl_plan_run",
-           "rl_plan_run_recurrent", "rl_prep_fold_batchnorm", "rl_plan_profile"]
+           "rl_plan_run_recurrent", "rl_plan_recurrent_workspace_bytes", "rl_prep_fold_batchnorm", "rl_plan_profile"]
 
 
 def lib():
@@ -106,6 +106,7 @@ def lib():
         L.rl_plan_destroy.argtypes = [c_void_p]; L.rl_plan_destroy.restype = None
         L.rl_plan_describe.argtypes = [c_void_p, c_char_p, c_size_t, POINTER(c_size_t)]
         L.rl_plan_workspace_bytes.argtypes = [c_void_p, POINTER(c_size_t)]
+        L.rl_plan_recurrent_workspace_bytes.argtypes = [c_void_p, c_int32, POINTER(c_size_t)]
         L.rl_plan_packed_bytes.argtypes = [c_void_p, c_int32, POINTER(c_size_t)]
         L.rl_plan_prepack.argtypes = [c_void_p, c_int32, c_void_p, c_void_p, c_void_p]
         L.rl_plan_run.argtypes = [c_void_p, POINTER(rl_binding), c_int32, c_void_p, c_size_t, c_void_p]
@@ -260,6 +261,11 @@ class Plan:
         buf = ctypes.create_string_buffer(need.value)
         self.ctx.check(lib().rl_plan_describe(self._h, buf, need.value, byref(need)))
         return json.loads(buf.value.decode())
+
+    def recurrent_workspace_bytes(self, steps: int) -> int:
+        n = c_size_t(0)
+        self.ctx.check(lib().rl_plan_recurrent_workspace_bytes(self._h, steps, byref(n)))
+        return n.value
 
     def workspace_bytes(self) -> int:
         n = c_size_t()

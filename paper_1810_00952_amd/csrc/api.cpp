@@ -1,4 +1,6 @@
 // C ABI of the library (see include/relayhip.h for the contract).
+#include <algorithm>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 
@@ -52,6 +54,25 @@ rl_status add_value(rl_graph *g, const rl_type *t, int role, int32_t *value_id)
 }
 
 // resolve the pointer of every buffer a plan touches
+// A cell plan that is exactly one fused [x, h] contraction + gate step in bf16 can run with the input projection
+// x_t . Wx^T of many steps hoisted into one large contraction (the recurrence only needs h_{t-1} . Wh^T per step).
+// Returns that step, or null if the plan is anything else.
+const Step *hoistable_cell(const Plan &p)
+{
+    if (p.steps.size() != 1 || getenv("RELAYHIP_NO_HOIST")) return nullptr;
+    const Step &s = p.steps[0];
+    const IgemmParams &g = s.ig;
+    if (s.kind != S_IGEMM || !s.il.gates || !s.il.avec || !s.il.dma || s.slot[SL_X2] < 0 || g.in_dtype != DT_BF16 || g.h_dtype != DT_BF16) return nullptr;
+    const int64_t I = g.K1, H = g.hidden;
+    if (I < 128 || I % 64 != 0 || H < 64 || H % 64 != 0 || g.K != I + H || g.Kp != g.K || g.N != 4 * H || g.x2s_n != H || g.xs_n != I) return nullptr;
+    if (g.epi.n_ops > 1 || (g.epi.n_ops == 1 && (epi_host_op(g.epi, 0) != E_BIAS || epi_host_dtype(g.epi, epi_host_arg(g.epi, 0)) != DT_F32)))
+        return nullptr;
+    if ((uint64_t)g.N * g.Kp * 2 >= 0x7fffffffull || (uint64_t)g.M * H * 16 >= 0x7fffffffull) return nullptr;
+    return &s;
+}
+size_t hoist_bytes_per_step(const Step &s) { return (size_t)s.ig.M * s.ig.N * sizeof(float); }
+size_t round256(size_t n) { return (n + 255) & ~(size_t)255; }
+
 rl_status resolve(const Plan &p, const rl_binding *b, int32_t nb, void *ws, size_t ws_bytes, std::vector<void *> &ptrs, std::string &msg)
 {
     const int nv = (int)p.values.size();
@@ -254,6 +275,15 @@ rl_status rl_plan_workspace_bytes(const rl_plan *plan, size_t *bytes)
     return RL_OK;
 }
 
+rl_status rl_plan_recurrent_workspace_bytes(const rl_plan *cell, int32_t steps, size_t *bytes)
+{
+    if (!cell || !bytes) return RL_ERR_NULL;
+    if (steps < 0) return fail(cell->p.err, RL_ERR_BINDING, "negative step count");
+    const Step *hs = hoistable_cell(cell->p);
+    *bytes = hs ? round256(cell->p.workspace_bytes) + (size_t)steps * hoist_bytes_per_step(*hs) : cell->p.workspace_bytes;
+    return RL_OK;
+}
+
 rl_status rl_plan_packed_bytes(const rl_plan *plan, int32_t v, size_t *bytes)
 {
     if (!plan || !bytes) return RL_ERR_NULL;
@@ -365,6 +395,55 @@ rl_status rl_plan_run_recurrent(const rl_plan *cell, int32_t steps, const rl_rec
         if (st != RL_OK) return fail(err, st, msg);
         (void)base;
         const int bx = p.bound_buf[io->x_id], bh = p.bound_buf[io->h_in_id], bo = p.bound_buf[io->h_out_id];
+        // Hoisted form: the input projection of a chunk of steps as one contraction into the workspace behind the
+        // plan's own, then one small recurrent kernel per step.  Taken when the cell has that form, the x_t are
+        // contiguous and the workspace holds at least 8 steps' projections (or all of them).
+        if (const Step *hs = hoistable_cell(p)) {
+            const IgemmParams &g0 = hs->ig;
+            const int64_t B = g0.M, I = g0.K1, H = g0.hidden;
+            const size_t base = round256(p.workspace_bytes), per = hoist_bytes_per_step(*hs);
+            int64_t chunk = (ws && ws_bytes > base) ? (int64_t)((ws_bytes - base) / per) : 0;
+            chunk = std::min<int64_t>(chunk, steps);
+            chunk = std::min<int64_t>(chunk, (int64_t)(0x7fffffffull / (uint64_t)(B * std::max<int64_t>(I * 2, 4 * H * 4))));   // operands below 2 GiB
+            const bool roles_ok = bx == hs->slot[SL_X] && bh == hs->slot[SL_X2] && bo == hs->slot[SL_HOUT] &&
+                                  hs->slot[SL_CIN] >= 0 && hs->slot[SL_COUT] >= 0;
+            if (roles_ok && steps > 0 && chunk >= std::min<int64_t>(steps, 8) && io->x_step_bytes == (size_t)(B * I * 2) &&
+                (((uintptr_t)ws + base) & 255) == 0) {
+                float *zx = (float *)((char *)ws + base);
+                const void *bias = g0.epi.n_ops == 1 ? ptrs[hs->slot[SL_E0 + epi_host_arg(g0.epi, 0)]] : nullptr;
+                const int bias_dt = g0.epi.n_ops == 1 ? epi_host_dtype(g0.epi, epi_host_arg(g0.epi, 0)) : DT_F32;
+                for (int64_t t0 = 0; t0 < steps; t0 += chunk) {
+                    const int64_t tc = std::min<int64_t>(chunk, steps - t0);
+                    IgemmParams g = g0;
+                    g.x = (const char *)io->x_seq_dev + (size_t)t0 * io->x_step_bytes; g.x2 = nullptr; g.x2_bytes = 0;
+                    g.w = ptrs[hs->slot[SL_W]]; g.y = zx; g.y_dtype = DT_F32;
+                    g.M = (int32_t)(tc * B); g.K = (int32_t)I; g.K1 = (int32_t)I; g.C = (int32_t)I;      // weight rows keep their stride Kp
+                    g.x_bytes = (uint32_t)(tc * B * I * 2); g.y_bytes = (uint32_t)std::min<uint64_t>((uint64_t)tc * per, 0x7fffffffull);
+                    g.ys_n = g.N; g.ys_p = g.N; g.ys_c = 1;
+                    g.epi = Epilogue{}; finalize_epilogue(g.epi);
+                    g.hidden = 0; g.c_in = nullptr; g.c_out = nullptr; g.h_out = nullptr;
+                    IgemmLaunch l{};
+                    l.avec = 1; l.dma = 1;
+                    const int64_t b128 = ((g.M + 127) / 128) * (int64_t)((g.N + 127) / 128), b64 = ((g.M + 127) / 128) * (int64_t)((g.N + 63) / 64);
+                    l.tile = b128 >= 192 ? TILE_128x128 : b64 >= 192 ? TILE_128x64 : TILE_64x64;
+                    hipError_t er = launch_igemm(g, l, (hipStream_t)stream);
+                    if (er != hipSuccess) return fail(err, RL_ERR_HIP, std::string("launch of the hoisted input projection failed: ") + hipGetErrorString(er));
+                    for (int64_t t = t0; t < t0 + tc; ++t) {
+                        LstmStepParams q{};
+                        q.h_prev = t == 0 ? io->h0_dev : (const void *)((const char *)io->h_seq_dev + (size_t)(t - 1) * io->h_step_bytes);
+                        q.w = g.w; q.zx = zx + (size_t)(t - t0) * B * g.N;
+                        q.bias = bias; q.bias_dtype = bias_dt;
+                        q.c_in = (const float *)ptrs[hs->slot[SL_CIN]]; q.c_out = (float *)ptrs[hs->slot[SL_COUT]];
+                        q.h_out = (char *)io->h_seq_dev + (size_t)t * io->h_step_bytes; q.h_dtype = g0.h_dtype;
+                        q.B = (int32_t)B; q.H = (int32_t)H; q.Kp = g0.Kp; q.k_off = (int32_t)I;
+                        q.h_bytes = (uint32_t)(B * H * 2); q.w_bytes = (uint32_t)((uint64_t)g0.N * g0.Kp * 2);
+                        er = launch_lstm_step(q, (hipStream_t)stream);
+                        if (er != hipSuccess) return fail(err, RL_ERR_HIP, std::string("launch of lstm_step failed: ") + hipGetErrorString(er));
+                    }
+                }
+                return RL_OK;
+            }
+        }
         for (int32_t t = 0; t < steps; ++t) {
             ptrs[bx] = (char *)io->x_seq_dev + (size_t)t * io->x_step_bytes;
             ptrs[bh] = t == 0 ? (void *)io->h0_dev : (void *)((char *)io->h_seq_dev + (size_t)(t - 1) * io->h_step_bytes);

@@ -98,6 +98,19 @@ struct IgemmLaunch {
 };
 hipError_t launch_igemm(const IgemmParams &p, const IgemmLaunch &l, hipStream_t s);
 
+// ---- one LSTM step on a precomputed input projection (lstm_step.hip) ------
+struct LstmStepParams {
+    const void *h_prev;                 // [B, H] bf16
+    const void *w;                      // packed cell weights [4H][Kp] bf16, gate-interleaved per 64 rows
+    const float *zx;                    // [B, 4H] f32: x_t . Wx^T in the packed column order
+    const void *bias; int32_t bias_dtype;   // [4H] f32 in declaration order (i, f, g, o blocks), or null
+    const float *c_in; float *c_out;    // [B, H] f32 (may alias)
+    void *h_out; int32_t h_dtype;       // [B, H]
+    int32_t B, H, Kp, k_off;            // k_off: first recurrent column of a weight row
+    uint32_t h_bytes, w_bytes;
+};
+hipError_t launch_lstm_step(const LstmStepParams &p, hipStream_t s);
+
 // ---- purely elementwise fused group ---------------------------------------
 struct EltwiseParams {
     const void *x; int32_t x_dtype;     // first operand: initial running value

@@ -312,7 +312,8 @@ def test_resnet18_bf16_batch64_sampled_images():
 
 
 # ------------------------------------------------------------------ LSTM
-def _lstm_hip(T, B, I, H, dtype, fused, d):
+def _lstm_hip(T, B, I, H, dtype, fused, d, hoist_steps=0):
+    # hoist_steps: room in the workspace for that many steps' input projections (0: only the cell plan's own)
     import torch
     from paper_1810_00952_amd import harness
     spec = W.lstm_cell_graph(B, I, H, dtype, fused)
@@ -323,7 +324,12 @@ def _lstm_hip(T, B, I, H, dtype, fused, d):
     h0 = torch.zeros((B, H), dtype=tdt, device="cuda:0")
     c = torch.zeros((B, H), dtype=torch.float32, device="cuda:0")
     hs = torch.empty((T, B, H), dtype=tdt, device="cuda:0")
-    ws = torch.empty(max(256, s.plan.workspace_bytes()), dtype=torch.uint8, device="cuda:0")
+    nws = s.plan.workspace_bytes()
+    if hoist_steps:
+        assert s.plan.recurrent_workspace_bytes(0) == (nws + 255) // 256 * 256
+        nws = s.plan.recurrent_workspace_bytes(hoist_steps)
+        assert nws == s.plan.recurrent_workspace_bytes(0) + hoist_steps * B * 4 * H * 4, "cell not recognised as hoistable"
+    ws = torch.empty(max(256, nws), dtype=torch.uint8, device="cuda:0")
     n = s.by_name
     roles = {"x": n["x"], "h_in": n["h"], "c_in": n["c"], "c_out": spec.outputs[0], "h_out": spec.outputs[1]}
     esz = 2 if dtype == "bf16" else 4
@@ -345,6 +351,23 @@ def test_lstm_recurrent(fused, dtype, T, B, I, H):
     assert_close(c, c_ref, dtype if dtype == "bf16" else "f32", f"lstm c {dtype} fused={fused}")
 
 
+# Hoisted form (input projection of many steps in one contraction, then one recurrent kernel per step):
+# batch tails inside and across 64-row blocks, hidden sizes that give the four waves 1, 2 or no K tiles each,
+# the whole sequence in one chunk and chunks of 8 and 9 steps with a ragged last chunk.
+@pytest.mark.parametrize("T,B,I,H,room", [(3, 64, 256, 128, 3), (5, 70, 128, 192, 5), (20, 8, 128, 64, 8), (19, 33, 192, 320, 9),
+                                          (4, 130, 128, 512, 4)])
+def test_lstm_recurrent_hoisted_projection(T, B, I, H, room):
+    d = W.lstm_data(T, B, I, H, "bf16")
+    hs_ref, c_ref = O.lstm_sequence(O.widen(d["x"], "bf16"), O.widen(d["w"], "bf16"), O.widen(d["b"], "f32"),
+                                    np.zeros((B, H)), np.zeros((B, H)), h_dtype="bf16")
+    hs, c = _lstm_hip(T, B, I, H, "bf16", True, d, hoist_steps=room)
+    assert_close(hs, hs_ref, "bf16", f"lstm hoisted h T={T} B={B} I={I} H={H}")
+    assert_close(c, c_ref, "bf16", f"lstm hoisted c T={T} B={B} I={I} H={H}")
+    # and against the per-step replay of the same cell on the same data: the two forms differ by summation order only
+    hs2, c2 = _lstm_hip(T, B, I, H, "bf16", True, d, hoist_steps=0)
+    assert np.abs(hs - hs2).max() <= 2e-2 and np.abs(c - c2).max() <= 2e-2 * max(1.0, np.abs(c2).max())
+
+
 def test_lstm_unrolled_graph_equals_recurrent_call():
     T, B, I, H = 3, 16, 32, 32
     d = W.lstm_data(T, B, I, H, "bf16")
@@ -361,7 +384,7 @@ def test_lstm_unrolled_graph_equals_recurrent_call():
 def test_lstm_full_configuration():
     T, B, I, H = 128, 64, 1024, 1024
     d = W.lstm_data(T, B, I, H, "bf16")
-    hs, c = _lstm_hip(T, B, I, H, "bf16", True, d)
+    hs, c = _lstm_hip(T, B, I, H, "bf16", True, d, hoist_steps=T)
     hs_ref, c_ref = O.lstm_sequence(O.widen(d["x"], "bf16"), O.widen(d["w"], "bf16"), O.widen(d["b"], "f32"),
                                     np.zeros((B, H)), np.zeros((B, H)), h_dtype="bf16")
     assert_close(hs, hs_ref, "bf16", "lstm full h")
