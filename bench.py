@@ -14,6 +14,7 @@ configurations and the HBM-bound groups:
   gates     stand-alone LSTM gate group on z 16384x4096 f32
   lstm      unrolled LSTM, batch 64, 1024 -> 1024, 128 steps, bf16 weights
   mlp       MLP 784 -> 128 -> 10, f32, batch 32
+  lenet     the LeNet-shaped example graph (conv5x5, tanh, maxpool2, conv5x5, tanh, maxpool2, dense 500, tanh, dense 10), f32, batch 64
   conv      single fused conv2d group 64 -> 64, 56x56, f32, batch 1
   resnet18_f32_b1  the ResNet-18-shaped graph in f32 at batch 1
   copy      y = -x on 24 Mi f32 elements: a plain copy kernel of known size
@@ -61,8 +62,18 @@ def cpu_baseline_graph(spec, data, unit_count: float, unit: str, what: str):
     return {"value": unit_count / dt, "unit": unit, "cores": O.num_threads(), "kind": "oracle", "sample": f"{what}, one oracle run, {dt:.1f} s"}
 
 
+GRAPH = False     # --graph: time replays of a HIP graph holding one step instead of eager launches
+
+
 def time_steps(run, steps, warmup):
     import torch
+    if GRAPH:
+        run()
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            run()
+        run = g.replay
     stream = torch.cuda.current_stream()
     for _ in range(warmup):
         run()
@@ -136,7 +147,7 @@ def kernels_json(by_kernel):
 
 
 def base_json(metric, value, unit, args, ms, dtype, workload, extra_cfg=None):
-    cfg = {"workload": workload}
+    cfg = {"workload": workload, "launch": "hip graph replay" if GRAPH else "eager"}
     cfg.update(extra_cfg or {})
     return {"metric": metric, "value": value, "unit": unit, "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
             "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": dtype, "data": "synthetic", "config": cfg,
@@ -240,13 +251,16 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="resnet18",
-                    choices=["resnet18", "resnet18_f32_b1", "eltwise", "eltwise32", "gates", "lstm", "mlp", "conv", "copy"])
+                    choices=["resnet18", "resnet18_f32_b1", "eltwise", "eltwise32", "gates", "lstm", "mlp", "lenet", "conv", "copy"])
     ap.add_argument("--batch", type=int, default=64)
     ap.add_argument("--cpu-images", type=int, default=128)
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--unfused", action="store_true", help="lstm: gate math as a group of its own")
     ap.add_argument("--profile-reps", type=int, default=20)
+    ap.add_argument("--graph", action="store_true", help="time replays of a HIP graph that holds one step (same kernels, no host launches)")
     args = ap.parse_args()
+    global GRAPH
+    GRAPH = args.graph
     if args.gpus != 1:
         print("bench.py measures one GPU: this path has no multi-GPU part (run with --gpus 1)", file=sys.stderr)
         sys.exit(2)
@@ -292,6 +306,12 @@ def main():
         out = bench_graph(args, spec, data, "samples/sec MLP 784-128-10 f32 b32", "samples/s", 32, "f32",
                           "MLP fusion graph, f32, batch 32: dense 784->128 + bias + ReLU, dense 128->10 + bias", PEAK_F32_TFLOPS,
                           cpu=lambda: cpu_baseline_graph(spec, data, 32, "samples/s", "the same 32-sample batch"))
+    elif wl == "lenet":
+        spec, data = W.lenet(64, "f32")
+        out = bench_graph(args, spec, data, "images/sec LeNet-shaped graph f32 b64", "images/s", 64, "f32",
+                          "the paper's LeNet-shaped example as a fusion graph, f32, batch 64, 1x28x28 N(0,1) inputs: conv5x5+bias+tanh, "
+                          "maxpool2, conv5x5+bias+tanh, maxpool2, flatten, dense 800->500+bias+tanh, dense 500->10+bias", PEAK_F32_TFLOPS,
+                          cpu=lambda: cpu_baseline_graph(spec, data, 64, "images/s", "the same 64-image batch"))
     else:
         spec, data = W.conv_group(1, 64, 64, 56, 56, 3, 1, 1, "f32")
         out = bench_graph(args, spec, data, "images/sec single conv2d group 64->64 56x56 f32 b1", "images/s", 1, "f32",

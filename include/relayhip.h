@@ -164,7 +164,10 @@ rl_status rl_plan_prepack(const rl_plan *plan, int32_t param_value_id, const voi
  * (packed copy where rl_plan_packed_bytes > 0) and output value id exactly
  * once; intermediates live in workspace_dev (>= rl_plan_workspace_bytes).
  * Inputs and params are read only; outputs and workspace are overwritten.
- * An output may alias an input only for lstm_gates' cell state (c' over c). */
+ * An output may alias an input only for lstm_gates' cell state (c' over c).
+ * The call only launches kernels on hip_stream (no allocation, no memset, no
+ * synchronisation), so it may be made while that stream is being captured into
+ * a HIP graph; replays then need the same device pointers to stay valid. */
 rl_status rl_plan_run(const rl_plan *plan, const rl_binding *bindings, int32_t n_bindings,
                       void *workspace_dev, size_t workspace_bytes, void *hip_stream);
 

@@ -82,5 +82,17 @@ class Session:
         self.plan.run({vid: t.data_ptr() for vid, t in self.tensors.items()}, self.workspace.data_ptr(),
                       self.workspace.numel(), stream_handle())
 
+    def capture(self) -> "torch.cuda.CUDAGraph":
+        """Record one run of the plan into a HIP graph (rl_plan_run only launches kernels: no allocation, no
+        synchronisation, no memset), for callers that replay a fixed plan many times."""
+        if self.workspace is None:
+            self.alloc()
+        self.run()                                   # first run outside the capture: lazy module loads happen here
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            self.run()
+        return g
+
     def output(self, i: int = 0) -> torch.Tensor:
         return self.tensors[self.spec.outputs[i]]

@@ -290,6 +290,46 @@ def test_resnet_small_end_to_end_and_per_group(dtype):
             assert_close(out[vid], allv[inv[vid]], sub.values[vid].type.dtype, f"resnet small {dtype} group {gi} ({spec.ops[spec.groups[gi][0]].kind})")
 
 
+@pytest.mark.parametrize("which", ["resnet_small_f32", "resnet_small_bf16", "conv_bf16", "mlp_f32"])
+def test_plan_replays_from_a_hip_graph(which):
+    # one rl_plan_run captured into a HIP graph, then replayed with fresh inputs, with eager work and
+    # synchronisation between the replays; every replay must reproduce the eager run bit for bit
+    import torch
+    from paper_1810_00952_amd import harness
+    if which.startswith("resnet"):
+        dtype = which.rsplit("_", 1)[1]
+        spec, raw, bn = W.resnet18(batch=2, dtype=dtype, image=64, width=16, classes=24)
+        s = harness.Session(spec)
+        fold_resnet_hip(s, raw, bn, dtype)
+    elif which == "conv_bf16":
+        spec, data = W.conv_group(3, 64, 128, 29, 29, 3, 1, 1, "bf16", residual=True, relu=True, tail=True)
+        s = harness.Session(spec); s.load(data)
+    else:
+        spec, data = W.mlp()
+        s = harness.Session(spec); s.load(data)
+    s.alloc()
+    g = s.capture()
+    xin = [vid for vid, v in enumerate(spec.values) if v.role == "input"]
+    gen = torch.Generator(device="cuda:0"); gen.manual_seed(7)
+    for rep in range(3):
+        for vid in xin:
+            t = s.tensors[vid]
+            t.copy_(torch.randn(t.shape, generator=gen, device="cuda:0", dtype=torch.float32).to(t.dtype))
+        for vid in spec.outputs:
+            s.tensors[vid].zero_()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        got = [s.tensors[vid].clone() for vid in spec.outputs]
+        for vid in spec.outputs:
+            s.tensors[vid].zero_()
+        s.run()
+        torch.cuda.synchronize()
+        for a, vid in zip(got, spec.outputs):
+            assert torch.equal(a.view(torch.uint8), s.tensors[vid].view(torch.uint8)), f"{which}: replay {rep} differs from the eager run"
+        assert all(bool(torch.isfinite(a.float()).all()) for a in got)
+
+
 def test_resnet18_f32_batch1():
     spec, raw, bn = W.resnet18(batch=1, dtype="f32")
     ref = OG.run(spec, fold_resnet_oracle(raw, bn, "f32"))[spec.outputs[0]]
@@ -309,6 +349,18 @@ def test_resnet18_bf16_batch64_sampled_images():
         assert_close(got[n:n + 1], ref, "bf16", f"resnet18 bf16 b64 image {n}")
     # images differ, so must the logits (guards against a batch-index bug that repeats one image)
     assert np.abs(got[0] - got[63]).max() > 1e-3
+
+
+# ------------------------------------------------------------------ the paper's LeNet-shaped example
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("batch", [1, 5, 64])
+def test_lenet_shaped_graph(dtype, batch):
+    # tanh epilogues on conv and dense anchors, unpadded 5x5 convolutions from one and from 20 channels,
+    # non-overlapping 2x2 pooling, flatten of a channel-last intermediate back to (N, C*H*W) order
+    spec, data = W.lenet(batch, dtype)
+    check_graph(spec, data, f"lenet {dtype} b{batch}")
+    # every op in a group of its own gives the same values up to the rounding of the stored intermediates
+    check_graph(spec.ungrouped(), data, f"lenet ungrouped {dtype} b{batch}", atol_scale=2.0 if dtype == "bf16" else 1.0)
 
 
 # ------------------------------------------------------------------ LSTM

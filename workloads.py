@@ -281,6 +281,64 @@ def resnet18(batch=1, dtype="f32", image=224, width=64, classes=1000, config=3,
     return g, raw, bn
 
 
+# --------------------------------------------------------------------------
+# the LeNet-shaped graph of the paper's decorator example (Fig. "dec_ex"): the
+# only model the paper writes down.  Shapes only: inputs are synthetic.
+# --------------------------------------------------------------------------
+def lenet(batch=64, dtype="f32", config=8):
+    """conv 5x5 (1->20) + bias + tanh | maxpool 2x2/2 | conv 5x5 (20->50) + bias + tanh | maxpool 2x2/2 | flatten |
+    dense 800->500 + bias + tanh | dense 500->10 + bias; one fusion group per `|` part.  x is N(0,1) of shape
+    (batch, 1, 28, 28) (MNIST-shaped, no dataset item), weights Kaiming-uniform, biases U(-0.1, 0.1)."""
+    rng = rng_for(config)
+    g = GraphSpec(f"lenet_b{batch}_{dtype}")
+    data = {}
+    x = g.input("x", dtype, (batch, 1, 28, 28))
+    data["x"] = as_dtype(normal(rng, (batch, 1, 28, 28)), dtype)
+
+    def conv_tanh(name, xin, cin, cout, k, hin):
+        ho = conv_out(hin, k, 1, 0)
+        data[name + ".w"] = as_dtype(kaiming_uniform(rng, (cout, cin, k, k), cin * k * k), dtype)
+        data[name + ".b"] = as_dtype(uniform(rng, (cout,), -0.1, 0.1), "f32")
+        wv = g.param(name + ".w", dtype, (cout, cin, k, k))
+        bv = g.param(name + ".b", "f32", (cout,))
+        ot = (dtype, (batch, cout, ho, ho))
+        o0, (y,) = g.op("conv2d", [xin, wv], [ot], name=name, stride=(1, 1), pad=(0, 0))
+        o1, (y,) = g.op("bias_add", [y, bv], [ot], axis=1)
+        o2, (y,) = g.op("tanh", [y], [ot])
+        g.group([o0, o1, o2])
+        return y, ho
+
+    def pool(xin, c, hin):
+        ho = conv_out(hin, 2, 2, 0)
+        o, (y,) = g.op("maxpool2d", [xin], [(dtype, (batch, c, ho, ho))], kernel=(2, 2), stride=(2, 2), pad=(0, 0))
+        g.group([o])
+        return y, ho
+
+    def dense(name, xin, cin, cout, act):
+        data[name + ".w"] = as_dtype(kaiming_uniform(rng, (cout, cin), cin), dtype)
+        data[name + ".b"] = as_dtype(uniform(rng, (cout,), -0.1, 0.1), "f32")
+        wv = g.param(name + ".w", dtype, (cout, cin))
+        bv = g.param(name + ".b", "f32", (cout,))
+        ot = (dtype, (batch, cout))
+        ids = []
+        o, (y,) = g.op("dense", [xin, wv], [ot], name=name); ids.append(o)
+        o, (y,) = g.op("bias_add", [y, bv], [ot], axis=1); ids.append(o)
+        if act:
+            o, (y,) = g.op("tanh", [y], [ot]); ids.append(o)
+        g.group(ids)
+        return y
+
+    y, h = conv_tanh("conv1", x, 1, 20, 5, 28)      # 24 x 24
+    y, h = pool(y, 20, h)                            # 12 x 12
+    y, h = conv_tanh("conv2", y, 20, 50, 5, h)       # 8 x 8
+    y, h = pool(y, 50, h)                            # 4 x 4
+    o, (y,) = g.op("flatten", [y], [(dtype, (batch, 50 * h * h))]); g.group([o])
+    y = dense("fc1", y, 50 * h * h, 500, True)
+    y = dense("fc2", y, 500, 10, False)
+    g.output(y)
+    return g, data
+
+
 BN_EPS = 1e-5
 
 
