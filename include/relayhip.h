@@ -142,6 +142,18 @@ rl_status rl_graph_op(rl_graph *g, int32_t op_kind, const int32_t *in_ids, int32
  * are known and again by rl_plan_create.  Calls left ungrouped run alone. */
 rl_status rl_graph_group(rl_graph *g, const int32_t *op_ids, int32_t n, int32_t *group_id);
 rl_status rl_graph_output(rl_graph *g, int32_t value_id);
+/* Automatic fusion: puts every call that has no group yet into one, by the same rules a declared group must
+ * satisfy.  In declaration order, the first ungrouped call opens a group (a concat whose only use is an
+ * ungrouped dense opens it together with that dense); the group then absorbs the consumer of its last result
+ * for as long as that result has exactly one use and is not a graph output, and the consumer is an ungrouped
+ * injective call taking it as first operand whose other operands are defined before the group (lstm_gates is
+ * absorbed too and closes the group).  Calls that are neither contractions nor injective stay alone.  Declare
+ * the graph outputs first: a value that is an output is never fused away.  Groups declared by hand are kept.
+ * *n_groups (nullable) gets the number of groups added.  On error nothing is guaranteed about which of the
+ * ungrouped calls were grouped; the graph stays valid. */
+rl_status rl_graph_autogroup(rl_graph *g, int32_t *n_groups);
+/* Group a call belongs to (the id rl_graph_group returned, or its position for automatic ones), -1 if none. */
+rl_status rl_graph_group_of(const rl_graph *g, int32_t op_id, int32_t *group_id);
 
 /* ---- plan ---------------------------------------------------------------
  * rl_plan_create re-checks the whole graph (types, groups, outputs reachable),

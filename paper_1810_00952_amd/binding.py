@@ -70,7 +70,7 @@ _lib = None
 
 # every symbol include/relayhip.h declares
 SYMBOLS = ["rl_ctx_create", "rl_ctx_destroy", "rl_last_error", "rl_graph_create", "rl_graph_destroy", "rl_graph_input",
-           "rl_graph_param", "rl_graph_op", "rl_graph_group", "rl_graph_output", "rl_plan_create", "rl_plan_destroy",
+           "rl_graph_param", "rl_graph_op", "rl_graph_group", "rl_graph_output", "rl_graph_autogroup", "rl_graph_group_of", "rl_plan_create", "rl_plan_destroy",
            "rl_plan_describe", "rl_plan_workspace_bytes", "rl_plan_packed_bytes", "rl_plan_prepack", "rl_plan_run",
            "rl_plan_run_recurrent", "rl_plan_recurrent_workspace_bytes", "rl_prep_fold_batchnorm", "rl_plan_profile"]
 
@@ -102,6 +102,8 @@ def lib():
                                   POINTER(c_int32), POINTER(c_int32)]
         L.rl_graph_group.argtypes = [c_void_p, POINTER(c_int32), c_int32, POINTER(c_int32)]
         L.rl_graph_output.argtypes = [c_void_p, c_int32]
+        L.rl_graph_autogroup.argtypes = [c_void_p, POINTER(c_int32)]
+        L.rl_graph_group_of.argtypes = [c_void_p, c_int32, POINTER(c_int32)]
         L.rl_plan_create.argtypes = [c_void_p, POINTER(c_void_p)]
         L.rl_plan_destroy.argtypes = [c_void_p]; L.rl_plan_destroy.restype = None
         L.rl_plan_describe.argtypes = [c_void_p, c_char_p, c_size_t, POINTER(c_size_t)]
@@ -210,6 +212,25 @@ class Graph:
     def output(self, vid: int) -> None:
         self.ctx.check(lib().rl_graph_output(self._h, vid))
 
+    def autogroup(self) -> int:
+        n = c_int32()
+        self.ctx.check(lib().rl_graph_autogroup(self._h, byref(n)))
+        return n.value
+
+    def group_of(self, op_id: int) -> int:
+        gid = c_int32()
+        self.ctx.check(lib().rl_graph_group_of(self._h, op_id, byref(gid)))
+        return gid.value
+
+    def groups(self, n_ops: int) -> List[List[int]]:
+        """Members of every group, in group order (ops without a group are left out)."""
+        by = {}
+        for o in range(n_ops):
+            gi = self.group_of(o)
+            if gi >= 0:
+                by.setdefault(gi, []).append(o)
+        return [by[k] for k in sorted(by)]
+
     def plan(self) -> "Plan":
         return Plan(self)
 
@@ -219,10 +240,11 @@ class Graph:
             self._h = None
 
 
-def graph_from_spec(ctx: Context, spec) -> Graph:
+def graph_from_spec(ctx: Context, spec, auto_groups: bool = False) -> Graph:
     """Replay a plain-data graph description (values, calls with declared result
     types, groups, outputs) through the C ABI, call by call.  Value and op ids
-    of the description and of the library coincide because both are append-only."""
+    of the description and of the library coincide because both are append-only.
+    auto_groups: ignore the description's groups and let rl_graph_autogroup form them."""
     g = Graph(ctx)
     first_out = {op.outputs[0]: oi for oi, op in enumerate(spec.ops)}
     for vid, v in enumerate(spec.values):
@@ -242,6 +264,11 @@ def graph_from_spec(ctx: Context, spec) -> Graph:
             continue            # second result of a two-result call, already declared
         if got != vid:
             raise AssertionError("id drift between description and library")
+    if auto_groups:
+        for o in spec.outputs:
+            g.output(o)
+        g.autogroup()
+        return g
     for grp in spec.groups:
         g.group(grp)
     for o in spec.outputs:

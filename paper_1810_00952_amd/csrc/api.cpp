@@ -221,6 +221,28 @@ rl_status rl_graph_group(rl_graph *g, const int32_t *op_ids, int32_t n, int32_t 
     });
 }
 
+rl_status rl_graph_autogroup(rl_graph *g, int32_t *n_groups)
+{
+    if (!g) return RL_ERR_NULL;
+    auto &err = g->g.err;
+    return guarded(err, [&]() -> rl_status {
+        std::string msg;
+        int n = 0;
+        rl_status st = auto_group(g->g, n, msg);
+        if (st != RL_OK) return fail(err, st, msg);
+        if (n_groups) *n_groups = n;
+        return RL_OK;
+    });
+}
+
+rl_status rl_graph_group_of(const rl_graph *g, int32_t op_id, int32_t *group_id)
+{
+    if (!g || !group_id) return RL_ERR_NULL;
+    if (op_id < 0 || op_id >= (int32_t)g->g.ops.size()) return fail(g->g.err, RL_ERR_GROUP, "unknown op id");
+    *group_id = g->g.ops[op_id].group;
+    return RL_OK;
+}
+
 rl_status rl_graph_output(rl_graph *g, int32_t value_id)
 {
     if (!g) return RL_ERR_NULL;

@@ -1,5 +1,6 @@
 // Typing rules and fusion-group legality (host only).
 #include "graph.h"
+#include "kernels.h"
 
 #include <algorithm>
 #include <set>
@@ -292,6 +293,71 @@ rl_status check_group(const Graph &g, const std::vector<int> &ops_in, std::strin
             for (int d = 0; same_shape && d < t.rank; ++d) same_shape = t.dims[d] == ref.dims[d];
             if (!same_shape) { msg = "fused operators differ in output shape"; return RL_ERR_GROUP; }
         }
+    }
+    return RL_OK;
+}
+
+// Fusion groups for every call that has none yet, by the rule the hand-written groupings follow: a group is
+// opened by the first ungrouped call in declaration order (a concat whose only use is an ungrouped dense
+// opens it together with that dense) and then follows the chain of results: the group's last result is
+// absorbed into its consumer while that result has exactly one use, is not a graph output, and the
+// consumer is an ungrouped injective call (or lstm_gates, which then closes the group) that takes the result
+// as its first operand, has every other operand defined before the group starts, keeps the group's output
+// shape and leaves the epilogue within its length limits.  Pools, flatten and anything else that is neither a
+// contraction nor injective stay alone.  Every group formed is checked by check_group like a declared one.
+rl_status auto_group(Graph &g, int &n_new, std::string &msg)
+{
+    n_new = 0;
+    std::vector<std::vector<int>> users(g.values.size());
+    for (size_t c = 0; c < g.ops.size(); ++c)
+        for (int v : g.ops[c].in) users[v].push_back((int)c);
+    std::set<int> outs(g.outputs.begin(), g.outputs.end());
+    auto sole_user = [&](int v) -> int {       // the one call that reads v (possibly through several operands), or -1
+        if (outs.count(v) || users[v].empty()) return -1;
+        for (int u : users[v]) if (u != users[v][0]) return -1;
+        return users[v][0];
+    };
+    for (size_t o = 0; o < g.ops.size(); ++o) {
+        if (g.ops[o].group >= 0) continue;
+        std::vector<int> mem{(int)o};
+        int kind = g.ops[o].kind;
+        if (kind == RL_OP_CONCAT && g.ops[o].out.size() == 1) {
+            const int d = sole_user(g.ops[o].out[0]);
+            if (d >= 0 && g.ops[d].group < 0 && g.ops[d].kind == RL_OP_DENSE && g.ops[d].in[0] == g.ops[o].out[0]) { mem.push_back(d); kind = RL_OP_DENSE; }
+        }
+        const bool grows = is_anchor(kind) || is_injective(kind);
+        int n_chain = 0, n_ptr = 0;            // epilogue steps and operand pointers used so far
+        while (grows) {
+            const OpNode &last = g.ops[mem.back()];
+            if (last.out.size() != 1) break;
+            const int v = last.out[0];
+            const int c = sole_user(v);
+            if (c < 0 || g.ops[c].group >= 0) break;
+            const OpNode &cn = g.ops[c];
+            if (!(is_injective(cn.kind) || cn.kind == RL_OP_LSTM_GATES) || cn.in.empty() || cn.in[0] != v) break;
+            bool ok = true;
+            int extra = 0;
+            for (size_t i = 1; i < cn.in.size(); ++i) {
+                const int u = cn.in[i];
+                if (u == v || (g.values[u].producer >= 0 && g.values[u].producer >= mem[0])) ok = false;
+                ++extra;
+            }
+            if (cn.kind == RL_OP_LSTM_GATES) extra = 0;      // its cell-state operand is not an epilogue pointer
+            if (!ok || n_chain + 1 > RL_EPI_MAX_OPS || n_ptr + extra > RL_EPI_MAX_PTRS) break;
+            std::vector<int> trial = mem;
+            trial.push_back(c);
+            std::string why;
+            if (check_group(g, trial, why) != RL_OK) break;
+            mem.swap(trial);
+            ++n_chain; n_ptr += extra;
+            if (cn.kind == RL_OP_LSTM_GATES) break;
+        }
+        rl_status st = check_group(g, mem, msg);
+        if (st != RL_OK) return st;
+        const int gi = (int)g.groups.size();
+        for (int m : mem) g.ops[m].group = gi;
+        g.groups.push_back(mem);
+        ++n_new;
     }
     return RL_OK;
 }

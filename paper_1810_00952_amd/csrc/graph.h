@@ -69,6 +69,8 @@ rl_status infer_type(int kind, const std::vector<rl_type> &in, const Attrs &a, c
 
 // Fusion-group legality over the finished graph.
 rl_status check_group(const Graph &g, const std::vector<int> &ops, std::string &msg);
+// Puts every call that has no group yet into one (see graph.cpp); n_new = groups added.
+rl_status auto_group(Graph &g, int &n_new, std::string &msg);
 
 const char *op_name(int kind);
 bool is_anchor(int kind);

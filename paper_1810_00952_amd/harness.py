@@ -35,11 +35,11 @@ def stream_handle() -> int:
 class Session:
     """One plan with its device buffers."""
 
-    def __init__(self, spec, ctx: Optional[Context] = None, device="cuda:0"):
+    def __init__(self, spec, ctx: Optional[Context] = None, device="cuda:0", auto_groups: bool = False):
         self.spec = spec
         self.device = device
         self.ctx = ctx or Context()
-        self.graph = graph_from_spec(self.ctx, spec)
+        self.graph = graph_from_spec(self.ctx, spec, auto_groups=auto_groups)
         self.plan = Plan(self.graph)
         self.tensors: Dict[int, torch.Tensor] = {}    # value id -> tensor whose pointer is bound
         self.raw: Dict[int, torch.Tensor] = {}

@@ -351,6 +351,29 @@ def test_resnet18_bf16_batch64_sampled_images():
     assert np.abs(got[0] - got[63]).max() > 1e-3
 
 
+# ------------------------------------------------------------------ automatic fusion
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_automatically_fused_graphs(dtype):
+    # groups formed by the library from the bare calls: where they differ from the declared ones (the trailing neg
+    # joins the conv group; the gate op joins its contraction) and where they coincide (a small ResNet)
+    spec, data = W.conv_group(3, 64, 72, 13, 11, 3, 1, 1, dtype, residual=True, relu=True, tail=True)
+    ref = OG.run(spec, data)
+    got, s = run_hip(spec, data, auto_groups=True)
+    assert len(s.plan.describe()["steps"]) < len(run_hip(spec, data)[1].plan.describe()["steps"])
+    for vid in spec.outputs:
+        assert_close(got[vid], ref[vid], dtype, f"auto-fused conv tail {dtype}")
+    spec, raw, bn = W.resnet18(batch=2, dtype=dtype, image=64, width=16, classes=24)
+    from paper_1810_00952_amd import harness
+    import torch
+    outs = []
+    for auto in (False, True):
+        s = harness.Session(spec, auto_groups=auto)
+        fold_resnet_hip(s, raw, bn, dtype)
+        s.alloc(); s.run(); torch.cuda.synchronize()
+        outs.append(harness.to_host(s.output()))
+    np.testing.assert_array_equal(outs[0], outs[1])
+
+
 # ------------------------------------------------------------------ the paper's LeNet-shaped example
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("batch", [1, 5, 64])

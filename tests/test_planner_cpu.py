@@ -141,3 +141,75 @@ def test_cyclic_group_dependency_is_rejected():
     with pytest.raises(B.RelayError) as ei:
         B.Plan(B.graph_from_spec(B.Context(), g))
     assert ei.value.category == "group"
+
+
+# ---------------------------------------------------------------- automatic fusion (host logic only)
+def _auto(spec):
+    g = B.graph_from_spec(B.Context(), spec, auto_groups=True)
+    return g, g.groups(len(spec.ops))
+
+
+@pytest.mark.parametrize("name,build", [
+    ("mlp", lambda: W.mlp()[0]),
+    ("conv group", lambda: W.conv_group()[0]),
+    ("resnet18 f32 b1", lambda: W.resnet18(1, "f32")[0]),
+    ("resnet18 bf16 b64", lambda: W.resnet18(64, "bf16")[0]),
+    ("lstm cell", lambda: W.lstm_cell_graph(64, 1024, 1024, "bf16", True)),
+    ("lstm unrolled", lambda: W.lstm_unrolled_graph(3, 16, 32, 32, "bf16", True)),
+    ("lenet", lambda: W.lenet()[0]),
+    ("eltwise", lambda: W.eltwise_bias_res_relu((4, 8, 6, 6))[0]),
+    ("eltwise chain", lambda: W.eltwise_chain()[0]),
+])
+def test_autogroup_reproduces_the_declared_groups(name, build):
+    # the pass, run on the bare calls, must arrive at the grouping every workload declares by hand,
+    # and the result must plan
+    spec = build()
+    g, got = _auto(spec)
+    assert got == [sorted(x) for x in spec.groups]
+    B.Plan(g)
+
+
+def test_autogroup_rules():
+    # y = relu(conv(x) + b); z = neg(y); outputs y and z: y is an output, so neg must not be absorbed
+    g = W.GraphSpec("t")
+    x = g.input("x", "f32", (1, 8, 6, 6)); w = g.param("w", "f32", (8, 8, 3, 3)); b = g.param("b", "f32", (8,))
+    t = ("f32", (1, 8, 6, 6))
+    o0, (y,) = g.op("conv2d", [x, w], [t], stride=(1, 1), pad=(1, 1))
+    o1, (y,) = g.op("bias_add", [y, b], [t], axis=1)
+    o2, (y,) = g.op("relu", [y], [t])
+    o3, (z,) = g.op("neg", [y], [t])
+    g.output(y); g.output(z)
+    assert _auto(g)[1] == [[o0, o1, o2], [o3]]
+
+    # a result with two uses ends its group.  Of its users, relu cannot take the add: the add's other operand (tanh's
+    # result) is defined after relu's group opened; tanh cannot either, because the add does not take tanh's result
+    # first.  With the operands the other way round tanh's group absorbs the add.
+    for swap, want in ((False, lambda o: [[o[0]], [o[1]], [o[2]], [o[3]]]), (True, lambda o: [[o[0]], [o[1]], [o[2], o[3]]])):
+        g = W.GraphSpec("t")
+        x = g.input("x", "f32", (4, 16)); w = g.param("w", "f32", (16, 16))
+        t = ("f32", (4, 16))
+        o0, (y,) = g.op("dense", [x, w], [t])
+        o1, (a,) = g.op("relu", [y], [t])
+        o2, (c,) = g.op("tanh", [y], [t])
+        o3, (d,) = g.op("add", [c, a] if swap else [a, c], [t])
+        g.output(d)
+        lib, got = _auto(g)
+        assert got == want([o0, o1, o2, o3])
+        B.Plan(lib)
+
+    # a second contraction never joins; pools stay alone; hand-declared groups are kept
+    g = W.GraphSpec("t")
+    x = g.input("x", "f32", (2, 8, 8, 8)); w1 = g.param("w1", "f32", (8, 8, 1, 1)); w2 = g.param("w2", "f32", (8, 8, 1, 1))
+    t = ("f32", (2, 8, 8, 8))
+    o0, (y,) = g.op("conv2d", [x, w1], [t], stride=(1, 1), pad=(0, 0))
+    o1, (y,) = g.op("relu", [y], [t])
+    o2, (y,) = g.op("conv2d", [y, w2], [t], stride=(1, 1), pad=(0, 0))
+    o3, (y,) = g.op("maxpool2d", [y], [("f32", (2, 8, 4, 4))], kernel=(2, 2), stride=(2, 2), pad=(0, 0))
+    o4, (y,) = g.op("relu", [y], [("f32", (2, 8, 4, 4))])
+    g.output(y)
+    assert _auto(g)[1] == [[o0, o1], [o2], [o3], [o4]]
+    g.groups = [[o0]]                                     # the caller fixes conv alone: relu must then stand alone too
+    lib = B.graph_from_spec(B.Context(), g)               # declares [o0], then outputs
+    lib.autogroup()
+    assert lib.groups(len(g.ops)) == [[o0], [o1], [o2], [o3], [o4]]
+    assert lib.autogroup() == 0                           # nothing left to group
