@@ -7,15 +7,16 @@
 // The recurrence leaves only a skinny contraction per step (batch x 4H x H with
 // a batch of 64 or so) that has to finish before the next step can start, so
 // what matters is latency and how many CUs share the weight traffic, not MFMA
-// throughput.  A workgroup (4 waves) owns 64 batch rows x 8 hidden units
-// (32 gate columns); with H = 1024 that is 128 workgroups, each reading its
-// 64 KB weight slice (which stays in its XCD's L2 from step to step) and the
-// 128 KB of h_prev.
+// throughput.  A workgroup (4 waves) owns 32 batch rows x 8 hidden units
+// (32 gate columns); with a batch of 64 and H = 1024 that is 256 workgroups,
+// each reading its 64 KB weight slice (which stays in its XCD's L2 from step
+// to step) and its 64 KB of h_prev: the split that moves the fewest bytes per
+// CU when every CU has one workgroup.
 //
 // The K loop is split between the four waves: wave w takes K tiles w, w+4,
 // w+8, ... in rounds of four.  A round requests everything it needs at once --
-// the four 64-row h_prev tiles by direct loads (global -> LDS, 8 KB each, into
-// the wave's private 32 KB), then the weight fragments of the four tiles
+// the four 32-row h_prev tiles by direct loads (global -> LDS, 4 KB each, into
+// the wave's private 16 KB), then the weight fragments of the four tiles
 // straight into registers (a lane loads the 16 bytes the MFMA wants from it)
 // -- so that one memory latency is paid per round, not per tile; H = 1024 is
 // one round.  Nothing is shared between waves until the end, so the loop has
@@ -23,8 +24,8 @@
 // them counts the sixteen fragment loads issued after them as the only ones
 // that may still be in flight, and the compiler's own waits on those
 // fragments are exact because nothing is issued behind them.  Each wave ends
-// with an fp32 partial sum of the whole 64 x 32 tile, parks it in its own LDS
-// space, and after one barrier the 256 threads finish two (row, unit) pairs
+// with an fp32 partial sum of the whole 32 x 32 tile, parks it in its own LDS
+// space, and after one barrier the 256 threads finish one (row, unit) pair
 // each: sum of the four partials + zx + bias, gate arithmetic, c' and h'.
 // The operands of that last part (zx, c, bias) are requested first of all.
 //
@@ -64,7 +65,7 @@ __device__ __forceinline__ uint32_t lds_addr_of(const void *p)
 }
 
 constexpr uint32_t OOB = 0x80000000u;
-constexpr int BM = 64, BNC = 32, UNITS = 8;       // batch rows, gate columns, hidden units per workgroup
+constexpr int BM = 32, BNC = 32, UNITS = 8;       // batch rows, gate columns, hidden units per workgroup
 constexpr int STAGE = BM * 128, NSTAGE = 4;       // one h_prev tile; tiles per round
 constexpr int PSTRIDE = 36;                       // floats per parked row (32 + 4: spreads the banks)
 static_assert(BM * PSTRIDE * 4 <= NSTAGE * STAGE && PSTRIDE >= BNC && BNC == 4 * UNITS, "a wave parks its partial tile in its own LDS space");
@@ -83,15 +84,16 @@ __global__ __launch_bounds__(256) void lstm_step_kernel(const LstmStepParams p)
     const int tile64 = nb >> 1, half = nb & 1;                // 64-row weight tile and which 8 of its 16 units
     const int unit0 = tile64 * 16 + half * UNITS;             // first hidden unit of the workgroup
 
-    // ---- the last part's operands, requested first: thread t finishes (row, unit) pairs t and t + 256.
+    // ---- the last part's operands, requested first: thread t finishes (row, unit) pair t.
     // Plain range-checked buffer loads (out of range reads as zero), so nothing here branches or waits.
-    float zx_r[2][4], bias_r[2][4], c_r[2];
+    constexpr int NPAIR = BM * UNITS / 256;                    // (row, unit) pairs per thread
+    float zx_r[NPAIR][4], bias_r[NPAIR][4], c_r[NPAIR];
     {
         const __amdgpu_buffer_rsrc_t rz = __builtin_amdgcn_make_buffer_rsrc((void *)p.zx, 0, (uint32_t)p.B * 4u * (uint32_t)p.H * 4u, 0x00020000);
         const __amdgpu_buffer_rsrc_t rc = __builtin_amdgcn_make_buffer_rsrc((void *)p.c_in, 0, (uint32_t)p.B * (uint32_t)p.H * 4u, 0x00020000);
         const __amdgpu_buffer_rsrc_t rb = __builtin_amdgcn_make_buffer_rsrc((void *)(p.bias ? p.bias : p.w), 0, p.bias ? 4u * (uint32_t)p.H * 4u : 0u, 0x00020000);
 #pragma unroll
-        for (int s = 0; s < 2; ++s) {
+        for (int s = 0; s < NPAIR; ++s) {
             const int idx = t + 256 * s, row = idx >> 3, j = idx & 7;
             const int m = m0 + row, unit = unit0 + j;
             const bool live = m < p.B && unit < p.H;
@@ -135,9 +137,10 @@ __global__ __launch_bounds__(256) void lstm_step_kernel(const LstmStepParams p)
     }
     const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc((void *)p.w, 0, p.w_bytes, 0x00020000);
 
-    f32x16 acc[2];
+    constexpr int TM = BM / 32;
+    f32x16 acc[TM];
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int q = 0; q < 16; ++q) acc[i][q] = 0.0f;
 
@@ -166,10 +169,11 @@ __global__ __launch_bounds__(256) void lstm_step_kernel(const LstmStepParams p)
             const unsigned char *sa = ring + q * STAGE;
 #pragma unroll
             for (int ks = 0; ks < 4; ++ks) {
-                const u32x4 fx0 = *(const u32x4 *)(sa + f_off[ks]);
-                const u32x4 fx1 = *(const u32x4 *)(sa + 32 * 128 + f_off[ks]);
-                acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fw[q][ks]), __builtin_bit_cast(bf16x8, fx0), acc[0], 0, 0, 0);
-                acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fw[q][ks]), __builtin_bit_cast(bf16x8, fx1), acc[1], 0, 0, 0);
+#pragma unroll
+                for (int i = 0; i < TM; ++i) {
+                    const u32x4 fx = *(const u32x4 *)(sa + i * 32 * 128 + f_off[ks]);
+                    acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fw[q][ks]), __builtin_bit_cast(bf16x8, fx), acc[i], 0, 0, 0);
+                }
             }
         }
         RL_WAIT_LGKM0();                                       // the tiles are read out: the next round may overwrite them
@@ -180,7 +184,7 @@ __global__ __launch_bounds__(256) void lstm_step_kernel(const LstmStepParams p)
     // register 4g + k of lane l is (gate column 8g + 4*(l >> 5) + k, batch row 32i + (l & 31)).
     float *park = (float *)ring;
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
             f32x4 v;
@@ -194,7 +198,7 @@ __global__ __launch_bounds__(256) void lstm_step_kernel(const LstmStepParams p)
 
     // ---- gate arithmetic: gate g of unit j sits in gate column 8g + j of every wave's partial tile
 #pragma unroll
-    for (int s = 0; s < 2; ++s) {
+    for (int s = 0; s < NPAIR; ++s) {
         const int idx = t + 256 * s, row = idx >> 3, j = idx & 7;
         const int m = m0 + row, unit = unit0 + j;
         if (m < p.B && unit < p.H) {
