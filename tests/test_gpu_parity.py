@@ -179,6 +179,66 @@ def test_eltwise_bias_residual_relu(dtype, shape):
     check_graph(spec, make(), f"bias+res+relu {dtype} {shape}")
 
 
+def test_eltwise_more_than_2_pow_31_elements():
+    # 72 x 8 x 2048 x 2048 bf16: 2.4e9 elements, 4.8 GB per tensor -- past 32-bit element and byte offsets.
+    # Inputs are drawn on the device (seeded); the oracle checks whole (image, channel) planes, among them the
+    # first and the last of the tensor, each as a 1 x 1 x H x W problem with that channel's bias.
+    import torch
+    from paper_1810_00952_amd import harness
+    shape = (72, 8, 2048, 2048)
+    spec, _ = W.eltwise_bias_res_relu(shape, "bf16")
+    s = harness.Session(spec)
+    gen = torch.Generator(device="cuda:0"); gen.manual_seed(11)
+    n = s.by_name
+    for name in ("x", "r"):
+        t = torch.empty(shape, dtype=torch.bfloat16, device="cuda:0")
+        for i in range(shape[0]):                     # image by image: no fp32 copy of the whole tensor
+            t[i] = torch.randn(shape[1:], generator=gen, device="cuda:0", dtype=torch.float32).to(torch.bfloat16)
+        s.tensors[n[name]] = t
+    b = np.linspace(-0.5, 0.5, shape[1]).astype(np.float32)
+    s.load({"b": b})
+    s.alloc(); s.run(); torch.cuda.synchronize()
+    y = s.output()
+    sub, _ = W.eltwise_bias_res_relu((1, 1) + shape[2:], "bf16")
+    for (i, c) in [(0, 0), (0, 7), (35, 3), (44, 5), (71, 0), (71, 7)]:
+        d = {"x": harness.to_host(s.tensors[n["x"]][i, c])[None, None], "r": harness.to_host(s.tensors[n["r"]][i, c])[None, None],
+             "b": b[c:c + 1]}
+        ref = OG.run(sub, d)[sub.outputs[0]]
+        got = O.widen(harness.to_host(y[i, c])[None, None], "bf16")
+        assert_close(got, ref, "bf16", f"large eltwise plane ({i},{c})")
+    # the planes on either side of flat element 2^31 (image 64, channel 0 starts exactly there)
+    assert 64 * 8 * 2048 * 2048 == 2 ** 31
+    for (i, c) in [(63, 7), (64, 0)]:
+        d = {"x": harness.to_host(s.tensors[n["x"]][i, c])[None, None], "r": harness.to_host(s.tensors[n["r"]][i, c])[None, None],
+             "b": b[c:c + 1]}
+        ref = OG.run(sub, d)[sub.outputs[0]]
+        assert_close(O.widen(harness.to_host(y[i, c])[None, None], "bf16"), ref, "bf16", f"large eltwise plane ({i},{c})")
+
+
+def test_conv_activations_beyond_2_gib():
+    # 66 x 8 x 1024 x 1024 f32 (2.2 GB in, 2.2 GB out): past the 32-bit byte offsets the vector-load kernels use, so
+    # the planner must fall back to the 64-bit gather kernel.  The oracle computes the first and the last image.
+    import torch
+    from paper_1810_00952_amd import harness
+    B_, C, H = 66, 8, 1024
+    spec, data1 = W.conv_group(1, C, C, H, H, 3, 1, 1, "f32", residual=False, relu=True, make_x=False)
+    big, _ = W.conv_group(B_, C, C, H, H, 3, 1, 1, "f32", residual=False, relu=True, make_x=False)
+    s = harness.Session(big)
+    n = s.by_name
+    gen = torch.Generator(device="cuda:0"); gen.manual_seed(12)
+    x = torch.randn((B_, C, H, H), generator=gen, device="cuda:0", dtype=torch.float32)
+    s.tensors[n["x"]] = x
+    s.load(data1)
+    s.alloc(); s.run(); torch.cuda.synchronize()
+    assert any(st["kernel"].endswith("_gather") for st in s.plan.describe()["steps"])
+    y = s.output()
+    for i in (0, B_ - 1):
+        d = dict(data1); d["x"] = harness.to_host(x[i:i + 1])
+        ref = OG.run(spec, d)[spec.outputs[0]]
+        assert_close(O.widen(harness.to_host(y[i:i + 1]), "f32"), ref, "f32", f"large conv image {i}")
+    assert float((y[0] - y[B_ - 1]).abs().max()) > 1e-3
+
+
 def test_eltwise_operand_order_and_self_operands():
     for dtype in ("f32", "bf16"):
         g = W.GraphSpec("order")

@@ -178,15 +178,18 @@ def mlp(batch=32, d_in=784, d_hidden=128, d_out=10, dtype="f32", config=1):
 # config 2: one fused conv2d group
 # --------------------------------------------------------------------------
 def conv_group(batch=1, cin=64, cout=64, h=56, w=56, k=3, stride=1, pad=1, dtype="f32",
-               residual=False, relu=True, config=2, tail=False):
+               residual=False, relu=True, config=2, tail=False, make_x=True):
     """One fused conv2d group.  tail=True appends a second group (neg) so that the
-    conv group's result is an intermediate the plan keeps in its private layout."""
+    conv group's result is an intermediate the plan keeps in its private layout.
+    make_x=False leaves x out of the data (the caller supplies it); weights and bias then
+    do not depend on the batch."""
     rng = rng_for(config)
     g = GraphSpec("conv_group")
     data = {}
     oh, ow = conv_out(h, k, stride, pad), conv_out(w, k, stride, pad)
     x = g.input("x", dtype, (batch, cin, h, w))
-    data["x"] = as_dtype(normal(rng, (batch, cin, h, w)), dtype)
+    if make_x:
+        data["x"] = as_dtype(normal(rng, (batch, cin, h, w)), dtype)
     wt = g.param("w", dtype, (cout, cin, k, k))
     data["w"] = as_dtype(kaiming_normal(rng, (cout, cin, k, k), cin * k * k), dtype)
     b = g.param("b", "f32", (cout,))
