@@ -98,6 +98,14 @@ struct IgemmLaunch {
 };
 hipError_t launch_igemm(const IgemmParams &p, const IgemmLaunch &l, hipStream_t s);
 
+// ---- stem convolution + bias/ReLU + 3x3/2 max-pool in one kernel (stem_pool.hip) ----
+struct StemPoolParams {
+    IgemmParams g;                      // the stem contraction (x: padded frame, w: packed weights, N = 64, K = 256); y unused
+    void *yp; uint32_t yp_bytes;        // pooled output [n_img, PH, PW, 64] bf16
+    int32_t n_img, PH, PW;
+};
+hipError_t launch_stem_pool(const StemPoolParams &q, hipStream_t s);
+
 // ---- one LSTM step on a precomputed input projection (lstm_step.hip) ------
 struct LstmStepParams {
     const void *h_prev;                 // [B, H] bf16

@@ -394,6 +394,7 @@ struct Planner {
         Step &s = add_step(S_IGEMM, std::string(op_name(an.kind)) + "#" + std::to_string(ops[ai]), kname);
         s.group = gi;
         s.ig = p; s.il = il;
+        s.stem = stem ? 1 : 0;
         s.slot[SL_X] = xbuf; s.slot[SL_X2] = x2buf; s.slot[SL_W] = bound(wv); s.slot[SL_Y] = ybuf;
         for (int i = 0; i < RL_EPI_MAX_PTRS; ++i) s.slot[SL_E0 + i] = eslots[i];
         s.slot[SL_CIN] = cin_buf; s.slot[SL_COUT] = cout_buf; s.slot[SL_HOUT] = hout_buf;
@@ -613,8 +614,46 @@ struct Planner {
                 return fail(RL_ERR_TYPE, "an output is never computed");
             }
         }
+        fuse_stem_pool();
         assign_workspace();
         return RL_OK;
+    }
+
+    // A stem convolution group whose only consumer is the 3x3 / stride 2 / pad 1 max-pool group right behind it
+    // runs as one kernel that pools the finished values in LDS: the full-size tensor between the two groups
+    // (the largest of the whole graph) is then never written.  Same values as the two kernels, bit for bit
+    // (max commutes with the bias, the ReLU and the rounding).
+    void fuse_stem_pool()
+    {
+        if (getenv("RELAYHIP_NO_STEM_POOL")) return;
+        for (size_t si = 0; si + 1 < plan.steps.size(); ++si) {
+            Step &c = plan.steps[si];
+            const Step &m = plan.steps[si + 1];
+            const IgemmParams &g = c.ig;
+            if (c.kind != S_IGEMM || !c.stem || !c.il.lp || m.kind != S_MAXPOOL) continue;
+            const int mid = c.slot[SL_Y];
+            if (mid < 0 || m.slot[SL_X] != mid || plan.bufs[mid].bound_value >= 0) continue;
+            bool other_use = false;
+            for (size_t sj = 0; sj < plan.steps.size(); ++sj)
+                if (sj != si && sj != si + 1)
+                    for (int b : plan.steps[sj].slot) other_use |= (b == mid);
+            const PoolParams &po = m.po;
+            Epilogue e = g.epi;                 // wanted: [f32 bias] [relu] and nothing else
+            finalize_epilogue(e);
+            if (other_use || g.sh != 2 || g.sw != 2 || g.N != 64 || g.K != 256 || g.Kp != 256 || g.KH != 4 || g.y_dtype != DT_BF16 || po.dtype != DT_BF16 || po.C != 64 ||
+                po.KH != 3 || po.KW != 3 || po.sh != 2 || po.sw != 2 || po.ph != 1 || po.pw != 1 || po.H != g.OH || po.W != g.OW ||
+                po.OH != (g.OH - 1) / 2 + 1 || po.OW != (g.OW - 1) / 2 + 1 || !e.simple || e.t_op >= 0 ||
+                (e.has_bias && e.bias_dtype != DT_F32) || (e.rest_n != 0 && !e.relu_last) ||
+                (uint64_t)po.N * po.OH * po.OW * 64 * 2 >= ((uint64_t)1 << 31))
+                continue;
+            c.kind = S_STEM_POOL;
+            c.sp_N = po.N; c.sp_PH = po.OH; c.sp_PW = po.OW;
+            c.slot[SL_Y] = m.slot[SL_Y];
+            c.name += "+" + m.name;
+            c.kernel = "igemm_conv2d_bf16_stem_maxpool";
+            c.bytes = c.bytes - (double)plan.bufs[mid].bytes + (double)plan.bufs[m.slot[SL_Y]].bytes;
+            plan.steps.erase(plan.steps.begin() + (long)si + 1);
+        }
     }
 
     // liveness-based first-fit packing of workspace buffers
@@ -764,6 +803,18 @@ rl_status run_steps(const Plan &plan, void *const *ptrs, hipStream_t stream, std
         case S_TO_NCHW:
             er = launch_nhwc_to_nchw(P(s, SL_X), P(s, SL_Y), s.t_dtype, s.t_N, s.t_C, s.t_P, stream);
             break;
+        case S_STEM_POOL: {
+            StemPoolParams q{};
+            q.g = s.ig;
+            q.g.x = P(s, SL_X); q.g.w = P(s, SL_W); q.g.y = nullptr;
+            for (int i = 0; i < RL_EPI_MAX_PTRS; ++i) q.g.epi.ptr[i] = P(s, SL_E0 + i);
+            finalize_epilogue(q.g.epi);
+            q.yp = P(s, SL_Y);
+            q.n_img = s.sp_N; q.PH = s.sp_PH; q.PW = s.sp_PW;
+            q.yp_bytes = (uint32_t)((uint64_t)s.sp_N * s.sp_PH * s.sp_PW * 64 * 2);
+            er = launch_stem_pool(q, stream);
+            break;
+        }
         case S_STEM_PAD:
             er = launch_stem_pad(P(s, SL_X), P(s, SL_Y), s.t_N, s.t_C, s.st_H, s.st_W, s.st_Hp, s.st_Wp, s.st_ph, s.st_pw, stream);
             break;

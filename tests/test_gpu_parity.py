@@ -120,6 +120,38 @@ def test_conv_stem_few_channels_bf16(case):
     check_graph(spec, data, f"conv stem {case}")
 
 
+# Stem convolution + max-pool 3x3/2/1 as one kernel: regions at every image border, images smaller than a region,
+# fewer and more regions than workgroups (so workgroups stream on from one region into the next), one, three and
+# four input channels, 7- and 8-wide filters, with and without ReLU, pooled tensor as output and as intermediate.
+STEM_POOL_CASES = [
+    # batch cin h    w   k s p relu  tail
+    (2, 3, 224, 224, 7, 2, 3, True, False),
+    (3, 3, 33, 35, 7, 2, 3, True, True),
+    (5, 1, 12, 12, 7, 2, 3, False, False),
+    (70, 3, 64, 64, 7, 2, 3, True, False),
+    (9, 4, 61, 127, 8, 2, 3, True, True),
+    (1, 3, 7, 250, 7, 2, 3, False, True),
+]
+
+
+@pytest.mark.parametrize("case", STEM_POOL_CASES, ids=[f"sp{i}" for i in range(len(STEM_POOL_CASES))])
+def test_stem_conv_with_maxpool_in_one_kernel(case, monkeypatch):
+    b, ci, h, w, k, s_, p, relu, tail = case
+    spec, data = W.conv_pool(b, ci, 64, h, w, k, s_, p, "bf16", relu=relu, tail=tail)
+    from paper_1810_00952_amd import binding
+    desc = binding.Plan(binding.graph_from_spec(binding.Context(), spec)).describe()
+    assert any(st["kernel"] == "igemm_conv2d_bf16_stem_maxpool" for st in desc["steps"]), [st["kernel"] for st in desc["steps"]]
+    print(f"stem+pool case {case}", flush=True)
+    got, _ = check_graph(spec, data, f"stem+pool {case}")
+    # the two-kernel form of the same plan gives the same bits: max commutes with bias, ReLU and the rounding
+    monkeypatch.setenv("RELAYHIP_NO_STEM_POOL", "1")
+    desc = binding.Plan(binding.graph_from_spec(binding.Context(), spec)).describe()
+    assert any(st["kernel"] == "maxpool_nhwc" for st in desc["steps"])
+    two, _ = run_hip(spec, data)
+    for vid in spec.outputs:
+        np.testing.assert_array_equal(got[vid], two[vid])
+
+
 def test_conv_large_tiles_many_blocks():
     # enough rows that the planner picks its largest tile (several tiles + ragged tail)
     for dtype in ("f32", "bf16"):

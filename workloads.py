@@ -284,6 +284,37 @@ def resnet18(batch=1, dtype="f32", image=224, width=64, classes=1000, config=3,
     return g, raw, bn
 
 
+def conv_pool(batch=2, cin=3, cout=64, h=224, w=224, k=7, stride=2, pad=3, dtype="bf16", relu=True, tail=False, config=9):
+    """conv2d + bias (+ ReLU) as one group, then max-pool 3x3 / 2 / pad 1 as the next: the ResNet stem's shape.
+    tail=True appends neg as a third group, so the pooled tensor is an intermediate too."""
+    rng = rng_for(config)
+    g = GraphSpec("conv_pool")
+    data = {}
+    oh, ow = conv_out(h, k, stride, pad), conv_out(w, k, stride, pad)
+    x = g.input("x", dtype, (batch, cin, h, w))
+    data["x"] = as_dtype(normal(rng, (batch, cin, h, w)), dtype)
+    wt = g.param("w", dtype, (cout, cin, k, k))
+    data["w"] = as_dtype(kaiming_normal(rng, (cout, cin, k, k), cin * k * k), dtype)
+    b = g.param("b", "f32", (cout,))
+    data["b"] = as_dtype(uniform(rng, (cout,), -0.5, 0.5), "f32")
+    ot = (dtype, (batch, cout, oh, ow))
+    ids = []
+    o, (y,) = g.op("conv2d", [x, wt], [ot], stride=(stride, stride), pad=(pad, pad)); ids.append(o)
+    o, (y,) = g.op("bias_add", [y, b], [ot], axis=1); ids.append(o)
+    if relu:
+        o, (y,) = g.op("relu", [y], [ot]); ids.append(o)
+    g.group(ids)
+    ph, pw = conv_out(oh, 3, 2, 1), conv_out(ow, 3, 2, 1)
+    pt = (dtype, (batch, cout, ph, pw))
+    o, (y,) = g.op("maxpool2d", [y], [pt], kernel=(3, 3), stride=(2, 2), pad=(1, 1))
+    g.group([o])
+    if tail:
+        o, (y,) = g.op("neg", [y], [pt])
+        g.group([o])
+    g.output(y)
+    return g, data
+
+
 # --------------------------------------------------------------------------
 # the LeNet-shaped graph of the paper's decorator example (Fig. "dec_ex"): the
 # only model the paper writes down.  Shapes only: inputs are synthetic.
