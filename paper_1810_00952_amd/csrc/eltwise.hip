@@ -5,6 +5,7 @@
 #include <algorithm>
 
 #include "device_utils.h"
+#include <cstdlib>
 
 namespace rl {
 
@@ -21,6 +22,50 @@ __global__ __launch_bounds__(256) void eltwise_kernel(const EltwiseParams p)
     const Epilogue &e = p.epi;
     const int64_t vi = (int64_t)blockIdx.x * 256 + threadIdx.x;
     const bool nt = p.nt != 0;
+    constexpr int UU = 4;
+    if (p.v2 == UU) {
+        // the common form on large 2-byte tensors: four vectors per thread, 256 vectors apart (every load instruction
+        // still covers 64 consecutive vectors), all loads requested before anything is computed
+        const int64_t va = (int64_t)blockIdx.x * (256 * UU) + threadIdx.x;
+        float v[UU][8], tt[UU][8];
+        float b[UU];
+        bool live[UU];
+#pragma unroll
+        for (int u = 0; u < UU; ++u) {
+            const int64_t vv = va + 256 * u;
+            live[u] = vv < (p.n >> 3);
+            const int64_t i0 = (live[u] ? vv : 0) << 3;
+            if (nt) { load8_nt(p.x, p.x_dtype, i0, v[u]); load8_nt(e.t_ptr, e.t_dtype, i0, tt[u]); }
+            else { load8(p.x, p.x_dtype, i0, v[u]); load8(e.t_ptr, e.t_dtype, i0, tt[u]); }
+            b[u] = 0.0f;
+            if (e.has_bias) {
+                const uint32_t run = p.vec_per_run == 1 ? (uint32_t)vv : (__umulhi((uint32_t)vv, p.run_mul) >> p.run_sh);
+                b[u] = load_as_f32(e.bias_ptr, e.bias_dtype, (int)(run % (uint32_t)p.ch_count));
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < UU; ++u) {
+#pragma unroll
+            for (int k = 0; k < 8; ++k) v[u][k] = binop(e.t_op, v[u][k] + b[u], tt[u][k]);
+            uint64_t codes = e.rest_ops;
+            for (int st = 0; st < e.rest_n; ++st, codes >>= 8) {
+                const int op = (int)(codes & 0xff);
+                if (op == E_RELU) {
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) v[u][k] = v[u][k] > 0.0f ? v[u][k] : 0.0f;
+                } else {
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) v[u][k] = unary_step(op, v[u][k]);
+                }
+            }
+            if (live[u]) {
+                const int64_t i0 = (va + 256 * u) << 3;
+                if (nt) store8_nt(p.y, p.y_dtype, i0, v[u]);
+                else store8(p.y, p.y_dtype, i0, v[u]);
+            }
+        }
+        return;
+    }
     if (vi < (p.n >> 3)) {
         const int64_t i0 = vi << 3;
         int ch_hint = -1;
@@ -81,7 +126,19 @@ hipError_t launch_eltwise(const EltwiseParams &p0, hipStream_t s)
         p.runs = 1;
         make_fast_div((uint32_t)p.vec_per_run, p.run_mul, p.run_sh);
     }
-    const int64_t blocks = std::max<int64_t>(1, (nvec + 255) / 256);
+    // four vectors per thread: large 2-byte tensors in the common form without a ragged tail
+    p.v2 = 0;
+    {
+        Epilogue e = p.epi;
+        finalize_epilogue(e);
+        const bool common = e.simple && e.t_op >= 0 && (p.runs > 0) == (e.has_bias != 0);
+        // measured on 256x64x112x112: bf16 4.3-5.0 TB/s with one vector per thread, 5.4-5.7 with four; f32 is fastest
+        // (5.6 TB/s) with its one 32-byte run per thread
+        if (common && p.x_dtype == DT_BF16 && p.y_dtype == DT_BF16 && e.t_dtype == DT_BF16 && (p.n & 7) == 0 && p.n >= ((int64_t)32 << 20) &&
+            nvec < ((int64_t)1 << 31))
+            p.v2 = 4;
+    }
+    const int64_t blocks = std::max<int64_t>(1, p.v2 ? (nvec + 256 * p.v2 - 1) / (256 * p.v2) : (nvec + 255) / 256);
     if (blocks > 0x7fffffff) return hipErrorInvalidValue;
     p.nt = p.n >= ((int64_t)32 << 20);           // tens of MB per tensor: beyond what the caches would keep for a consumer
     hipLaunchKernelGGL(eltwise_kernel, dim3((unsigned)blocks), dim3(256), 0, s, p);

@@ -129,6 +129,7 @@ struct EltwiseParams {
     // filled by launch_eltwise.  runs > 0: a per-channel operand is constant over runs of vec_per_run
     // 8-element vectors; the run of vector v is v / vec_per_run by multiply-high (make_fast_div)
     int64_t vec_per_run; int32_t runs; uint32_t run_mul, run_sh; int32_t nt;   // nt: streaming accesses
+    int32_t v2;                         // 4: four vectors per thread, 256 vectors apart (large 2-byte tensors, common form); else 0
 };
 hipError_t launch_eltwise(const EltwiseParams &p, hipStream_t s);
 
