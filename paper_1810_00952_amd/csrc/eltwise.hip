@@ -407,9 +407,25 @@ __global__ __launch_bounds__(256) void pack_weight_kernel(const T *__restrict__ 
     }
 }
 
+// second copy of a 64 x (9 x 64) bf16 weight in the fragment order of the kernel that keeps it in registers
+__global__ __launch_bounds__(256) void pack_weight_frag64_kernel(const uint16_t *__restrict__ src, uint16_t *__restrict__ dst)
+{
+    const int idx = blockIdx.x * 256 + threadIdx.x;             // 64 * 576 elements, grid 144
+    const int e = idx & 7, lane = (idx >> 3) & 63, ks = (idx >> 9) & 3, ht = idx >> 11;
+    const int h = ht / 9, tap = ht - 9 * h;
+    const int o = 32 * h + (lane & 31), c = 16 * ks + 8 * (lane >> 5) + e;
+    dst[idx] = src[(o * 64 + c) * 9 + tap];
+}
+
 hipError_t launch_pack_weight(const void *src, void *dst, int32_t dtype, int32_t O, int32_t C, int32_t T, int32_t Kp,
                               int32_t perm_block, hipStream_t s)
 {
+    if (perm_block == -1) {
+        if (dtype != DT_BF16 || O != 64 || C != 64 || T != 9 || Kp != 576) return hipErrorInvalidValue;
+        hipLaunchKernelGGL(pack_weight_kernel<uint16_t>, dim3(grid_for((int64_t)O * Kp)), dim3(256), 0, s, (const uint16_t *)src, (uint16_t *)dst, O, C, T, Kp, 0);
+        hipLaunchKernelGGL(pack_weight_frag64_kernel, dim3(64 * 576 / 256), dim3(256), 0, s, (const uint16_t *)src, (uint16_t *)dst + 64 * 576);
+        return hipGetLastError();
+    }
     unsigned grid = grid_for((int64_t)O * Kp);
     if (dtype == DT_BF16) hipLaunchKernelGGL(pack_weight_kernel<uint16_t>, dim3(grid), dim3(256), 0, s, (const uint16_t *)src, (uint16_t *)dst, O, C, T, Kp, perm_block);
     else hipLaunchKernelGGL(pack_weight_kernel<float>, dim3(grid), dim3(256), 0, s, (const float *)src, (float *)dst, O, C, T, Kp, perm_block);

@@ -95,8 +95,10 @@ struct IgemmLaunch {
     int32_t dma;        // 1: K tiles go global -> LDS directly (needs avec, C and K multiples of the K tile, >= 2 tiles)
     int32_t lp;         // 1: pixel-on-lane variant with the register epilogue (bf16, [bias] [+residual] [relu])
     int32_t ws;         // 1 (with lp): weights-stationary persistent variant (N <= 64, K <= 576)
+    int32_t c64;        // 1 (with lp): 3x3 / stride 1 / pad 1, 64 -> 64 channels, image rows of at most 63 pixels (conv3x3_c64.hip)
 };
 hipError_t launch_igemm(const IgemmParams &p, const IgemmLaunch &l, hipStream_t s);
+hipError_t launch_conv3x3_c64(const IgemmParams &p, hipStream_t s);
 
 // ---- stem convolution + bias/ReLU + 3x3/2 max-pool in one kernel (stem_pool.hip) ----
 struct StemPoolParams {
@@ -154,6 +156,8 @@ hipError_t launch_nhwc_to_nchw(const void *src, void *dst, int32_t dtype, int32_
 // conv weight [O, C, KH*KW] -> [O, KH*KW, C] padded with zeros to Kp per row.
 // perm_block > 0: output row j holds source row gate*(O/4) + blk*(perm_block/4) + u
 // for j = blk*perm_block + gate*(perm_block/4) + u (LSTM gate interleave).
+// perm_block == -1 (bf16, O = C = 64, T = 9, Kp = 576 only): the plain matrix is followed by a second copy in MFMA
+// fragment order, dst2[(((h*9 + tap)*4 + ks)*64 + lane)*8 + e] = W[32h + lane%32][tap*64 + 16ks + 8*(lane/32) + e].
 hipError_t launch_pack_weight(const void *src, void *dst, int32_t dtype, int32_t O, int32_t C, int32_t T,
                               int32_t Kp, int32_t perm_block, hipStream_t s);
 // Few-channel stem convolutions (C <= 4, KW <= 8): the input is copied once into a zero-padded

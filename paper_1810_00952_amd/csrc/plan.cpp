@@ -309,6 +309,10 @@ struct Planner {
             pack.dtype = in_dt; pack.O = p.N; pack.C = p.K; pack.T = 1; pack.Kp = p.Kp; pack.perm_block = gates ? 64 : 0;
             p.ys_n = p.N; p.ys_p = p.N; p.ys_c = 1;
         }
+        // 3x3 bf16 weights from 64 to 64 channels carry, behind the matrix, a second copy in the fragment order of the
+        // kernel that keeps them in registers (whichever kernel a step ends up with, so that every user agrees)
+        const bool dual = an.kind == RL_OP_CONV2D && !stem && in_dt == RL_BF16 && p.N == 64 && p.C == 64 && p.KH == 3 && p.KW == 3 && p.Kp == p.K;
+        if (dual) pack.perm_block = -1;
         pack.bytes = (size_t)pack.O * pack.Kp * dtype_size(in_dt);
         // the vector-load kernel addresses its operands with 32-bit byte offsets and wants a K tile
         // (128 bytes per row) to lie inside one operand of a concatenation
@@ -318,6 +322,7 @@ struct Planner {
             p.x_bytes = (uint32_t)std::min(x_extent, lim - 1);
             p.x2_bytes = x2 >= 0 ? (uint32_t)std::min(bytes_of(x2), lim - 1) : 0;
             p.w_bytes = (uint32_t)std::min(pack.bytes, lim - 1);
+            if (dual) pack.bytes *= 2;
             // LDS-DMA variant: a K tile must lie inside one filter tap (and one concat operand)
             const int bke = 8 * KV;
             const size_t halo = (size_t)((int64_t)p.ph * p.xs_h + (int64_t)p.pw * p.xs_w) * dtype_size(in_dt);
@@ -331,6 +336,12 @@ struct Planner {
             // weights-stationary persistent variant: pays off when the weights leave LDS for a deep ring (K <= 320);
             // RELAYHIP_WS_ALL=1 also takes it up to K = 576, where its shallower ring is latency-bound
             il.ws = il.lp && p.N <= 64 && (p.K / bke <= 5 || (p.K / bke <= 9 && getenv("RELAYHIP_WS_ALL"))) && !getenv("RELAYHIP_NO_WS");
+            // 3x3 / stride 1 / pad 1 from 64 to 64 channels on rows of at most 63 pixels: weights in registers, every
+            // input pixel fetched once per region
+            il.c64 = il.lp && !stem && an.kind == RL_OP_CONV2D && p.C == 64 && p.N == 64 && p.KH == 3 && p.KW == 3 && p.sh == 1 && p.sw == 1 &&
+                     p.ph == 1 && p.pw == 1 && p.OH == p.H && p.OW == p.W && p.W <= 63 && p.Kp == p.K && p.ys_p == 64 && !getenv("RELAYHIP_NO_C64");
+            il.c64 = il.c64 && dual;
+            if (il.c64) { il.ws = 0; p.w_bytes = (uint32_t)pack.bytes; }
             p.y_bytes = vout >= 0 ? (uint32_t)std::min(bytes_of(vout), lim - 1) : 0;
             make_fast_div((uint32_t)p.OHW, p.div_ohw_mul, p.div_ohw_sh);
             make_fast_div((uint32_t)p.OW, p.div_ow_mul, p.div_ow_sh);
@@ -390,7 +401,7 @@ struct Planner {
         p.epi = chain.epi;
         static const char *tile_names[] = {"128x128", "128x64", "64x64"};
         std::string kname = std::string(an.kind == RL_OP_CONV2D ? "igemm_conv2d_" : "igemm_dense_") + (in_dt == RL_BF16 ? "bf16_" : "f32_") +
-                            (il.ws ? "128x64_ws" : tile_names[il.tile]) + (il.ws ? "" : il.lp ? "_lp" : il.avec ? (il.dma ? "_dma" : "") : "_gather") + (gates ? "_gates" : "");
+                            (il.c64 ? "3x3_c64" : il.ws ? "128x64_ws" : tile_names[il.tile]) + (il.c64 || il.ws ? "" : il.lp ? "_lp" : il.avec ? (il.dma ? "_dma" : "") : "_gather") + (gates ? "_gates" : "");
         Step &s = add_step(S_IGEMM, std::string(op_name(an.kind)) + "#" + std::to_string(ops[ai]), kname);
         s.group = gi;
         s.ig = p; s.il = il;

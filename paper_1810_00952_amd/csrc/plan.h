@@ -39,7 +39,7 @@ struct Step {
 };
 
 struct PackSpec {
-    int dtype = 0, O = 0, C = 0, T = 0, Kp = 0, perm_block = 0;
+    int dtype = 0, O = 0, C = 0, T = 0, Kp = 0, perm_block = 0;   // perm_block -1: matrix, then the 64x64x3x3 fragment-order copy
     int stem = 0, KH = 0, KW = 0;      // stem = 1: few-channel stem layout (launch_pack_weight_stem)
     size_t bytes = 0;
 };

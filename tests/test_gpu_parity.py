@@ -79,7 +79,8 @@ LP_CASES = [
 
 
 @pytest.mark.parametrize("case", LP_CASES, ids=[f"lp{i}" for i in range(len(LP_CASES))])
-def test_conv_group_internal_layout_bf16(case):
+def test_conv_group_internal_layout_bf16(case, monkeypatch):
+    monkeypatch.setenv("RELAYHIP_NO_C64", "1")       # the general kernel also on the shapes that have one of their own
     b, ci, co, h, w, k, s, p, res, relu = case
     spec, data = W.conv_group(b, ci, co, h, w, k, s, p, "bf16", residual=res, relu=relu, tail=True)
     from paper_1810_00952_amd import binding
@@ -91,6 +92,7 @@ def test_conv_group_internal_layout_bf16(case):
 def test_conv_weights_stationary_shallow_ring(monkeypatch):
     # K = 576 (9 weight tiles, 5-stage ring, residual through the ring): opt-in, the planner prefers the per-tile kernel there
     monkeypatch.setenv("RELAYHIP_WS_ALL", "1")
+    monkeypatch.setenv("RELAYHIP_NO_C64", "1")
     for case in [(16, 64, 64, 56, 56, 3, 1, 1, True, True), (3, 64, 48, 29, 31, 3, 1, 1, False, True)]:
         b, ci, co, h, w, k, s, p, res, relu = case
         spec, data = W.conv_group(b, ci, co, h, w, k, s, p, "bf16", residual=res, relu=relu, tail=True)
@@ -150,6 +152,40 @@ def test_stem_conv_with_maxpool_in_one_kernel(case, monkeypatch):
     two, _ = run_hip(spec, data)
     for vid in spec.outputs:
         np.testing.assert_array_equal(got[vid], two[vid])
+
+
+# 3x3 / stride 1 / pad 1 convolution from 64 to 64 channels with weights in registers: images smaller than a region,
+# exactly one region, regions that end inside an image row, rows of 1 and of 63 pixels (the widest it takes), one
+# image row, fewer and more regions than workgroups, every epilogue form it accepts.
+C64_CASES = [
+    # batch h   w  bias  residual relu
+    (2, 56, 56, True, True, True),
+    (1, 5, 7, True, False, True),
+    (5, 16, 16, True, True, False),
+    (3, 9, 63, False, True, True),
+    (2, 40, 1, True, False, False),
+    (2, 1, 40, False, False, False),
+    (1, 33, 31, False, False, True),
+    (70, 28, 30, True, True, True),
+]
+
+
+@pytest.mark.parametrize("case", C64_CASES, ids=[f"c64_{i}" for i in range(len(C64_CASES))])
+def test_conv3x3_c64_weights_in_registers(case, monkeypatch):
+    b, h, w, bias, res, relu = case
+    spec, data = W.conv_group(b, 64, 64, h, w, 3, 1, 1, "bf16", residual=res, relu=relu, tail=True, bias=bias)
+    from paper_1810_00952_amd import binding
+    desc = binding.Plan(binding.graph_from_spec(binding.Context(), spec)).describe()
+    assert any(st["kernel"] == "igemm_conv2d_bf16_3x3_c64" for st in desc["steps"]), [st["kernel"] for st in desc["steps"]]
+    print(f"conv3x3_c64 case {case}", flush=True)
+    got, _ = check_graph(spec, data, f"conv3x3_c64 {case}")
+    # the general kernel accumulates the same 16-element slices of K in the same order: same bits
+    monkeypatch.setenv("RELAYHIP_NO_C64", "1")
+    desc = binding.Plan(binding.graph_from_spec(binding.Context(), spec)).describe()
+    assert not any(st["kernel"] == "igemm_conv2d_bf16_3x3_c64" for st in desc["steps"])
+    gen, _ = run_hip(spec, data)
+    for vid in spec.outputs:
+        np.testing.assert_array_equal(got[vid], gen[vid])
 
 
 def test_conv_large_tiles_many_blocks():

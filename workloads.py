@@ -178,7 +178,7 @@ def mlp(batch=32, d_in=784, d_hidden=128, d_out=10, dtype="f32", config=1):
 # config 2: one fused conv2d group
 # --------------------------------------------------------------------------
 def conv_group(batch=1, cin=64, cout=64, h=56, w=56, k=3, stride=1, pad=1, dtype="f32",
-               residual=False, relu=True, config=2, tail=False, make_x=True):
+               residual=False, relu=True, config=2, tail=False, make_x=True, bias=True):
     """One fused conv2d group.  tail=True appends a second group (neg) so that the
     conv group's result is an intermediate the plan keeps in its private layout.
     make_x=False leaves x out of the data (the caller supplies it); weights and bias then
@@ -192,12 +192,14 @@ def conv_group(batch=1, cin=64, cout=64, h=56, w=56, k=3, stride=1, pad=1, dtype
         data["x"] = as_dtype(normal(rng, (batch, cin, h, w)), dtype)
     wt = g.param("w", dtype, (cout, cin, k, k))
     data["w"] = as_dtype(kaiming_normal(rng, (cout, cin, k, k), cin * k * k), dtype)
-    b = g.param("b", "f32", (cout,))
-    data["b"] = as_dtype(uniform(rng, (cout,), -0.1, 0.1), "f32")
+    if bias:
+        b = g.param("b", "f32", (cout,))
+        data["b"] = as_dtype(uniform(rng, (cout,), -0.1, 0.1), "f32")
     ot = (dtype, (batch, cout, oh, ow))
     ids = []
     o, (y,) = g.op("conv2d", [x, wt], [ot], stride=(stride, stride), pad=(pad, pad)); ids.append(o)
-    o, (y,) = g.op("bias_add", [y, b], [ot], axis=1); ids.append(o)
+    if bias:
+        o, (y,) = g.op("bias_add", [y, b], [ot], axis=1); ids.append(o)
     if residual:
         r = g.input("r", dtype, ot[1])
         data["r"] = as_dtype(normal(rng, ot[1]), dtype)
