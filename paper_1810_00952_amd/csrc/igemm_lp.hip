@@ -93,15 +93,17 @@ constexpr uint32_t OOB = 0x80000000u;
 }  // namespace
 
 template <int BM, int BN, int WGM, int WGN, int STAGES>
-__global__ __launch_bounds__(256) void igemm_lp_kernel(const IgemmParams p)
+__global__ __launch_bounds__(WGM * WGN * 64) void igemm_lp_kernel(const IgemmParams p)
 {
 #if defined(__HIP_DEVICE_COMPILE__)   // the host pass only needs the launch stub; the body uses gfx950-only builtins
-    static_assert(WGM * WGN == 4, "four waves");
+    constexpr int NW = WGM * WGN;                   // waves: four (one per SIMD) or eight (two per SIMD)
+    static_assert(NW == 4 || NW == 8, "four or eight waves");
     static_assert(STAGES == 3 || STAGES == 4, "three or four stages");
     constexpr int BKE = 64;                         // K elements per tile (128 bytes per row)
     constexpr int WTM = BM / WGM, WTN = BN / WGN;   // wave tile: pixels x channels
     constexpr int TM = WTM / 32, TN = WTN / 32;
-    constexpr int AG = BM / 32, BG = BN / 32;       // 8-row direct-load groups per wave
+    constexpr int AG = BM / (8 * NW), BG = BN / (8 * NW);   // 8-row direct-load groups per wave
+    static_assert(AG >= 1 && BG >= 1, "every wave requests rows of both operands");
     constexpr int LPT = AG + BG;                    // direct loads per wave per tile
     constexpr int A_BYTES = BM * 128, B_BYTES = BN * 128, STAGE = A_BYTES + B_BYTES;
 
@@ -372,7 +374,7 @@ __global__ __launch_bounds__(256) void igemm_lp_kernel(const IgemmParams p)
     // the barrier is crossed; from there on each wave works alone in its own piece of the stages.
     wg_barrier();
     constexpr int WBYTES = WTM * WTN * 4, ROWB = WTN * 4;
-    static_assert((4 + STAGES - 1) / STAGES * WBYTES <= STAGE, "a stage must hold its waves' parked tiles");
+    static_assert((NW + STAGES - 1) / STAGES * WBYTES <= STAGE, "a stage must hold its waves' parked tiles");
     const int wsel = wave % STAGES;
     unsigned char *park = (wsel == 0 ? st0 : wsel == 1 ? st1 : wsel == 2 ? st2 : st3) + (wave / STAGES) * WBYTES;
 #pragma unroll
@@ -416,7 +418,7 @@ __global__ __launch_bounds__(256) void igemm_lp_kernel(const IgemmParams p)
 }
 
 #define RL_INST(BM, BN, WGM, WGN, ST) template __global__ void igemm_lp_kernel<BM, BN, WGM, WGN, ST>(const IgemmParams);
-RL_INST(128, 128, 2, 2, 4) RL_INST(128, 64, 4, 1, 3) RL_INST(128, 64, 4, 1, 4) RL_INST(64, 64, 2, 2, 4)
+RL_INST(128, 128, 2, 4, 4) RL_INST(128, 64, 4, 1, 3) RL_INST(128, 64, 4, 1, 4) RL_INST(64, 64, 2, 2, 4)
 #undef RL_INST
 
 template <int BM, int BN, int WGM, int WGN, int STAGES>
@@ -427,7 +429,7 @@ static hipError_t launch_lp(const IgemmParams &p0, hipStream_t s)
     p.nblk_n = (p.N + BN - 1) / BN;
     int64_t nblk = (int64_t)p.nblk_m * p.nblk_n;
     if (nblk <= 0 || nblk > 0x7fffffff) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((igemm_lp_kernel<BM, BN, WGM, WGN, STAGES>), dim3((unsigned)nblk), dim3(256), 0, s, p);
+    hipLaunchKernelGGL((igemm_lp_kernel<BM, BN, WGM, WGN, STAGES>), dim3((unsigned)nblk), dim3(WGM * WGN * 64), 0, s, p);
     return hipGetLastError();
 }
 
@@ -435,7 +437,10 @@ hipError_t launch_igemm_lp(const IgemmParams &p, const IgemmLaunch &l, hipStream
 {
     if (p.in_dtype != DT_BF16 || p.y_dtype != DT_BF16 || l.gates || p.x2) return hipErrorInvalidValue;
     switch (l.tile) {
-    case TILE_128x128: return launch_lp<128, 128, 2, 2, 4>(p, s);
+    case TILE_128x128:
+        // eight waves of 64 pixels x 32 channels, two per SIMD: one wave's fragment reads and request stalls are
+        // covered by the other's MFMAs (measured 4% faster than four waves of 64 x 64 on the ResNet shapes)
+        return launch_lp<128, 128, 2, 4, 4>(p, s);
     case TILE_128x64:
         // few workgroups (at most one per CU anyway): four stages, so fragments are prefetched across the barrier;
         // many: three stages, so two workgroups share a CU and cover each other's barriers and epilogues
