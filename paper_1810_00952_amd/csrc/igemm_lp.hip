@@ -418,7 +418,7 @@ __global__ __launch_bounds__(WGM * WGN * 64) void igemm_lp_kernel(const IgemmPar
 }
 
 #define RL_INST(BM, BN, WGM, WGN, ST) template __global__ void igemm_lp_kernel<BM, BN, WGM, WGN, ST>(const IgemmParams);
-RL_INST(128, 128, 2, 4, 4) RL_INST(128, 64, 4, 1, 3) RL_INST(128, 64, 4, 1, 4) RL_INST(64, 64, 2, 2, 4)
+RL_INST(128, 128, 2, 4, 4) RL_INST(256, 128, 4, 2, 3) RL_INST(128, 64, 4, 1, 3) RL_INST(128, 64, 4, 1, 4) RL_INST(64, 64, 2, 2, 4)
 #undef RL_INST
 
 template <int BM, int BN, int WGM, int WGN, int STAGES>
@@ -441,6 +441,9 @@ hipError_t launch_igemm_lp(const IgemmParams &p, const IgemmLaunch &l, hipStream
         // eight waves of 64 pixels x 32 channels, two per SIMD: one wave's fragment reads and request stalls are
         // covered by the other's MFMAs (measured 4% faster than four waves of 64 x 64 on the ResNet shapes)
         return launch_lp<128, 128, 2, 4, 4>(p, s);
+    case TILE_256x128:
+        // eight waves of 64 x 64, two per SIMD, three stages of 48 KB
+        return launch_lp<256, 128, 4, 2, 3>(p, s);
     case TILE_128x64:
         // few workgroups (at most one per CU anyway): four stages, so fragments are prefetched across the barrier;
         // many: three stages, so two workgroups share a CU and cover each other's barriers and epilogues

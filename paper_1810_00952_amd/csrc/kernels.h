@@ -87,7 +87,7 @@ struct IgemmParams {
 // q = n / d for n < 2^31:  d == 1 ? n : (mulhi(n, mul) >> sh)
 void make_fast_div(uint32_t d, uint32_t &mul, uint32_t &sh);
 
-enum IgemmTile { TILE_128x128 = 0, TILE_128x64 = 1, TILE_64x64 = 2, TILE_COUNT };
+enum IgemmTile { TILE_128x128 = 0, TILE_128x64 = 1, TILE_64x64 = 2, TILE_256x128 = 3 /* pixel-on-lane variant only */, TILE_COUNT };
 struct IgemmLaunch {
     int32_t tile;       // IgemmTile
     int32_t avec;       // 1: A rows are 16-byte-vector loadable (channel-contiguous, aligned)

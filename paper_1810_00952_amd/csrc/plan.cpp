@@ -369,6 +369,8 @@ struct Planner {
             p.h_dtype = T(g.ops[ops.back()].out[1]).dtype;
         } else if (!il.avec) {
             il.tile = TILE_64x64;
+        } else if (il.lp && p.N > 64 && nblk(256, 128) >= 190 && !getenv("RELAYHIP_NO_LP_256")) {
+            il.tile = TILE_256x128;        // a quarter fewer operand bytes per MFMA than 128x128
         } else if (p.N > 64 && nblk(128, 128) >= 192) {
             il.tile = TILE_128x128;
         } else if (nblk(128, 64) >= 192) {
@@ -399,7 +401,7 @@ struct Planner {
             bytes += (double)bytes_of(vout);
         }
         p.epi = chain.epi;
-        static const char *tile_names[] = {"128x128", "128x64", "64x64"};
+        static const char *tile_names[] = {"128x128", "128x64", "64x64", "256x128"};
         std::string kname = std::string(an.kind == RL_OP_CONV2D ? "igemm_conv2d_" : "igemm_dense_") + (in_dt == RL_BF16 ? "bf16_" : "f32_") +
                             (il.c64 ? "3x3_c64" : il.ws ? "128x64_ws" : tile_names[il.tile]) + (il.c64 || il.ws ? "" : il.lp ? "_lp" : il.avec ? (il.dma ? "_dma" : "") : "_gather") + (gates ? "_gates" : "");
         Step &s = add_step(S_IGEMM, std::string(op_name(an.kind)) + "#" + std::to_string(ops[ai]), kname);

@@ -75,6 +75,7 @@ LP_CASES = [
     (1, 192, 64, 5, 5, 5, 1, 2, False, True),        # 25 taps, 3 K tiles per tap
     (2, 256, 512, 7, 7, 3, 1, 1, True, True),        # image smaller than a tile row block
     (40, 64, 64, 30, 30, 1, 1, 0, True, True),       # 1x1, M = 36000: many tiles, K = one tile
+    (17, 64, 136, 55, 55, 3, 1, 1, True, True),      # 256x128 tile (eight waves), ragged M tail, N tail of 8
 ]
 
 
