@@ -347,6 +347,7 @@ hipError_t launch_igemm_ws(const IgemmParams &p, hipStream_t s);
 hipError_t launch_igemm(const IgemmParams &p, const IgemmLaunch &l, hipStream_t s)
 {
     if (l.lp && l.c64) return launch_conv3x3_c64(p, s);
+    if (l.lp && l.run) return launch_conv3x3_run(p, l, s);
     if (l.lp && l.ws) return launch_igemm_ws(p, s);
     if (l.lp) return launch_igemm_lp(p, l, s);
     if (l.avec && l.dma) return launch_igemm_dma(p, l, s);

@@ -379,6 +379,12 @@ struct Planner {
             il.tile = TILE_64x64;
         }
 
+        // 3x3 / stride 1 / pad 1 on short image rows with whole 64-channel slices: the nine taps of a slice are read
+        // from one copy of the input rows (needs one of the larger tiles)
+        il.run = il.lp && !il.c64 && !il.ws && !stem && an.kind == RL_OP_CONV2D && p.KH == 3 && p.KW == 3 && p.sh == 1 && p.sw == 1 && p.ph == 1 &&
+                 p.pw == 1 && p.OH == p.H && p.OW == p.W && p.W <= 30 && p.C % 64 == 0 && p.Kp == p.K && il.tile != TILE_64x64 &&
+                 !getenv("RELAYHIP_NO_RUN");
+
         double bytes = (double)bytes_of(x) + (x2 >= 0 ? (double)bytes_of(x2) : 0.0) + (double)bytes_of(wv);
         std::vector<int> eslots(RL_EPI_MAX_PTRS, -1);
         {
@@ -403,7 +409,7 @@ struct Planner {
         p.epi = chain.epi;
         static const char *tile_names[] = {"128x128", "128x64", "64x64", "256x128"};
         std::string kname = std::string(an.kind == RL_OP_CONV2D ? "igemm_conv2d_" : "igemm_dense_") + (in_dt == RL_BF16 ? "bf16_" : "f32_") +
-                            (il.c64 ? "3x3_c64" : il.ws ? "128x64_ws" : tile_names[il.tile]) + (il.c64 || il.ws ? "" : il.lp ? "_lp" : il.avec ? (il.dma ? "_dma" : "") : "_gather") + (gates ? "_gates" : "");
+                            (il.c64 ? "3x3_c64" : il.ws ? "128x64_ws" : tile_names[il.tile]) + (il.c64 || il.ws ? "" : il.run ? "_run" : il.lp ? "_lp" : il.avec ? (il.dma ? "_dma" : "") : "_gather") + (gates ? "_gates" : "");
         Step &s = add_step(S_IGEMM, std::string(op_name(an.kind)) + "#" + std::to_string(ops[ai]), kname);
         s.group = gi;
         s.ig = p; s.il = il;

@@ -82,6 +82,7 @@ LP_CASES = [
 @pytest.mark.parametrize("case", LP_CASES, ids=[f"lp{i}" for i in range(len(LP_CASES))])
 def test_conv_group_internal_layout_bf16(case, monkeypatch):
     monkeypatch.setenv("RELAYHIP_NO_C64", "1")       # the general kernel also on the shapes that have one of their own
+    monkeypatch.setenv("RELAYHIP_NO_RUN", "1")
     b, ci, co, h, w, k, s, p, res, relu = case
     spec, data = W.conv_group(b, ci, co, h, w, k, s, p, "bf16", residual=res, relu=relu, tail=True)
     from paper_1810_00952_amd import binding
@@ -187,6 +188,36 @@ def test_conv3x3_c64_weights_in_registers(case, monkeypatch):
     gen, _ = run_hip(spec, data)
     for vid in spec.outputs:
         np.testing.assert_array_equal(got[vid], gen[vid])
+
+
+# 3x3 / stride 1 / pad 1 convolutions on short image rows, nine taps read from one copy of the input rows: each of
+# its three tiles, one, two, three and four 64-channel slices, rows of 7 to 30 pixels, images smaller than a tile
+# (so that a tile spans several), ragged M and N tails, every epilogue form.
+RUN_CASES = [
+    # batch cin cout h   w  bias  residual relu   tile
+    (16, 128, 128, 28, 28, True, True, True, "128x64"),
+    (196, 192, 72, 7, 9, True, False, False, "128x64"),
+    (140, 64, 128, 3, 30, False, True, True, "128x64"),
+    (16, 128, 256, 28, 28, True, True, True, "128x128"),
+    (64, 256, 256, 14, 14, False, False, True, "128x128"),
+    (63, 128, 128, 28, 28, True, True, True, "256x128"),
+]
+
+
+@pytest.mark.parametrize("case", RUN_CASES, ids=[f"run{i}" for i in range(len(RUN_CASES))])
+def test_conv3x3_taps_from_one_copy_of_the_rows(case, monkeypatch):
+    b, ci, co, h, w, bias, res, relu, tile = case
+    spec, data = W.conv_group(b, ci, co, h, w, 3, 1, 1, "bf16", residual=res, relu=relu, tail=True, bias=bias)
+    from paper_1810_00952_amd import binding
+    desc = binding.Plan(binding.graph_from_spec(binding.Context(), spec)).describe()
+    assert any(st["kernel"] == f"igemm_conv2d_bf16_{tile}_run" for st in desc["steps"]), [st["kernel"] for st in desc["steps"]]
+    print(f"conv3x3 run case {case}", flush=True)
+    got, _ = check_graph(spec, data, f"conv3x3 run {case}")
+    # against the general kernel: same products, another summation order
+    monkeypatch.setenv("RELAYHIP_NO_RUN", "1")
+    gen, _ = run_hip(spec, data)
+    for vid in spec.outputs:
+        assert_close(got[vid], gen[vid], "bf16", f"run vs general {case}")
 
 
 def test_conv_large_tiles_many_blocks():
