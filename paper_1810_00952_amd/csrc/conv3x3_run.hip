@@ -221,6 +221,14 @@ __global__ __launch_bounds__(WGM * WGN * 64) void conv3x3_run_kernel(const Igemm
               (live && k < RUN_LOADS) ? r_voff[k < RUN_LOADS ? k : 0] : OOB, live ? (uint32_t)(s * 128) : 0u);
     };
 
+    // ---- prologue: run of slice 0, weight tiles 0, 1, 2 (on their way while the lane state below is set up)
+#pragma unroll
+    for (int k = 0; k < RUN_LOADS; ++k) issue_r(k, 0, 0, true);
+#pragma unroll
+    for (int u = 0; u < 3; ++u)
+#pragma unroll
+        for (int d = 0; d < BG; ++d) issue_b(d, u, 0, u, u < NT);
+
     // ---- the lane's pixels: fragment base address in a run buffer, tap validity
     uint32_t fa[TM], tmask[TM];
 #pragma unroll
@@ -240,13 +248,6 @@ __global__ __launch_bounds__(WGM * WGN * 64) void conv3x3_run_kernel(const Igemm
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) fb[ks] = (uint32_t)(B_OFF + (wn * WTN + frow) * 128 + (((2 * ks + fhalf) ^ ((frow >> 1) & 7)) << 4));
 
-    // ---- prologue: run of slice 0, weight tiles 0, 1, 2
-#pragma unroll
-    for (int k = 0; k < RUN_LOADS; ++k) issue_r(k, 0, 0, true);
-#pragma unroll
-    for (int u = 0; u < 3; ++u)
-#pragma unroll
-        for (int d = 0; d < BG; ++d) issue_b(d, u, 0, u, u < NT);
     wait_vm<BG>();                                  // all but weight tile 2
     wg_barrier();
 
