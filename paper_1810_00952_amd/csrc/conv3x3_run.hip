@@ -40,6 +40,7 @@
 // activations, output rows contiguous in n with N a multiple of 8, tensors
 // below 2 GiB.
 #include "device_utils.h"
+#include <cstdlib>
 
 namespace rl {
 
@@ -102,7 +103,9 @@ constexpr int PITCH = 144;                        // bytes per run pixel in LDS
 
 }  // namespace
 
-template <int BM, int BN, int WGM, int WGN>
+// NB: weight-tile stages.  Weight tile u + NB - 1 is requested while tile u is multiplied, and at the end of a tile
+// the requests of the last NB - 3 tiles may still be in flight: more stages, more time for a request to return.
+template <int BM, int BN, int WGM, int WGN, int NB>
 __global__ __launch_bounds__(WGM * WGN * 64) void conv3x3_run_kernel(const IgemmParams p)
 {
 #if defined(__HIP_DEVICE_COMPILE__)   // the host pass only needs the launch stub; the body uses gfx950-only builtins
@@ -112,12 +115,13 @@ __global__ __launch_bounds__(WGM * WGN * 64) void conv3x3_run_kernel(const Igemm
     constexpr int RUN_LOADS = ((RUN_PIX * 9 + 63) / 64 + NW - 1) / NW;   // direct loads (64 units each) per wave per run
     constexpr int RUN_BYTES = RUN_LOADS * NW * 1024;
     constexpr int BG = BN / (8 * NW);                             // weight-tile loads (8 rows each) per wave per K tile
-    constexpr int B_BYTES = BN * 128, NB = 4;
+    constexpr int B_BYTES = BN * 128;
     constexpr int B_OFF = 2 * RUN_BYTES, LDS_BYTES = B_OFF + NB * B_BYTES;
     constexpr int PER_TILE = BG + 1;                              // requests per wave per K tile: the weights, one of the next run
+    constexpr int FLY = NB - 3;                                   // tiles whose requests may be in flight at the end of a tile
     constexpr int NRD = TM + TN, NMM = TM * TN;                   // fragment reads and MFMAs per k-step
-    static_assert(TM >= 1 && TN >= 1 && BG >= 1 && PER_TILE <= 4, "tile geometry");
-    static_assert(RUN_LOADS <= 7, "the next run is requested in the first seven K tiles of a slice");
+    static_assert(TM >= 1 && TN >= 1 && BG >= 1 && PER_TILE <= 4 && NB >= 4 && NB <= 6, "tile geometry");
+    static_assert(RUN_LOADS <= 8 - FLY, "the next run is requested in the first K tiles of a slice and must have landed by the last");
     static_assert((RUN_LOADS * NW - 1) * 1024 >= RUN_PIX * PITCH, "the run buffer's last KB is the zero operand");
     static_assert(LDS_BYTES <= 160 * 1024, "LDS");
     __shared__ __attribute__((aligned(1024))) unsigned char lds[LDS_BYTES];
@@ -221,13 +225,18 @@ __global__ __launch_bounds__(WGM * WGN * 64) void conv3x3_run_kernel(const Igemm
               (live && k < RUN_LOADS) ? r_voff[k < RUN_LOADS ? k : 0] : OOB, live ? (uint32_t)(s * 128) : 0u);
     };
 
-    // ---- prologue: run of slice 0, weight tiles 0, 1, 2 (on their way while the lane state below is set up)
+    // ---- prologue: run of slice 0, weight tiles 0 .. NB-2 (on their way while the lane state below is set up)
 #pragma unroll
     for (int k = 0; k < RUN_LOADS; ++k) issue_r(k, 0, 0, true);
+    // (each weight tile goes out with as many requests as a K tile of the loop issues, padded with ones that only
+    // count, so that the loop's wait counts hold from its first tile on)
 #pragma unroll
-    for (int u = 0; u < 3; ++u)
+    for (int u = 0; u < NB - 1; ++u) {
 #pragma unroll
         for (int d = 0; d < BG; ++d) issue_b(d, u, 0, u, u < NT);
+#pragma unroll
+        for (int d = BG; d < PER_TILE; ++d) issue_r(RUN_LOADS, 0, 0, false);
+    }
 
     // ---- the lane's pixels: fragment base address in a run buffer, tap validity
     uint32_t fa[TM], tmask[TM];
@@ -248,7 +257,7 @@ __global__ __launch_bounds__(WGM * WGN * 64) void conv3x3_run_kernel(const Igemm
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) fb[ks] = (uint32_t)(B_OFF + (wn * WTN + frow) * 128 + (((2 * ks + fhalf) ^ ((frow >> 1) & 7)) << 4));
 
-    wait_vm<BG>();                                  // all but weight tile 2
+    wait_vm<FLY * PER_TILE>();                      // all but weight tiles 2 .. NB-2
     wg_barrier();
 
     f32x16 acc[TM][TN];
@@ -277,19 +286,19 @@ __global__ __launch_bounds__(WGM * WGN * 64) void conv3x3_run_kernel(const Igemm
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
     __builtin_amdgcn_sched_barrier(0);
 
+    int st_cur = 0;                                 // weight stage of the current K tile: u % NB
 #pragma unroll 1
     for (int s = 0; s < nsl; ++s) {
         const uint32_t rb = (uint32_t)((s & 1) * RUN_BYTES), rbn = (uint32_t)(((s + 1) & 1) * RUN_BYTES);
         const bool more = s + 1 < nsl;
 #pragma unroll
         for (int tp = 0; tp < 9; ++tp) {
-            // K tile u = 9s + tp lives in weight stage u % 4 = (s + tp) % 4; on entry the barrier of this tile has been
-            // passed, the weight tiles u and u+1 and this slice's run have landed, and the fragments of k-step 0 are
-            // in register set 0
-            const int st_cur = (s + tp) & 3;
-            const uint32_t bcur = (uint32_t)(st_cur * B_BYTES), bnext = (uint32_t)(((st_cur + 1) & 3) * B_BYTES);
-            // this tile's requests: weight tile u + 3 into the stage tile u - 1 has left, one piece of the next run
-            const int tb = (tp + 3) % 9, sb = s + (tp + 3) / 9;
+            // K tile u = 9s + tp; on entry the barrier of this tile has been passed, the weight tiles u and u+1 and
+            // this slice's run have landed, and the fragments of k-step 0 are in register set 0
+            const int st_next = st_cur + 1 == NB ? 0 : st_cur + 1, st_iss = st_cur == 0 ? NB - 1 : st_cur - 1;
+            const uint32_t bcur = (uint32_t)(st_cur * B_BYTES), bnext = (uint32_t)(st_next * B_BYTES);
+            // this tile's requests: weight tile u + NB - 1 into the stage tile u - 1 has left, one piece of the next run
+            const int tb = (tp + NB - 1) % 9, sb = s + (tp + NB - 1) / 9;
             const bool blive = sb < nsl;
 #pragma unroll
             for (int ks = 0; ks < 4; ++ks) {
@@ -306,7 +315,7 @@ __global__ __launch_bounds__(WGM * WGN * 64) void conv3x3_run_kernel(const Igemm
                         if (r < NRD) { frag_read(r, set ^ 1, ks == 3 ? 0 : ks + 1, ks == 3 ? bnext : bcur, ks == 3 ? a0n : a0); ++r; }
                         // ... and, behind the first MFMA of k-step d, request d of the tile
                         if (i == 0 && j == 0) {
-                            if (ks < BG) issue_b(ks, (st_cur + 3) & 3, sb, tb, blive);
+                            if (ks < BG) issue_b(ks, st_iss, sb, tb, blive);
                             else if (ks == BG) issue_r(tp, (s + 1) & 1, s + 1, more);
                             if (ks == 2) tap_addr(tp == 8 ? 0 : tp + 1, tp == 8 ? rbn : rb, a0n);   // the next tile's pixels
                         }
@@ -318,7 +327,8 @@ __global__ __launch_bounds__(WGM * WGN * 64) void conv3x3_run_kernel(const Igemm
             }
 #pragma unroll
             for (int i = 0; i < TM; ++i) a0[i] = a0n[i];
-            wait_vm<PER_TILE>();                    // everything but this tile's own requests: weight tile u + 2 has landed
+            st_cur = st_next;
+            wait_vm<FLY * PER_TILE>();              // everything but the last FLY tiles' requests: weight tile u + 2 has landed
             wg_barrier();
         }
     }
@@ -369,7 +379,267 @@ __global__ __launch_bounds__(WGM * WGN * 64) void conv3x3_run_kernel(const Igemm
 #endif
 }
 
-template <int BM, int BN, int WGM, int WGN>
+// The same contraction with K split over the waves: four waves, each multiplying the *whole* BM x BN tile for one of
+// the four k-steps of every K tile (BM/32 + BN/32 fragment reads for BM/32 * BN/32 MFMAs: 0.75 per MFMA for 128x64,
+// where a 32x32 wave tile needs two), and the four partial accumulator tiles summed through LDS at the end.
+// Needs an even number of channel slices (the two fragment register sets alternate from K tile to K tile and a
+// slice has nine).
+template <int BM, int BN, int NB>
+__global__ __launch_bounds__(256) void conv3x3_run_ks_kernel(const IgemmParams p)
+{
+#if defined(__HIP_DEVICE_COMPILE__)   // the host pass only needs the launch stub; the body uses gfx950-only builtins
+    constexpr int NW = 4;
+    constexpr int TM = BM / 32, TN = BN / 32;
+    constexpr int RUN_PIX = BM + 2 * RUN_W_MAX + 2;
+    constexpr int RUN_LOADS = ((RUN_PIX * 9 + 63) / 64 + NW - 1) / NW;
+    constexpr int RUN_BYTES = RUN_LOADS * NW * 1024;
+    constexpr int BG = BN / (8 * NW);
+    constexpr int B_BYTES = BN * 128;
+    constexpr int B_OFF = 2 * RUN_BYTES;
+    constexpr int PBYTES = BM * BN * 4;                           // one partial accumulator tile, fp32
+    constexpr int LDS_BYTES = NW * PBYTES > B_OFF + NB * B_BYTES ? NW * PBYTES : B_OFF + NB * B_BYTES;
+    constexpr int FLY = NB - 3;                                   // tiles whose requests may be in flight at the end of a tile
+    constexpr int NR = (RUN_LOADS + 7 - FLY) / (8 - FLY);         // pieces of the next run requested per K tile
+    constexpr int PER_TILE = BG + NR;
+    constexpr int NRD = TM + TN, NMM = TM * TN;
+    static_assert(BN == 64, "the finishing pass assumes rows of 64 channels");
+    static_assert(BG >= 1 && 2 * PER_TILE <= NMM && NRD <= NMM - 1 && NB >= 4 && NB <= 6, "tile geometry");
+    static_assert(NR * (8 - FLY) >= RUN_LOADS, "the next run is requested in the first K tiles of a slice and must have landed by the last");
+    static_assert((RUN_LOADS * NW - 1) * 1024 >= RUN_PIX * PITCH, "the run buffer's last KB is the zero operand");
+    static_assert(LDS_BYTES <= 160 * 1024, "LDS");
+    __shared__ __attribute__((aligned(1024))) unsigned char lds[LDS_BYTES];
+
+    const int t = threadIdx.x;
+    const int lane = t & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(t >> 6);     // also the wave's k-step
+    const int W = p.W, HW = p.H * p.W, C = p.C;
+
+    const int nblk = p.nblk_m * p.nblk_n;
+    int bid = blockIdx.x;
+    {
+        const int per = nblk / NUM_XCD, main = per * NUM_XCD;
+        if (bid < main) bid = (bid % NUM_XCD) * per + bid / NUM_XCD;
+    }
+    const int bm = bid / p.nblk_n, bn = bid - bm * p.nblk_n;
+    const int m0 = bm * BM, n0 = bn * BN;
+
+    const u32x4 dx = make_desc(p.x, p.x_bytes);
+    const u32x4 dw = make_desc(p.w, p.w_bytes);
+    const uint32_t lds_a = lds_addr_of(lds);
+    const int frow = lane & 31, fhalf = lane >> 5;
+
+    // ---- operands of the finishing pass first: thread t finishes, in pass q, row 32q + t/8, channels 8*(t%8) .. +7
+    const Epilogue &e = p.epi;
+    constexpr int NPASS = BM / 32;
+    const int rr = t >> 3, pp = t & 7;
+    f32x4 bias_lo, bias_hi;
+    u32x4 res_r[NPASS];
+    uint32_t y_off[NPASS];
+    const uint32_t y_bytes = p.y_bytes;
+    {
+        const bool has_res = e.t_op >= 0;
+        const rsrc_t rb = make_rsrc(e.has_bias ? e.bias_ptr : p.w, e.has_bias ? (uint32_t)p.N * 4u : 0u);
+        const rsrc_t rres = make_rsrc(has_res ? e.t_ptr : p.w, has_res ? y_bytes : 0u);
+        const int n = n0 + 8 * pp;
+        bias_lo = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rb, n < p.N ? (uint32_t)n * 4u : OOB, 0, 0));
+        bias_hi = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rb, n < p.N ? (uint32_t)n * 4u + 16u : OOB, 0, 0));
+#pragma unroll
+        for (int q = 0; q < NPASS; ++q) {
+            const int m = m0 + 32 * q + rr;
+            y_off[q] = (m < p.M && n < p.N) ? (uint32_t)(((int64_t)m * p.ys_p + n) * 2) : OOB;
+            res_r[q] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(rres, y_off[q], 0, 0));
+        }
+    }
+
+    // ---- request state (as in the kernel above)
+    const int run_len = BM + 2 * W + 2;
+    uint32_t r_voff[RUN_LOADS];
+#pragma unroll
+    for (int k = 0; k < RUN_LOADS; ++k) {
+        const uint32_t u = (uint32_t)(64 * (RUN_LOADS * wave + k) + lane);
+        const uint32_t px = u / 9u, c = u - 9u * px;
+        const int q = m0 - W - 1 + (int)px;
+        const bool ok = (int)px < run_len && q >= 0 && q < p.M;
+        r_voff[k] = ok ? (uint32_t)((int64_t)q * C * 2) + (c < 8u ? c : 7u) * 16u : OOB;
+    }
+    uint32_t b_voff[BG];
+    {
+        const int r8 = lane >> 3, pos = lane & 7;
+#pragma unroll
+        for (int j = 0; j < BG; ++j) {
+            const int row = wave * 8 * BG + 8 * j + r8;
+            const int chunk = pos ^ ((row >> 1) & 7);
+            int n = n0 + row;
+            if (n > p.N - 1) n = p.N - 1;
+            b_voff[j] = (uint32_t)((int64_t)n * p.Kp * 2) + chunk * 16;
+        }
+    }
+    const int nsl = C / 64, NT = nsl * 9;
+    auto issue_b = [&](int d, int stage, int s, int tp, bool live) {
+        dma16(dw, lds_a + B_OFF + stage * B_BYTES + (wave * BG + d) * 1024, live ? b_voff[d < BG ? d : 0] : OOB, live ? (uint32_t)((tp * C + 64 * s) * 2) : 0u);
+    };
+    auto issue_r = [&](int k, int buf, int s, bool live) {
+        dma16(dx, lds_a + buf * RUN_BYTES + (k < RUN_LOADS ? RUN_LOADS * wave + k : RUN_LOADS * NW - 1) * 1024,
+              (live && k < RUN_LOADS) ? r_voff[k < RUN_LOADS ? k : 0] : OOB, live ? (uint32_t)(s * 128) : 0u);
+    };
+#pragma unroll
+    for (int k = 0; k < RUN_LOADS; ++k) issue_r(k, 0, 0, true);
+    // (each weight tile goes out with as many requests as a K tile of the loop issues, padded with ones that only
+    // count, so that the loop's wait counts hold from its first tile on)
+#pragma unroll
+    for (int u = 0; u < NB - 1; ++u) {
+#pragma unroll
+        for (int d = 0; d < BG; ++d) issue_b(d, u, 0, u, u < NT);
+#pragma unroll
+        for (int d = BG; d < PER_TILE; ++d) issue_r(RUN_LOADS, 0, 0, false);
+    }
+
+    // ---- the lane's pixels (one per 32-row tile of the block): fragment address of the wave's k-step, tap validity
+    uint32_t fa[TM], tmask[TM];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        const int j = 32 * i + frow;
+        fa[i] = (uint32_t)(j * PITCH + fhalf * 16 + wave * 32);
+        const int m = m0 + j;
+        const int img = (int)fast_div((uint32_t)m, (uint32_t)HW, p.div_ohw_mul, p.div_ohw_sh);
+        const int pix = m - img * HW;
+        const int oh = (int)fast_div((uint32_t)pix, (uint32_t)W, p.div_ow_mul, p.div_ow_sh), ow = pix - oh * W;
+        const uint32_t rows = (oh > 0 ? 0x007u : 0u) | 0x038u | (oh < p.H - 1 ? 0x1c0u : 0u);
+        const uint32_t cols = (ow > 0 ? 0x049u : 0u) | 0x092u | (ow < W - 1 ? 0x124u : 0u);
+        tmask[i] = m < p.M ? (rows & cols) : 0u;
+    }
+    const uint32_t fbk = (uint32_t)(B_OFF + frow * 128 + (((2 * wave + fhalf) ^ ((frow >> 1) & 7)) << 4));
+
+    wait_vm<FLY * PER_TILE>();                      // all but weight tiles 2 .. NB-2
+    wg_barrier();
+
+    f32x16 acc[TM][TN];
+    u32x4 fx[2][TM], fw[2][TN];
+    uint32_t an[TM], an2[TM];                       // pixel fragment addresses of the next K tile and of the one after it
+    auto frag_read = [&](int r, int set, uint32_t bstage, const uint32_t *pix) {
+        if (r < TM) fx[set][r < TM ? r : 0] = *(const u32x4 *)(lds + pix[r < TM ? r : 0]);
+        else fw[set][r >= TM ? r - TM : 0] = *(const u32x4 *)(lds + fbk + bstage + (r >= TM ? r - TM : 0) * 4096);
+    };
+    auto tap_addr = [&](int tp, uint32_t rb, uint32_t *out) {
+        const uint32_t toff = (uint32_t)(((tp / 3) * W + tp % 3) * PITCH) + rb;
+        const uint32_t zoff = rb + (uint32_t)(RUN_BYTES - 128);
+#pragma unroll
+        for (int i = 0; i < TM; ++i) out[i] = ((tmask[i] >> tp) & 1u) ? fa[i] + toff : zoff;
+    };
+    tap_addr(0, 0u, an);
+#pragma unroll
+    for (int r = 0; r < NRD; ++r) frag_read(r, 0, 0u, an);
+    tap_addr(1, 0u, an);
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+    __builtin_amdgcn_sched_barrier(0);
+
+    int st_cur = 0;                                 // weight stage of the current K tile: u % NB
+#pragma unroll 1
+    for (int s2 = 0; s2 < nsl; s2 += 2) {
+#pragma unroll
+        for (int hh = 0; hh < 2; ++hh) {
+            const int s = s2 + hh;
+            const uint32_t rb = (uint32_t)(hh * RUN_BYTES), rbn = (uint32_t)((hh ^ 1) * RUN_BYTES);   // slice s lives in buffer s % 2
+            const bool more = s + 1 < nsl;
+#pragma unroll
+            for (int tp = 0; tp < 9; ++tp) {
+                // on entry: the barrier of K tile u = 9s + tp has been passed, weight tiles u and u+1 and this slice's
+                // run have landed, the wave's fragments of tile u are in register set u % 2, an[] addresses tile u+1
+                const int set = (hh * 9 + tp) & 1;
+                const int st_next = st_cur + 1 == NB ? 0 : st_cur + 1, st_iss = st_cur == 0 ? NB - 1 : st_cur - 1;
+                const uint32_t bnext = (uint32_t)(st_next * B_BYTES);
+                const int tb = (tp + NB - 1) % 9, sb = s + (tp + NB - 1) / 9;
+                const bool blive = sb < nsl;
+                int q = 0;
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) {
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fw[set][j]), __builtin_bit_cast(bf16x8, fx[set][i]),
+                                                                           acc[i][j], 0, 0, 0);
+                        __builtin_amdgcn_sched_barrier(0);
+                        // behind the MFMA: one fragment read of the next tile, or the addresses of the tile after it,
+                        // and after every second MFMA one request
+                        if (q < NRD) frag_read(q, set ^ 1, bnext, an);
+                        else if (q == NRD) tap_addr((tp + 2) % 9, tp >= 7 ? rbn : rb, an2);
+                        if ((q & 1) && (q >> 1) < PER_TILE) {
+                            const int d = q >> 1;
+                            if (d < BG) issue_b(d, st_iss, sb, tb, blive);
+                            else issue_r(NR * tp + (d - BG), (s + 1) & 1, s + 1, more);
+                        }
+                        __builtin_amdgcn_sched_barrier(0);
+                        ++q;
+                    }
+#pragma unroll
+                for (int i = 0; i < TM; ++i) an[i] = an2[i];
+                st_cur = st_next;
+                wait_vm<FLY * PER_TILE>();          // everything but the last FLY tiles' requests: weight tile u + 2 has landed
+                wg_barrier();
+            }
+        }
+    }
+    wait_vm<0>();
+    wg_barrier();
+
+    // ---- the four partial tiles go to LDS (16-byte chunks of a row XOR-swizzled by the row) ...
+    {
+        unsigned char *park = lds + wave * PBYTES;
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const int row = i * 32 + frow;
+                    const int c = j * 8 + 2 * g + fhalf;                 // 4-channel chunk of the row, 0..15
+                    f32x4 v;
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) v[k] = acc[i][j][4 * g + k];
+                    *(f32x4 *)(park + row * (BN * 4) + ((c ^ (row & 15)) << 4)) = v;
+                }
+    }
+    RL_WAIT_LGKM0;
+    wg_barrier();
+    // ... and are summed row-wise: k-steps 0, 1, 2, 3 in that order, then bias, residual, ReLU, one rounding
+    const rsrc_t ry = make_rsrc(p.y, y_bytes);
+    const float lo = e.relu_last ? 0.0f : -INFINITY;
+#pragma unroll
+    for (int q = 0; q < NPASS; ++q) {
+        const int row = 32 * q + rr;
+        float v[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) v[k] = 0.0f;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) {
+            const unsigned char *prow = lds + w * PBYTES + row * (BN * 4);
+            const f32x4 a = *(const f32x4 *)(prow + (((2 * pp) ^ (row & 15)) << 4));
+            const f32x4 b = *(const f32x4 *)(prow + (((2 * pp + 1) ^ (row & 15)) << 4));
+#pragma unroll
+            for (int k = 0; k < 4; ++k) { v[k] += a[k]; v[4 + k] += b[k]; }
+        }
+        const u32x4 rs = res_r[q];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) { v[k] += bias_lo[k]; v[4 + k] += bias_hi[k]; }
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            v[2 * k] += __uint_as_float(rs[k] << 16);
+            v[2 * k + 1] += __uint_as_float(rs[k] & 0xffff0000u);
+        }
+        u32x4 o;
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+            o[k] = pack_bf16x2(fmaxf(v[2 * k], lo), fmaxf(v[2 * k + 1], lo));
+        __builtin_amdgcn_raw_buffer_store_b128(o, ry, y_off[q], 0, 0);
+    }
+#endif
+}
+
+template <int BM, int BN, int WGM, int WGN, int NB>
 static hipError_t launch_run(const IgemmParams &p0, hipStream_t s)
 {
     IgemmParams p = p0;
@@ -377,7 +647,7 @@ static hipError_t launch_run(const IgemmParams &p0, hipStream_t s)
     p.nblk_n = (p.N + BN - 1) / BN;
     int64_t nblk = (int64_t)p.nblk_m * p.nblk_n;
     if (nblk <= 0 || nblk > 0x7fffffff) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((conv3x3_run_kernel<BM, BN, WGM, WGN>), dim3((unsigned)nblk), dim3(WGM * WGN * 64), 0, s, p);
+    hipLaunchKernelGGL((conv3x3_run_kernel<BM, BN, WGM, WGN, NB>), dim3((unsigned)nblk), dim3(WGM * WGN * 64), 0, s, p);
     return hipGetLastError();
 }
 
@@ -393,9 +663,17 @@ hipError_t launch_conv3x3_run(const IgemmParams &p, const IgemmLaunch &l, hipStr
         (p.epi.t_op >= 0 && (p.epi.t_op != E_ADD || p.epi.t_dtype != DT_BF16)) || (p.epi.rest_n != 0 && !p.epi.relu_last))
         return hipErrorInvalidValue;
     switch (l.tile) {
-    case TILE_256x128: return launch_run<256, 128, 4, 2>(p, s);
-    case TILE_128x128: return launch_run<128, 128, 2, 4>(p, s);
-    case TILE_128x64: return launch_run<128, 64, 4, 2>(p, s);
+    case TILE_256x128: return launch_run<256, 128, 4, 2, 4>(p, s);      // 160 KB of LDS with four stages
+    case TILE_128x128: return launch_run<128, 128, 2, 4, 5>(p, s);
+    case TILE_128x64:
+        if (p.C % 128 == 0 && !getenv("RELAYHIP_NO_RUN_KS")) {
+            IgemmParams q = p;
+            q.nblk_m = (p.M + 127) / 128;
+            q.nblk_n = (p.N + 63) / 64;
+            hipLaunchKernelGGL((conv3x3_run_ks_kernel<128, 64, 6>), dim3((unsigned)(q.nblk_m * q.nblk_n)), dim3(256), 0, s, q);
+            return hipGetLastError();
+        }
+        return launch_run<128, 64, 4, 2, 6>(p, s);
     default: return hipErrorInvalidValue;
     }
 }

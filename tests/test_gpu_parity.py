@@ -198,6 +198,7 @@ RUN_CASES = [
     (16, 128, 128, 28, 28, True, True, True, "128x64"),
     (196, 192, 72, 7, 9, True, False, False, "128x64"),
     (140, 64, 128, 3, 30, False, True, True, "128x64"),
+    (196, 256, 72, 7, 9, False, True, True, "128x64"),      # even slice count: K split over the waves; N tail
     (16, 128, 256, 28, 28, True, True, True, "128x128"),
     (64, 256, 256, 14, 14, False, False, True, "128x128"),
     (63, 128, 128, 28, 28, True, True, True, "256x128"),
