@@ -201,6 +201,7 @@ RUN_CASES = [
     (196, 256, 72, 7, 9, False, True, True, "128x64"),      # even slice count: K split over the waves; N tail
     (16, 128, 256, 28, 28, True, True, True, "128x128"),
     (64, 256, 256, 14, 14, False, False, True, "128x128"),
+    (16, 192, 264, 28, 28, True, False, True, "128x128"),    # odd slice count: eight waves with 64x32 tiles; N tail
     (63, 128, 128, 28, 28, True, True, True, "256x128"),
 ]
 
