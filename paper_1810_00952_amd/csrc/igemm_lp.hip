@@ -92,8 +92,9 @@ constexpr uint32_t OOB = 0x80000000u;
 
 }  // namespace
 
+// The workgroup's work: tile number bid_in of the contraction p.
 template <int BM, int BN, int WGM, int WGN, int STAGES>
-__global__ __launch_bounds__(WGM * WGN * 64) void igemm_lp_kernel(const IgemmParams p)
+__device__ __forceinline__ void igemm_lp_body(const IgemmParams &p, const int bid_in)
 {
 #if defined(__HIP_DEVICE_COMPILE__)   // the host pass only needs the launch stub; the body uses gfx950-only builtins
     constexpr int NW = WGM * WGN;                   // waves: four (one per SIMD) or eight (two per SIMD)
@@ -119,7 +120,7 @@ __global__ __launch_bounds__(WGM * WGN * 64) void igemm_lp_kernel(const IgemmPar
 
     // consecutive workgroup ids go to different XCDs; give each XCD a contiguous run of tiles
     const int nblk = p.nblk_m * p.nblk_n;
-    int bid = blockIdx.x;
+    int bid = bid_in;
     {
         const int per = nblk / NUM_XCD, main = per * NUM_XCD;
         if (bid < main) bid = (bid % NUM_XCD) * per + bid / NUM_XCD;
@@ -417,6 +418,23 @@ __global__ __launch_bounds__(WGM * WGN * 64) void igemm_lp_kernel(const IgemmPar
 #endif
 }
 
+template <int BM, int BN, int WGM, int WGN, int STAGES>
+__global__ __launch_bounds__(WGM * WGN * 64) void igemm_lp_kernel(const IgemmParams p)
+{
+    igemm_lp_body<BM, BN, WGM, WGN, STAGES>(p, (int)blockIdx.x);
+}
+
+// Two independent contractions of the same tile shape in one launch: the first pa.nblk_m * pa.nblk_n workgroups work on
+// pa, the rest on pb.  A stage's stride-2 convolution and its 1x1 projection each fill three quarters of the chip
+// when launched alone; launched together, the short projection tiles run on the CUs the other leaves idle.
+template <int BM, int BN, int WGM, int WGN, int STAGES>
+__global__ __launch_bounds__(WGM * WGN * 64) void igemm_lp_pair_kernel(const IgemmParams pa, const IgemmParams pb)
+{
+    const int na = pa.nblk_m * pa.nblk_n;
+    if ((int)blockIdx.x < na) igemm_lp_body<BM, BN, WGM, WGN, STAGES>(pa, (int)blockIdx.x);
+    else igemm_lp_body<BM, BN, WGM, WGN, STAGES>(pb, (int)blockIdx.x - na);
+}
+
 #define RL_INST(BM, BN, WGM, WGN, ST) template __global__ void igemm_lp_kernel<BM, BN, WGM, WGN, ST>(const IgemmParams);
 RL_INST(128, 128, 2, 4, 4) RL_INST(256, 128, 4, 2, 3) RL_INST(128, 64, 4, 1, 3) RL_INST(128, 64, 4, 1, 4) RL_INST(64, 64, 2, 2, 4)
 #undef RL_INST
@@ -431,6 +449,47 @@ static hipError_t launch_lp(const IgemmParams &p0, hipStream_t s)
     if (nblk <= 0 || nblk > 0x7fffffff) return hipErrorInvalidValue;
     hipLaunchKernelGGL((igemm_lp_kernel<BM, BN, WGM, WGN, STAGES>), dim3((unsigned)nblk), dim3(WGM * WGN * 64), 0, s, p);
     return hipGetLastError();
+}
+
+template <int BM, int BN, int WGM, int WGN, int STAGES>
+static hipError_t launch_lp_pair(const IgemmParams &a0, const IgemmParams &b0, hipStream_t s)
+{
+    IgemmParams a = a0, b = b0;
+    a.nblk_m = (a.M + BM - 1) / BM; a.nblk_n = (a.N + BN - 1) / BN;
+    b.nblk_m = (b.M + BM - 1) / BM; b.nblk_n = (b.N + BN - 1) / BN;
+    const int64_t na = (int64_t)a.nblk_m * a.nblk_n, nb = (int64_t)b.nblk_m * b.nblk_n;
+    if (na <= 0 || nb <= 0 || na + nb > 0x7fffffff) return hipErrorInvalidValue;
+    hipLaunchKernelGGL((igemm_lp_pair_kernel<BM, BN, WGM, WGN, STAGES>), dim3((unsigned)(na + nb)), dim3(WGM * WGN * 64), 0, s, a, b);
+    return hipGetLastError();
+}
+
+// the kernel variant launch_igemm_lp picks for a contraction (two contractions can share a launch when it is the same)
+static int lp_variant(const IgemmParams &p, const IgemmLaunch &l)
+{
+    switch (l.tile) {
+    case TILE_128x128: return 0;
+    case TILE_256x128: return 1;
+    case TILE_128x64: return (int64_t)((p.M + 127) / 128) * ((p.N + 63) / 64) <= 320 ? 2 : 3;
+    default: return 4;
+    }
+}
+
+bool igemm_lp_can_pair(const IgemmParams &a, const IgemmLaunch &la, const IgemmParams &b, const IgemmLaunch &lb)
+{
+    return la.lp && lb.lp && !la.ws && !lb.ws && !la.c64 && !lb.c64 && !la.run && !lb.run && !la.gates && !lb.gates && !a.x2 && !b.x2 &&
+           a.in_dtype == DT_BF16 && b.in_dtype == DT_BF16 && a.y_dtype == DT_BF16 && b.y_dtype == DT_BF16 && lp_variant(a, la) == lp_variant(b, lb);
+}
+
+hipError_t launch_igemm_lp_pair(const IgemmParams &a, const IgemmLaunch &la, const IgemmParams &b, const IgemmLaunch &lb, hipStream_t s)
+{
+    if (!igemm_lp_can_pair(a, la, b, lb)) return hipErrorInvalidValue;
+    switch (lp_variant(a, la)) {
+    case 0: return launch_lp_pair<128, 128, 2, 4, 4>(a, b, s);
+    case 1: return launch_lp_pair<256, 128, 4, 2, 3>(a, b, s);
+    case 2: return launch_lp_pair<128, 64, 4, 1, 4>(a, b, s);
+    case 3: return launch_lp_pair<128, 64, 4, 1, 3>(a, b, s);
+    default: return launch_lp_pair<64, 64, 2, 2, 4>(a, b, s);
+    }
 }
 
 hipError_t launch_igemm_lp(const IgemmParams &p, const IgemmLaunch &l, hipStream_t s)

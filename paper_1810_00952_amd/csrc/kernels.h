@@ -99,6 +99,9 @@ struct IgemmLaunch {
     int32_t run;        // 1 (with lp): 3x3 / stride 1 / pad 1, C a multiple of 64, image rows of at most 30 pixels, tile not 64x64 (conv3x3_run.hip)
 };
 hipError_t launch_igemm(const IgemmParams &p, const IgemmLaunch &l, hipStream_t s);
+// two independent pixel-on-lane contractions that use the same kernel variant, in one launch (igemm_lp.hip)
+bool igemm_lp_can_pair(const IgemmParams &a, const IgemmLaunch &la, const IgemmParams &b, const IgemmLaunch &lb);
+hipError_t launch_igemm_lp_pair(const IgemmParams &a, const IgemmLaunch &la, const IgemmParams &b, const IgemmLaunch &lb, hipStream_t s);
 hipError_t launch_conv3x3_c64(const IgemmParams &p, hipStream_t s);
 hipError_t launch_conv3x3_run(const IgemmParams &p, const IgemmLaunch &l, hipStream_t s);
 
@@ -107,6 +110,7 @@ struct StemPoolParams {
     IgemmParams g;                      // the stem contraction (x: padded frame, w: packed weights, N = 64, K = 256); y unused
     void *yp; uint32_t yp_bytes;        // pooled output [n_img, PH, PW, 64] bf16
     int32_t n_img, PH, PW;
+    int32_t kh;                         // the filter's own height (2*g.KH or one less: the last frame row then meets zero weights and is skipped)
 };
 hipError_t launch_stem_pool(const StemPoolParams &q, hipStream_t s);
 

@@ -414,6 +414,7 @@ struct Planner {
         s.group = gi;
         s.ig = p; s.il = il;
         s.stem = stem ? 1 : 0;
+        s.stem_kh = stem ? pack.KH : 0;
         s.slot[SL_X] = xbuf; s.slot[SL_X2] = x2buf; s.slot[SL_W] = bound(wv); s.slot[SL_Y] = ybuf;
         for (int i = 0; i < RL_EPI_MAX_PTRS; ++i) s.slot[SL_E0 + i] = eslots[i];
         s.slot[SL_CIN] = cin_buf; s.slot[SL_COUT] = cout_buf; s.slot[SL_HOUT] = hout_buf;
@@ -634,6 +635,7 @@ struct Planner {
             }
         }
         fuse_stem_pool();
+        pair_contractions();
         assign_workspace();
         return RL_OK;
     }
@@ -675,6 +677,32 @@ struct Planner {
         }
     }
 
+    // Two consecutive contraction steps of which the second does not use the first one's result, and which run the
+    // same variant of the pixel-on-lane kernel (a stage's stride-2 convolution and its 1x1 projection), share one
+    // launch: each alone leaves a quarter of the CUs idle, and the projection's short tiles fit into that gap.
+    void pair_contractions()
+    {
+        if (getenv("RELAYHIP_NO_PAIR")) return;
+        for (size_t si = 0; si + 1 < plan.steps.size(); ++si) {
+            Step &a = plan.steps[si];
+            Step &b = plan.steps[si + 1];
+            if (a.kind != S_IGEMM || b.kind != S_IGEMM || a.pair || b.pair || a.stem || b.stem) continue;
+            if (!igemm_lp_can_pair(a.ig, a.il, b.ig, b.il)) continue;
+            const int ya = a.slot[SL_Y], yb = b.slot[SL_Y];
+            if (ya < 0 || yb < 0 || ya == yb) continue;
+            bool dep = false;
+            for (int s : b.slot) dep |= (s == ya);          // b reads (or overwrites) a's result
+            for (int s : a.slot) dep |= (s == yb);          // a reads what b writes
+            if (dep) continue;
+            a.pair = 1; b.pair = 2;
+            a.flops += b.flops; a.bytes += b.bytes;
+            b.flops = 0; b.bytes = 0;
+            a.name += " | " + b.name;
+            b.kernel = "(launched with the step before)";
+            ++si;
+        }
+    }
+
     // liveness-based first-fit packing of workspace buffers
     void assign_workspace()
     {
@@ -682,7 +710,9 @@ struct Planner {
             for (int b : plan.steps[si].slot)
                 if (b >= 0) {
                     BufDesc &d = plan.bufs[b];
-                    if (d.first < 0) d.first = (int)si;
+                    // the second step of a pair runs when the first is launched
+                    const int at = plan.steps[si].pair == 2 ? (int)si - 1 : (int)si;
+                    if (d.first < 0) d.first = at;
                     d.last = (int)si;
                 }
         std::vector<int> ws;
@@ -788,12 +818,21 @@ rl_status run_steps(const Plan &plan, void *const *ptrs, hipStream_t stream, std
         ++si;
         if (er == hipSuccess) switch (s.kind) {
         case S_IGEMM: {
-            IgemmParams p = s.ig;
-            p.x = P(s, SL_X); p.x2 = P(s, SL_X2); p.w = P(s, SL_W); p.y = P(s, SL_Y);
-            for (int i = 0; i < RL_EPI_MAX_PTRS; ++i) p.epi.ptr[i] = P(s, SL_E0 + i);
-            finalize_epilogue(p.epi);
-            p.c_in = (const float *)P(s, SL_CIN); p.c_out = (float *)P(s, SL_COUT); p.h_out = P(s, SL_HOUT);
-            er = launch_igemm(p, s.il, stream);
+            if (s.pair == 2) break;                 // went out with the step before
+            auto params = [&](const Step &t) {
+                IgemmParams p = t.ig;
+                p.x = P(t, SL_X); p.x2 = P(t, SL_X2); p.w = P(t, SL_W); p.y = P(t, SL_Y);
+                for (int i = 0; i < RL_EPI_MAX_PTRS; ++i) p.epi.ptr[i] = P(t, SL_E0 + i);
+                finalize_epilogue(p.epi);
+                p.c_in = (const float *)P(t, SL_CIN); p.c_out = (float *)P(t, SL_COUT); p.h_out = P(t, SL_HOUT);
+                return p;
+            };
+            if (s.pair == 1) {
+                const Step &t = plan.steps[si];     // si already counts this step: the next one
+                er = launch_igemm_lp_pair(params(s), s.il, params(t), t.il, stream);
+            } else {
+                er = launch_igemm(params(s), s.il, stream);
+            }
             break;
         }
         case S_ELTWISE: {
@@ -830,6 +869,7 @@ rl_status run_steps(const Plan &plan, void *const *ptrs, hipStream_t stream, std
             finalize_epilogue(q.g.epi);
             q.yp = P(s, SL_Y);
             q.n_img = s.sp_N; q.PH = s.sp_PH; q.PW = s.sp_PW;
+            q.kh = s.stem_kh;
             q.yp_bytes = (uint32_t)((uint64_t)s.sp_N * s.sp_PH * s.sp_PW * 64 * 2);
             er = launch_stem_pool(q, stream);
             break;

@@ -33,6 +33,9 @@ struct Step {
     int st_H = 0, st_W = 0, st_Hp = 0, st_Wp = 0, st_ph = 0, st_pw = 0;   // S_STEM_PAD geometry (t_N, t_C: batch, channels)
     int stem = 0;                       // S_IGEMM: the few-channel stem form (padded 4-channel frame, regrouped taps)
     int sp_N = 0, sp_PH = 0, sp_PW = 0; // S_STEM_POOL: images and pooled size (ig: the stem contraction)
+    int stem_kh = 0;                    // stem contractions: the filter's own height (ig.KH counts pairs of frame rows)
+    int pair = 0;                       // S_IGEMM: 1: launched together with the next step (an independent contraction of the
+                                        // same tile shape); 2: that next step, which launches nothing itself
     int slot[SL_COUNT];
     double flops = 0, bytes = 0;
     Step() { for (int &s : slot) s = -1; }

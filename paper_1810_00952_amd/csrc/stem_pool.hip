@@ -107,7 +107,8 @@ static_assert(RPX <= BM, "a region fits the tile");
 
 }  // namespace
 
-template <bool RELU>
+// ODD: odd filter height: the second frame row of the last K tile meets zero weights only; its two k-steps are skipped
+template <bool RELU, bool ODD>
 __global__ __launch_bounds__(256) void stem_pool_kernel(const StemPoolParams q)
 {
 #if defined(__HIP_DEVICE_COMPILE__)   // the host pass only needs the launch stub; the body uses gfx950-only builtins
@@ -255,15 +256,16 @@ __global__ __launch_bounds__(256) void stem_pool_kernel(const StemPoolParams q)
             for (int j = 0; j < 2; ++j)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
-        // ---- K loop: 16 k-steps, fragments of the next one read while the current one is multiplied
+        // ---- K loop: 16 (14) k-steps, fragments of the next one read while the current one is multiplied
+        constexpr int NKS = NKT * 4 - (ODD ? 2 : 0);
         u32x4 fx[2][2];
         fx[0][0] = *(const u32x4 *)(pa + fx_base[0] + fx_ks[0]);
         fx[0][1] = *(const u32x4 *)(pa + fx_base[1] + fx_ks[0]);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int kk = 0; kk < NKT * 4; ++kk) {
+        for (int kk = 0; kk < NKS; ++kk) {
             const int kt = kk >> 2, ks = kk & 3;
-            if (kk + 1 < NKT * 4) {
+            if (kk + 1 < NKS) {
                 const int kt1 = (kk + 1) >> 2, ks1 = (kk + 1) & 3;
                 fx[(kk + 1) & 1][0] = *(const u32x4 *)(pa + fx_base[0] + fx_ks[ks1] + kt1 * 2 * PITCH);
                 fx[(kk + 1) & 1][1] = *(const u32x4 *)(pa + fx_base[1] + fx_ks[ks1] + kt1 * 2 * PITCH);
@@ -334,8 +336,6 @@ __global__ __launch_bounds__(256) void stem_pool_kernel(const StemPoolParams q)
 #endif
 }
 
-template __global__ void stem_pool_kernel<true>(const StemPoolParams);
-template __global__ void stem_pool_kernel<false>(const StemPoolParams);
 
 hipError_t launch_stem_pool(const StemPoolParams &q, hipStream_t s)
 {
@@ -353,8 +353,15 @@ hipError_t launch_stem_pool(const StemPoolParams &q, hipStream_t s)
     if (nreg > 0x7fffffff) return hipErrorInvalidValue;
     int grid = 256;                                 // one workgroup per CU, a multiple of the XCD count
     if (nreg < grid) grid = (int)((nreg + NUM_XCD - 1) / NUM_XCD * NUM_XCD);
-    if (p.epi.relu_last) hipLaunchKernelGGL(stem_pool_kernel<true>, dim3((unsigned)grid), dim3(256), 0, s, q);
-    else hipLaunchKernelGGL(stem_pool_kernel<false>, dim3((unsigned)grid), dim3(256), 0, s, q);
+    if (q.kh != 2 * NKT && q.kh != 2 * NKT - 1) return hipErrorInvalidValue;
+    const bool odd = q.kh == 2 * NKT - 1;
+    if (p.epi.relu_last) {
+        if (odd) hipLaunchKernelGGL((stem_pool_kernel<true, true>), dim3((unsigned)grid), dim3(256), 0, s, q);
+        else hipLaunchKernelGGL((stem_pool_kernel<true, false>), dim3((unsigned)grid), dim3(256), 0, s, q);
+    } else {
+        if (odd) hipLaunchKernelGGL((stem_pool_kernel<false, true>), dim3((unsigned)grid), dim3(256), 0, s, q);
+        else hipLaunchKernelGGL((stem_pool_kernel<false, false>), dim3((unsigned)grid), dim3(256), 0, s, q);
+    }
     return hipGetLastError();
 }
 

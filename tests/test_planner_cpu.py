@@ -78,7 +78,10 @@ def test_resnet18_plan_structure():
     plan = B.Plan(B.graph_from_spec(ctx, spec))
     d = plan.describe()
     kernels = [s["kernel"] for s in d["steps"]]
-    assert sum(k.startswith("igemm_conv2d") for k in kernels) == 20
+    # 20 convolutions; each of the three stride-2 convolutions shares its launch with the 1x1 projection next to it
+    assert sum(k.startswith("igemm_conv2d") for k in kernels) == 17
+    assert kernels.count("(launched with the step before)") == 3
+    assert sum(" | " in s["name"] for s in d["steps"]) == 3
     assert sum(k.startswith("igemm_dense") for k in kernels) == 1
     # the stem group and the max-pool group behind it run as one kernel; the pool kernel is gone from the plan
     assert kernels.count("igemm_conv2d_bf16_stem_maxpool") == 1 and kernels.count("maxpool_nhwc") == 0
