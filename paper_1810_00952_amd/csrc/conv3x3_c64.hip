@@ -158,6 +158,10 @@ __global__ __launch_bounds__(256, 2) void conv3x3_c64_kernel(const IgemmParams p
 
     // ---- weights: the fragment-order copy behind the packed matrix.  Fragment (tap, ks) of lane l of a wave with
     // channel half nh: 16 bytes at (((nh*9 + tap)*4 + ks)*64 + l)*16
+    // (the bias is requested before them: a value requested behind the weights could only be used once they all
+    // have arrived)
+    float bias_v = 0.0f;
+    if (t < CH && e.has_bias) bias_v = ((const float *)e.bias_ptr)[t];
     u32x4 wreg[NTAP][4];
     {
         const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc((void *)((const unsigned char *)p.w + C64_W_BYTES), 0, C64_W_BYTES, 0x00020000);
@@ -168,13 +172,8 @@ __global__ __launch_bounds__(256, 2) void conv3x3_c64_kernel(const IgemmParams p
                 wreg[tp][ks] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(rw, (uint32_t)((((nh * NTAP + tp) * 4 + ks) * 64 + lane) * 16), 0, 0));
     }
     // bias and the zeros, in LDS for the whole kernel
-    if (t < CH) {
-        float b = 0.0f;
-        if (e.has_bias) b = ((const float *)e.bias_ptr)[t];
-        *(float *)(lds + BIAS_OFF + t * 4) = b;
-    } else if (t < CH + 32) {
-        *(uint32_t *)(lds + ZERO_OFF + (t - CH) * 4) = 0u;
-    }
+    if (t < CH) *(float *)(lds + BIAS_OFF + t * 4) = bias_v;
+    else if (t < CH + 32) *(uint32_t *)(lds + ZERO_OFF + (t - CH) * 4) = 0u;
 
 
     // the lane's two pixels within a region, and their fragment base addresses within a run buffer
@@ -185,11 +184,10 @@ __global__ __launch_bounds__(256, 2) void conv3x3_c64_kernel(const IgemmParams p
         pj[i] = mh * 64 + 32 * i + frow;
         fa[i] = (uint32_t)(pj[i] * PITCH + fhalf * 16);
     }
-    RL_WAIT_VM(0);                                  // first run (this wave's part) and the weights
-#pragma unroll
-    for (int tp = 0; tp < NTAP; ++tp)
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) asm volatile("" : "+v"(wreg[tp][ks]));   // the weights are in registers from here on
+    // the first run (this wave's part) has arrived once at most the 36 weight requests behind it are in flight; the
+    // weights themselves are waited for tap by tap, by the compiler's own counting at their first use in the loop, so
+    // that the first region starts multiplying while most of them are still on their way
+    RL_WAIT_VM(36);
     RL_WAIT_LGKM0;                                  // bias and zeros written before the loop's first barrier
 
     f32x16 acc[2];
