@@ -250,14 +250,9 @@ __global__ __launch_bounds__(256) void stem_pool_kernel(const StemPoolParams q)
         RL_WAIT_VM(0);                              // this wave's part of the patch (and the last region's stores)
         wg_barrier();                               // the whole patch is there; the last region's pooling is done
         if (ri + 1 < my) issue_patch(reg + nslot, (ri + 1) & 1);
-#pragma unroll
-        for (int i = 0; i < 2; ++i)
-#pragma unroll
-            for (int j = 0; j < 2; ++j)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
         // ---- K loop: 16 (14) k-steps, fragments of the next one read while the current one is multiplied
         constexpr int NKS = NKT * 4 - (ODD ? 2 : 0);
+        const f32x16 zero = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};   // the first k-step starts the sums
         u32x4 fx[2][2];
         fx[0][0] = *(const u32x4 *)(pa + fx_base[0] + fx_ks[0]);
         fx[0][1] = *(const u32x4 *)(pa + fx_base[1] + fx_ks[0]);
@@ -276,7 +271,7 @@ __global__ __launch_bounds__(256) void stem_pool_kernel(const StemPoolParams q)
 #pragma unroll
                 for (int j = 0; j < 2; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, wreg[kt][ks][j]),
-                                                                        __builtin_bit_cast(bf16x8, fx[kk & 1][i]), acc[i][j], 0, 0, 0);
+                                                                        __builtin_bit_cast(bf16x8, fx[kk & 1][i]), kk == 0 ? zero : acc[i][j], 0, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
         }
 
