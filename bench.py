@@ -228,7 +228,7 @@ def bench_lstm(args):
         # input projection of all steps as one contraction (x, Wx read once, zx written once), then per step the
         # recurrent weights, that step's zx, h in and out, c in and out
         nbytes = (T * B * I * 2 + 4 * H * I * 2 + T * B * 4 * H * 4) + T * (4 * H * H * 2 + B * 4 * H * 4 + 2 * B * H * 2 + 2 * B * H * 4)
-        kernels, launches = "igemm_dense_bf16_128x128_dma (once) + lstm_step_kernel (per step)", T + 1
+        kernels, launches = "igemm_lp_f32out_kernel 256x128 (once) + lstm_step_kernel (per step)", T + 1
     else:
         nbytes = sum(st["bytes"] for st in desc["steps"]) * T
         kernels, launches = "+".join(st["kernel"] for st in desc["steps"]), T * len(desc["steps"])

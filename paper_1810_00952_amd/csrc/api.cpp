@@ -447,7 +447,14 @@ rl_status rl_plan_run_recurrent(const rl_plan *cell, int32_t steps, const rl_rec
                     IgemmLaunch l{};
                     l.avec = 1; l.dma = 1;
                     const int64_t b128 = ((g.M + 127) / 128) * (int64_t)((g.N + 127) / 128), b64 = ((g.M + 127) / 128) * (int64_t)((g.N + 63) / 64);
+                    const int64_t b256 = ((g.M + 255) / 256) * (int64_t)((g.N + 127) / 128);
                     l.tile = b128 >= 192 ? TILE_128x128 : b64 >= 192 ? TILE_128x64 : TILE_64x64;
+                    // the pixel-on-lane kernel with fp32 output where one of its two large tiles fills the chip
+                    if (g.N % 8 == 0 && (b256 >= 190 || b128 >= 192) && !getenv("RELAYHIP_NO_LP")) {
+                        l.lp = 1;
+                        l.tile = b256 >= 190 ? TILE_256x128 : TILE_128x128;
+                        g.seg_stride = 64; g.ts_h = 0; g.ts_w = 0; g.tap_rep = 1;
+                    }
                     hipError_t er = launch_igemm(g, l, (hipStream_t)stream);
                     if (er != hipSuccess) return fail(err, RL_ERR_HIP, std::string("launch of the hoisted input projection failed: ") + hipGetErrorString(er));
                     for (int64_t t = t0; t < t0 + tc; ++t) {

@@ -92,8 +92,8 @@ constexpr uint32_t OOB = 0x80000000u;
 
 }  // namespace
 
-// The workgroup's work: tile number bid_in of the contraction p.
-template <int BM, int BN, int WGM, int WGN, int STAGES>
+// The workgroup's work: tile number bid_in of the contraction p.  YF32: the output is fp32 (no residual then).
+template <int BM, int BN, int WGM, int WGN, int STAGES, bool YF32 = false>
 __device__ __forceinline__ void igemm_lp_body(const IgemmParams &p, const int bid_in)
 {
 #if defined(__HIP_DEVICE_COMPILE__)   // the host pass only needs the launch stub; the body uses gfx950-only builtins
@@ -288,7 +288,7 @@ __device__ __forceinline__ void igemm_lp_body(const IgemmParams &p, const int bi
             pA[q] = 2 * pp + (key & 1);                                                                               \
             const int cc = pp ^ (key >> 1);                  /* 8-channel chunk this lane finishes in pass q */      \
             const int m = m0 + wm * WTM + row, n = n0 + wn * WTN + cc * 8;                                            \
-            y_off[q] = (m < p.M && n < p.N) ? (uint32_t)(((int64_t)m * p.ys_p + n) * 2) : OOB;                        \
+            y_off[q] = (m < p.M && n < p.N) ? (uint32_t)(((int64_t)m * p.ys_p + n) * (YF32 ? 4 : 2)) : OOB;           \
             res_r[q] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(rres, y_off[q], 0, 0));        \
         }                                                                                                             \
     }
@@ -413,7 +413,14 @@ __device__ __forceinline__ void igemm_lp_body(const IgemmParams &p, const int bi
 #pragma unroll
         for (int k = 0; k < 4; ++k)
             o[k] = pack_bf16x2(fmaxf(v[2 * k], lo), fmaxf(v[2 * k + 1], lo));
-        __builtin_amdgcn_raw_buffer_store_b128(o, ry, y_off[q], 0, 0);
+        if (YF32) {
+            const u32x4 o0 = {__float_as_uint(fmaxf(v[0], lo)), __float_as_uint(fmaxf(v[1], lo)), __float_as_uint(fmaxf(v[2], lo)), __float_as_uint(fmaxf(v[3], lo))};
+            const u32x4 o1 = {__float_as_uint(fmaxf(v[4], lo)), __float_as_uint(fmaxf(v[5], lo)), __float_as_uint(fmaxf(v[6], lo)), __float_as_uint(fmaxf(v[7], lo))};
+            __builtin_amdgcn_raw_buffer_store_b128(o0, ry, y_off[q], 0, 0);
+            __builtin_amdgcn_raw_buffer_store_b128(o1, ry, y_off[q] != OOB ? y_off[q] + 16u : OOB, 0, 0);
+        } else {
+            __builtin_amdgcn_raw_buffer_store_b128(o, ry, y_off[q], 0, 0);
+        }
     }
 #endif
 }
@@ -422,6 +429,13 @@ template <int BM, int BN, int WGM, int WGN, int STAGES>
 __global__ __launch_bounds__(WGM * WGN * 64) void igemm_lp_kernel(const IgemmParams p)
 {
     igemm_lp_body<BM, BN, WGM, WGN, STAGES>(p, (int)blockIdx.x);
+}
+
+// fp32 output (a projection whose result feeds further fp32 arithmetic: the recurrent executor's hoisted x . Wx^T)
+template <int BM, int BN, int WGM, int WGN, int STAGES>
+__global__ __launch_bounds__(WGM * WGN * 64) void igemm_lp_f32out_kernel(const IgemmParams p)
+{
+    igemm_lp_body<BM, BN, WGM, WGN, STAGES, true>(p, (int)blockIdx.x);
 }
 
 // Two independent contractions of the same tile shape in one launch: the first pa.nblk_m * pa.nblk_n workgroups work on
@@ -492,8 +506,26 @@ hipError_t launch_igemm_lp_pair(const IgemmParams &a, const IgemmLaunch &la, con
     }
 }
 
+template <int BM, int BN, int WGM, int WGN, int STAGES>
+static hipError_t launch_lp_f32out(const IgemmParams &p0, hipStream_t s)
+{
+    IgemmParams p = p0;
+    p.nblk_m = (p.M + BM - 1) / BM;
+    p.nblk_n = (p.N + BN - 1) / BN;
+    int64_t nblk = (int64_t)p.nblk_m * p.nblk_n;
+    if (nblk <= 0 || nblk > 0x7fffffff) return hipErrorInvalidValue;
+    hipLaunchKernelGGL((igemm_lp_f32out_kernel<BM, BN, WGM, WGN, STAGES>), dim3((unsigned)nblk), dim3(WGM * WGN * 64), 0, s, p);
+    return hipGetLastError();
+}
+
 hipError_t launch_igemm_lp(const IgemmParams &p, const IgemmLaunch &l, hipStream_t s)
 {
+    if (p.in_dtype == DT_BF16 && p.y_dtype == DT_F32 && !l.gates && !p.x2 && p.epi.t_op < 0) {
+        // fp32 output: the two large tiles only
+        if (l.tile == TILE_256x128) return launch_lp_f32out<256, 128, 4, 2, 3>(p, s);
+        if (l.tile == TILE_128x128) return launch_lp_f32out<128, 128, 2, 4, 4>(p, s);
+        return hipErrorInvalidValue;
+    }
     if (p.in_dtype != DT_BF16 || p.y_dtype != DT_BF16 || l.gates || p.x2) return hipErrorInvalidValue;
     switch (l.tile) {
     case TILE_128x128:
