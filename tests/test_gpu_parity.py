@@ -222,6 +222,35 @@ def test_conv3x3_taps_from_one_copy_of_the_rows(case, monkeypatch):
         assert_close(got[vid], gen[vid], "bf16", f"run vs general {case}")
 
 
+# A stage's stride-2 convolution and its 1x1 projection go out as one grid: every kernel variant that can be
+# shared (64x64, 128x64 in both depths, 128x128, 256x128), and the same bits as two launches.
+PAIR_CASES = [
+    # batch cin cout h   w
+    (4, 64, 128, 32, 32),        # 64x64 tiles
+    (27, 64, 128, 56, 56),       # 128x64, three stages (two workgroups per CU)
+    (16, 64, 128, 56, 56),       # 128x64, four stages
+    (17, 64, 136, 55, 57),       # 128x128, odd image, N tail
+    (64, 64, 128, 56, 56),       # 256x128
+]
+
+
+@pytest.mark.parametrize("case", PAIR_CASES, ids=[f"pair{i}" for i in range(len(PAIR_CASES))])
+def test_independent_contractions_in_one_launch(case, monkeypatch):
+    b, ci, co, h, w = case
+    spec, data = W.downsample_block(b, ci, co, h, w, "bf16")
+    from paper_1810_00952_amd import binding
+    desc = binding.Plan(binding.graph_from_spec(binding.Context(), spec)).describe()
+    assert sum(st["kernel"] == "(launched with the step before)" for st in desc["steps"]) == 1, [st["kernel"] for st in desc["steps"]]
+    print(f"paired launch case {case}: {[st['kernel'] for st in desc['steps']]}", flush=True)
+    got, _ = check_graph(spec, data, f"paired launch {case}")
+    monkeypatch.setenv("RELAYHIP_NO_PAIR", "1")
+    desc = binding.Plan(binding.graph_from_spec(binding.Context(), spec)).describe()
+    assert not any(st["kernel"] == "(launched with the step before)" for st in desc["steps"])
+    two, _ = run_hip(spec, data)
+    for vid in spec.outputs:
+        np.testing.assert_array_equal(got[vid], two[vid])
+
+
 def test_conv_large_tiles_many_blocks():
     # enough rows that the planner picks its largest tile (several tiles + ragged tail)
     for dtype in ("f32", "bf16"):

@@ -214,6 +214,39 @@ def conv_group(batch=1, cin=64, cout=64, h=56, w=56, k=3, stride=1, pad=1, dtype
     return g, data
 
 
+def downsample_block(batch=4, cin=64, cout=128, h=32, w=32, dtype="bf16", config=10):
+    """The first block of a ResNet stage on its own: y = relu(conv3x3(relu(conv3x3/2(x) + b1)) + b3 + (conv1x1/2(x) + b2)).
+    The stride-2 convolution and the 1x1 projection both read x and neither needs the other."""
+    rng = rng_for(config)
+    g = GraphSpec("downsample_block")
+    data = {}
+    oh, ow = conv_out(h, 3, 2, 1), conv_out(w, 3, 2, 1)
+    x = g.input("x", dtype, (batch, cin, h, w))
+    data["x"] = as_dtype(normal(rng, (batch, cin, h, w)), dtype)
+    ot = (dtype, (batch, cout, oh, ow))
+
+    def conv(name, xin, ci, k, stride, pad, extra=None, relu=True):
+        wt = g.param(name + ".w", dtype, (cout, ci, k, k))
+        data[name + ".w"] = as_dtype(kaiming_normal(rng, (cout, ci, k, k), ci * k * k), dtype)
+        b = g.param(name + ".b", "f32", (cout,))
+        data[name + ".b"] = as_dtype(uniform(rng, (cout,), -0.1, 0.1), "f32")
+        ids = []
+        o, (y,) = g.op("conv2d", [xin, wt], [ot], stride=(stride, stride), pad=(pad, pad)); ids.append(o)
+        o, (y,) = g.op("bias_add", [y, b], [ot], axis=1); ids.append(o)
+        if extra is not None:
+            o, (y,) = g.op("add", [y, extra], [ot]); ids.append(o)
+        if relu:
+            o, (y,) = g.op("relu", [y], [ot]); ids.append(o)
+        g.group(ids)
+        return y
+
+    c1 = conv("c1", x, cin, 3, 2, 1)
+    d = conv("ds", x, cin, 1, 2, 0, relu=False)
+    y = conv("c2", c1, cout, 3, 1, 1, extra=d)
+    g.output(y)
+    return g, data
+
+
 # --------------------------------------------------------------------------
 # configs 3 and 4: ResNet-18-shaped inference graph with folded batch-norm
 # --------------------------------------------------------------------------
