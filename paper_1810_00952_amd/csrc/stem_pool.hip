@@ -12,13 +12,16 @@
 // Work unit: a region of 7 x 8 pooled pixels of one image, which needs the
 // 15 x 17 = 255 convolution outputs around it (neighbouring regions share one
 // row and one column of outputs: 14 % recomputation).  Those are the 256 rows
-// of an implicit-GEMM tile, 64 per wave (two 32-row MFMA tiles x two 32-channel
-// tiles); rows that fall outside the image are requested out of range (zeros)
-// and ignored by the pooling.
+// of an implicit-GEMM tile; a wave multiplies 128 of them (four 32-row MFMA
+// tiles) by 32 of the 64 channels; rows that fall outside the image are
+// requested out of range (zeros) and ignored by the pooling.
 //
-// Workgroups are persistent (one per CU; each XCD owns a contiguous run of
-// regions).  The packed weights (32 KB) are read once into registers, 128 per
-// lane, and stay there.  Activations are NOT expanded into GEMM rows on their
+// Workgroups are persistent, two per CU (each XCD owns a contiguous run of
+// regions): staging and pooling are VALU and LDS work that keeps the MFMA pipe
+// idle, and the second workgroup multiplies meanwhile.  That needs the kernel
+// within 256 registers, which is why a wave takes half the channels: its share
+// of the packed weights (32 KB in all) is read once into registers, 64 per
+// lane, and stays there.  Activations are NOT expanded into GEMM rows on their
 // way in: a GEMM row of this stem is 4 filter-row pairs x 2 rows x 8 pixels x
 // 4 channels of the padded frame, and neighbouring output pixels share all but
 // two of those pixels, so fetching rows tile by tile moves every input byte
@@ -31,7 +34,7 @@
 // patch buffers: the next region's patch arrives while this one is multiplied.
 //
 // Per region: wait for the patch, barrier, request the next patch, 64 MFMAs
-// per wave (32 fragment reads), accumulators + bias, ReLU, rounded to bf16 into
+// per wave (as many fragment reads, each issued behind an MFMA), accumulators + bias, ReLU, rounded to bf16 into
 // a 256-row staging tile in LDS (16-byte chunks XOR-swizzled by the row),
 // barrier, then every thread pools one or two (pooled pixel, 8 channels)
 // items, nine 16-byte reads each, and stores 16 bytes.  The staged values are
@@ -109,7 +112,7 @@ static_assert(RPX <= BM, "a region fits the tile");
 
 // ODD: odd filter height: the second frame row of the last K tile meets zero weights only; its two k-steps are skipped
 template <bool RELU, bool ODD>
-__global__ __launch_bounds__(256) void stem_pool_kernel(const StemPoolParams q)
+__global__ __launch_bounds__(256, 2) void stem_pool_kernel(const StemPoolParams q)
 {
 #if defined(__HIP_DEVICE_COMPILE__)   // the host pass only needs the launch stub; the body uses gfx950-only builtins
     const IgemmParams &p = q.g;
@@ -119,6 +122,7 @@ __global__ __launch_bounds__(256) void stem_pool_kernel(const StemPoolParams q)
     const int t = threadIdx.x;
     const int lane = t & 63;
     const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
+    const int wm = wave >> 1, wn = wave & 1;        // the wave's half of the region's 256 rows and of the 64 channels
 
     // ---- this workgroup's regions: XCD x = blockIdx % 8 owns the run [x*per, (x+1)*per) of the region
     // list (image-major, then region rows, then region columns); its workgroups take them in turn
@@ -138,7 +142,7 @@ __global__ __launch_bounds__(256) void stem_pool_kernel(const StemPoolParams q)
     const int frow = lane & 31, fhalf = lane >> 5;
 
     // ---- weights: four K tiles of 64 rows x 128 bytes through the staging tile into registers, once
-    u32x4 wreg[NKT][4][2];
+    u32x4 wreg[NKT][4];                             // the wave's 32 channels
     {
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
@@ -154,29 +158,25 @@ __global__ __launch_bounds__(256) void stem_pool_kernel(const StemPoolParams q)
         for (int kt = 0; kt < NKT; ++kt)
 #pragma unroll
             for (int ks = 0; ks < 4; ++ks)
-#pragma unroll
-                for (int j = 0; j < 2; ++j)
-                    wreg[kt][ks][j] = *(const u32x4 *)(stg + kt * 8192 + (j * 32 + frow) * 128 + (((2 * ks + fhalf) ^ ((frow >> 1) & 7)) << 4));
+                wreg[kt][ks] = *(const u32x4 *)(stg + kt * 8192 + (wn * 32 + frow) * 128 + (((2 * ks + fhalf) ^ ((frow >> 1) & 7)) << 4));
     }
-    // bias in accumulator layout (lane holds channels j*32 + 8g + 4*fhalf .. +3)
+    // bias in accumulator layout (lane holds channels wn*32 + 8g + 4*fhalf .. +3)
     const Epilogue &e = p.epi;
-    f32x4 bias_r[2][4];
+    f32x4 bias_r[4];
     {
         const __amdgpu_buffer_rsrc_t rb = __builtin_amdgcn_make_buffer_rsrc((void *)(e.has_bias ? e.bias_ptr : p.w), 0, e.has_bias ? (uint32_t)NCH * 4u : 0u, 0x00020000);
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-            for (int g = 0; g < 4; ++g)
-                bias_r[j][g] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rb, (uint32_t)(j * 32 + 8 * g + 4 * fhalf) * 4u, 0, 0));
+        for (int g = 0; g < 4; ++g)
+            bias_r[g] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rb, (uint32_t)(wn * 32 + 8 * g + 4 * fhalf) * 4u, 0, 0));
     }
 
-    // ---- fragment addresses inside a patch.  Tile row m = wave*64 + 32i + frow is output pixel (dy, dx) of the
+    // ---- fragment addresses inside a patch.  Tile row m = wm*128 + 32i + frow is output pixel (dy, dx) of the
     // region; its K tile kt, k-step ks is 16-byte chunk c = 2ks + fhalf of a 128-byte GEMM row, i.e. frame row
     // 2dy + 2kt + (c >> 2), pixels 2dx + 2(c & 3) and the next: patch byte (that row) * PITCH + (dx + (c & 3)) * 16.
-    int fx_base[2], fx_ks[4];
+    int fx_base[4], fx_ks[4];
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-        const int m = wave * 64 + 32 * i + frow;
+    for (int i = 0; i < 4; ++i) {
+        const int m = wm * 128 + 32 * i + frow;
         const int dy = m / RW, dxx = m - dy * RW;
         fx_base[i] = 2 * dy * PITCH + dxx * 16;
     }
@@ -242,7 +242,7 @@ __global__ __launch_bounds__(256) void stem_pool_kernel(const StemPoolParams q)
     if (t == 0) *(u32x4 *)(stg + low_addr) = u32x4{LOWEST, LOWEST, LOWEST, LOWEST};   // stands in for window elements outside the image
     issue_patch(first, 0);
 
-    f32x16 acc[2][2];
+    f32x16 acc[4];
 #pragma unroll 1
     for (int ri = 0; ri < my; ++ri) {
         const int reg = first + ri * nslot;
@@ -253,45 +253,42 @@ __global__ __launch_bounds__(256) void stem_pool_kernel(const StemPoolParams q)
         // ---- K loop: 16 (14) k-steps, fragments of the next one read while the current one is multiplied
         constexpr int NKS = NKT * 4 - (ODD ? 2 : 0);
         const f32x16 zero = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};   // the first k-step starts the sums
-        u32x4 fx[2][2];
-        fx[0][0] = *(const u32x4 *)(pa + fx_base[0] + fx_ks[0]);
-        fx[0][1] = *(const u32x4 *)(pa + fx_base[1] + fx_ks[0]);
+        u32x4 fx[2][4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) fx[0][i] = *(const u32x4 *)(pa + fx_base[i] + fx_ks[0]);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int kk = 0; kk < NKS; ++kk) {
             const int kt = kk >> 2, ks = kk & 3;
-            if (kk + 1 < NKS) {
-                const int kt1 = (kk + 1) >> 2, ks1 = (kk + 1) & 3;
-                fx[(kk + 1) & 1][0] = *(const u32x4 *)(pa + fx_base[0] + fx_ks[ks1] + kt1 * 2 * PITCH);
-                fx[(kk + 1) & 1][1] = *(const u32x4 *)(pa + fx_base[1] + fx_ks[ks1] + kt1 * 2 * PITCH);
+            // every fragment read of the next k-step follows an MFMA of this one, so that it is issued while that runs
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, wreg[kt][ks]), __builtin_bit_cast(bf16x8, fx[kk & 1][i]),
+                                                                 kk == 0 ? zero : acc[i], 0, 0, 0);
                 __builtin_amdgcn_sched_barrier(0);
+                if (kk + 1 < NKS) {
+                    const int kt1 = (kk + 1) >> 2, ks1 = (kk + 1) & 3;
+                    fx[(kk + 1) & 1][i] = *(const u32x4 *)(pa + fx_base[i] + fx_ks[ks1] + kt1 * 2 * PITCH);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
             }
-#pragma unroll
-            for (int i = 0; i < 2; ++i)
-#pragma unroll
-                for (int j = 0; j < 2; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, wreg[kt][ks][j]),
-                                                                        __builtin_bit_cast(bf16x8, fx[kk & 1][i]), kk == 0 ? zero : acc[i][j], 0, 0, 0);
-            __builtin_amdgcn_sched_barrier(0);
         }
 
         // ---- finished bf16 values into the staging tile (row m, chunk c at position c ^ (m & 7)), as 16-bit
         // integers in numeric order: after a ReLU that is the bf16 pattern itself.
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            const int m = wave * 64 + i * 32 + frow;
+        for (int i = 0; i < 4; ++i) {
+            const int m = wm * 128 + i * 32 + frow;
             unsigned char *dst = stg + m * 128 + fhalf * 8;
 #pragma unroll
-            for (int j = 0; j < 2; ++j)
+            for (int g = 0; g < 4; ++g) {
+                float v[4];
 #pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    float v[4];
-#pragma unroll
-                    for (int k = 0; k < 4; ++k) v[k] = fmaxf(acc[i][j][4 * g + k] + bias_r[j][g][k], lo);
-                    u32x2 o = {pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])};
-                    if (!RELU) o = u32x2{bf16x2_order(o[0]), bf16x2_order(o[1])};
-                    *(u32x2 *)(dst + (((j * 4 + g) ^ (m & 7)) << 4)) = o;
-                }
+                for (int k = 0; k < 4; ++k) v[k] = fmaxf(acc[i][4 * g + k] + bias_r[g][k], lo);
+                u32x2 o = {pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])};
+                if (!RELU) o = u32x2{bf16x2_order(o[0]), bf16x2_order(o[1])};
+                *(u32x2 *)(dst + (((wn * 4 + g) ^ (m & 7)) << 4)) = o;
+            }
         }
         wg_barrier();
         // ---- pooling.  All nine reads are issued before the first max; nothing branches.
@@ -346,7 +343,7 @@ hipError_t launch_stem_pool(const StemPoolParams &q, hipStream_t s)
     const int ntr = (q.PH + TPH - 1) / TPH, ntc = (q.PW + TPW - 1) / TPW;
     const int64_t nreg = (int64_t)q.n_img * ntr * ntc;
     if (nreg > 0x7fffffff) return hipErrorInvalidValue;
-    int grid = 256;                                 // one workgroup per CU, a multiple of the XCD count
+    int grid = 512;                                 // two workgroups per CU, a multiple of the XCD count
     if (nreg < grid) grid = (int)((nreg + NUM_XCD - 1) / NUM_XCD * NUM_XCD);
     if (q.kh != 2 * NKT && q.kh != 2 * NKT - 1) return hipErrorInvalidValue;
     const bool odd = q.kh == 2 * NKT - 1;
