@@ -27,11 +27,12 @@
 // two of those pixels, so fetching rows tile by tile moves every input byte
 // about fifteen times (and in half cache lines).  Instead the region's raw
 // patch of the frame -- 38 rows x 40 pixels x 8 bytes = 12 KB -- is copied to
-// LDS once (direct loads, twelve per region) and the MFMA fragments are read
-// straight out of it: the 16 bytes a lane needs for a k-step are 4 pixels of
-// one frame row, and lanes that hold neighbouring output pixels read
-// neighbouring 16-byte slots, which the banks serve without conflicts.  Two
-// patch buffers: the next region's patch arrives while this one is multiplied.
+// LDS once (direct loads, twenty per region, into a 20 KB layout whose row
+// pitch keeps the fragment reads free of bank conflicts) and the MFMA
+// fragments are read straight out of it: the 16 bytes a lane needs for a
+// k-step are 4 pixels of one frame row, and lanes that hold neighbouring
+// output pixels read neighbouring 16-byte slots.  Two patch buffers: the next
+// region's patch arrives while this one is multiplied.
 //
 // Per region: wait for the patch, barrier, request the next patch, 64 MFMAs
 // per wave (as many fragment reads, each issued behind an MFMA), accumulators + bias, ReLU, rounded to bf16 into
@@ -93,6 +94,13 @@ __device__ __forceinline__ uint32_t pk_max_i16(uint32_t a, uint32_t b)
 }
 constexpr uint32_t LOWEST = 0x80008000u;          // below every mapped value
 
+// Row m of the staging tile sits in 128-byte slot m with bits 0 and 2 exchanged.  A pooling read has eight
+// lanes per row and rows two apart; the LDS serves lanes 0-15 and 16-31 of a half-wave four by four, a quad
+// of the first sixteen together with the neighbouring quad of the second sixteen, so rows m and m + 4 must
+// lie in different halves of the 256-byte bank line (measured: 4.9 cycles per read against 7.8 with row m
+// in slot m; the 8-byte writes of the accumulator layout cost the same either way).
+__device__ __forceinline__ int stg_row(int m) { return (m & ~5) | ((m & 1) << 2) | ((m >> 2) & 1); }
+
 constexpr int NUM_XCD = 8;
 constexpr uint32_t OOB = 0x80000000u;
 constexpr int TPH = 7, TPW = 8;                   // pooled pixels per region
@@ -100,10 +108,18 @@ constexpr int RH = 2 * TPH + 1, RW = 2 * TPW + 1; // convolution outputs a regio
 constexpr int RPX = RH * RW;                      // 255 of the tile's 256 rows
 constexpr int BM = 256, NKT = 4, NCH = 64;
 constexpr int PROWS = 2 * (RH + 1) + 6;           // frame rows under a region (38; one spare output row: tile row 255)
-constexpr int PCH = (2 * RW + 6) / 2;             // 16-byte chunks (2 pixels x 4 channels) per patch row: 20
-constexpr int PITCH = PCH * 16;                   // 320 bytes
-constexpr int PLOADS = (PROWS * PCH + 63) / 64;   // direct loads per patch: 12, three per wave
-constexpr int PATCH = PLOADS * 1024;              // 12 KB
+constexpr int PCH = (2 * RW + 6) / 2;             // 16-byte chunks (2 pixels x 4 channels) of a frame row under a region: 20
+// The patch in LDS: even frame rows in one area, odd ones in another (a k-step reads rows of one parity), a row
+// every 33 chunks.  Output pixel (dy, dx) then reads chunk 33 dy + dx + const, and 33 = 2*16 + 1 makes that
+// tile row m = 17 dy + dx plus a constant modulo 16: the 32 rows of an MFMA tile read consecutive 16-byte bank
+// groups, whatever the row wrap (measured: 4.0 cycles per fragment read against 6-7.5 with frame rows 20 chunks
+// apart).  Chunks 20..32 of a row are requested out of range and never read.
+constexpr int PCHS = 2 * 16 + 1;                  // chunks from one row of an area to the next
+constexpr int AROWS = PROWS / 2;                  // 19 rows per area
+constexpr int AREA = AROWS * PCHS * 16;           // 10 032 bytes
+constexpr int PLOADS = (2 * AROWS * PCHS + 63) / 64;   // direct loads per patch: 20, five per wave
+constexpr int PATCH = PLOADS * 1024;              // 20 KB
+static_assert(PROWS % 2 == 0 && PCHS >= PCH, "two areas of whole rows");
 constexpr int STG_BYTES = BM * NCH * 2;           // finished bf16 outputs of a region
 static_assert(PLOADS % 4 == 0, "patch loads split evenly over the four waves");
 static_assert(RPX <= BM, "a region fits the tile");
@@ -172,31 +188,35 @@ __global__ __launch_bounds__(256, 2) void stem_pool_kernel(const StemPoolParams 
 
     // ---- fragment addresses inside a patch.  Tile row m = wm*128 + 32i + frow is output pixel (dy, dx) of the
     // region; its K tile kt, k-step ks is 16-byte chunk c = 2ks + fhalf of a 128-byte GEMM row, i.e. frame row
-    // 2dy + 2kt + (c >> 2), pixels 2dx + 2(c & 3) and the next: patch byte (that row) * PITCH + (dx + (c & 3)) * 16.
+    // 2dy + 2kt + (c >> 2), pixels 2dx + 2(c & 3) and the next: area (c >> 2), row dy + kt, chunk dx + (c & 3).
     int fx_base[4], fx_ks[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int m = wm * 128 + 32 * i + frow;
         const int dy = m / RW, dxx = m - dy * RW;
-        fx_base[i] = 2 * dy * PITCH + dxx * 16;
+        fx_base[i] = (dy * PCHS + dxx) * 16;
     }
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
         const int c = 2 * ks + fhalf;
-        fx_ks[ks] = (c >> 2) * PITCH + (c & 3) * 16;
+        fx_ks[ks] = (c >> 2) * AREA + (c & 3) * 16;
     }
-    // ---- patch requests: load k of the wave covers patch bytes (wave*3 + k)*1024 + lane*16, i.e. 16-byte chunk
-    // s = (wave*3 + k)*64 + lane = (patch row s / 20, chunk s % 20): frame row 2*(14 tr - 1) + row, pixels
-    // 2*(16 tc - 1) + 2*chunk and the next.  Outside the frame: out of range, zeros.
+    // ---- patch requests: load k of the wave covers patch bytes (wave*5 + k)*1024 + lane*16, i.e. chunk slot
+    // s = (wave*5 + k)*64 + lane = (area s / 627, row (s % 627) / 33, chunk s % 33): frame row
+    // 2*(14 tr - 1) + 2*row + area, pixels 2*(16 tc - 1) + 2*chunk and the next.  Slots that hold nothing
+    // (chunk >= 20, past the second area) and chunks outside the frame: out of range, zeros.
     const int Hp = p.H, Wp = p.W;                  // the padded frame
     int pt_row[PLOADS / 4], pt_col[PLOADS / 4];
     uint32_t pt_off[PLOADS / 4];
 #pragma unroll
     for (int k = 0; k < PLOADS / 4; ++k) {
         const int sidx = (wave * (PLOADS / 4) + k) * 64 + lane;
-        pt_row[k] = sidx / PCH; pt_col[k] = 2 * (sidx - pt_row[k] * PCH);
-        if (pt_row[k] >= PROWS) pt_row[k] = 1 << 20;          // past the patch: never inside the frame
-        pt_off[k] = (uint32_t)((pt_row[k] * Wp + pt_col[k]) * 8);
+        const int area = sidx / (AROWS * PCHS), rem = sidx - area * (AROWS * PCHS);
+        const int arow = rem / PCHS, ch = rem - arow * PCHS;
+        const bool holds = area < 2 && ch < PCH;
+        pt_row[k] = holds ? 2 * arow + area : 1 << 20;        // an empty slot: never inside the frame
+        pt_col[k] = holds ? 2 * ch : 0;
+        pt_off[k] = holds ? (uint32_t)((pt_row[k] * Wp + pt_col[k]) * 8) : 0u;
     }
     auto issue_patch = [&](int reg, int buf) {
         const int img = reg / (ntr * ntc), rr = reg - img * (ntr * ntc);
@@ -233,7 +253,7 @@ __global__ __launch_bounds__(256, 2) void stem_pool_kernel(const StemPoolParams 
 #pragma unroll
             for (int b = 0; b < 3; ++b) {
                 const int m = (2 * pl_pr[s] + a) * RW + 2 * pl_pc[s] + b;
-                pl_addr[s][a * 3 + b] = m * 128 + ((cq ^ (m & 7)) << 4);
+                pl_addr[s][a * 3 + b] = stg_row(m) * 128 + ((cq ^ (m & 7)) << 4);
             }
     }
     constexpr int low_addr = STG_BYTES;             // 16 bytes of the lowest value behind the staging tile (written below)
@@ -268,18 +288,18 @@ __global__ __launch_bounds__(256, 2) void stem_pool_kernel(const StemPoolParams 
                 __builtin_amdgcn_sched_barrier(0);
                 if (kk + 1 < NKS) {
                     const int kt1 = (kk + 1) >> 2, ks1 = (kk + 1) & 3;
-                    fx[(kk + 1) & 1][i] = *(const u32x4 *)(pa + fx_base[i] + fx_ks[ks1] + kt1 * 2 * PITCH);
+                    fx[(kk + 1) & 1][i] = *(const u32x4 *)(pa + fx_base[i] + fx_ks[ks1] + kt1 * (PCHS * 16));
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
         }
 
-        // ---- finished bf16 values into the staging tile (row m, chunk c at position c ^ (m & 7)), as 16-bit
+        // ---- finished bf16 values into the staging tile (row m in slot stg_row(m), chunk c at position c ^ (m & 7)), as 16-bit
         // integers in numeric order: after a ReLU that is the bf16 pattern itself.
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int m = wm * 128 + i * 32 + frow;
-            unsigned char *dst = stg + m * 128 + fhalf * 8;
+            unsigned char *dst = stg + stg_row(m) * 128 + fhalf * 8;
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
                 float v[4];
