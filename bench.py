@@ -260,7 +260,7 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="resnet18",
-                    choices=["resnet18", "resnet18_f32_b1", "eltwise", "eltwise32", "gates", "lstm", "mlp", "lenet", "conv", "copy"])
+                    choices=["resnet18", "resnet18_f32_b1", "eltwise", "eltwise32", "gates", "lstm", "mlp", "lenet", "conv", "copy", "layout", "layout32", "block_nhwc"])
     ap.add_argument("--batch", type=int, default=64)
     ap.add_argument("--cpu-images", type=int, default=128)
     ap.add_argument("--no-cpu", action="store_true")
@@ -308,6 +308,17 @@ def main():
         data = {"x": W.as_dtype(W.normal(W.rng_for(6, salt=3), (n,)), "f32")}
         out = bench_graph(args, g, data, "elements/sec y = -x f32", "elements/s", n, "f32",
                           f"y = -x on {n} f32 elements (reads {4 * n} bytes, writes {4 * n} bytes)", PEAK_F32_TFLOPS)
+    elif wl in ("layout", "layout32"):
+        dtype, shape = ("bf16", (256, 64, 112, 112)) if wl == "layout" else ("f32", (128, 64, 112, 112))
+        spec, data = W.layout_case(shape, (0, 2, 3, 1), dtype)
+        n = shape[0] * shape[1] * shape[2] * shape[3]
+        out = bench_graph(args, spec, data, f"elements/sec channel-first to channel-last {dtype}", "elements/s", n, dtype,
+                          f"layout_transform (0,2,3,1) of {'x'.join(map(str, shape))} {dtype}, N(0,1) input", PEAK_F32_TFLOPS)
+    elif wl == "block_nhwc":
+        spec, data = W.channel_last_block(64, 64, 56, 56, "bf16")
+        out = bench_graph(args, spec, data, "images/sec residual block 64ch 56x56 bf16 b64 between channel-last tensors", "images/s", 64, "bf16",
+                          "channel-last input -> layout_transform -> two 3x3 64->64 convolution groups (+bias, +input, ReLU) -> layout_transform "
+                          "-> channel-last output, bf16, batch 64", PEAK_BF16_TFLOPS)
     elif wl == "lstm":
         out = bench_lstm(args)
     elif wl == "mlp":

@@ -94,7 +94,14 @@ enum {
     RL_OP_LSTM_GATES = 15,    /* (z f32[B,4H] as i|f|g|o blocks, c f32[B,H]) -> (c' f32[B,H], h' f32|bf16[B,H]) */
     RL_OP_CAST = 16,          /* explicit (Type) Expr; attrs rl_attr_cast */
     RL_OP_CONCAT = 17,        /* (a[B,K1], b[B,K2]) -> [B,K1+K2]; only as the operand of a dense in the same group */
-    RL_OP_KIND_COUNT = 18
+    RL_OP_LAYOUT_TRANSFORM = 18, /* (x[d0..d(r-1)]) -> [d(perm[0]) .. d(perm[r-1])], y[i0..] = x at index j with j[perm[k]] = i[k];
+                                    attrs rl_attr_layout.  The paper's types carry no layout (its section on extensions
+                                    proposes tracking it); here a layout IS the order of the Shape, so a change of layout
+                                    is an operator whose arrow type permutes the Shape, and the typed graph shows it.
+                                    Always a group of its own.  On rank-4 tensors the two channel-first <-> channel-last
+                                    permutations (0,2,3,1) and (0,3,1,2) cost nothing when the other side of the value is
+                                    a convolution, pool or elementwise group: those run channel-last internally. */
+    RL_OP_KIND_COUNT = 19
 };
 
 typedef struct rl_attr_contract { int32_t out_dtype; /* operand dtype, or RL_F32 */ } rl_attr_contract;
@@ -106,6 +113,7 @@ typedef struct rl_attr_conv2d {
 typedef struct rl_attr_axis { int32_t axis; } rl_attr_axis;
 typedef struct rl_attr_pool2d { int32_t kernel_h, kernel_w, stride_h, stride_w, pad_h, pad_w; } rl_attr_pool2d;
 typedef struct rl_attr_cast { int32_t to; } rl_attr_cast;
+typedef struct rl_attr_layout { int32_t perm[RL_MAX_RANK]; /* a permutation of 0..rank-1 in the first rank entries; else RL_ERR_KIND */ } rl_attr_layout;
 
 typedef struct rl_binding { int32_t value_id; void *dev_ptr; } rl_binding;
 

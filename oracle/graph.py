@@ -14,6 +14,11 @@ Typing follows the paper's rules (figures "Rules for constructing types" and
     notes quantified variables are already instantiated), and the caller's
     declared result type must equal it.
 
+A change of layout is typed like any declared operator: its arrow type
+permutes the Shape (the paper's types carry no layout; its section on
+extensions proposes tracking it in types, and with row-major storage the
+order of the Shape is the layout).
+
 Execution evaluates one operator at a time in float64 and materialises every
 intermediate.  A value leaving a fusion group is rounded once (nearest-even)
 to its declared dtype; inside a group nothing is rounded.
@@ -152,6 +157,13 @@ def infer(kind: str, ins: List[Tuple[str, Tuple[int, ...]]], attrs: Dict) -> Lis
         if to not in DTYPES:
             raise IllTyped("kind", f"cast to {to!r}")
         return [(to, ins[0][1])]
+    if kind == "layout_transform":
+        need(1)
+        (dx, sx), = ins
+        perm = tuple(int(v) for v in attrs.get("perm", ()))
+        if sorted(perm) != list(range(len(sx))):
+            raise IllTyped("kind", f"perm {perm} is not a permutation of the {len(sx)} axes")
+        return [(dx, tuple(sx[p] for p in perm))]
     if kind == "lstm_gates":
         need(2)
         (dz, sz), (dc, sc) = ins
@@ -294,6 +306,9 @@ def run(spec, data: Dict[str, np.ndarray], keep_all: bool = False) -> Dict[int, 
             out = [a[0].reshape(a[0].shape[0], -1)]
         elif k == "concat":
             out = [np.concatenate([a[0], a[1]], axis=1)]
+        elif k == "layout_transform":
+            # result[i0, i1, ...] = operand[j] with j[perm[k]] = i[k]: the library routine for exactly that
+            out = [np.ascontiguousarray(np.transpose(a[0], tuple(int(v) for v in op.attrs["perm"])))]
         elif k == "cast":
             out = [a[0]]
         elif k == "lstm_gates":

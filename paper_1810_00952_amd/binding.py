@@ -19,7 +19,7 @@ DTYPE_BYTES = {"f32": 4, "bf16": 2}
 
 OPS = {"dense": 0, "conv2d": 1, "bias_add": 2, "add": 3, "sub": 4, "mul": 5, "div": 6, "neg": 7, "sq": 8, "relu": 9,
        "sigmoid": 10, "tanh": 11, "maxpool2d": 12, "global_avgpool": 13, "flatten": 14, "lstm_gates": 15, "cast": 16,
-       "concat": 17}
+       "concat": 17, "layout_transform": 18}
 
 STATUS = {0: "ok", -1: "null", -2: "kind", -3: "shape", -4: "type", -5: "group", -6: "binding", -7: "workspace",
           -8: "align", -9: "unsupported", -10: "hip"}
@@ -47,6 +47,10 @@ class rl_attr_pool2d(ctypes.Structure):
 
 class rl_attr_cast(ctypes.Structure):
     _fields_ = [("to", c_int32)]
+
+
+class rl_attr_layout(ctypes.Structure):
+    _fields_ = [("perm", c_int32 * RL_MAX_RANK)]
 
 
 class rl_binding(ctypes.Structure):
@@ -173,6 +177,11 @@ def _attrs_for(kind: str, attrs: Dict):
         return rl_attr_pool2d(k[0], k[1], s[0], s[1], p[0], p[1])
     if kind == "cast":
         return rl_attr_cast(DTYPES.get(attrs.get("to"), -1))
+    if kind == "layout_transform":
+        perm = [int(v) for v in attrs.get("perm", ())]
+        if len(perm) > RL_MAX_RANK:
+            perm = perm[:RL_MAX_RANK - 1] + [-1]        # cannot be marshalled: let the library reject it
+        return rl_attr_layout((c_int32 * RL_MAX_RANK)(*(perm + [-1] * (RL_MAX_RANK - len(perm)))))
     return None
 
 

@@ -360,12 +360,93 @@ __global__ __launch_bounds__(256) void transpose_kernel(const T *__restrict__ sr
     }
 }
 
+// The same for R and Q multiples of the 16-byte vector (8 bf16 / 4 f32) and 16-byte aligned tensors, without
+// LDS: a lane reads a VEC x VEC block as VEC row vectors, transposes it in registers and writes VEC column
+// vectors.  A wave covers 8 x 8 such blocks; eight lanes read 128 contiguous bytes of a row, and eight lanes
+// write 128 contiguous bytes of a result row.
+template <typename T>
+__global__ __launch_bounds__(256) void transpose_vec_kernel(const T *__restrict__ src, T *__restrict__ dst, int R, int Q, int tiles_r, int tiles_q,
+                                                            int64_t total_tiles)
+{
+    constexpr int VEC = 16 / (int)sizeof(T);
+    constexpr int TS = 8 * VEC;                       // tile side
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lr = lane >> 3, lq = lane & 7;
+    for (int64_t tile = (int64_t)blockIdx.x * 4 + wave; tile < total_tiles; tile += (int64_t)gridDim.x * 4) {
+        const int tq = (int)(tile % tiles_q);
+        const int64_t rest = tile / tiles_q;
+        const int tr = (int)(rest % tiles_r);
+        const int64_t n = rest / tiles_r;
+        const int r0 = tr * TS + lr * VEC, q0 = tq * TS + lq * VEC;
+        if (r0 >= R || q0 >= Q) continue;             // R and Q are multiples of VEC: a block is inside or outside
+        const T *sp = src + (n * R + r0) * Q + q0;
+        u32x4 in[VEC];
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) in[i] = *(const u32x4 *)(sp + (int64_t)i * Q);
+        T *dp = dst + (n * Q + q0) * R + r0;
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) {
+            u32x4 o;
+            if (sizeof(T) == 4) {
+#pragma unroll
+                for (int k = 0; k < 4; ++k) o[k] = in[k < VEC ? k : 0][j & 3];
+            } else {
+                // element j of row i is half (j & 1) of dword j >> 1; result dword k holds rows 2k and 2k + 1
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const uint32_t a = in[(2 * k) % VEC][(j >> 1) & 3], b = in[(2 * k + 1) % VEC][(j >> 1) & 3];
+                    o[k] = (j & 1) ? ((a >> 16) | (b & 0xffff0000u)) : ((a & 0xffffu) | (b << 16));
+                }
+            }
+            *(u32x4 *)(dp + (int64_t)j * R) = o;
+        }
+    }
+}
+
 static hipError_t launch_transpose(const void *src, void *dst, int dtype, int N, int R, int Q, hipStream_t s)
 {
+    const int vec = dtype == DT_BF16 ? 8 : 4;
+    if (R % vec == 0 && Q % vec == 0 && (((uintptr_t)src | (uintptr_t)dst) & 15) == 0 && N > 0) {
+        const int ts = 8 * vec;
+        const int tiles_r = (R + ts - 1) / ts, tiles_q = (Q + ts - 1) / ts;
+        const int64_t total = (int64_t)N * tiles_r * tiles_q;
+        const unsigned grid = (unsigned)std::min<int64_t>((total + 3) / 4, 256 * 64);
+        if (dtype == DT_BF16) hipLaunchKernelGGL(transpose_vec_kernel<uint16_t>, dim3(grid), dim3(256), 0, s, (const uint16_t *)src, (uint16_t *)dst, R, Q, tiles_r, tiles_q, total);
+        else hipLaunchKernelGGL(transpose_vec_kernel<float>, dim3(grid), dim3(256), 0, s, (const float *)src, (float *)dst, R, Q, tiles_r, tiles_q, total);
+        return hipGetLastError();
+    }
     dim3 grid((Q + 31) / 32, (R + 31) / 32, N);
     if (grid.y > 65535 || grid.z > 65535) return hipErrorInvalidValue;
     if (dtype == DT_BF16) hipLaunchKernelGGL(transpose_kernel<uint16_t>, grid, dim3(256), 0, s, (const uint16_t *)src, (uint16_t *)dst, R, Q);
     else hipLaunchKernelGGL(transpose_kernel<float>, grid, dim3(256), 0, s, (const float *)src, (float *)dst, R, Q);
+    return hipGetLastError();
+}
+
+// general permutation: one element per thread, result-major (the writes coalesce, the reads gather)
+template <typename T>
+__global__ __launch_bounds__(256) void permute_kernel(const PermuteParams p)
+{
+    const T *x = (const T *)p.x;
+    T *y = (T *)p.y;
+    for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < p.n; idx += (int64_t)gridDim.x * blockDim.x) {
+        int64_t rem = idx, off = 0;
+#pragma unroll
+        for (int k = 5; k >= 0; --k)
+            if (k < p.rank) {
+                const int64_t q = rem / p.ydims[k];
+                off += (rem - q * p.ydims[k]) * p.xstride[k];
+                rem = q;
+            }
+        y[idx] = x[off];
+    }
+}
+
+hipError_t launch_permute(const PermuteParams &p, hipStream_t s)
+{
+    if (p.rank < 0 || p.rank > 6 || p.n < 0) return hipErrorInvalidValue;
+    if (p.n == 0) return hipSuccess;
+    if (p.dtype == DT_BF16) hipLaunchKernelGGL(permute_kernel<uint16_t>, dim3(grid_for(p.n)), dim3(256), 0, s, p);
+    else hipLaunchKernelGGL(permute_kernel<float>, dim3(grid_for(p.n)), dim3(256), 0, s, p);
     return hipGetLastError();
 }
 

@@ -10,7 +10,7 @@ namespace rl {
 
 static const char *kOpNames[RL_OP_KIND_COUNT] = {
     "dense", "conv2d", "bias_add", "add", "sub", "mul", "div", "neg", "sq", "relu", "sigmoid", "tanh",
-    "maxpool2d", "global_avgpool", "flatten", "lstm_gates", "cast", "concat"};
+    "maxpool2d", "global_avgpool", "flatten", "lstm_gates", "cast", "concat", "layout_transform"};
 
 const char *op_name(int kind) { return (kind >= 0 && kind < RL_OP_KIND_COUNT) ? kOpNames[kind] : "?"; }
 bool is_anchor(int kind) { return kind == RL_OP_DENSE || kind == RL_OP_CONV2D; }
@@ -102,6 +102,12 @@ rl_status parse_attrs(int kind, const void *attrs, size_t size, Attrs &a, std::s
         a.to = ((const rl_attr_cast *)attrs)->to;
         if (a.to != RL_F32 && a.to != RL_BF16) { msg = "cast to unknown base type"; return RL_ERR_KIND; }
         break;
+    case RL_OP_LAYOUT_TRANSFORM: {
+        if (!attrs) { msg = "layout_transform needs rl_attr_layout"; return RL_ERR_KIND; }
+        if (!want(sizeof(rl_attr_layout))) return RL_ERR_KIND;
+        for (int i = 0; i < RL_MAX_RANK; ++i) a.perm[i] = ((const rl_attr_layout *)attrs)->perm[i];
+        break;                                  // checked against the operand's rank in infer_type
+    }
     default:
         break;
     }
@@ -219,6 +225,19 @@ rl_status infer_type(int kind, const std::vector<rl_type> &in, const Attrs &a, c
         out.push_back(in[0]);
         out[0].dtype = a.to;
         return RL_OK;
+    case RL_OP_LAYOUT_TRANSFORM: {
+        if (!arity(1)) return RL_ERR_TYPE;
+        const int r = in[0].rank;
+        uint32_t seen = 0;
+        for (int i = 0; i < r; ++i) {
+            if (a.perm[i] < 0 || a.perm[i] >= r || (seen >> a.perm[i] & 1u)) { msg = "layout_transform: perm is not a permutation of the operand's axes"; return RL_ERR_KIND; }
+            seen |= 1u << a.perm[i];
+        }
+        rl_type t = in[0];
+        for (int i = 0; i < r; ++i) t.dims[i] = in[0].dims[a.perm[i]];
+        out.push_back(t);
+        return RL_OK;
+    }
     case RL_OP_LSTM_GATES: {
         if (!arity(2)) return RL_ERR_TYPE;
         const rl_type &z = in[0], &c = in[1];

@@ -25,6 +25,7 @@ struct Attrs {
     int32_t kernel[2] = {1, 1};                   // pool
     int32_t axis = 1;                             // bias_add / concat
     int32_t to = 0;                               // cast
+    int32_t perm[RL_MAX_RANK] = {0, 1, 2, 3, 4, 5};   // layout_transform
 };
 
 enum Role { ROLE_INPUT = 0, ROLE_PARAM = 1, ROLE_OP = 2 };

@@ -159,6 +159,14 @@ hipError_t launch_gavgpool_nhwc(const PoolParams &p, hipStream_t s);   // y: [N,
 // dst[n, p, c] (pixel-major, channel-last) <-> src[n, c, p]
 hipError_t launch_nchw_to_nhwc(const void *src, void *dst, int32_t dtype, int32_t N, int32_t C, int32_t P, hipStream_t s);
 hipError_t launch_nhwc_to_nchw(const void *src, void *dst, int32_t dtype, int32_t N, int32_t C, int32_t P, hipStream_t s);
+// any permutation of up to six axes (element gather): y[i0..] = x[sum_k i_k * xstride[k]], i over ydims
+struct PermuteParams {
+    const void *x; void *y; int32_t dtype; int32_t rank;
+    int64_t n;                          // elements
+    int32_t ydims[6];                   // result shape
+    int64_t xstride[6];                 // operand stride (elements) of the axis that result axis k comes from
+};
+hipError_t launch_permute(const PermuteParams &p, hipStream_t s);
 // conv weight [O, C, KH*KW] -> [O, KH*KW, C] padded with zeros to Kp per row.
 // perm_block > 0: output row j holds source row gate*(O/4) + blk*(perm_block/4) + u
 // for j = blk*perm_block + gate*(perm_block/4) + u (LSTM gate interleave).

@@ -63,11 +63,24 @@ struct Planner {
         phys[layout][v] = buf;
         if (layout_free(v)) phys[1 - layout][v] = buf;
     }
+    // A graph output that is the channel-last view (layout_transform with axes 0,2,3,1) of rank-4 value v, or -1:
+    // v's channel-last storage then is that output's own buffer.
+    int channel_last_output_of(int v) const
+    {
+        for (int c : consumers[v]) {
+            const OpNode &o = g.ops[c];
+            if (o.kind == RL_OP_LAYOUT_TRANSFORM && T(v).rank == 4 && o.attrs.perm[0] == 0 && o.attrs.perm[1] == 2 && o.attrs.perm[2] == 3 &&
+                o.attrs.perm[3] == 1 && out_set.count(o.out[0]))
+                return o.out[0];
+        }
+        return -1;
+    }
     // buffer a step writes value v into, in `layout`
     int out_buf(int v, int layout)
     {
-        int b;
+        int b, home;
         if (out_set.count(v) && (layout == L_NATIVE || layout_free(v))) b = bound(v);
+        else if (layout == L_NHWC && !layout_free(v) && (home = channel_last_output_of(v)) >= 0) b = bound(home);
         else b = new_ws(bytes_of(v));
         set_phys(v, layout, b);
         return b;
@@ -506,6 +519,78 @@ struct Planner {
         return RL_OK;
     }
 
+    // A change of layout (a permutation of the axes).  Rank-4 values live channel-last inside convolution, pool and
+    // elementwise groups, so the two permutations between channel-first and channel-last Shapes are the other
+    // view of storage that exists anyway: the result aliases it.  A permutation that keeps a prefix of the axes
+    // and exchanges two blocks behind it is a batched transposition (LDS-tiled kernel); the rest gathers.
+    rl_status plan_layout(int gi, int oi)
+    {
+        const OpNode &o = g.ops[oi];
+        const int x = o.in[0], y = o.out[0];
+        const rl_type &xt = T(x), &yt = T(y);
+        const int r = xt.rank;
+        const int32_t *pm = o.attrs.perm;
+        bool ident = true;
+        for (int i = 0; i < r; ++i) ident &= pm[i] == i;
+        const bool to_last = r == 4 && pm[0] == 0 && pm[1] == 2 && pm[2] == 3 && pm[3] == 1;
+        const bool to_first = r == 4 && pm[0] == 0 && pm[1] == 3 && pm[2] == 1 && pm[3] == 2;
+        int buf;
+        if (ident || (to_last && layout_free(x)) || (to_first && layout_free(y))) {     // same order in memory
+            rl_status st = need(x, L_NATIVE, buf);
+            if (st != RL_OK) return st;
+            set_phys(y, L_NATIVE, buf);
+            return RL_OK;
+        }
+        if (to_last && phys[L_NHWC][x] >= 0) { set_phys(y, L_NATIVE, phys[L_NHWC][x]); return RL_OK; }
+        if (to_first) {
+            rl_status st = need(x, L_NATIVE, buf);
+            if (st != RL_OK) return st;
+            set_phys(y, L_NHWC, buf);               // a consumer that wants y in Shape order gets the transposition then
+            return RL_OK;
+        }
+        rl_status st = need(x, L_NATIVE, buf);
+        if (st != RL_OK) return st;
+        // identity prefix of length a, then blocks [a, a+R) and [a+R, r) exchanged?
+        int a = 0;
+        while (a < r && pm[a] == a) ++a;
+        int split = -1;                             // first axis of the block that moves to the front
+        if (a < r) {
+            split = pm[a];
+            bool ok = split > a;
+            for (int i = a; i < r && ok; ++i) ok = pm[i] == (i - a + split < r ? i - a + split : i - a + split - r + a);
+            if (!ok) split = -1;
+        }
+        const int ybuf = out_buf(y, L_NATIVE);
+        if (split > 0) {
+            int64_t outer = 1, R = 1, Q = 1;
+            for (int i = 0; i < a; ++i) outer *= xt.dims[i];
+            for (int i = a; i < split; ++i) R *= xt.dims[i];
+            for (int i = split; i < r; ++i) Q *= xt.dims[i];
+            if (outer <= 65535 && (R + 31) / 32 <= 65535 && Q <= 0x7fffffff && R <= 0x7fffffff) {
+                Step &s = add_step(S_TO_NHWC, "layout_transform#" + std::to_string(oi), "transpose_tiled");
+                s.group = gi;
+                s.t_dtype = xt.dtype; s.t_N = (int)outer; s.t_C = (int)R; s.t_P = (int)Q;
+                s.slot[SL_X] = buf; s.slot[SL_Y] = ybuf;
+                s.bytes = 2.0 * bytes_of(x);
+                if (to_last) phys[L_NHWC][x] = ybuf;     // the result doubles as the operand's channel-last form
+                return RL_OK;
+            }
+        }
+        PermuteParams pe{};
+        pe.dtype = xt.dtype; pe.rank = r; pe.n = numel(xt);
+        int64_t xs[RL_MAX_RANK];
+        int64_t acc = 1;
+        for (int i = r - 1; i >= 0; --i) { xs[i] = acc; acc *= xt.dims[i]; }
+        for (int k = 0; k < r; ++k) { pe.ydims[k] = (int32_t)yt.dims[k]; pe.xstride[k] = xs[pm[k]]; }
+        for (int k = 0; k < r; ++k) if (yt.dims[k] > 0x7fffffff) return fail(RL_ERR_UNSUPPORTED, "layout_transform: axis too long");
+        Step &s = add_step(S_PERMUTE, "layout_transform#" + std::to_string(oi), "permute_gather");
+        s.group = gi;
+        s.pe = pe;
+        s.slot[SL_X] = buf; s.slot[SL_Y] = ybuf;
+        s.bytes = 2.0 * bytes_of(x);
+        return RL_OK;
+    }
+
     rl_status plan_gates(int gi, int oi)
     {
         const OpNode &o = g.ops[oi];
@@ -540,6 +625,7 @@ struct Planner {
             if (k0 == RL_OP_MAXPOOL2D || k0 == RL_OP_GLOBAL_AVGPOOL) return plan_pool(gi, ops[0]);
             if (k0 == RL_OP_FLATTEN) return plan_flatten(ops[0]);
             if (k0 == RL_OP_LSTM_GATES) return plan_gates(gi, ops[0]);
+            if (k0 == RL_OP_LAYOUT_TRANSFORM) return plan_layout(gi, ops[0]);
             if (k0 == RL_OP_CONCAT) return fail(RL_ERR_UNSUPPORTED, "concat is only implemented as the operand of a dense in its group");
         }
         return plan_eltwise(gi, ops);
@@ -556,6 +642,9 @@ struct Planner {
         phys[1].assign(nv, -1);
         out_set.insert(g.outputs.begin(), g.outputs.end());
         if (g.outputs.empty()) return fail(RL_ERR_TYPE, "graph has no output");
+        consumers.assign(nv, {});
+        for (size_t o = 0; o < g.ops.size(); ++o)
+            for (int v : g.ops[o].in) consumers[v].push_back((int)o);
         for (int v = 0; v < nv; ++v)
             if (g.values[v].role != ROLE_OP) set_phys(v, L_NATIVE, bound(v));
 
@@ -872,6 +961,12 @@ rl_status run_steps(const Plan &plan, void *const *ptrs, hipStream_t stream, std
             q.kh = s.stem_kh;
             q.yp_bytes = (uint32_t)((uint64_t)s.sp_N * s.sp_PH * s.sp_PW * 64 * 2);
             er = launch_stem_pool(q, stream);
+            break;
+        }
+        case S_PERMUTE: {
+            PermuteParams p = s.pe;
+            p.x = P(s, SL_X); p.y = P(s, SL_Y);
+            er = launch_permute(p, stream);
             break;
         }
         case S_STEM_PAD:

@@ -10,7 +10,7 @@
 
 namespace rl {
 
-enum StepKind { S_IGEMM = 0, S_ELTWISE, S_GATES, S_MAXPOOL, S_GAVG, S_TO_NHWC, S_TO_NCHW, S_STEM_PAD, S_STEM_POOL };
+enum StepKind { S_IGEMM = 0, S_ELTWISE, S_GATES, S_MAXPOOL, S_GAVG, S_TO_NHWC, S_TO_NCHW, S_STEM_PAD, S_STEM_POOL, S_PERMUTE };
 enum Slot { SL_X = 0, SL_X2, SL_W, SL_Y, SL_E0, SL_E1, SL_E2, SL_E3, SL_E4, SL_E5, SL_CIN, SL_COUT, SL_HOUT, SL_COUNT };
 
 struct BufDesc {
@@ -29,6 +29,7 @@ struct Step {
     EltwiseParams el{};
     GatesParams ga{};
     PoolParams po{};
+    PermuteParams pe{};
     int t_dtype = 0, t_N = 0, t_C = 0, t_P = 0;
     int st_H = 0, st_W = 0, st_Hp = 0, st_Wp = 0, st_ph = 0, st_pw = 0;   // S_STEM_PAD geometry (t_N, t_C: batch, channels)
     int stem = 0;                       // S_IGEMM: the few-channel stem form (padded 4-channel frame, regrouped taps)

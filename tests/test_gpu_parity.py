@@ -657,6 +657,65 @@ def test_lstm_full_configuration():
     assert_close(c, c_ref, "bf16", "lstm full c")
 
 
+# ---- typed changes of layout -----------------------------------------------------------------------------
+LAYOUT_CASES = [
+    ((3, 5, 7, 4), (0, 2, 3, 1), "f32"), ((3, 5, 7, 4), (0, 3, 1, 2), "bf16"), ((37, 70), (1, 0), "bf16"), ((2, 3, 33, 65), (0, 1, 3, 2), "f32"),
+    ((2, 3, 4, 5, 6), (0, 1, 4, 2, 3), "bf16"), ((5, 3, 9, 4), (2, 0, 3, 1), "f32"), ((2, 3, 2, 3, 2, 5), (5, 0, 4, 1, 3, 2), "bf16"),
+    ((2, 3, 4), (0, 1, 2), "f32"), ((2, 1, 4, 5), (0, 2, 3, 1), "bf16"), ((1,), (0,), "f32"), ((4, 64, 56, 56), (0, 2, 3, 1), "bf16"),
+    ((70000, 3), (1, 0), "f32"),
+]
+
+
+@pytest.mark.parametrize("shape,perm,dtype", LAYOUT_CASES, ids=[f"{'x'.join(map(str, c[0]))}-{''.join(map(str, c[1]))}-{c[2]}" for c in LAYOUT_CASES])
+def test_layout_transform_moves_every_element(shape, perm, dtype):
+    # data movement only: every element, bit for bit (tiled transposition, element gather, aliases and the copy-out)
+    spec, data = W.layout_case(shape, perm, dtype)
+    got, _ = run_hip(spec, data)
+    ref = OG.run(spec, data)
+    v = spec.outputs[0]
+    np.testing.assert_array_equal(got[v], ref[v])
+
+
+@pytest.mark.parametrize("batch,c,h,w,dtype", [(3, 64, 14, 14, "bf16"), (2, 128, 14, 14, "bf16"), (2, 24, 9, 7, "f32"), (1, 256, 7, 7, "bf16")])
+def test_block_between_channel_last_tensors(batch, c, h, w, dtype):
+    # channel-last input -> to_first -> two convolution groups (the second adds the input) -> to_last -> output:
+    # the two changes of layout are views of the storage the groups use anyway
+    from paper_1810_00952_amd import binding
+    spec, data = W.channel_last_block(batch, c, h, w, dtype)
+    desc = binding.Plan(binding.graph_from_spec(binding.Context(), spec)).describe()
+    assert [st["kernel"].split("_")[0] for st in desc["steps"]] == ["igemm", "igemm"], [st["kernel"] for st in desc["steps"]]
+    got, _ = run_hip(spec, data)
+    ref = OG.run(spec, data)
+    v = spec.outputs[0]
+    assert_close(got[v], ref[v], dtype, "channel-last block")
+
+
+def test_layout_views_inside_a_graph():
+    # the same value wanted channel-last (an output) and channel-first (another output), and a channel-last view
+    # feeding an elementwise group declared on the permuted Shape
+    g = W.GraphSpec("views")
+    rng = W.rng_for(13)
+    dt = "bf16"
+    x = g.input("x", dt, (2, 16, 6, 5)); w = g.param("w", dt, (16, 16, 3, 3)); b = g.param("b", "f32", (16,))
+    data = {"x": W.as_dtype(W.normal(rng, (2, 16, 6, 5)), dt), "w": W.as_dtype(W.kaiming_normal(rng, (16, 16, 3, 3), 144), dt),
+            "b": W.as_dtype(W.uniform(rng, (16,), -0.1, 0.1), "f32")}
+    t = (dt, (2, 16, 6, 5)); tl = (dt, (2, 6, 5, 16))
+    o0, (y,) = g.op("conv2d", [x, w], [t], stride=(1, 1), pad=(1, 1))
+    o1, (y,) = g.op("bias_add", [y, b], [t], axis=1)
+    g.group([o0, o1])
+    o2, (yl,) = g.op("layout_transform", [y], [tl], perm=(0, 2, 3, 1)); g.group([o2])
+    o3, (z,) = g.op("tanh", [yl], [tl])
+    o4, (z,) = g.op("mul", [z, yl], [tl])
+    g.group([o3, o4])
+    o5, (zf,) = g.op("layout_transform", [z], [t], perm=(0, 3, 1, 2)); g.group([o5])
+    g.output(y); g.output(yl); g.output(zf)
+    got, _ = run_hip(g, data)
+    ref = OG.run(g, data)
+    np.testing.assert_array_equal(got[yl], np.transpose(got[y], (0, 2, 3, 1)))
+    for v in (y, yl, zf):
+        assert_close(got[v], ref[v], dt, f"views value {v}")
+
+
 def test_library_loaded_before_torch_shares_one_hip_runtime():
     # Planning needs no GPU, so a caller may well load the library (and build plans) before anything imports
     # torch.  Both must then end up on one HIP runtime: with two copies in a process the second to

@@ -97,3 +97,38 @@ def test_unrolled_lstm_equals_recurrence():
     # unfused grouping differs only by the f32 rounding of z
     out2 = OG.run(W.lstm_unrolled_graph(T, B, I, H, "bf16", fused=False), data)
     np.testing.assert_allclose(out2[g.outputs[T]], c, rtol=1e-2, atol=1e-3)
+
+
+def test_layout_transform_is_the_index_permutation():
+    # pin: written out with loops over every index of small tensors of rank 2..5: y[i] = x[j], j[perm[k]] = i[k]
+    import itertools
+    for shape, perm in (((3, 4), (1, 0)), ((2, 3, 4), (2, 0, 1)), ((2, 3, 4, 5), (0, 2, 3, 1)), ((2, 3, 4, 5), (0, 3, 1, 2)),
+                        ((2, 3, 2, 3, 2), (4, 0, 3, 1, 2))):
+        g, data = W.layout_case(shape, perm, "f32")
+        y = OG.run(g, data)[g.outputs[0]]
+        x = data["x"].astype(np.float64)
+        assert y.shape == tuple(shape[p] for p in perm)
+        for i in itertools.product(*(range(d) for d in y.shape)):
+            j = [0] * len(shape)
+            for k, p in enumerate(perm):
+                j[p] = i[k]
+            assert y[i] == x[tuple(j)]
+        # the inverse permutation brings the operand back
+        inv = tuple(int(v) for v in np.argsort(perm))
+        g2 = W.GraphSpec("back")
+        a = g2.input("x", "f32", y.shape)
+        o, (b,) = g2.op("layout_transform", [a], [("f32", shape)], perm=inv)
+        g2.output(b)
+        np.testing.assert_array_equal(OG.run(g2, {"x": y.astype(np.float32)})[b], x)
+
+
+def test_channel_last_block_equals_the_channel_first_block():
+    # the typed changes of layout around a block do not change its values: compare with the same block on the
+    # transposed input, written with the op functions
+    g, data = W.channel_last_block(batch=2, c=8, h=5, w=6, dtype="f32")
+    y = OG.run(g, data)[g.outputs[0]]
+    x = np.transpose(O.widen(data["x"], "f32"), (0, 3, 1, 2))
+    w1, b1, w2, b2 = (O.widen(data[k], "f32") for k in ("c1.w", "c1.b", "c2.w", "c2.b"))
+    c1 = O.round_to(O.unary("relu", O.bias_add(O.conv2d(x, w1, (1, 1), (1, 1)), b1, 1)), "f32")
+    c2 = O.round_to(O.unary("relu", O.binary("add", O.bias_add(O.conv2d(c1, w2, (1, 1), (1, 1)), b2, 1), x)), "f32")
+    np.testing.assert_array_equal(y, np.transpose(c2, (0, 2, 3, 1)))

@@ -164,6 +164,7 @@ def _auto(spec):
     ("lenet", lambda: W.lenet()[0]),
     ("eltwise", lambda: W.eltwise_bias_res_relu((4, 8, 6, 6))[0]),
     ("eltwise chain", lambda: W.eltwise_chain()[0]),
+    ("channel-last block", lambda: W.channel_last_block()[0]),
 ])
 def test_autogroup_reproduces_the_declared_groups(name, build):
     # the pass, run on the bare calls, must arrive at the grouping every workload declares by hand,
@@ -218,3 +219,30 @@ def test_autogroup_rules():
     lib.autogroup()
     assert lib.groups(len(g.ops)) == [[o0], [o1], [o2], [o3], [o4]]
     assert lib.autogroup() == 0                           # nothing left to group
+
+
+# ---------------------------------------------------------------- typed changes of layout (host logic only)
+def _plan_steps(spec):
+    plan = B.Plan(B.graph_from_spec(B.Context(), spec))
+    return [(s["name"], s["kernel"]) for s in plan.describe()["steps"]]
+
+
+def test_channel_last_views_cost_no_kernel():
+    # channel-last input and output around two convolution groups: the planner runs those channel-last anyway, so
+    # the two layout_transform calls alias storage: two launches, no transposition, no copy
+    steps = _plan_steps(W.channel_last_block(3, 64, 14, 14, "bf16")[0])
+    assert len(steps) == 2 and all(k.startswith("igemm_conv2d") for _, k in steps), steps
+    # without the typed view a channel-first input is transposed first (and the last group writes channel-first)
+    g, _ = W.conv_group(batch=3, cin=64, cout=64, h=14, w=14, dtype="bf16")
+    assert [k for _, k in _plan_steps(g)][0] == "nchw_to_nhwc"
+
+
+def test_layout_transform_kernel_choice():
+    kern = lambda shape, perm: [k for _, k in _plan_steps(W.layout_case(shape, perm, "f32")[0])]
+    assert kern((3, 5, 7, 4), (0, 2, 3, 1)) == ["transpose_tiled"]          # batched transposition
+    assert kern((3, 5, 7, 4), (0, 3, 1, 2)) == ["nhwc_to_nchw"]             # the result is wanted in Shape order: one transposition
+    assert kern((6, 10), (1, 0)) == ["transpose_tiled"]
+    assert kern((2, 3, 4, 5, 6), (0, 1, 4, 2, 3)) == ["transpose_tiled"]
+    assert kern((2, 3, 4, 5), (2, 0, 3, 1)) == ["permute_gather"]
+    assert kern((2, 3, 4), (0, 1, 2)) == ["eltwise_chain"]                  # identity: the copy into the output buffer
+    assert kern((2, 1, 4, 5), (0, 2, 3, 1)) == ["eltwise_chain"]            # one channel: same order in memory

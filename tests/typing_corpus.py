@@ -213,6 +213,39 @@ def _cast_wrong_declared():
     o, (y,) = g.op("cast", [x], [("f32", (2, 4))], to="bf16"); g.output(y); return g
 
 
+# ---- change of layout: an operator whose arrow type permutes the Shape
+def _layout_ok():
+    g = GraphSpec("t"); x = g.input("x", "bf16", (2, 3, 4, 5))
+    o, (y,) = g.op("layout_transform", [x], [("bf16", (2, 4, 5, 3))], perm=(0, 2, 3, 1)); g.output(y); return g
+
+
+def _layout_wrong_declared():        # the inverse permutation's Shape
+    g = GraphSpec("t"); x = g.input("x", "bf16", (2, 3, 4, 5))
+    o, (y,) = g.op("layout_transform", [x], [("bf16", (2, 5, 3, 4))], perm=(0, 2, 3, 1)); g.output(y); return g
+
+
+def _layout_not_a_permutation():
+    g = GraphSpec("t"); x = g.input("x", "f32", (2, 3, 4))
+    o, (y,) = g.op("layout_transform", [x], [("f32", (2, 4, 4))], perm=(0, 2, 2)); g.output(y); return g
+
+
+def _layout_perm_too_short():
+    g = GraphSpec("t"); x = g.input("x", "f32", (2, 3, 4))
+    o, (y,) = g.op("layout_transform", [x], [("f32", (3, 2))], perm=(1, 0)); g.output(y); return g
+
+
+def _layout_changes_dtype():
+    g = GraphSpec("t"); x = g.input("x", "f32", (2, 3))
+    o, (y,) = g.op("layout_transform", [x], [("bf16", (3, 2))], perm=(1, 0)); g.output(y); return g
+
+
+def _group_layout_fused():           # a change of layout is not injective on the group's output shape
+    g = GraphSpec("t"); x = g.input("x", "f32", (2, 3))
+    o0, (y,) = g.op("relu", [x], [("f32", (2, 3))])
+    o1, (y,) = g.op("layout_transform", [y], [("f32", (3, 2))], perm=(1, 0))
+    g.group([o0, o1]); g.output(y); return g
+
+
 # ---- fusion-group legality
 def _group_two_anchors():
     g = GraphSpec("t"); x = g.input("x", "f32", (2, 8)); w1 = g.param("w1", "f32", (8, 8)); w2 = g.param("w2", "f32", (4, 8))
@@ -308,6 +341,12 @@ CASES = [
     ("lstm_gates_bf16_z", _lstm_gates_bf16_z, "type"),
     ("cast_ok", _cast_ok, None),
     ("cast_wrong_declared", _cast_wrong_declared, "type"),
+    ("layout_ok", _layout_ok, None),
+    ("layout_wrong_declared", _layout_wrong_declared, "type"),
+    ("layout_not_a_permutation", _layout_not_a_permutation, "kind"),
+    ("layout_perm_too_short", _layout_perm_too_short, "kind"),
+    ("layout_changes_dtype", _layout_changes_dtype, "type"),
+    ("group_layout_fused", _group_layout_fused, "group"),
     ("group_two_anchors", _group_two_anchors, "group"),
     ("group_anchor_not_first", _group_anchor_not_first, "group"),
     ("group_intermediate_escapes", _group_intermediate_escapes, "group"),

@@ -247,6 +247,53 @@ def downsample_block(batch=4, cin=64, cout=128, h=32, w=32, dtype="bf16", config
     return g, data
 
 
+def layout_case(shape=(3, 5, 7, 4), perm=(0, 2, 3, 1), dtype="f32", config=11):
+    """One change of layout on its own: y = layout_transform(x; perm), y's Shape is x's Shape permuted."""
+    rng = rng_for(config, salt=len(shape) * 100 + sum((i + 1) * p for i, p in enumerate(perm)))
+    g = GraphSpec("layout_case")
+    x = g.input("x", dtype, shape)
+    data = {"x": as_dtype(normal(rng, shape), dtype)}
+    o, (y,) = g.op("layout_transform", [x], [(dtype, tuple(shape[p] for p in perm))], perm=tuple(perm))
+    g.group([o])
+    g.output(y)
+    return g, data
+
+
+def channel_last_block(batch=3, c=64, h=14, w=14, dtype="bf16", config=12):
+    """A residual block between channel-last tensors: the caller holds x as [N, H, W, C] and wants the result
+    in the same order, and says so with typed changes of layout around the block:
+    y = to_last(relu(conv3x3(relu(conv3x3(to_first(x)) + b1)) + b2 + to_first(x)))."""
+    rng = rng_for(config)
+    g = GraphSpec("channel_last_block")
+    data = {}
+    xl = g.input("x", dtype, (batch, h, w, c))
+    data["x"] = as_dtype(normal(rng, (batch, h, w, c)), dtype)
+    ot = (dtype, (batch, c, h, w))
+    o, (x,) = g.op("layout_transform", [xl], [ot], perm=(0, 3, 1, 2))
+    g.group([o])
+
+    def conv(name, xin, extra=None):
+        wt = g.param(name + ".w", dtype, (c, c, 3, 3))
+        data[name + ".w"] = as_dtype(kaiming_normal(rng, (c, c, 3, 3), c * 9), dtype)
+        b = g.param(name + ".b", "f32", (c,))
+        data[name + ".b"] = as_dtype(uniform(rng, (c,), -0.1, 0.1), "f32")
+        ids = []
+        o, (y,) = g.op("conv2d", [xin, wt], [ot], stride=(1, 1), pad=(1, 1)); ids.append(o)
+        o, (y,) = g.op("bias_add", [y, b], [ot], axis=1); ids.append(o)
+        if extra is not None:
+            o, (y,) = g.op("add", [y, extra], [ot]); ids.append(o)
+        o, (y,) = g.op("relu", [y], [ot]); ids.append(o)
+        g.group(ids)
+        return y
+
+    c1 = conv("c1", x)
+    c2 = conv("c2", c1, extra=x)
+    o, (yl,) = g.op("layout_transform", [c2], [(dtype, (batch, h, w, c))], perm=(0, 2, 3, 1))
+    g.group([o])
+    g.output(yl)
+    return g, data
+
+
 # --------------------------------------------------------------------------
 # configs 3 and 4: ResNet-18-shaped inference graph with folded batch-norm
 # --------------------------------------------------------------------------
