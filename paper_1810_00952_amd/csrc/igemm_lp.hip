@@ -500,7 +500,12 @@ hipError_t launch_igemm_lp_pair(const IgemmParams &a, const IgemmLaunch &la, con
     switch (lp_variant(a, la)) {
     case 0: return launch_lp_pair<128, 128, 2, 4, 4>(a, b, s);
     case 1: return launch_lp_pair<256, 128, 4, 2, 3>(a, b, s);
-    case 2: return launch_lp_pair<128, 64, 4, 1, 4>(a, b, s);
+    case 2:
+        // together the two fill more than one workgroup per CU: three stages (72 KB), so that two share a CU and the
+        // projection's short tiles run inside the stalls of the other's
+        if ((int64_t)((a.M + 127) / 128) * ((a.N + 63) / 64) + (int64_t)((b.M + 127) / 128) * ((b.N + 63) / 64) > 320)
+            return launch_lp_pair<128, 64, 4, 1, 3>(a, b, s);
+        return launch_lp_pair<128, 64, 4, 1, 4>(a, b, s);
     case 3: return launch_lp_pair<128, 64, 4, 1, 3>(a, b, s);
     default: return launch_lp_pair<64, 64, 2, 2, 4>(a, b, s);
     }
