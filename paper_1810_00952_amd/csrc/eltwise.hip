@@ -260,17 +260,20 @@ __global__ __launch_bounds__(256) void maxpool_nhwc_kernel(const PoolParams p)
     }
 }
 
-// One workgroup per (image, slab of 64 channel vectors): the 256 threads split the pixels four ways,
-// each sums its share in fp32, and the four partial sums meet in LDS (fixed order, so the result does
-// not depend on timing).
-template <typename T, int VEC>
+// One workgroup per (image, slab of SLAB channel vectors): the 256 threads split the pixels 256 / SLAB ways,
+// each sums its share in fp32, and the partial sums meet in LDS (fixed order, so the result does not depend
+// on timing).  SLAB = 16 (sixteen pixel groups) gives four times the workgroups and a quarter of the serial
+// loads per thread of SLAB = 64: the kernel is one memory latency after another, not bandwidth.
+template <typename T, int VEC, int SLAB>
 __global__ __launch_bounds__(256) void gavgpool_nhwc_kernel(const PoolParams p)
 {
-    __shared__ float part[4][64][VEC];
+    constexpr int PG = 256 / SLAB;
+    __shared__ float part[PG][SLAB][VEC];
     const int cv = p.C / VEC;
-    const int slabs = (cv + 63) / 64;
+    const int slabs = (cv + SLAB - 1) / SLAB;
     const int n = blockIdx.x / slabs, slab = blockIdx.x - n * slabs;
-    const int v = slab * 64 + (threadIdx.x & 63), g = threadIdx.x >> 6;
+    const int u = threadIdx.x % SLAB, g = threadIdx.x / SLAB;
+    const int v = slab * SLAB + u;
     const T *x = (const T *)p.x;
     T *y = (T *)p.y;
     const int HW = p.H * p.W;
@@ -278,19 +281,24 @@ __global__ __launch_bounds__(256) void gavgpool_nhwc_kernel(const PoolParams p)
 #pragma unroll
     for (int k = 0; k < VEC; ++k) acc[k] = 0.0f;
     if (v < cv)
-        for (int q = g; q < HW; q += 4) {
+        for (int q = g; q < HW; q += PG) {
             float t[VEC];
             VecIO<T, VEC>::load(x + ((int64_t)n * HW + q) * p.C + v * VEC, t);
 #pragma unroll
             for (int k = 0; k < VEC; ++k) acc[k] += t[k];
         }
 #pragma unroll
-    for (int k = 0; k < VEC; ++k) part[g][threadIdx.x & 63][k] = acc[k];
+    for (int k = 0; k < VEC; ++k) part[g][u][k] = acc[k];
     __syncthreads();
     if (g == 0 && v < cv) {
         const float inv = 1.0f / (float)HW;
 #pragma unroll
-        for (int k = 0; k < VEC; ++k) acc[k] = (((part[0][threadIdx.x][k] + part[1][threadIdx.x][k]) + part[2][threadIdx.x][k]) + part[3][threadIdx.x][k]) * inv;
+        for (int k = 0; k < VEC; ++k) {
+            float sum = part[0][u][k];
+#pragma unroll
+            for (int j = 1; j < PG; ++j) sum += part[j][u][k];
+            acc[k] = sum * inv;
+        }
         VecIO<T, VEC>::store(y + (int64_t)n * p.C + v * VEC, acc);
     }
 }
@@ -318,20 +326,25 @@ hipError_t launch_maxpool_nhwc(const PoolParams &p, hipStream_t s)
     return hipGetLastError();
 }
 
+template <typename T, int VEC>
+static hipError_t launch_gavgpool_t(const PoolParams &p, hipStream_t s)
+{
+    const int cv = p.C / VEC;
+    // few workgroups of 64-vector slabs leave most of the chip idle: narrower slabs, more pixel groups
+    const bool narrow = (int64_t)p.N * ((cv + 63) / 64) < 256 && p.H * p.W >= 16;
+    const int slab = narrow ? 16 : 64;
+    const int64_t nb = (int64_t)p.N * ((cv + slab - 1) / slab);
+    if (nb <= 0 || nb > 0x7fffffff) return hipErrorInvalidValue;
+    if (narrow) hipLaunchKernelGGL((gavgpool_nhwc_kernel<T, VEC, 16>), dim3((unsigned)nb), dim3(256), 0, s, p);
+    else hipLaunchKernelGGL((gavgpool_nhwc_kernel<T, VEC, 64>), dim3((unsigned)nb), dim3(256), 0, s, p);
+    return hipGetLastError();
+}
+
 hipError_t launch_gavgpool_nhwc(const PoolParams &p, hipStream_t s)
 {
-    auto blocks = [&](int vec) { return (int64_t)p.N * ((p.C / vec + 63) / 64); };
     const bool wide = p.dtype == DT_BF16 ? p.C % 8 == 0 : p.C % 4 == 0;
-    const int64_t nb = blocks(wide ? (p.dtype == DT_BF16 ? 8 : 4) : 1);
-    if (nb <= 0 || nb > 0x7fffffff) return hipErrorInvalidValue;
-    if (p.dtype == DT_BF16) {
-        if (wide) hipLaunchKernelGGL((gavgpool_nhwc_kernel<uint16_t, 8>), dim3((unsigned)nb), dim3(256), 0, s, p);
-        else hipLaunchKernelGGL((gavgpool_nhwc_kernel<uint16_t, 1>), dim3((unsigned)nb), dim3(256), 0, s, p);
-    } else {
-        if (wide) hipLaunchKernelGGL((gavgpool_nhwc_kernel<float, 4>), dim3((unsigned)nb), dim3(256), 0, s, p);
-        else hipLaunchKernelGGL((gavgpool_nhwc_kernel<float, 1>), dim3((unsigned)nb), dim3(256), 0, s, p);
-    }
-    return hipGetLastError();
+    if (p.dtype == DT_BF16) return wide ? launch_gavgpool_t<uint16_t, 8>(p, s) : launch_gavgpool_t<uint16_t, 1>(p, s);
+    return wide ? launch_gavgpool_t<float, 4>(p, s) : launch_gavgpool_t<float, 1>(p, s);
 }
 
 // ---------------------------------------------------------------------------
