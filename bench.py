@@ -155,7 +155,8 @@ def roofline_of(name, k, peak_tflops):
         roof = {"bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS}
     roof.update({"traffic": None, "kernel": name, "launches_per_step": k["launches"], "avg_launch_us": k["ms"] * 1e3 / k["launches"],
                  "event_overhead_us_removed_per_launch": EVENT_OVERHEAD_US[-1] if EVENT_OVERHEAD_US else 0.0,
-                 "algorithmic_flops_per_step": k["flops"], "algorithmic_bytes_per_step": k["bytes"]})
+                 "algorithmic_flops_per_step": k["flops"], "algorithmic_bytes_per_step": k["bytes"],
+                 "algorithmic_bytes_per_launch": k["bytes"] / max(1, k["launches"])})
     return roof
 
 
@@ -193,7 +194,9 @@ def bench_resnet(args, batch, dtype):
     out["tflops_whole_graph"] = total_flops / (ms * 1e-3) / 1e12
     out["roofline"] = roofline_of(dom_name, dom, peak)
     if dtype == "bf16" and batch == 64:
-        out["roofline"]["traffic"] = measured_traffic(dom_name, "resnet18_b64_bf16_hbm_traffic.txt")
+        per_step = measured_traffic(dom_name, "resnet18_b64_bf16_hbm_traffic.txt")
+        out["roofline"]["traffic"] = per_step / dom["launches"] if per_step is not None else None      # bytes per launch
+        out["roofline"]["traffic_per_step"] = per_step
     out["kernels"] = kernels_json(by_kernel)
     if not args.no_cpu and dtype == "bf16" and batch == 64:
         out["cpu_baseline"] = cpu_baseline_resnet(args.cpu_images)
