@@ -27,6 +27,8 @@
 //     wait(my DMAs of tile t) ; barrier ; issue DMA of tile t+2 ; MFMAs on tile t
 // After the barrier every wave's part of tile t has landed and every wave has
 // left tile t-1, whose stage the new DMA overwrites.
+#include <algorithm>
+
 #include "igemm_epilogue.h"
 
 namespace rl {
@@ -155,8 +157,18 @@ __global__ __launch_bounds__(256) void igemm_dma_kernel(const IgemmParams p)
     // every K-loop body has the same number of DMA instructions in flight (the explicit vmcnt
     // waits count on it); past the last tile all lanes are sent out of range, which costs no
     // memory traffic and only zero-fills a stage nobody reads.
-    const int nk = p.K / BKE;          // >= 2, exact
-    int f_kt = 0, f_c0 = 0, f_tap = 0, f_kh = 0, f_kw = 0;
+    // K tiles [kt0, nk) of the contraction's p.K / BKE (>= 2, exact): all of them, or this workgroup's slice
+    const int split = p.splits > 1 ? (int)blockIdx.y : 0;
+    const int kt0 = p.splits > 1 ? split * p.split_tiles : 0;
+    const int nk = p.splits > 1 ? min(p.K / BKE, kt0 + p.split_tiles) : p.K / BKE;
+    int f_kt = kt0, f_c0 = 0, f_tap = 0, f_kh = 0, f_kw = 0;
+    if (kt0 > 0) {
+        const int tpt = p.C / BKE;      // K tiles per filter tap (a dense contraction is one tap)
+        f_tap = kt0 / tpt;
+        f_c0 = (kt0 - f_tap * tpt) * BKE;
+        f_kh = f_tap / p.KW;
+        f_kw = f_tap - f_kh * p.KW;
+    }
 #define RL_ISSUE(ST)                                                                                                  \
     {                                                                                                                 \
         const bool live = f_kt < nk;                                                                                  \
@@ -226,7 +238,7 @@ __global__ __launch_bounds__(256) void igemm_dma_kernel(const IgemmParams p)
     }
     RL_ISSUE(st0)
     RL_ISSUE(st1)
-    int kt = 0;
+    int kt = kt0;
 #pragma unroll 1
     for (; kt + 3 <= nk; kt += 3) {
         RL_BODY(st0, st2)
@@ -246,6 +258,31 @@ __global__ __launch_bounds__(256) void igemm_dma_kernel(const IgemmParams p)
     // the residual rows of the next pass are fetched while this pass is staged and stored
     using TE = TileEpilogue<BN>;
     float *sC = (float *)st0;
+    if (!GATES && p.splits > 1) {
+        // a slice of K: the bare fp32 sums, row-major [M][N], into this slice's part of the scratch tensor
+        float *dst = p.partial + (int64_t)split * p.M * p.N;
+#pragma unroll
+        for (int q = 0; q < BM / 32; ++q) {
+            wg_barrier();
+            if (wm == q / TM) {
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        int row = 8 * (r >> 2) + 4 * fhalf + (r & 3);
+                        int col = wn * WTN + j * 32 + frow;
+                        sC[row * LDC + col] = acc[q % TM][j][r];
+                    }
+            }
+            __syncthreads();
+            for (int idx = t; idx < 32 * BN; idx += 256) {
+                const int row = idx / BN, col = idx - row * BN;
+                const int m = m0 + q * 32 + row, n = n0 + col;
+                if (m < p.M && n < p.N) dst[(int64_t)m * p.N + n] = sC[row * LDC + col];
+            }
+        }
+        return;
+    }
     const bool rowmajor = (p.ys_n == (int64_t)p.OHW * p.ys_p) && p.ys_c == 1;
     const bool vec_ok = !GATES && rowmajor && (p.N & 7) == 0 && (p.ys_p & 7) == 0;
     const bool pre = vec_ok && p.epi.simple;
@@ -279,6 +316,23 @@ __global__ __launch_bounds__(256) void igemm_dma_kernel(const IgemmParams p)
 #endif
 }
 
+// The second kernel of a split contraction: y[m, n] = epilogue(partial[0][m][n] + partial[1][m][n] + ...), one element
+// per thread, slices added in order (so the result does not depend on timing), any output strides.
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const IgemmParams p)
+{
+    const Epilogue &e = p.epi;
+    const int64_t total = (int64_t)p.M * p.N;
+    for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += (int64_t)gridDim.x * blockDim.x) {
+        const int m = (int)(idx / p.N), n = (int)(idx - (int64_t)m * p.N);
+        float val = p.partial[idx];
+        for (int z = 1; z < p.splits; ++z) val += p.partial[(int64_t)z * total + idx];
+        const int img = m / p.OHW, pix = m - img * p.OHW;
+        const int64_t off = (int64_t)img * p.ys_n + (int64_t)pix * p.ys_p + (int64_t)n * p.ys_c;
+        for (int s = 0; s < e.n_ops; ++s) val = epi_step(e, s, val, off, n);
+        store_from_f32(p.y, p.y_dtype, off, val);
+    }
+}
+
 // explicit instantiations (the host-side launch stubs of a kernel template with function-local
 // __shared__ arrays are not emitted implicitly)
 #define RL_INST(T, BM, BN, G) template __global__ void igemm_dma_kernel<T, BM, BN, G>(const IgemmParams);
@@ -294,6 +348,20 @@ static hipError_t launch_dma(const IgemmParams &p0, hipStream_t s)
     p.nblk_n = (p.N + BN - 1) / BN;
     int64_t nblk = (int64_t)p.nblk_m * p.nblk_n;
     if (nblk <= 0 || nblk > 0x7fffffff) return hipErrorInvalidValue;
+    if (p.splits > 1) {
+        constexpr int BKE = 128 / (int)sizeof(T);
+        const int nk = p.K / BKE;
+        // every slice holds at least one K tile and the slices cover K exactly once
+        if (GATES || !p.partial || p.splits > 64 || p.split_tiles < 1 || (int64_t)(p.splits - 1) * p.split_tiles >= nk ||
+            (int64_t)p.splits * p.split_tiles < nk || p.C % BKE != 0 || p.K1 != p.K)
+            return hipErrorInvalidValue;
+        hipLaunchKernelGGL((igemm_dma_kernel<T, BM, BN, GATES>), dim3((unsigned)nblk, (unsigned)p.splits), dim3(256), 0, s, p);
+        hipError_t er = hipGetLastError();
+        if (er != hipSuccess) return er;
+        const int64_t total = (int64_t)p.M * p.N;
+        hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)std::min<int64_t>((total + 255) / 256, 256 * 16)), dim3(256), 0, s, p);
+        return hipGetLastError();
+    }
     hipLaunchKernelGGL((igemm_dma_kernel<T, BM, BN, GATES>), dim3((unsigned)nblk), dim3(256), 0, s, p);
     return hipGetLastError();
 }

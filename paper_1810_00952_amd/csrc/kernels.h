@@ -83,6 +83,11 @@ struct IgemmParams {
     int64_t ts_h, ts_w;                    // element strides of one filter-tap step (xs_h, xs_w unless the taps are regrouped)
     uint32_t div_ohw_mul, div_ohw_sh, div_ow_mul, div_ow_sh;   // m / OHW and pix / OW by multiply-high (make_fast_div)
     uint32_t tap_rep;                      // bit kh*KW set for every kh < KH (KH*KW <= 32)
+    // K split over `splits` workgroups per tile (direct-load variant only; 0 or 1: no split): workgroup (tile, z)
+    // multiplies K tiles [z*per, (z+1)*per) and writes its fp32 sums to partial[z][M][N]; a second kernel adds the
+    // slices in order z = 0, 1, ... and applies the epilogue
+    int32_t splits, split_tiles;           // split_tiles: K tiles per slice
+    float *partial;
 };
 // q = n / d for n < 2^31:  d == 1 ? n : (mulhi(n, mul) >> sh)
 void make_fast_div(uint32_t d, uint32_t &mul, uint32_t &sh);
@@ -97,6 +102,7 @@ struct IgemmLaunch {
     int32_t ws;         // 1 (with lp): weights-stationary persistent variant (N <= 64, K <= 576)
     int32_t c64;        // 1 (with lp): 3x3 / stride 1 / pad 1, 64 -> 64 channels, image rows of at most 63 pixels (conv3x3_c64.hip)
     int32_t run;        // 1 (with lp): 3x3 / stride 1 / pad 1, C a multiple of 64, image rows of at most 30 pixels, tile not 64x64 (conv3x3_run.hip)
+    int32_t splits;     // > 1 (with dma, no lp, no gates): K split over that many workgroups per tile (IgemmParams::splits)
 };
 hipError_t launch_igemm(const IgemmParams &p, const IgemmLaunch &l, hipStream_t s);
 // two independent pixel-on-lane contractions that use the same kernel variant, in one launch (igemm_lp.hip)

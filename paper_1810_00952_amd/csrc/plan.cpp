@@ -420,9 +420,26 @@ struct Planner {
             bytes += (double)bytes_of(vout);
         }
         p.epi = chain.epi;
+        // Few tiles and a long K (small batches, late stages): K is split over several workgroups per tile, whose fp32
+        // sums meet in a scratch tensor [splits][M][N] that a second kernel adds up in order before the epilogue.
+        int part_buf = -1;
+        if (il.avec && il.dma && !il.lp && !gates && x2 < 0 && !stem && !getenv("RELAYHIP_NO_SPLITK")) {
+            static const int tbm[] = {128, 128, 64, 256}, tbn[] = {128, 64, 64, 128};
+            const int64_t tiles = nblk(tbm[il.tile], tbn[il.tile]);
+            const int nk = p.K / (8 * KV);
+            int want = (int)std::min<int64_t>(std::min<int64_t>(16, 256 / std::max<int64_t>(tiles, 1)), nk / 4);
+            if (tiles <= 64 && want >= 2 && (int64_t)want * p.M * p.N * 4 < (int64_t)1 << 28) {
+                const int per = (nk + want - 1) / want;
+                il.splits = (nk + per - 1) / per;
+                p.splits = il.splits; p.split_tiles = per;
+                part_buf = new_ws((size_t)il.splits * p.M * p.N * 4);
+                bytes += 2.0 * il.splits * p.M * (double)p.N * 4;
+            }
+        }
         static const char *tile_names[] = {"128x128", "128x64", "64x64", "256x128"};
         std::string kname = std::string(an.kind == RL_OP_CONV2D ? "igemm_conv2d_" : "igemm_dense_") + (in_dt == RL_BF16 ? "bf16_" : "f32_") +
-                            (il.c64 ? "3x3_c64" : il.ws ? "128x64_ws" : tile_names[il.tile]) + (il.c64 || il.ws ? "" : il.run ? "_run" : il.lp ? "_lp" : il.avec ? (il.dma ? "_dma" : "") : "_gather") + (gates ? "_gates" : "");
+                            (il.c64 ? "3x3_c64" : il.ws ? "128x64_ws" : tile_names[il.tile]) + (il.c64 || il.ws ? "" : il.run ? "_run" : il.lp ? "_lp" : il.avec ? (il.dma ? "_dma" : "") : "_gather") + (gates ? "_gates" : "") +
+                            (il.splits > 1 ? "_splitk" : "");
         Step &s = add_step(S_IGEMM, std::string(op_name(an.kind)) + "#" + std::to_string(ops[ai]), kname);
         s.group = gi;
         s.ig = p; s.il = il;
@@ -431,6 +448,7 @@ struct Planner {
         s.slot[SL_X] = xbuf; s.slot[SL_X2] = x2buf; s.slot[SL_W] = bound(wv); s.slot[SL_Y] = ybuf;
         for (int i = 0; i < RL_EPI_MAX_PTRS; ++i) s.slot[SL_E0 + i] = eslots[i];
         s.slot[SL_CIN] = cin_buf; s.slot[SL_COUT] = cout_buf; s.slot[SL_HOUT] = hout_buf;
+        s.slot[SL_PART] = part_buf;
         s.flops = flops;
         s.bytes = bytes;
         return RL_OK;
@@ -914,6 +932,7 @@ rl_status run_steps(const Plan &plan, void *const *ptrs, hipStream_t stream, std
                 for (int i = 0; i < RL_EPI_MAX_PTRS; ++i) p.epi.ptr[i] = P(t, SL_E0 + i);
                 finalize_epilogue(p.epi);
                 p.c_in = (const float *)P(t, SL_CIN); p.c_out = (float *)P(t, SL_COUT); p.h_out = P(t, SL_HOUT);
+                p.partial = (float *)P(t, SL_PART);
                 return p;
             };
             if (s.pair == 1) {

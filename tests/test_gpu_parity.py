@@ -657,6 +657,36 @@ def test_lstm_full_configuration():
     assert_close(c, c_ref, "bf16", "lstm full c")
 
 
+# ---- K split over several workgroups per tile (few tiles, long K) --------------------------------------
+SPLITK_CASES = [
+    # batch cin cout h  w  k s p residual relu dtype tail
+    (1, 256, 256, 14, 14, 3, 1, 1, False, True, "f32", False),     # 16 tiles, 72 K tiles: 16 slices
+    (1, 512, 512, 7, 7, 3, 1, 1, True, True, "f32", False),        # 8 tiles, 144 K tiles, residual
+    (1, 256, 512, 14, 14, 3, 2, 1, False, True, "f32", True),      # stride 2, result kept channel-last
+    (2, 64, 72, 9, 11, 3, 1, 1, True, False, "f32", False),        # ragged M and N, 18 K tiles: 4 slices of 5, 5, 5, 3
+    (1, 512, 40, 5, 5, 1, 1, 0, False, False, "f32", False),       # 1x1: one tap, 16 K tiles
+    (3, 128, 136, 7, 7, 3, 1, 1, True, True, "bf16", False),       # bf16 through the same kernel (result in Shape order)
+]
+
+
+@pytest.mark.parametrize("case", SPLITK_CASES, ids=[f"sk{i}" for i in range(len(SPLITK_CASES))])
+def test_contraction_with_k_split_over_workgroups(case, monkeypatch):
+    from paper_1810_00952_amd import binding
+    b, ci, co, h, w, k, s, p, res, relu, dtype, tail = case
+    spec, data = W.conv_group(b, ci, co, h, w, k, s, p, dtype, residual=res, relu=relu, tail=tail)
+    desc = binding.Plan(binding.graph_from_spec(binding.Context(), spec)).describe()
+    assert any(st["kernel"].endswith("_splitk") for st in desc["steps"]), [st["kernel"] for st in desc["steps"]]
+    got, _ = run_hip(spec, data)
+    ref = OG.run(spec, data)
+    v = spec.outputs[0]
+    assert_close(got[v], ref[v], dtype, f"split-K {case}")
+    again, _ = run_hip(spec, data)
+    np.testing.assert_array_equal(got[v], again[v])               # slices are added in a fixed order
+    monkeypatch.setenv("RELAYHIP_NO_SPLITK", "1")
+    whole, _ = run_hip(spec, data)
+    assert_close(whole[v], ref[v], dtype, f"unsplit {case}")
+
+
 # ---- typed changes of layout -----------------------------------------------------------------------------
 LAYOUT_CASES = [
     ((3, 5, 7, 4), (0, 2, 3, 1), "f32"), ((3, 5, 7, 4), (0, 3, 1, 2), "bf16"), ((37, 70), (1, 0), "bf16"), ((2, 3, 33, 65), (0, 1, 3, 2), "f32"),
