@@ -282,7 +282,7 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="resnet18",
-                    choices=["resnet18", "resnet18_f32_b1", "eltwise", "eltwise32", "gates", "lstm", "mlp", "lenet", "conv", "copy", "layout", "layout32", "block_nhwc"])
+                    choices=["resnet18", "resnet18_f32_b1", "eltwise", "eltwise32", "gates", "lstm", "mlp", "lenet", "conv", "copy", "layout", "layout32", "block_nhwc", "maxpool"])
     ap.add_argument("--batch", type=int, default=64)
     ap.add_argument("--cpu-images", type=int, default=128)
     ap.add_argument("--no-cpu", action="store_true")
@@ -336,6 +336,10 @@ def main():
         n = shape[0] * shape[1] * shape[2] * shape[3]
         out = bench_graph(args, spec, data, f"elements/sec channel-first to channel-last {dtype}", "elements/s", n, dtype,
                           f"layout_transform (0,2,3,1) of {'x'.join(map(str, shape))} {dtype}, N(0,1) input", PEAK_F32_TFLOPS)
+    elif wl == "maxpool":
+        spec, data = W.channel_last_maxpool(64, 64, 112, 112, 3, 2, 1, "bf16")
+        out = bench_graph(args, spec, data, "output elements/sec max-pool 3x3/2 bf16", "elements/s", 64 * 64 * 56 * 56, "bf16",
+                          "maxpool2d 3x3 stride 2 pad 1 on 64x64x112x112 bf16 (between channel-last tensors), N(0,1) input", PEAK_F32_TFLOPS)
     elif wl == "block_nhwc":
         spec, data = W.channel_last_block(64, 64, 56, 56, "bf16")
         out = bench_graph(args, spec, data, "images/sec residual block 64ch 56x56 bf16 b64 between channel-last tensors", "images/s", 64, "bf16",

@@ -720,6 +720,20 @@ def test_block_between_channel_last_tensors(batch, c, h, w, dtype):
     assert_close(got[v], ref[v], dtype, "channel-last block")
 
 
+@pytest.mark.parametrize("batch,c,h,w,k,s,p,dtype", [(2, 16, 33, 31, 3, 2, 1, "bf16"), (1, 8, 40, 17, 3, 2, 0, "f32"), (2, 64, 112, 112, 3, 2, 1, "bf16"),
+                                                   (3, 24, 16, 16, 3, 2, 1, "f32"), (1, 8, 9, 9, 2, 2, 0, "bf16")])
+def test_maxpool_between_channel_last_tensors(batch, c, h, w, k, s, p, dtype):
+    # signed inputs: taps outside the image must be ignored, not read as zeros; bit-exact (a selection)
+    from paper_1810_00952_amd import binding
+    spec, data = W.channel_last_maxpool(batch, c, h, w, k, s, p, dtype)
+    desc = binding.Plan(binding.graph_from_spec(binding.Context(), spec)).describe()
+    assert [st["kernel"] for st in desc["steps"]] == ["maxpool_nhwc"]
+    got, _ = run_hip(spec, data)
+    ref = OG.run(spec, data)
+    v = spec.outputs[0]
+    np.testing.assert_array_equal(got[v], ref[v])
+
+
 def test_layout_views_inside_a_graph():
     # the same value wanted channel-last (an output) and channel-first (another output), and a channel-last view
     # feeding an elementwise group declared on the permuted Shape

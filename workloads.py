@@ -259,6 +259,20 @@ def layout_case(shape=(3, 5, 7, 4), perm=(0, 2, 3, 1), dtype="f32", config=11):
     return g, data
 
 
+def channel_last_maxpool(batch=64, c=64, h=112, w=112, k=3, stride=2, pad=1, dtype="bf16", config=14):
+    """A max-pool between channel-last tensors (typed views around it): y = to_last(maxpool(to_first(x)))."""
+    rng = rng_for(config)
+    g = GraphSpec("channel_last_maxpool")
+    xl = g.input("x", dtype, (batch, h, w, c))
+    data = {"x": as_dtype(normal(rng, (batch, h, w, c)), dtype)}
+    oh, ow = conv_out(h, k, stride, pad), conv_out(w, k, stride, pad)
+    o, (x,) = g.op("layout_transform", [xl], [(dtype, (batch, c, h, w))], perm=(0, 3, 1, 2)); g.group([o])
+    o, (y,) = g.op("maxpool2d", [x], [(dtype, (batch, c, oh, ow))], kernel=(k, k), stride=(stride, stride), pad=(pad, pad)); g.group([o])
+    o, (yl,) = g.op("layout_transform", [y], [(dtype, (batch, oh, ow, c))], perm=(0, 2, 3, 1)); g.group([o])
+    g.output(yl)
+    return g, data
+
+
 def channel_last_block(batch=3, c=64, h=14, w=14, dtype="bf16", config=12):
     """A residual block between channel-last tensors: the caller holds x as [N, H, W, C] and wants the result
     in the same order, and says so with typed changes of layout around the block:
