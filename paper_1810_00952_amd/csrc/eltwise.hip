@@ -235,7 +235,14 @@ __global__ __launch_bounds__(256) void maxpool_nhwc_kernel(const PoolParams p)
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     const T *x = (const T *)p.x;
     T *y = (T *)p.y;
-    for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += stride) {
+    // consecutive workgroup ids go to different XCDs: give each XCD a contiguous run of the output, so that windows
+    // that share input rows share an L2
+    int64_t bid = blockIdx.x;
+    {
+        const int64_t per = gridDim.x / 8, main = per * 8;
+        if (bid < main) bid = (bid % 8) * per + bid / 8;
+    }
+    for (int64_t idx = bid * blockDim.x + threadIdx.x; idx < total; idx += stride) {
         int c = (int)(idx % cv) * VEC;
         int64_t q = idx / cv;
         int ow = (int)(q % p.OW); q /= p.OW;
