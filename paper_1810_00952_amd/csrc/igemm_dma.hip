@@ -122,6 +122,7 @@ __global__ __launch_bounds__(256) void igemm_dma_kernel(const IgemmParams p)
     // ---- per-lane DMA state.  Lane l of a group writes LDS row (l >> 3), position (l & 7).
     const int r8 = lane >> 3, pos = lane & 7;
     uint32_t a_voff[AG], a_mask[AG], a2_voff[AG], b_voff[BG];
+    int a_kc[AG];                       // first K element (within a tile) of the 16-byte chunk this lane fetches
 #pragma unroll
     for (int i = 0; i < AG; ++i) {
         const int row = wave * 8 * AG + 8 * i + r8;
@@ -141,6 +142,7 @@ __global__ __launch_bounds__(256) void igemm_dma_kernel(const IgemmParams p)
             off = ((int64_t)img * p.xs_n + (int64_t)ih0 * p.xs_h + (int64_t)iw0 * p.xs_w) * ES;
         }
         a_mask[i] = mask;
+        a_kc[i] = chunk * KV;
         a_voff[i] = (uint32_t)(off + bias) + chunk * 16;
         a2_voff[i] = (uint32_t)((int64_t)m * p.x2s_n * ES) + chunk * 16;     // second operand of a concatenation: row m
     }
@@ -157,13 +159,16 @@ __global__ __launch_bounds__(256) void igemm_dma_kernel(const IgemmParams p)
     // every K-loop body has the same number of DMA instructions in flight (the explicit vmcnt
     // waits count on it); past the last tile all lanes are sent out of range, which costs no
     // memory traffic and only zero-fills a stage nobody reads.
-    // K tiles [kt0, nk) of the contraction's p.K / BKE (>= 2, exact): all of them, or this workgroup's slice
+    // K tiles [kt0, nk) of the contraction's ceil(p.K / BKE) (>= 2): all of them, or this workgroup's slice.  Only a
+    // one-tap contraction (dense, 1x1) may end in a partial tile: the weights are packed with zeros up to the tile,
+    // the activation chunks past K are requested out of range.
+    const int nk_all = (p.K + BKE - 1) / BKE;
     const int split = p.splits > 1 ? (int)blockIdx.y : 0;
     const int kt0 = p.splits > 1 ? split * p.split_tiles : 0;
-    const int nk = p.splits > 1 ? min(p.K / BKE, kt0 + p.split_tiles) : p.K / BKE;
+    const int nk = p.splits > 1 ? min(nk_all, kt0 + p.split_tiles) : nk_all;
     int f_kt = kt0, f_c0 = 0, f_tap = 0, f_kh = 0, f_kw = 0;
     if (kt0 > 0) {
-        const int tpt = p.C / BKE;      // K tiles per filter tap (a dense contraction is one tap)
+        const int tpt = p.KH * p.KW == 1 ? nk_all : p.C / BKE;      // K tiles per filter tap
         f_tap = kt0 / tpt;
         f_c0 = (kt0 - f_tap * tpt) * BKE;
         f_kh = f_tap / p.KW;
@@ -177,9 +182,10 @@ __global__ __launch_bounds__(256) void igemm_dma_kernel(const IgemmParams p)
         if (k0 < p.K1 || !live) {                                                                                     \
             const uint32_t tapbit = live ? (1u << f_tap) : 0u;                                                        \
             const uint32_t soff_a = live ? (uint32_t)(((int64_t)f_kh * p.xs_h + (int64_t)f_kw * p.xs_w + f_c0) * ES) : 0u; \
+            const int krem = p.K - k0;      /* K elements from this tile's start on: >= BKE except in a partial last tile */ \
             _Pragma("unroll") for (int i = 0; i < AG; ++i)                                                            \
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(rx, RL_LDS_PTR(ST + (wave * AG + i) * 1024), 16,             \
-                                                         (a_mask[i] & tapbit) ? a_voff[i] : OOB, soff_a, 0, 0);       \
+                                                         ((a_mask[i] & tapbit) && a_kc[i] < krem) ? a_voff[i] : OOB, soff_a, 0, 0); \
         } else {                                                                                                      \
             const uint32_t soff_a = (uint32_t)(k0 - p.K1) * ES;                                                       \
             _Pragma("unroll") for (int i = 0; i < AG; ++i)                                                            \
@@ -344,16 +350,21 @@ template <typename T, int BM, int BN, bool GATES>
 static hipError_t launch_dma(const IgemmParams &p0, hipStream_t s)
 {
     IgemmParams p = p0;
+    {
+        // a partial last K tile: one tap, no concatenation, weight rows padded to whole tiles
+        constexpr int BKE = 128 / (int)sizeof(T);
+        if (p.K % BKE != 0 && (p.KH * p.KW != 1 || p.K1 != p.K || p.x2 || p.Kp % BKE != 0 || p.Kp < p.K || GATES)) return hipErrorInvalidValue;
+    }
     p.nblk_m = (p.M + BM - 1) / BM;
     p.nblk_n = (p.N + BN - 1) / BN;
     int64_t nblk = (int64_t)p.nblk_m * p.nblk_n;
     if (nblk <= 0 || nblk > 0x7fffffff) return hipErrorInvalidValue;
     if (p.splits > 1) {
         constexpr int BKE = 128 / (int)sizeof(T);
-        const int nk = p.K / BKE;
+        const int nk = (p.K + BKE - 1) / BKE;
         // every slice holds at least one K tile and the slices cover K exactly once
         if (GATES || !p.partial || p.splits > 64 || p.split_tiles < 1 || (int64_t)(p.splits - 1) * p.split_tiles >= nk ||
-            (int64_t)p.splits * p.split_tiles < nk || p.C % BKE != 0 || p.K1 != p.K)
+            (int64_t)p.splits * p.split_tiles < nk || (p.C % BKE != 0 && p.KH * p.KW != 1) || p.K1 != p.K)
             return hipErrorInvalidValue;
         hipLaunchKernelGGL((igemm_dma_kernel<T, BM, BN, GATES>), dim3((unsigned)nblk, (unsigned)p.splits), dim3(256), 0, s, p);
         hipError_t er = hipGetLastError();

@@ -341,6 +341,17 @@ struct Planner {
             const size_t halo = (size_t)((int64_t)p.ph * p.xs_h + (int64_t)p.pw * p.xs_w) * dtype_size(in_dt);
             il.dma = !stem && il.avec && p.C % bke == 0 && p.K % bke == 0 && p.K / bke >= 2 && p.KH * p.KW <= 32 &&
                      (x2 < 0 || p.K1 % bke == 0) && x_extent + halo < lim && !getenv("RELAYHIP_NO_DMA");
+            // a dense contraction whose K is a multiple of the vector but not of the K tile: the weights are packed
+            // with zeros up to whole tiles and the kernel requests the activation chunks past K out of range
+            if (!il.dma && an.kind == RL_OP_DENSE && !stem && !gates && x2 < 0 && il.avec && p.K % bke != 0 && p.K / bke >= 2 &&
+                x_extent < lim && (size_t)p.N * round_up(p.K, bke) * dtype_size(in_dt) < lim && !getenv("RELAYHIP_NO_DMA")) {
+                il.dma = 1;
+                p.Kp = (int)round_up(p.K, bke);
+                need_pack = true;
+                pack.Kp = p.Kp;
+                pack.bytes = (size_t)pack.O * pack.Kp * dtype_size(in_dt);
+                p.w_bytes = (uint32_t)pack.bytes;
+            }
             // pixel-on-lane variant: bf16 throughout, output rows contiguous in n, epilogue [bias] [+residual] [relu]
             bool y_ok = vout >= 0 && T(vout).dtype == RL_BF16 && p.ys_c == 1 && p.ys_n == (int64_t)p.OHW * p.ys_p && p.N % 8 == 0 &&
                         bytes_of(vout) < lim;
@@ -426,7 +437,7 @@ struct Planner {
         if (il.avec && il.dma && !il.lp && !gates && x2 < 0 && !stem && !getenv("RELAYHIP_NO_SPLITK")) {
             static const int tbm[] = {128, 128, 64, 256}, tbn[] = {128, 64, 64, 128};
             const int64_t tiles = nblk(tbm[il.tile], tbn[il.tile]);
-            const int nk = p.K / (8 * KV);
+            const int nk = (p.K + 8 * KV - 1) / (8 * KV);
             int want = (int)std::min<int64_t>(std::min<int64_t>(16, 256 / std::max<int64_t>(tiles, 1)), nk / 4);
             if (tiles <= 64 && want >= 2 && (int64_t)want * p.M * p.N * 4 < (int64_t)1 << 28) {
                 const int per = (nk + want - 1) / want;

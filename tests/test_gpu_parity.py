@@ -36,6 +36,26 @@ def test_dense_gather_path_odd_k():
         check_graph(spec, data, f"mlp odd K {dtype} {k}")
 
 
+def test_dense_with_a_partial_last_k_tile():
+    # K a multiple of the 16-byte vector but not of the K tile: direct-load kernel on zero-padded weight rows, the
+    # activation chunks past K requested out of range
+    from paper_1810_00952_amd import binding
+    for dtype, batch, k, hidden in (("f32", 5, 100, 36), ("bf16", 70, 200, 136), ("f32", 3, 68, 8), ("bf16", 33, 456, 72)):
+        spec, data = W.mlp(batch, k, hidden, 8, dtype)
+        desc = binding.Plan(binding.graph_from_spec(binding.Context(), spec)).describe()
+        assert "_dma" in desc["steps"][0]["kernel"], desc["steps"][0]["kernel"]
+        got, _ = check_graph(spec, data, f"mlp partial K tile {dtype} {k}")
+        # what lies behind a row's K elements (the next row) must not leak into it, whatever it is
+        x = data["x"].copy()
+        if dtype == "bf16":
+            x[1:, :16] = 0x7F80                        # +inf in bf16
+        else:
+            x[1:, :16] = np.inf
+        poisoned, _ = run_hip(spec, dict(data, x=x))
+        v = spec.outputs[0]
+        np.testing.assert_array_equal(poisoned[v][0], got[v][0])
+
+
 # ------------------------------------------------------------------ conv groups
 CONV_CASES = [
     # batch cin cout h  w  k s p residual relu
