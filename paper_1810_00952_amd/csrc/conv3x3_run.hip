@@ -420,7 +420,11 @@ __global__ __launch_bounds__(256) void conv3x3_run_ks_kernel(const IgemmParams p
         const int per = nblk / NUM_XCD, main = per * NUM_XCD;
         if (bid < main) bid = (bid % NUM_XCD) * per + bid / NUM_XCD;
     }
-    const int bm = bid / p.nblk_n, bn = bid - bm * p.nblk_n;
+    // Channel-tile-major order when the weights of all channel tiles (N x K) would not stay in an XCD's L2 beside the
+    // activations: each XCD then multiplies every pixel tile by one or two channel tiles' weights.
+    int bm, bn;
+    if (p.nmajor) { bn = bid / p.nblk_m; bm = bid - bn * p.nblk_m; }
+    else { bm = bid / p.nblk_n; bn = bid - bm * p.nblk_n; }
     const int m0 = bm * BM, n0 = bn * BN;
 
     const u32x4 dx = make_desc(p.x, p.x_bytes);
@@ -670,6 +674,7 @@ hipError_t launch_conv3x3_run(const IgemmParams &p, const IgemmLaunch &l, hipStr
             IgemmParams q = p;
             q.nblk_m = (p.M + 127) / 128;
             q.nblk_n = (p.N + 63) / 64;
+            q.nmajor = (int64_t)p.N * p.K * 2 > (3 << 20) ? 1 : 0;      // layer4 of the benchmark: 4.7 MB of weights, 4 MB of L2 per XCD
             hipLaunchKernelGGL((conv3x3_run_ks_kernel<128, 64, 6>), dim3((unsigned)(q.nblk_m * q.nblk_n)), dim3(256), 0, s, q);
             return hipGetLastError();
         }

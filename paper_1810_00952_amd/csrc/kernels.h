@@ -86,6 +86,7 @@ struct IgemmParams {
     // K split over `splits` workgroups per tile (direct-load variant only; 0 or 1: no split): workgroup (tile, z)
     // multiplies K tiles [z*per, (z+1)*per) and writes its fp32 sums to partial[z][M][N]; a second kernel adds the
     // slices in order z = 0, 1, ... and applies the epilogue
+    int32_t nmajor;                        // conv3x3_run_ks_kernel: 1: tiles in channel-tile-major order
     int32_t splits, split_tiles;           // split_tiles: K tiles per slice
     float *partial;
 };
