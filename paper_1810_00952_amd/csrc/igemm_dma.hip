@@ -327,11 +327,19 @@ __global__ __launch_bounds__(256) void igemm_dma_kernel(const IgemmParams p)
 __global__ __launch_bounds__(256) void splitk_reduce_kernel(const IgemmParams p)
 {
     const Epilogue &e = p.epi;
-    const int64_t total = (int64_t)p.M * p.N;
-    for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += (int64_t)gridDim.x * blockDim.x) {
-        const int m = (int)(idx / p.N), n = (int)(idx - (int64_t)m * p.N);
-        float val = p.partial[idx];
-        for (int z = 1; z < p.splits; ++z) val += p.partial[(int64_t)z * total + idx];
+    const uint32_t total = (uint32_t)p.M * (uint32_t)p.N;            // below 2^31 (checked by the launcher): 32-bit index arithmetic
+    for (uint32_t idx = blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += gridDim.x * blockDim.x) {
+        const int m = (int)(idx / (uint32_t)p.N), n = (int)(idx - (uint32_t)m * (uint32_t)p.N);
+        // eight slices' values are requested before the first is added (the additions stay in slice order)
+        float val = 0.0f;
+        for (int z0 = 0; z0 < p.splits; z0 += 8) {
+            float v[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) v[j] = z0 + j < p.splits ? p.partial[(int64_t)(z0 + j) * total + idx] : 0.0f;    // splits * total < 2^26 floats
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                if (z0 + j < p.splits) val = z0 + j == 0 ? v[j] : val + v[j];
+        }
         const int img = m / p.OHW, pix = m - img * p.OHW;
         const int64_t off = (int64_t)img * p.ys_n + (int64_t)pix * p.ys_p + (int64_t)n * p.ys_c;
         for (int s = 0; s < e.n_ops; ++s) val = epi_step(e, s, val, off, n);
@@ -363,7 +371,7 @@ static hipError_t launch_dma(const IgemmParams &p0, hipStream_t s)
         constexpr int BKE = 128 / (int)sizeof(T);
         const int nk = (p.K + BKE - 1) / BKE;
         // every slice holds at least one K tile and the slices cover K exactly once
-        if (GATES || !p.partial || p.splits > 64 || p.split_tiles < 1 || (int64_t)(p.splits - 1) * p.split_tiles >= nk ||
+        if (GATES || !p.partial || p.splits > 64 || (int64_t)p.M * p.N * p.splits >= (int64_t)1 << 31 || p.split_tiles < 1 || (int64_t)(p.splits - 1) * p.split_tiles >= nk ||
             (int64_t)p.splits * p.split_tiles < nk || (p.C % BKE != 0 && p.KH * p.KW != 1) || p.K1 != p.K)
             return hipErrorInvalidValue;
         hipLaunchKernelGGL((igemm_dma_kernel<T, BM, BN, GATES>), dim3((unsigned)nblk, (unsigned)p.splits), dim3(256), 0, s, p);
