@@ -501,7 +501,7 @@ def test_resnet_small_end_to_end_and_per_group(dtype):
             assert_close(out[vid], allv[inv[vid]], sub.values[vid].type.dtype, f"resnet small {dtype} group {gi} ({spec.ops[spec.groups[gi][0]].kind})")
 
 
-@pytest.mark.parametrize("which", ["resnet_small_f32", "resnet_small_bf16", "conv_bf16", "mlp_f32"])
+@pytest.mark.parametrize("which", ["resnet_small_f32", "resnet_small_bf16", "conv_bf16", "mlp_f32", "splitk_f32", "channel_last_bf16"])
 def test_plan_replays_from_a_hip_graph(which):
     # one rl_plan_run captured into a HIP graph, then replayed with fresh inputs, with eager work and
     # synchronisation between the replays; every replay must reproduce the eager run bit for bit
@@ -514,6 +514,13 @@ def test_plan_replays_from_a_hip_graph(which):
         fold_resnet_hip(s, raw, bn, dtype)
     elif which == "conv_bf16":
         spec, data = W.conv_group(3, 64, 128, 29, 29, 3, 1, 1, "bf16", residual=True, relu=True, tail=True)
+        s = harness.Session(spec); s.load(data)
+    elif which == "splitk_f32":                     # two kernels per step and a scratch tensor in the workspace
+        spec, data = W.conv_group(1, 256, 256, 14, 14, 3, 1, 1, "f32", residual=True, relu=True)
+        s = harness.Session(spec); s.load(data)
+        assert any(st["kernel"].endswith("_splitk") for st in s.plan.describe()["steps"])
+    elif which == "channel_last_bf16":              # typed views: the first group reads the caller's buffer, the last writes the output
+        spec, data = W.channel_last_block(3, 64, 14, 14, "bf16")
         s = harness.Session(spec); s.load(data)
     else:
         spec, data = W.mlp()
