@@ -246,3 +246,24 @@ def test_layout_transform_kernel_choice():
     assert kern((2, 3, 4, 5), (2, 0, 3, 1)) == ["permute_gather"]
     assert kern((2, 3, 4), (0, 1, 2)) == ["eltwise_chain"]                  # identity: the copy into the output buffer
     assert kern((2, 1, 4, 5), (0, 2, 3, 1)) == ["eltwise_chain"]            # one channel: same order in memory
+
+
+# ---------------------------------------------------------------- K split over workgroups (host logic only)
+def test_split_k_is_planned_for_few_tiles_and_long_k(monkeypatch):
+    def kernels(spec):
+        d = B.Plan(B.graph_from_spec(B.Context(), spec)).describe()
+        return [s["kernel"] for s in d["steps"] if s["kernel"].startswith("igemm")], d["workspace_bytes"]
+    # batch 1, 512 -> 512 channels on 7x7: 8 tiles of 64x64, 144 K tiles of 32: split, and the scratch tensor
+    # [16 slices][49][512] f32 is part of the workspace
+    spec = W.conv_group(1, 512, 512, 7, 7, 3, 1, 1, "f32")[0]
+    k, ws = kernels(spec)
+    assert k == ["igemm_conv2d_f32_64x64_dma_splitk"] and ws >= 16 * 49 * 512 * 4
+    monkeypatch.setenv("RELAYHIP_NO_SPLITK", "1")
+    k1, ws1 = kernels(spec)
+    assert k1 == ["igemm_conv2d_f32_64x64_dma"] and ws1 < ws
+    monkeypatch.delenv("RELAYHIP_NO_SPLITK")
+    # many tiles: no split; the benchmark graph (batch 64, bf16) has none either
+    assert not any(x.endswith("_splitk") for x in kernels(W.conv_group(16, 64, 64, 56, 56, 3, 1, 1, "f32")[0])[0])
+    assert not any(x.endswith("_splitk") for x in kernels(W.resnet18(64, "bf16")[0])[0])
+    # a dense contraction with a partial last K tile (784 = 24.5 x 32) takes the direct-load kernel
+    assert kernels(W.mlp(32, 784, 128, 10, "f32")[0])[0][0] == "igemm_dense_f32_64x64_dma_splitk"
