@@ -164,10 +164,36 @@ rl_status rl_graph_autogroup(rl_graph *g, int32_t *n_groups);
 rl_status rl_graph_group_of(const rl_graph *g, int32_t op_id, int32_t *group_id);
 
 /* ---- plan ---------------------------------------------------------------
- * rl_plan_create re-checks the whole graph (types, groups, outputs reachable),
- * picks kernels, tiles and private layouts and sizes the workspace.  It needs
- * no GPU.  The graph may be destroyed afterwards. */
-rl_status rl_plan_create(rl_graph *g, rl_plan **out);
+ * Plan-time options.  The paper leaves the choice of an operator's implementation to the layer below the typed
+ * graph (section "Runtime System": one type-specialised operator per call); these switches steer that choice
+ * and nothing else: each non-zero field takes one kernel form out of the planner's repertoire (ws_all widens
+ * one), so that the next form down runs on the same shapes -- results stay within summation order.  The choices
+ * are fixed inside the plan when it is created; no environment variable and no later call changes them.
+ * All zero (or a NULL pointer) = the planner's own choices. */
+typedef struct rl_plan_opts {
+    uint32_t struct_size;   /* sizeof(rl_plan_opts) of the caller's build; must be <= the library's (else RL_ERR_KIND);
+                               fields the caller's struct does not have read as 0 */
+    int32_t no_lp;          /* no pixel-on-lane bf16 contraction kernels (nor their register/LDS-row epilogue) */
+    int32_t no_lp_256;      /* no 256x128 tile in that family */
+    int32_t no_ws;          /* no weights-stationary persistent kernel for N <= 64, K <= 320 */
+    int32_t ws_all;         /* take that kernel up to K = 576 as well */
+    int32_t no_stem;        /* few-channel stems: no padded 4-channel frame, gather from the operand instead */
+    int32_t no_stem_pool;   /* stem convolution and the max-pool behind it stay two kernels */
+    int32_t no_dma;         /* no direct global->LDS operand path (register-staged vector loads instead) */
+    int32_t no_c64;         /* no weights-in-registers kernel for 3x3 64->64 convolutions */
+    int32_t no_run;         /* no nine-taps-from-one-copy kernel for 3x3 stride-1 convolutions on short rows */
+    int32_t no_run_ks;      /* in that kernel's 128x64 form: do not split K over the waves */
+    int32_t no_pair;        /* a stride-2 convolution and the 1x1 projection beside it go out as two launches */
+    int32_t no_splitk;      /* never split K over several workgroups per tile */
+    int32_t no_hoist;       /* rl_plan_run_recurrent: never hoist the input projection out of the step loop */
+} rl_plan_opts;
+
+/* rl_plan_create re-checks the whole graph (Type-Call on every call, group legality, outputs reachable), picks
+ * one kernel per fusion group, tiles and private layouts, and sizes the workspace -- the paper's evaluator
+ * "producing a type-specialised operator per call" (section "Runtime System"), done once ahead of the runs.
+ * It needs no GPU.  opts may be NULL.  The graph may be destroyed afterwards.  Errors: RL_ERR_NULL, RL_ERR_KIND
+ * (opts->struct_size larger than the library knows), RL_ERR_TYPE / RL_ERR_GROUP (graph), RL_ERR_UNSUPPORTED. */
+rl_status rl_plan_create(rl_graph *g, const rl_plan_opts *opts, rl_plan **out);
 void rl_plan_destroy(rl_plan *plan);
 /* JSON text describing the steps (kernel, tile, flops, algorithmic bytes).
  * Writes at most cap bytes including the terminator; *needed gets the full size. */

@@ -232,10 +232,18 @@ def check(spec) -> None:
             raise IllTyped("group", "anchor is not the group's first operator")
         tail = ops[lead + 1:] if anchors else ops
         if len(ops) > 1:
-            for o in tail:
-                last_gate = o.kind == "lstm_gates" and o is ops[-1]
+            for idx, o in enumerate(tail):
+                # the gate operator closes a group only as the epilogue of a dense contraction: its pre-activations
+                # are the value the rest of the group computes and its cell state comes from outside
+                last_gate = o.kind == "lstm_gates" and o is ops[-1] and bool(anchors) and kinds[lead] == "dense"
                 if o.kind not in INJECTIVE and not last_gate:
                     raise IllTyped("group", f"{o.kind} cannot be fused")
+                if last_gate:
+                    prev = ops[-2]
+                    if o.inputs[0] not in prev.outputs:
+                        raise IllTyped("group", "lstm_gates must take the group's last result as its first operand")
+                    if producer.get(o.inputs[1]) in gset:
+                        raise IllTyped("group", "lstm_gates' cell state must come from outside the group")
         # connectivity + single escape
         for idx, o in enumerate(ops):
             if idx > 0 and not any(producer.get(v) in gset for v in o.inputs):

@@ -63,6 +63,27 @@ class rl_recurrent(ctypes.Structure):
                 ("h_seq_dev", c_void_p), ("h_step_bytes", c_size_t)]
 
 
+PLAN_OPT_FIELDS = ("no_lp", "no_lp_256", "no_ws", "ws_all", "no_stem", "no_stem_pool", "no_dma", "no_c64", "no_run", "no_run_ks",
+                   "no_pair", "no_splitk", "no_hoist")
+
+
+class rl_plan_opts(ctypes.Structure):
+    _fields_ = [("struct_size", ctypes.c_uint32)] + [(n, c_int32) for n in PLAN_OPT_FIELDS]
+
+
+def make_opts(opts: Optional[Dict[str, int]]):
+    """{field: value} -> rl_plan_opts (None stays None: the planner's own choices)."""
+    if opts is None:
+        return None
+    o = rl_plan_opts()
+    o.struct_size = ctypes.sizeof(rl_plan_opts)
+    for k, v in opts.items():
+        if k not in PLAN_OPT_FIELDS:
+            raise KeyError(f"unknown plan option {k!r}")
+        setattr(o, k, int(v))
+    return o
+
+
 class RelayError(RuntimeError):
     def __init__(self, status: int, text: str):
         super().__init__(f"relayhip error {status} ({STATUS.get(status, '?')}): {text}")
@@ -108,7 +129,7 @@ def lib():
         L.rl_graph_output.argtypes = [c_void_p, c_int32]
         L.rl_graph_autogroup.argtypes = [c_void_p, POINTER(c_int32)]
         L.rl_graph_group_of.argtypes = [c_void_p, c_int32, POINTER(c_int32)]
-        L.rl_plan_create.argtypes = [c_void_p, POINTER(c_void_p)]
+        L.rl_plan_create.argtypes = [c_void_p, POINTER(rl_plan_opts), POINTER(c_void_p)]
         L.rl_plan_destroy.argtypes = [c_void_p]; L.rl_plan_destroy.restype = None
         L.rl_plan_describe.argtypes = [c_void_p, c_char_p, c_size_t, POINTER(c_size_t)]
         L.rl_plan_workspace_bytes.argtypes = [c_void_p, POINTER(c_size_t)]
@@ -240,8 +261,8 @@ class Graph:
                 by.setdefault(gi, []).append(o)
         return [by[k] for k in sorted(by)]
 
-    def plan(self) -> "Plan":
-        return Plan(self)
+    def plan(self, opts: Optional[Dict[str, int]] = None) -> "Plan":
+        return Plan(self, opts)
 
     def __del__(self):
         if getattr(self, "_h", None) and _lib is not None:
@@ -286,10 +307,11 @@ def graph_from_spec(ctx: Context, spec, auto_groups: bool = False) -> Graph:
 
 
 class Plan:
-    def __init__(self, graph: Graph):
+    def __init__(self, graph: Graph, opts: Optional[Dict[str, int]] = None):
         self.ctx = graph.ctx
         self._h = c_void_p()
-        self.ctx.check(lib().rl_plan_create(graph._h, byref(self._h)))
+        o = make_opts(opts)
+        self.ctx.check(lib().rl_plan_create(graph._h, byref(o) if o is not None else None, byref(self._h)))
 
     def describe(self) -> dict:
         need = c_size_t()

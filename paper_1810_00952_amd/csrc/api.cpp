@@ -1,6 +1,5 @@
 // C ABI of the library (see include/relayhip.h for the contract).
 #include <algorithm>
-#include <cstdlib>
 #include <cstring>
 #include <new>
 
@@ -59,7 +58,7 @@ rl_status add_value(rl_graph *g, const rl_type *t, int role, int32_t *value_id)
 // Returns that step, or null if the plan is anything else.
 const Step *hoistable_cell(const Plan &p)
 {
-    if (p.steps.size() != 1 || getenv("RELAYHIP_NO_HOIST")) return nullptr;
+    if (p.steps.size() != 1 || p.opts.no_hoist) return nullptr;
     const Step &s = p.steps[0];
     const IgemmParams &g = s.ig;
     if (s.kind != S_IGEMM || !s.il.gates || !s.il.avec || !s.il.dma || s.slot[SL_X2] < 0 || g.in_dtype != DT_BF16 || g.h_dtype != DT_BF16) return nullptr;
@@ -256,12 +255,16 @@ rl_status rl_graph_output(rl_graph *g, int32_t value_id)
     });
 }
 
-rl_status rl_plan_create(rl_graph *g, rl_plan **out)
+rl_status rl_plan_create(rl_graph *g, const rl_plan_opts *opts, rl_plan **out)
 {
     if (!g || !out) return RL_ERR_NULL;
     auto err = g->g.err;
     return guarded(err, [&]() -> rl_status {
+        if (opts && (opts->struct_size < sizeof(uint32_t) || opts->struct_size > sizeof(rl_plan_opts)))
+            return fail(err, RL_ERR_KIND, "rl_plan_opts.struct_size is not one this library knows");
         rl_plan *p = new rl_plan;
+        if (opts) memcpy(&p->p.opts, opts, opts->struct_size);
+        p->p.opts.struct_size = (uint32_t)sizeof(rl_plan_opts);
         std::string msg;
         rl_status st = build_plan(g->g, p->p, msg);
         if (st != RL_OK) {
@@ -404,6 +407,17 @@ rl_status rl_plan_run_recurrent(const rl_plan *cell, int32_t steps, const rl_rec
             for (int j = 0; j < i; ++j)
                 if (ids[i] == ids[j]) return fail(err, RL_ERR_BINDING, "one value id given two recurrent roles");
         }
+        // the step loop feeds h' back as h and c' back as c: each pair must be one tensor type, and a step's slice of
+        // the sequences must hold a whole operand
+        if (!same_type(p.values[io->h_in_id].type, p.values[io->h_out_id].type))
+            return fail(err, RL_ERR_BINDING, "recurrent h input " + type_str(p.values[io->h_in_id].type) + " and h output " +
+                                             type_str(p.values[io->h_out_id].type) + " differ in type");
+        if (!same_type(p.values[io->c_in_id].type, p.values[io->c_out_id].type))
+            return fail(err, RL_ERR_BINDING, "recurrent c input " + type_str(p.values[io->c_in_id].type) + " and c output " +
+                                             type_str(p.values[io->c_out_id].type) + " differ in type");
+        auto vbytes = [&](int v) { return (size_t)numel(p.values[v].type) * dtype_size(p.values[v].type.dtype); };
+        if (io->x_step_bytes < vbytes(io->x_id)) return fail(err, RL_ERR_BINDING, "x_step_bytes is smaller than the cell's x operand");
+        if (io->h_step_bytes < vbytes(io->h_out_id)) return fail(err, RL_ERR_BINDING, "h_step_bytes is smaller than the cell's h result");
         std::vector<rl_binding> b(pb, pb + (npb > 0 ? npb : 0));
         const size_t base = b.size();
         b.push_back({io->x_id, (void *)io->x_seq_dev});
@@ -450,7 +464,7 @@ rl_status rl_plan_run_recurrent(const rl_plan *cell, int32_t steps, const rl_rec
                     const int64_t b256 = ((g.M + 255) / 256) * (int64_t)((g.N + 127) / 128);
                     l.tile = b128 >= 192 ? TILE_128x128 : b64 >= 192 ? TILE_128x64 : TILE_64x64;
                     // the pixel-on-lane kernel with fp32 output where one of its two large tiles fills the chip
-                    if (g.N % 8 == 0 && (b256 >= 190 || b128 >= 192) && !getenv("RELAYHIP_NO_LP")) {
+                    if (g.N % 8 == 0 && (b256 >= 190 || b128 >= 192) && !p.opts.no_lp) {
                         l.lp = 1;
                         l.tile = b256 >= 190 ? TILE_256x128 : TILE_128x128;
                         g.seg_stride = 64; g.ts_h = 0; g.ts_w = 0; g.tap_rep = 1;

@@ -40,7 +40,6 @@
 // activations, output rows contiguous in n with N a multiple of 8, tensors
 // below 2 GiB.
 #include "device_utils.h"
-#include <cstdlib>
 
 namespace rl {
 
@@ -670,7 +669,8 @@ hipError_t launch_conv3x3_run(const IgemmParams &p, const IgemmLaunch &l, hipStr
     case TILE_256x128: return launch_run<256, 128, 4, 2, 4>(p, s);      // 160 KB of LDS with four stages
     case TILE_128x128: return launch_run<128, 128, 2, 4, 5>(p, s);
     case TILE_128x64:
-        if (p.C % 128 == 0 && !getenv("RELAYHIP_NO_RUN_KS")) {
+        if (l.run == 2) {
+            if (p.C % 128 != 0) return hipErrorInvalidValue;      // each of the four waves takes whole k-steps of a 128-channel pair of slices
             IgemmParams q = p;
             q.nblk_m = (p.M + 127) / 128;
             q.nblk_n = (p.N + 63) / 64;

@@ -5,7 +5,6 @@
 #include <algorithm>
 
 #include "device_utils.h"
-#include <cstdlib>
 
 namespace rl {
 

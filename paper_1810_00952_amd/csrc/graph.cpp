@@ -278,8 +278,17 @@ rl_status check_group(const Graph &g, const std::vector<int> &ops_in, std::strin
     if (ops.size() > 1) {
         for (size_t i = tail0; i < ops.size(); ++i) {
             int k = g.ops[ops[i]].kind;
-            bool last_gate = (k == RL_OP_LSTM_GATES && i + 1 == ops.size());
+            // lstm_gates closes a group only behind a dense contraction (it is the contraction's epilogue there);
+            // behind a bare injective chain it stays a group of its own
+            bool last_gate = (k == RL_OP_LSTM_GATES && i + 1 == ops.size() && n_anchor == 1 && g.ops[ops[lead]].kind == RL_OP_DENSE);
             if (!is_injective(k) && !last_gate) { msg = std::string(op_name(k)) + " cannot be fused"; return RL_ERR_GROUP; }
+            if (last_gate) {
+                // its pre-activations are the value the rest of the group computes, its cell state comes from outside
+                const OpNode &go = g.ops[ops[i]];
+                const int zprod = g.values[go.in[0]].producer, cprod = g.values[go.in[1]].producer;
+                if (zprod != ops[i - 1]) { msg = "lstm_gates must take the group's last result as its first operand"; return RL_ERR_GROUP; }
+                if (cprod >= 0 && gset.count(cprod)) { msg = "lstm_gates' cell state must come from outside the group"; return RL_ERR_GROUP; }
+            }
         }
     }
     // connected: every op after the first consumes something produced inside the group

@@ -102,7 +102,8 @@ struct IgemmLaunch {
     int32_t lp;         // 1: pixel-on-lane variant with the register epilogue (bf16, [bias] [+residual] [relu])
     int32_t ws;         // 1 (with lp): weights-stationary persistent variant (N <= 64, K <= 576)
     int32_t c64;        // 1 (with lp): 3x3 / stride 1 / pad 1, 64 -> 64 channels, image rows of at most 63 pixels (conv3x3_c64.hip)
-    int32_t run;        // 1 (with lp): 3x3 / stride 1 / pad 1, C a multiple of 64, image rows of at most 30 pixels, tile not 64x64 (conv3x3_run.hip)
+    int32_t run;        // 1 (with lp): 3x3 / stride 1 / pad 1, C a multiple of 64, image rows of at most 30 pixels, tile not 64x64 (conv3x3_run.hip);
+                        // 2: its 128x64 form with K split over the waves (C a multiple of 128)
     int32_t splits;     // > 1 (with dma, no lp, no gates): K split over that many workgroups per tile (IgemmParams::splits)
 };
 hipError_t launch_igemm(const IgemmParams &p, const IgemmLaunch &l, hipStream_t s);

@@ -10,7 +10,6 @@
 #include "plan.h"
 
 #include <algorithm>
-#include <cstdlib>
 #include <set>
 #include <sstream>
 
@@ -223,6 +222,11 @@ struct Planner {
         rl_status st = build_chain(ops, ai + 1, gates ? ops.size() - 1 : ops.size(), an.out[0], gset, chain);
         if (st != RL_OK) return st;
         if (chain.bias_axis >= 0 && chain.bias_axis != 1) return fail(RL_ERR_UNSUPPORTED, "bias_add fused into a contraction must be along axis 1");
+        if (gates) {
+            const OpNode &go = g.ops[ops.back()];
+            const int cprod = g.values[go.in[1]].producer;
+            if (go.in[0] != chain.last_value || (cprod >= 0 && gset.count(cprod))) return fail(RL_ERR_UNSUPPORTED, "fused group is not a single chain");
+        }
         if (gates)
             for (int i = 0; i < chain.epi.n_ops; ++i)
                 if (epi_host_op(chain.epi, i) != E_BIAS) return fail(RL_ERR_UNSUPPORTED, "only bias_add may sit between the contraction and lstm_gates");
@@ -267,7 +271,7 @@ struct Planner {
             const int64_t Hp = (int64_t)(p.OH - 1) * p.sh + 2 * KH2, Wp = (int64_t)(p.OW - 1) * p.sw + 8;
             const size_t frame = (size_t)xt.dims[0] * Hp * Wp * 8;
             stem = in_dt == RL_BF16 && p.C <= 4 && p.KW <= 8 && p.sw % 2 == 0 && KH2 <= 32 && epi_lp && vout >= 0 && T(vout).dtype == RL_BF16 &&
-                   out_layout == L_NHWC && p.N % 8 == 0 && bytes_of(vout) < lim && frame < lim && phys[L_NATIVE][x] >= 0 && !getenv("RELAYHIP_NO_STEM");
+                   out_layout == L_NHWC && p.N % 8 == 0 && bytes_of(vout) < lim && frame < lim && phys[L_NATIVE][x] >= 0 && !plan.opts.no_stem;
             if (stem) {
                 int xnat;
                 st = need(x, L_NATIVE, xnat);
@@ -340,11 +344,11 @@ struct Planner {
             const int bke = 8 * KV;
             const size_t halo = (size_t)((int64_t)p.ph * p.xs_h + (int64_t)p.pw * p.xs_w) * dtype_size(in_dt);
             il.dma = !stem && il.avec && p.C % bke == 0 && p.K % bke == 0 && p.K / bke >= 2 && p.KH * p.KW <= 32 &&
-                     (x2 < 0 || p.K1 % bke == 0) && x_extent + halo < lim && !getenv("RELAYHIP_NO_DMA");
+                     (x2 < 0 || p.K1 % bke == 0) && x_extent + halo < lim && !plan.opts.no_dma;
             // a dense contraction whose K is a multiple of the vector but not of the K tile: the weights are packed
             // with zeros up to whole tiles and the kernel requests the activation chunks past K out of range
             if (!il.dma && an.kind == RL_OP_DENSE && !stem && !gates && x2 < 0 && il.avec && p.K % bke != 0 && p.K / bke >= 2 &&
-                x_extent < lim && (size_t)p.N * round_up(p.K, bke) * dtype_size(in_dt) < lim && !getenv("RELAYHIP_NO_DMA")) {
+                x_extent < lim && (size_t)p.N * round_up(p.K, bke) * dtype_size(in_dt) < lim && !plan.opts.no_dma) {
                 il.dma = 1;
                 p.Kp = (int)round_up(p.K, bke);
                 need_pack = true;
@@ -356,14 +360,14 @@ struct Planner {
             bool y_ok = vout >= 0 && T(vout).dtype == RL_BF16 && p.ys_c == 1 && p.ys_n == (int64_t)p.OHW * p.ys_p && p.N % 8 == 0 &&
                         bytes_of(vout) < lim;
             il.lp = stem || (il.avec && in_dt == RL_BF16 && p.C % bke == 0 && p.K % bke == 0 && p.KH * p.KW <= 32 && x2 < 0 && !gates &&
-                             x_extent + halo < lim && epi_lp && y_ok && !getenv("RELAYHIP_NO_LP"));
+                             x_extent + halo < lim && epi_lp && y_ok && !plan.opts.no_lp);
             // weights-stationary persistent variant: pays off when the weights leave LDS for a deep ring (K <= 320);
             // RELAYHIP_WS_ALL=1 also takes it up to K = 576, where its shallower ring is latency-bound
-            il.ws = il.lp && p.N <= 64 && (p.K / bke <= 5 || (p.K / bke <= 9 && getenv("RELAYHIP_WS_ALL"))) && !getenv("RELAYHIP_NO_WS");
+            il.ws = il.lp && p.N <= 64 && (p.K / bke <= 5 || (p.K / bke <= 9 && plan.opts.ws_all)) && !plan.opts.no_ws;
             // 3x3 / stride 1 / pad 1 from 64 to 64 channels on rows of at most 63 pixels: weights in registers, every
             // input pixel fetched once per region
             il.c64 = il.lp && !stem && an.kind == RL_OP_CONV2D && p.C == 64 && p.N == 64 && p.KH == 3 && p.KW == 3 && p.sh == 1 && p.sw == 1 &&
-                     p.ph == 1 && p.pw == 1 && p.OH == p.H && p.OW == p.W && p.W <= 63 && p.Kp == p.K && p.ys_p == 64 && !getenv("RELAYHIP_NO_C64");
+                     p.ph == 1 && p.pw == 1 && p.OH == p.H && p.OW == p.W && p.W <= 63 && p.Kp == p.K && p.ys_p == 64 && !plan.opts.no_c64;
             il.c64 = il.c64 && dual;
             if (il.c64) { il.ws = 0; p.w_bytes = (uint32_t)pack.bytes; }
             p.y_bytes = vout >= 0 ? (uint32_t)std::min(bytes_of(vout), lim - 1) : 0;
@@ -393,7 +397,7 @@ struct Planner {
             p.h_dtype = T(g.ops[ops.back()].out[1]).dtype;
         } else if (!il.avec) {
             il.tile = TILE_64x64;
-        } else if (il.lp && p.N > 64 && nblk(256, 128) >= 190 && !getenv("RELAYHIP_NO_LP_256")) {
+        } else if (il.lp && p.N > 64 && nblk(256, 128) >= 190 && !plan.opts.no_lp_256) {
             il.tile = TILE_256x128;        // a quarter fewer operand bytes per MFMA than 128x128
         } else if (p.N > 64 && nblk(128, 128) >= 192) {
             il.tile = TILE_128x128;
@@ -407,7 +411,8 @@ struct Planner {
         // from one copy of the input rows (needs one of the larger tiles)
         il.run = il.lp && !il.c64 && !il.ws && !stem && an.kind == RL_OP_CONV2D && p.KH == 3 && p.KW == 3 && p.sh == 1 && p.sw == 1 && p.ph == 1 &&
                  p.pw == 1 && p.OH == p.H && p.OW == p.W && p.W <= 30 && p.C % 64 == 0 && p.Kp == p.K && il.tile != TILE_64x64 &&
-                 !getenv("RELAYHIP_NO_RUN");
+                 !plan.opts.no_run;
+        if (il.run && il.tile == TILE_128x64 && p.C % 128 == 0 && !plan.opts.no_run_ks) il.run = 2;     // K split over the waves
 
         double bytes = (double)bytes_of(x) + (x2 >= 0 ? (double)bytes_of(x2) : 0.0) + (double)bytes_of(wv);
         std::vector<int> eslots(RL_EPI_MAX_PTRS, -1);
@@ -434,7 +439,7 @@ struct Planner {
         // Few tiles and a long K (small batches, late stages): K is split over several workgroups per tile, whose fp32
         // sums meet in a scratch tensor [splits][M][N] that a second kernel adds up in order before the epilogue.
         int part_buf = -1;
-        if (il.avec && il.dma && !il.lp && !gates && x2 < 0 && !stem && !getenv("RELAYHIP_NO_SPLITK")) {
+        if (il.avec && il.dma && !il.lp && !gates && x2 < 0 && !stem && !plan.opts.no_splitk) {
             static const int tbm[] = {128, 128, 64, 256}, tbn[] = {128, 64, 64, 128};
             const int64_t tiles = nblk(tbm[il.tile], tbn[il.tile]);
             const int nk = (p.K + 8 * KV - 1) / (8 * KV);
@@ -764,7 +769,7 @@ struct Planner {
     // (max commutes with the bias, the ReLU and the rounding).
     void fuse_stem_pool()
     {
-        if (getenv("RELAYHIP_NO_STEM_POOL")) return;
+        if (plan.opts.no_stem_pool) return;
         for (size_t si = 0; si + 1 < plan.steps.size(); ++si) {
             Step &c = plan.steps[si];
             const Step &m = plan.steps[si + 1];
@@ -800,7 +805,7 @@ struct Planner {
     // launch: each alone leaves a quarter of the CUs idle, and the projection's short tiles fit into that gap.
     void pair_contractions()
     {
-        if (getenv("RELAYHIP_NO_PAIR")) return;
+        if (plan.opts.no_pair) return;
         for (size_t si = 0; si + 1 < plan.steps.size(); ++si) {
             Step &a = plan.steps[si];
             Step &b = plan.steps[si + 1];
@@ -877,9 +882,20 @@ std::string describe_plan(const Plan &p)
         o << (i ? ", " : "") << "{\"name\": \"" << s.name << "\", \"kernel\": \"" << s.kernel << "\", \"group\": " << s.group
           << ", \"flops\": " << (long long)s.flops << ", \"bytes\": " << (long long)s.bytes;
         if (s.kind == S_IGEMM)
-            o << ", \"M\": " << s.ig.M << ", \"N\": " << s.ig.N << ", \"K\": " << s.ig.K << ", \"epilogue_ops\": " << s.ig.epi.n_ops;
+            o << ", \"M\": " << s.ig.M << ", \"N\": " << s.ig.N << ", \"K\": " << s.ig.K << ", \"epilogue_ops\": " << s.ig.epi.n_ops
+              << ", \"k_split_waves\": " << (s.il.run == 2 ? 1 : 0) << ", \"k_split_workgroups\": " << (s.il.splits > 1 ? s.il.splits : 1);
         if (s.kind == S_ELTWISE) o << ", \"n\": " << (long long)s.el.n << ", \"chain_ops\": " << s.el.epi.n_ops;
         o << "}";
+    }
+    // workspace buffers with the steps between which each one holds live data (first writer .. last reader)
+    o << "], \"buffers\": [";
+    bool firstb = true;
+    for (size_t i = 0; i < p.bufs.size(); ++i) {
+        const BufDesc &d = p.bufs[i];
+        if (d.bound_value >= 0 || d.first < 0) continue;
+        o << (firstb ? "" : ", ") << "{\"offset\": " << d.offset << ", \"bytes\": " << d.bytes << ", \"first\": " << d.first << ", \"last\": " << d.last
+          << "}";
+        firstb = false;
     }
     o << "], \"packed_params\": [";
     bool firstp = true;

@@ -57,6 +57,7 @@ struct Plan {
     std::vector<int> bound_buf;          // value id -> buffer index of its bound pointer, or -1
     std::map<int, PackSpec> packs;       // param value id -> packing
     size_t workspace_bytes = 0;
+    rl_plan_opts opts{};                 // the caller's plan-time switches, fixed at creation
 };
 
 rl_status build_plan(const Graph &g, Plan &plan, std::string &msg);

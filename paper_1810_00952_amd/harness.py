@@ -35,12 +35,12 @@ def stream_handle() -> int:
 class Session:
     """One plan with its device buffers."""
 
-    def __init__(self, spec, ctx: Optional[Context] = None, device="cuda:0", auto_groups: bool = False):
+    def __init__(self, spec, ctx: Optional[Context] = None, device="cuda:0", auto_groups: bool = False, opts: Optional[Dict[str, int]] = None):
         self.spec = spec
         self.device = device
         self.ctx = ctx or Context()
         self.graph = graph_from_spec(self.ctx, spec, auto_groups=auto_groups)
-        self.plan = Plan(self.graph)
+        self.plan = Plan(self.graph, opts)
         self.tensors: Dict[int, torch.Tensor] = {}    # value id -> tensor whose pointer is bound
         self.raw: Dict[int, torch.Tensor] = {}
         self.workspace = None

@@ -35,12 +35,13 @@ def assert_close(got, ref, dtype, what="", atol_scale=1.0):
                              f"(max abs err {err.max():.3e}, atol {atol:.3e}, rtol {rtol})")
 
 
-def run_hip(spec, data, auto_groups=False):
+def run_hip(spec, data, auto_groups=False, opts=None):
     """Run a graph description through the C ABI on cuda:0; returns {output value id: float64 array}.
-    auto_groups: let the library form the fusion groups instead of declaring the description's."""
+    auto_groups: let the library form the fusion groups instead of declaring the description's.
+    opts: plan-time switches ({field of rl_plan_opts: value})."""
     import torch
     from paper_1810_00952_amd import harness
-    s = harness.Session(spec, auto_groups=auto_groups)
+    s = harness.Session(spec, auto_groups=auto_groups, opts=opts)
     s.load(data)
     s.alloc()
     s.run()

@@ -11,9 +11,9 @@ from helpers import assert_close, extract_group, fold_resnet_hip, fold_resnet_or
 pytestmark = pytest.mark.gpu
 
 
-def check_graph(spec, data, what, atol_scale=1.0):
+def check_graph(spec, data, what, atol_scale=1.0, opts=None):
     ref = OG.run(spec, data)
-    got, _ = run_hip(spec, data)
+    got, _ = run_hip(spec, data, opts=opts)
     for vid in spec.outputs:
         assert_close(got[vid], ref[vid], spec.values[vid].type.dtype, f"{what} value {vid}", atol_scale)
     return got, ref
@@ -100,28 +100,26 @@ LP_CASES = [
 
 
 @pytest.mark.parametrize("case", LP_CASES, ids=[f"lp{i}" for i in range(len(LP_CASES))])
-def test_conv_group_internal_layout_bf16(case, monkeypatch):
-    monkeypatch.setenv("RELAYHIP_NO_C64", "1")       # the general kernel also on the shapes that have one of their own
-    monkeypatch.setenv("RELAYHIP_NO_RUN", "1")
+def test_conv_group_internal_layout_bf16(case):
+    opts = {"no_c64": 1, "no_run": 1}                # the general kernel also on the shapes that have one of their own
     b, ci, co, h, w, k, s, p, res, relu = case
     spec, data = W.conv_group(b, ci, co, h, w, k, s, p, "bf16", residual=res, relu=relu, tail=True)
     from paper_1810_00952_amd import binding
-    desc = binding.Plan(binding.graph_from_spec(binding.Context(), spec)).describe()
+    desc = binding.Plan(binding.graph_from_spec(binding.Context(), spec), opts).describe()
     assert any(st["kernel"].endswith(("_lp", "_ws")) for st in desc["steps"]), [st["kernel"] for st in desc["steps"]]
-    check_graph(spec, data, f"conv lp {case}")
+    check_graph(spec, data, f"conv lp {case}", opts=opts)
 
 
-def test_conv_weights_stationary_shallow_ring(monkeypatch):
+def test_conv_weights_stationary_shallow_ring():
     # K = 576 (9 weight tiles, 5-stage ring, residual through the ring): opt-in, the planner prefers the per-tile kernel there
-    monkeypatch.setenv("RELAYHIP_WS_ALL", "1")
-    monkeypatch.setenv("RELAYHIP_NO_C64", "1")
+    opts = {"ws_all": 1, "no_c64": 1}
     for case in [(16, 64, 64, 56, 56, 3, 1, 1, True, True), (3, 64, 48, 29, 31, 3, 1, 1, False, True)]:
         b, ci, co, h, w, k, s, p, res, relu = case
         spec, data = W.conv_group(b, ci, co, h, w, k, s, p, "bf16", residual=res, relu=relu, tail=True)
         from paper_1810_00952_amd import binding
-        desc = binding.Plan(binding.graph_from_spec(binding.Context(), spec)).describe()
+        desc = binding.Plan(binding.graph_from_spec(binding.Context(), spec), opts).describe()
         assert any(st["kernel"].endswith("_ws") for st in desc["steps"]), [st["kernel"] for st in desc["steps"]]
-        check_graph(spec, data, f"conv ws {case}")
+        check_graph(spec, data, f"conv ws {case}", opts=opts)
 
 
 STEM_CASES = [
@@ -159,7 +157,7 @@ STEM_POOL_CASES = [
 
 
 @pytest.mark.parametrize("case", STEM_POOL_CASES, ids=[f"sp{i}" for i in range(len(STEM_POOL_CASES))])
-def test_stem_conv_with_maxpool_in_one_kernel(case, monkeypatch):
+def test_stem_conv_with_maxpool_in_one_kernel(case):
     b, ci, h, w, k, s_, p, relu, tail = case
     spec, data = W.conv_pool(b, ci, 64, h, w, k, s_, p, "bf16", relu=relu, tail=tail)
     from paper_1810_00952_amd import binding
@@ -168,10 +166,9 @@ def test_stem_conv_with_maxpool_in_one_kernel(case, monkeypatch):
     print(f"stem+pool case {case}", flush=True)
     got, _ = check_graph(spec, data, f"stem+pool {case}")
     # the two-kernel form of the same plan gives the same bits: max commutes with bias, ReLU and the rounding
-    monkeypatch.setenv("RELAYHIP_NO_STEM_POOL", "1")
-    desc = binding.Plan(binding.graph_from_spec(binding.Context(), spec)).describe()
+    desc = binding.Plan(binding.graph_from_spec(binding.Context(), spec), {"no_stem_pool": 1}).describe()
     assert any(st["kernel"] == "maxpool_nhwc" for st in desc["steps"])
-    two, _ = run_hip(spec, data)
+    two, _ = run_hip(spec, data, opts={"no_stem_pool": 1})
     for vid in spec.outputs:
         np.testing.assert_array_equal(got[vid], two[vid])
 
@@ -193,7 +190,7 @@ C64_CASES = [
 
 
 @pytest.mark.parametrize("case", C64_CASES, ids=[f"c64_{i}" for i in range(len(C64_CASES))])
-def test_conv3x3_c64_weights_in_registers(case, monkeypatch):
+def test_conv3x3_c64_weights_in_registers(case):
     b, h, w, bias, res, relu = case
     spec, data = W.conv_group(b, 64, 64, h, w, 3, 1, 1, "bf16", residual=res, relu=relu, tail=True, bias=bias)
     from paper_1810_00952_amd import binding
@@ -202,10 +199,9 @@ def test_conv3x3_c64_weights_in_registers(case, monkeypatch):
     print(f"conv3x3_c64 case {case}", flush=True)
     got, _ = check_graph(spec, data, f"conv3x3_c64 {case}")
     # the general kernel accumulates the same 16-element slices of K in the same order: same bits
-    monkeypatch.setenv("RELAYHIP_NO_C64", "1")
-    desc = binding.Plan(binding.graph_from_spec(binding.Context(), spec)).describe()
+    desc = binding.Plan(binding.graph_from_spec(binding.Context(), spec), {"no_c64": 1}).describe()
     assert not any(st["kernel"] == "igemm_conv2d_bf16_3x3_c64" for st in desc["steps"])
-    gen, _ = run_hip(spec, data)
+    gen, _ = run_hip(spec, data, opts={"no_c64": 1})
     for vid in spec.outputs:
         np.testing.assert_array_equal(got[vid], gen[vid])
 
@@ -227,7 +223,7 @@ RUN_CASES = [
 
 
 @pytest.mark.parametrize("case", RUN_CASES, ids=[f"run{i}" for i in range(len(RUN_CASES))])
-def test_conv3x3_taps_from_one_copy_of_the_rows(case, monkeypatch):
+def test_conv3x3_taps_from_one_copy_of_the_rows(case):
     b, ci, co, h, w, bias, res, relu, tile = case
     spec, data = W.conv_group(b, ci, co, h, w, 3, 1, 1, "bf16", residual=res, relu=relu, tail=True, bias=bias)
     from paper_1810_00952_amd import binding
@@ -236,8 +232,7 @@ def test_conv3x3_taps_from_one_copy_of_the_rows(case, monkeypatch):
     print(f"conv3x3 run case {case}", flush=True)
     got, _ = check_graph(spec, data, f"conv3x3 run {case}")
     # against the general kernel: same products, another summation order
-    monkeypatch.setenv("RELAYHIP_NO_RUN", "1")
-    gen, _ = run_hip(spec, data)
+    gen, _ = run_hip(spec, data, opts={"no_run": 1})
     for vid in spec.outputs:
         assert_close(got[vid], gen[vid], "bf16", f"run vs general {case}")
 
@@ -255,7 +250,7 @@ PAIR_CASES = [
 
 
 @pytest.mark.parametrize("case", PAIR_CASES, ids=[f"pair{i}" for i in range(len(PAIR_CASES))])
-def test_independent_contractions_in_one_launch(case, monkeypatch):
+def test_independent_contractions_in_one_launch(case):
     b, ci, co, h, w = case
     spec, data = W.downsample_block(b, ci, co, h, w, "bf16")
     from paper_1810_00952_amd import binding
@@ -263,10 +258,9 @@ def test_independent_contractions_in_one_launch(case, monkeypatch):
     assert sum(st["kernel"] == "(launched with the step before)" for st in desc["steps"]) == 1, [st["kernel"] for st in desc["steps"]]
     print(f"paired launch case {case}: {[st['kernel'] for st in desc['steps']]}", flush=True)
     got, _ = check_graph(spec, data, f"paired launch {case}")
-    monkeypatch.setenv("RELAYHIP_NO_PAIR", "1")
-    desc = binding.Plan(binding.graph_from_spec(binding.Context(), spec)).describe()
+    desc = binding.Plan(binding.graph_from_spec(binding.Context(), spec), {"no_pair": 1}).describe()
     assert not any(st["kernel"] == "(launched with the step before)" for st in desc["steps"])
-    two, _ = run_hip(spec, data)
+    two, _ = run_hip(spec, data, opts={"no_pair": 1})
     for vid in spec.outputs:
         np.testing.assert_array_equal(got[vid], two[vid])
 
@@ -697,7 +691,7 @@ SPLITK_CASES = [
 
 
 @pytest.mark.parametrize("case", SPLITK_CASES, ids=[f"sk{i}" for i in range(len(SPLITK_CASES))])
-def test_contraction_with_k_split_over_workgroups(case, monkeypatch):
+def test_contraction_with_k_split_over_workgroups(case):
     from paper_1810_00952_amd import binding
     b, ci, co, h, w, k, s, p, res, relu, dtype, tail = case
     spec, data = W.conv_group(b, ci, co, h, w, k, s, p, dtype, residual=res, relu=relu, tail=tail)
@@ -709,8 +703,8 @@ def test_contraction_with_k_split_over_workgroups(case, monkeypatch):
     assert_close(got[v], ref[v], dtype, f"split-K {case}")
     again, _ = run_hip(spec, data)
     np.testing.assert_array_equal(got[v], again[v])               # slices are added in a fixed order
-    monkeypatch.setenv("RELAYHIP_NO_SPLITK", "1")
-    whole, _ = run_hip(spec, data)
+    whole, s1 = run_hip(spec, data, opts={"no_splitk": 1})
+    assert not any(st["kernel"].endswith("_splitk") for st in s1.plan.describe()["steps"])
     assert_close(whole[v], ref[v], dtype, f"unsplit {case}")
 
 

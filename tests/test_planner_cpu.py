@@ -96,12 +96,87 @@ def test_resnet18_plan_structure():
 
 
 def test_workspace_reuse_is_liveness_safe():
-    # two buffers alive at the same step never overlap (checked from the description)
-    spec, raw, bn = W.resnet18(batch=2, dtype="f32", image=64)
-    plan = B.Plan(B.graph_from_spec(B.Context(), spec))
-    total = sum(v.type.shape[0] * v.type.shape[1] * v.type.shape[2] * v.type.shape[3] * 4
-                for v in spec.values if v.role == "op" and len(v.type.shape) == 4)
-    assert plan.workspace_bytes() < total        # reuse happened
+    # two workspace buffers that hold live data at the same step never overlap, and all lie inside the workspace
+    for spec in (W.resnet18(batch=2, dtype="f32", image=64)[0], W.resnet18(batch=64, dtype="bf16")[0], W.resnet18(batch=1, dtype="f32")[0],
+                 W.lenet(5, "bf16")[0], W.mlp()[0], W.lstm_unrolled_graph(4, 8, 64, 64, "bf16", fused=False)):
+        plan = B.Plan(B.graph_from_spec(B.Context(), spec))
+        d = plan.describe()
+        bufs = d["buffers"]
+        ws = plan.workspace_bytes()
+        assert d["workspace_bytes"] == ws
+        n_steps = len(d["steps"])
+        for b in bufs:
+            assert b["offset"] % 256 == 0 and b["bytes"] > 0 and b["offset"] + b["bytes"] <= ws
+            assert 0 <= b["first"] <= b["last"] < n_steps
+        n_shared = 0
+        for i, a in enumerate(bufs):
+            for b in bufs[i + 1:]:
+                live_together = a["first"] <= b["last"] and b["first"] <= a["last"]
+                overlap = a["offset"] < b["offset"] + b["bytes"] and b["offset"] < a["offset"] + a["bytes"]
+                assert not (live_together and overlap), (spec.name, a, b)
+                n_shared += overlap
+        if len(bufs) > 3:
+            assert n_shared > 0 and ws < sum(b["bytes"] for b in bufs), spec.name        # reuse happened
+
+
+def test_plan_options_are_fixed_in_the_plan():
+    # the switches travel in the options struct and stay with the plan; a struct larger than the library's is refused
+    spec = W.conv_group(16, 64, 64, 56, 56, 3, 1, 1, "bf16", residual=True, relu=True, tail=True)[0]
+    ctx = B.Context()
+    g = B.graph_from_spec(ctx, spec)
+    k = lambda opts: [s["kernel"] for s in B.Plan(g, opts).describe()["steps"] if s["kernel"].startswith("igemm")]
+    assert k(None) == ["igemm_conv2d_bf16_3x3_c64"] == k({})
+    assert k({"no_c64": 1}) == ["igemm_conv2d_bf16_128x64_lp"]
+    assert k({"no_c64": 1, "ws_all": 1}) == ["igemm_conv2d_bf16_128x64_ws"]
+    assert k({"no_c64": 1, "no_lp": 1}) == ["igemm_conv2d_bf16_128x64_dma"]
+    assert k(None) == ["igemm_conv2d_bf16_3x3_c64"]
+    o = B.make_opts({})
+    o.struct_size = ctypes.sizeof(B.rl_plan_opts) + 4
+    h = ctypes.c_void_p()
+    assert B.lib().rl_plan_create(g._h, ctypes.byref(o), ctypes.byref(h)) == -2 and "struct_size" in ctx.last_error()
+    o.struct_size = 8                              # an older caller that only knows the first switch
+    o.no_lp = 1; o.no_c64 = 1                      # the second lies beyond its struct and must be ignored
+    assert B.lib().rl_plan_create(g._h, ctypes.byref(o), ctypes.byref(h)) == 0
+    B.lib().rl_plan_destroy(h)
+    with pytest.raises(KeyError):
+        B.make_opts({"no_such_switch": 1})
+
+
+def test_recurrent_call_rejects_mismatched_roles_on_the_host():
+    fake = 0x10000
+    ctx = B.Context()
+    # h' declared f32 while the cell's h operand is bf16: feeding h' back as h would reinterpret the bytes
+    g = W.GraphSpec("cell")
+    Bt, I, H = 4, 32, 32
+    x = g.input("x", "bf16", (Bt, I)); h = g.input("h", "bf16", (Bt, H)); c = g.input("c", "f32", (Bt, H))
+    w = g.param("w", "bf16", (4 * H, I + H)); b = g.param("b", "f32", (4 * H,))
+    o0, (xh,) = g.op("concat", [x, h], [("bf16", (Bt, I + H))], axis=1)
+    o1, (z,) = g.op("dense", [xh, w], [("f32", (Bt, 4 * H))], out_dtype="f32")
+    o2, (z,) = g.op("bias_add", [z, b], [("f32", (Bt, 4 * H))], axis=1)
+    o3, (c2, h2) = g.op("lstm_gates", [z, c], [("f32", (Bt, H)), ("f32", (Bt, H))])
+    g.group([o0, o1, o2, o3]); g.output(c2); g.output(h2)
+    plan = B.Plan(B.graph_from_spec(ctx, g))
+    roles = {"x": x, "h_in": h, "c_in": c, "c_out": c2, "h_out": h2}
+    with pytest.raises(B.RelayError) as ei:
+        plan.run_recurrent(3, roles, fake, Bt * I * 2, fake, fake, fake, Bt * H * 4, {w: fake, b: fake}, fake, 1 << 20)
+    assert ei.value.category == "binding" and "h input" in str(ei.value)
+    # well-typed cell: strides smaller than a step's tensors would make the steps overlap
+    spec = W.lstm_cell_graph(Bt, I, H, "bf16", True)
+    n = {v.name: i for i, v in enumerate(spec.values)}
+    plan = B.Plan(B.graph_from_spec(ctx, spec))
+    roles = {"x": n["x"], "h_in": n["h"], "c_in": n["c"], "c_out": spec.outputs[0], "h_out": spec.outputs[1]}
+    params = {n["w"]: fake, n["b"]: fake}
+    for xs, hs, what in ((Bt * I * 2 - 16, Bt * H * 2, "x_step_bytes"), (Bt * I * 2, Bt * H * 2 - 16, "h_step_bytes")):
+        with pytest.raises(B.RelayError) as ei:
+            plan.run_recurrent(3, roles, fake, xs, fake, fake, fake, hs, params, fake, 1 << 20)
+        assert ei.value.category == "binding" and what in str(ei.value)
+    # c' played by a value of another type than c
+    with pytest.raises(B.RelayError) as ei:
+        plan.run_recurrent(3, dict(roles, c_out=spec.outputs[1], h_out=spec.outputs[0]), fake, Bt * I * 2, fake, fake, fake, Bt * H * 4, params,
+                           fake, 1 << 20)
+    assert ei.value.category == "binding"
+    # zero steps of a well-formed call launch nothing and succeed without a GPU
+    plan.run_recurrent(0, roles, fake, Bt * I * 2, fake, fake, fake, Bt * H * 2, params, fake, 1 << 20)
 
 
 def test_host_side_error_paths_without_gpu():
@@ -203,6 +278,21 @@ def test_autogroup_rules():
         assert got == want([o0, o1, o2, o3])
         B.Plan(lib)
 
+    # the gate operator joins a dense contraction's group (through its bias), but behind a bare injective chain it stays
+    # a group of its own -- and either graph plans
+    g = W.lstm_cell_graph(2, 64, 64, "bf16", True); g.groups.clear()
+    lib, got = _auto(g)
+    assert got == [[0, 1, 2, 3]]
+    B.Plan(lib)
+    g = W.GraphSpec("t")
+    z = g.input("z", "f32", (2, 64)); b = g.param("b", "f32", (64,)); c = g.input("c", "f32", (2, 16))
+    o0, (zb,) = g.op("bias_add", [z, b], [("f32", (2, 64))], axis=1)
+    o1, (c2, h2) = g.op("lstm_gates", [zb, c], [("f32", (2, 16)), ("f32", (2, 16))])
+    g.output(c2); g.output(h2)
+    lib, got = _auto(g)
+    assert got == [[o0], [o1]]
+    assert [s["kernel"] for s in B.Plan(lib).describe()["steps"]] == ["eltwise_chain", "lstm_gates"]
+
     # a second contraction never joins; pools stay alone; hand-declared groups are kept
     g = W.GraphSpec("t")
     x = g.input("x", "f32", (2, 8, 8, 8)); w1 = g.param("w1", "f32", (8, 8, 1, 1)); w2 = g.param("w2", "f32", (8, 8, 1, 1))
@@ -249,19 +339,17 @@ def test_layout_transform_kernel_choice():
 
 
 # ---------------------------------------------------------------- K split over workgroups (host logic only)
-def test_split_k_is_planned_for_few_tiles_and_long_k(monkeypatch):
-    def kernels(spec):
-        d = B.Plan(B.graph_from_spec(B.Context(), spec)).describe()
+def test_split_k_is_planned_for_few_tiles_and_long_k():
+    def kernels(spec, opts=None):
+        d = B.Plan(B.graph_from_spec(B.Context(), spec), opts).describe()
         return [s["kernel"] for s in d["steps"] if s["kernel"].startswith("igemm")], d["workspace_bytes"]
     # batch 1, 512 -> 512 channels on 7x7: 8 tiles of 64x64, 144 K tiles of 32: split, and the scratch tensor
     # [16 slices][49][512] f32 is part of the workspace
     spec = W.conv_group(1, 512, 512, 7, 7, 3, 1, 1, "f32")[0]
     k, ws = kernels(spec)
     assert k == ["igemm_conv2d_f32_64x64_dma_splitk"] and ws >= 16 * 49 * 512 * 4
-    monkeypatch.setenv("RELAYHIP_NO_SPLITK", "1")
-    k1, ws1 = kernels(spec)
+    k1, ws1 = kernels(spec, {"no_splitk": 1})
     assert k1 == ["igemm_conv2d_f32_64x64_dma"] and ws1 < ws
-    monkeypatch.delenv("RELAYHIP_NO_SPLITK")
     # many tiles: no split; the benchmark graph (batch 64, bf16) has none either
     assert not any(x.endswith("_splitk") for x in kernels(W.conv_group(16, 64, 64, 56, 56, 3, 1, 1, "f32")[0])[0])
     assert not any(x.endswith("_splitk") for x in kernels(W.resnet18(64, "bf16")[0])[0])

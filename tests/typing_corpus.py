@@ -203,6 +203,26 @@ def _lstm_gates_bf16_z():
     o, (c2, h2) = g.op("lstm_gates", [z, c], [("f32", (2, 4)), ("bf16", (2, 4))]); g.output(h2); return g
 
 
+def _group_gates_behind_injective_chain():      # the gate operator is a contraction's epilogue or a group of its own
+    g = GraphSpec("t"); z = g.input("z", "f32", (2, 16)); b = g.param("b", "f32", (16,)); c = g.input("c", "f32", (2, 4))
+    o0, (zb,) = g.op("bias_add", [z, b], [("f32", (2, 16))], axis=1)
+    o1, (c2, h2) = g.op("lstm_gates", [zb, c], [("f32", (2, 4)), ("f32", (2, 4))])
+    g.group([o0, o1]); g.output(c2); g.output(h2); return g
+
+
+def _gates_behind_injective_chain_ungrouped_ok():
+    g = _group_gates_behind_injective_chain(); g.groups.clear(); return g
+
+
+def _group_gates_skip_the_bias():               # the gate operator reads the contraction's bare result, not the chain's last one
+    g = GraphSpec("t"); x = g.input("x", "bf16", (2, 8)); w = g.param("w", "bf16", (16, 8)); b = g.param("b", "f32", (16,))
+    c = g.input("c", "f32", (2, 4))
+    o0, (z,) = g.op("dense", [x, w], [("f32", (2, 16))], out_dtype="f32")
+    o1, (zb,) = g.op("bias_add", [z, b], [("f32", (2, 16))], axis=1)
+    o2, (c2, h2) = g.op("lstm_gates", [z, c], [("f32", (2, 4)), ("bf16", (2, 4))])
+    g.group([o0, o1, o2]); g.output(c2); g.output(h2); return g
+
+
 def _cast_ok():
     g = GraphSpec("t"); x = g.input("x", "f32", (2, 4))
     o, (y,) = g.op("cast", [x], [("bf16", (2, 4))], to="bf16"); g.output(y); return g
@@ -339,6 +359,9 @@ CASES = [
     ("lstm_unfused_ok", _lstm_unfused_ok, None),
     ("lstm_gates_wrong_width", _lstm_gates_wrong_width, "type"),
     ("lstm_gates_bf16_z", _lstm_gates_bf16_z, "type"),
+    ("group_gates_behind_injective_chain", _group_gates_behind_injective_chain, "group"),
+    ("gates_behind_injective_chain_ungrouped_ok", _gates_behind_injective_chain_ungrouped_ok, None),
+    ("group_gates_skip_the_bias", _group_gates_skip_the_bias, "group"),
     ("cast_ok", _cast_ok, None),
     ("cast_wrong_declared", _cast_wrong_declared, "type"),
     ("layout_ok", _layout_ok, None),
