@@ -264,13 +264,14 @@ def check(spec) -> None:
                     raise IllTyped("group", "fused operators differ in output shape")
 
 
-def run(spec, data: Dict[str, np.ndarray], keep_all: bool = False) -> Dict[int, np.ndarray]:
+def run(spec, data: Dict[str, np.ndarray], keep_all: bool = False, keep=()) -> Dict[int, np.ndarray]:
     """Evaluate the graph.  `data` maps the names of input/param values to
     stored arrays (float32, or uint16 bf16 bits).  Returns float64 arrays for
-    the graph outputs (every value when keep_all), each holding numbers exactly
-    representable in that value's declared dtype if it crossed a group
-    boundary."""
+    the graph outputs (every value when keep_all; the outputs and the value ids
+    in `keep` otherwise), each holding numbers exactly representable in that
+    value's declared dtype if it crossed a group boundary."""
     check(spec)
+    keep = set(keep)
     group_of = {}
     for gi, grp in enumerate(spec.groups):
         for oi in grp:
@@ -331,8 +332,8 @@ def run(spec, data: Dict[str, np.ndarray], keep_all: bool = False) -> Dict[int, 
         if not keep_all:
             # free operands no later op needs
             for v in op.inputs:
-                if v in val and all(c <= oi for c in consumers.get(v, [])) and v not in spec.outputs:
+                if v in val and all(c <= oi for c in consumers.get(v, [])) and v not in spec.outputs and v not in keep:
                     del val[v]
     if keep_all:
         return val
-    return {v: val[v] for v in spec.outputs}
+    return {v: val[v] for v in list(spec.outputs) + [k for k in keep if k not in spec.outputs]}

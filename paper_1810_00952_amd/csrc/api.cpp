@@ -3,13 +3,9 @@
 #include <cstring>
 #include <new>
 
-#include "plan.h"
+#include "handles.h"
 
 using namespace rl;
-
-struct rl_ctx { std::shared_ptr<ErrBox> err; };
-struct rl_graph { Graph g; };
-struct rl_plan { Plan p; };
 
 namespace {
 

@@ -674,7 +674,6 @@ hipError_t launch_conv3x3_run(const IgemmParams &p, const IgemmLaunch &l, hipStr
             IgemmParams q = p;
             q.nblk_m = (p.M + 127) / 128;
             q.nblk_n = (p.N + 63) / 64;
-            q.nmajor = (int64_t)p.N * p.K * 2 > (3 << 20) ? 1 : 0;      // layer4 of the benchmark: 4.7 MB of weights, 4 MB of L2 per XCD
             hipLaunchKernelGGL((conv3x3_run_ks_kernel<128, 64, 6>), dim3((unsigned)(q.nblk_m * q.nblk_n)), dim3(256), 0, s, q);
             return hipGetLastError();
         }

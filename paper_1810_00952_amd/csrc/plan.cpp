@@ -412,7 +412,12 @@ struct Planner {
         il.run = il.lp && !il.c64 && !il.ws && !stem && an.kind == RL_OP_CONV2D && p.KH == 3 && p.KW == 3 && p.sh == 1 && p.sw == 1 && p.ph == 1 &&
                  p.pw == 1 && p.OH == p.H && p.OW == p.W && p.W <= 30 && p.C % 64 == 0 && p.Kp == p.K && il.tile != TILE_64x64 &&
                  !plan.opts.no_run;
-        if (il.run && il.tile == TILE_128x64 && p.C % 128 == 0 && !plan.opts.no_run_ks) il.run = 2;     // K split over the waves
+        if (il.run && il.tile == TILE_128x64 && p.C % 128 == 0 && !plan.opts.no_run_ks) {
+            il.run = 2;                                                 // K split over the waves
+            // weights of all channel tiles larger than an XCD's share of L2 (4 MB): tiles are numbered channel-tile-major,
+            // so that an XCD multiplies every pixel tile by one channel tile's weights
+            p.nmajor = (int64_t)p.N * p.K * 2 > (3 << 20) ? 1 : 0;
+        }
 
         double bytes = (double)bytes_of(x) + (x2 >= 0 ? (double)bytes_of(x2) : 0.0) + (double)bytes_of(wv);
         std::vector<int> eslots(RL_EPI_MAX_PTRS, -1);
@@ -883,7 +888,7 @@ std::string describe_plan(const Plan &p)
           << ", \"flops\": " << (long long)s.flops << ", \"bytes\": " << (long long)s.bytes;
         if (s.kind == S_IGEMM)
             o << ", \"M\": " << s.ig.M << ", \"N\": " << s.ig.N << ", \"K\": " << s.ig.K << ", \"epilogue_ops\": " << s.ig.epi.n_ops
-              << ", \"k_split_waves\": " << (s.il.run == 2 ? 1 : 0) << ", \"k_split_workgroups\": " << (s.il.splits > 1 ? s.il.splits : 1);
+              << ", \"k_split_waves\": " << (s.il.run == 2 ? 1 : 0) << ", \"channel_tile_major\": " << s.ig.nmajor << ", \"k_split_workgroups\": " << (s.il.splits > 1 ? s.il.splits : 1);
         if (s.kind == S_ELTWISE) o << ", \"n\": " << (long long)s.el.n << ", \"chain_ops\": " << s.el.epi.n_ops;
         o << "}";
     }

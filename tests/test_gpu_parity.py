@@ -6,16 +6,20 @@ import pytest
 import oracle as O
 from oracle import graph as OG
 import workloads as W
-from helpers import assert_close, extract_group, fold_resnet_hip, fold_resnet_oracle, run_hip, store_as
+from helpers import assert_close, error_budget, extract_group, extract_groups_channel_last, fold_resnet_hip, fold_resnet_oracle, run_hip, store_as
 
 pytestmark = pytest.mark.gpu
 
 
-def check_graph(spec, data, what, atol_scale=1.0, opts=None):
+def check_graph(spec, data, what, opts=None, rms_scaled=False):
+    # fp32: the stated gate; an element outside it must lie within the first-order fp32 error budget of the graph
+    # (computed only when needed); rms_scaled is for deep graphs, where that budget is vacuous
     ref = OG.run(spec, data)
     got, _ = run_hip(spec, data, opts=opts)
     for vid in spec.outputs:
-        assert_close(got[vid], ref[vid], spec.values[vid].type.dtype, f"{what} value {vid}", atol_scale)
+        dt = spec.values[vid].type.dtype
+        budget = None if (dt == "bf16" or rms_scaled) else (lambda vid=vid: error_budget(spec, data)[vid])
+        assert_close(got[vid], ref[vid], dt, f"{what} value {vid}", budget=budget, rms_scaled=rms_scaled)
     return got, ref
 
 
@@ -153,6 +157,7 @@ STEM_POOL_CASES = [
     (70, 3, 64, 64, 7, 2, 3, True, False),
     (9, 4, 61, 127, 8, 2, 3, True, True),
     (1, 3, 7, 250, 7, 2, 3, False, True),
+    (64, 3, 224, 224, 7, 2, 3, True, True),          # the benchmark's stem at full size: 12 544 regions streaming through 512 workgroups
 ]
 
 
@@ -219,6 +224,7 @@ RUN_CASES = [
     (64, 256, 256, 14, 14, False, False, True, "128x128"),
     (16, 192, 264, 28, 28, True, False, True, "128x128"),    # odd slice count: eight waves with 64x32 tiles; N tail
     (63, 128, 128, 28, 28, True, True, True, "256x128"),
+    (64, 512, 512, 7, 7, True, True, True, "128x64"),       # the benchmark's last stage: K split over the waves, tiles numbered channel-tile-major
 ]
 
 
@@ -229,6 +235,9 @@ def test_conv3x3_taps_from_one_copy_of_the_rows(case):
     from paper_1810_00952_amd import binding
     desc = binding.Plan(binding.graph_from_spec(binding.Context(), spec)).describe()
     assert any(st["kernel"] == f"igemm_conv2d_bf16_{tile}_run" for st in desc["steps"]), [st["kernel"] for st in desc["steps"]]
+    if ci == 512:
+        st = [st for st in desc["steps"] if st["kernel"].endswith("_run")][0]
+        assert st["k_split_waves"] == 1 and st["channel_tile_major"] == 1, st
     print(f"conv3x3 run case {case}", flush=True)
     got, _ = check_graph(spec, data, f"conv3x3 run {case}")
     # against the general kernel: same products, another summation order
@@ -276,7 +285,7 @@ def test_fused_equals_unfused_on_device():
     spec, data = W.conv_group(2, 16, 32, 12, 12, 3, 1, 1, "f32", residual=True)
     fused, _ = run_hip(spec, data)
     unf, _ = run_hip(spec.ungrouped(), data)
-    assert_close(fused[spec.outputs[0]], unf[spec.outputs[0]], "f32", "fused vs unfused")
+    assert_close(fused[spec.outputs[0]], unf[spec.outputs[0]], "f32", "fused vs unfused", budget=lambda: 2 * error_budget(spec, data)[spec.outputs[0]])
     # and the unfused plan itself matches the oracle's unfused run
     check_graph(spec.ungrouped(), data, "unfused conv group")
 
@@ -294,7 +303,7 @@ def test_conv1x1_equals_dense_on_device():
     d2 = {"x": np.ascontiguousarray(data["x"].transpose(0, 2, 3, 1).reshape(-1, c)), "w": data["w"].reshape(o, c), "b": data["b"]}
     z, _ = run_hip(g, d2)
     z = z[g.outputs[0]].reshape(b, h, w, o).transpose(0, 3, 1, 2)
-    assert_close(y, z, "f32", "1x1 conv vs dense")
+    assert_close(y, z, "f32", "1x1 conv vs dense", budget=lambda: 2 * error_budget(spec, data)[spec.outputs[0]])
 
 
 def test_run_twice_is_bitwise_identical():
@@ -380,7 +389,7 @@ def test_conv_activations_beyond_2_gib():
     for i in (0, B_ - 1):
         d = dict(data1); d["x"] = harness.to_host(x[i:i + 1])
         ref = OG.run(spec, d)[spec.outputs[0]]
-        assert_close(O.widen(harness.to_host(y[i:i + 1]), "f32"), ref, "f32", f"large conv image {i}")
+        assert_close(O.widen(harness.to_host(y[i:i + 1]), "f32"), ref, "f32", f"large conv image {i}", budget=lambda: error_budget(spec, d)[spec.outputs[0]])
     assert float((y[0] - y[B_ - 1]).abs().max()) > 1e-3
 
 
@@ -479,7 +488,7 @@ def test_resnet_small_end_to_end_and_per_group(dtype):
     data = fold_resnet_oracle(raw, bn, dtype)
     allv = OG.run(spec, data, keep_all=True)
     got, _ = _resnet_hip(spec, raw, bn, dtype)
-    assert_close(got, allv[spec.outputs[0]], dtype, f"resnet small {dtype} end to end")
+    assert_close(got, allv[spec.outputs[0]], dtype, f"resnet small {dtype} end to end", rms_scaled=True)      # 20 contractions deep
     # every group on its own, fed the oracle's values at its boundary
     for gi in range(len(spec.groups)):
         sub, vmap = extract_group(spec, gi)
@@ -492,7 +501,8 @@ def test_resnet_small_end_to_end_and_per_group(dtype):
         out, _ = run_hip(sub, sd)
         inv = {n: o for o, n in vmap.items()}
         for vid in sub.outputs:
-            assert_close(out[vid], allv[inv[vid]], sub.values[vid].type.dtype, f"resnet small {dtype} group {gi} ({spec.ops[spec.groups[gi][0]].kind})")
+            assert_close(out[vid], allv[inv[vid]], sub.values[vid].type.dtype, f"resnet small {dtype} group {gi} ({spec.ops[spec.groups[gi][0]].kind})",
+                         budget=None if dtype == "bf16" else (lambda: error_budget(sub, sd)[vid]))
 
 
 @pytest.mark.parametrize("which", ["resnet_small_f32", "resnet_small_bf16", "conv_bf16", "mlp_f32", "splitk_f32", "channel_last_bf16"])
@@ -546,21 +556,70 @@ def test_resnet18_f32_batch1():
     spec, raw, bn = W.resnet18(batch=1, dtype="f32")
     ref = OG.run(spec, fold_resnet_oracle(raw, bn, "f32"))[spec.outputs[0]]
     got, _ = _resnet_hip(spec, raw, bn, "f32")
-    assert_close(got, ref, "f32", "resnet18 f32 b1")
+    assert_close(got, ref, "f32", "resnet18 f32 b1", rms_scaled=True)          # 21 contractions deep: the worst-case budget is vacuous
 
 
-def test_resnet18_bf16_batch64_sampled_images():
-    # full benchmark configuration on the device; the oracle computes images 0 and 63 (inference is independent per image)
+def test_resnet18_bf16_batch64_every_image_and_every_group():
+    # The benchmark configuration at full size.
+    # (1) The plan bench.py times: all 64 images' logits against the oracle, over the batch and image by image.
+    # (2) Every fusion group at full size on the oracle's values at its boundary (so that nothing but the group's own
+    #     arithmetic separates the two sides), in the kernel and launch shape it has inside the whole plan (asserted):
+    #     groups are cut out with channel-last inputs and results behind views, the stem with the max-pool behind it and
+    #     each stride-2 convolution with the 1x1 projection beside it, as the plan launches them.  Every element of
+    #     every group's result, all 64 images.
+    from paper_1810_00952_amd import binding
     spec, raw, bn = W.resnet18(batch=64, dtype="bf16")
-    got, _ = _resnet_hip(spec, raw, bn, "bf16")
-    assert got.shape == (64, 1000) and np.all(np.isfinite(got))
-    for n in (0, 63):
-        s1, raw1, bn1 = W.resnet18(batch=1, dtype="bf16")
-        raw1 = dict(raw1); raw1["x"] = raw["x"][n:n + 1]
-        ref = OG.run(s1, fold_resnet_oracle(raw1, bn, "bf16"))[s1.outputs[0]]
-        assert_close(got[n:n + 1], ref, "bf16", f"resnet18 bf16 b64 image {n}")
+    data = fold_resnet_oracle(raw, bn, "bf16")
+    gout = {gi: spec.ops[sorted(g)[-1]].outputs[0] for gi, g in enumerate(spec.groups)}
+    print("oracle: 64 images, every group's result", flush=True)
+    ref = OG.run(spec, data, keep=list(gout.values()) + [i for i, v in enumerate(spec.values) if v.role == "input"])
+    print("device: whole plan", flush=True)
+    got, s = _resnet_hip(spec, raw, bn, "bf16")
+    assert got.shape == (64, 1000)
+    assert_close(got, ref[spec.outputs[0]], "bf16", "resnet18 bf16 b64 logits, 64 images")
+    for n in range(64):                           # image by image, so that one bad image cannot hide in the batch's RMS
+        assert_close(got[n], ref[spec.outputs[0]][n], "bf16", f"resnet18 bf16 b64 logits of image {n}")
     # images differ, so must the logits (guards against a batch-index bug that repeats one image)
     assert np.abs(got[0] - got[63]).max() > 1e-3
+    whole = {st["name"]: (st["kernel"], st.get("M"), st.get("N"), st.get("K")) for st in s.plan.describe()["steps"]}
+    del s
+    # launches of the whole plan -> the groups each one covers
+    def name_of(gi):                              # a convolution group goes by its weight's name
+        op = spec.ops[sorted(spec.groups[gi])[0]]
+        return spec.values[op.inputs[1]].name[:-len(".wf")] if op.kind == "conv2d" else op.kind
+    gi_of = {name_of(gi): gi for gi in range(len(spec.groups))}
+    units = [[gi_of["conv1"], gi_of["maxpool2d"]]]
+    for st in range(1, 5):
+        for b in range(2):
+            pre = f"l{st}.b{b}"
+            units.append([gi_of[pre + ".c1"]] + ([gi_of[pre + ".ds"]] if pre + ".ds" in gi_of else []))
+            units.append([gi_of[pre + ".c2"]])
+    units.append([gi_of["global_avgpool"], gi_of["flatten"], gi_of["dense"]])
+    xid = [i for i, v in enumerate(spec.values) if v.role == "input"][0]
+    seen_kernels = set()
+    for gis in units:
+        sub, feeds, results = extract_groups_channel_last(spec, gis, native_inputs=(xid,))
+        sd = {}
+        for old, (name, cl) in feeds.items():
+            a = ref[old]
+            sd[name] = store_as(np.ascontiguousarray(np.transpose(a, (0, 2, 3, 1))) if cl else a, spec.values[old].type.dtype)
+        for v in sub.values:
+            if v.role == "param":
+                sd[v.name] = data[v.name]
+        label = "+".join(name_of(g) for g in gis)
+        print(f"device: {label}", flush=True)
+        out, ss = run_hip(sub, sd)
+        for st in ss.plan.describe()["steps"]:
+            k = (st["kernel"], st.get("M"), st.get("N"), st.get("K"))
+            assert k in whole.values(), (label, k)           # the kernel and shape this group has inside the whole plan
+            seen_kernels.add(k)
+        for old, new in results.items():
+            r = ref[old]
+            r = np.ascontiguousarray(np.transpose(r, (0, 2, 3, 1))) if r.ndim == 4 else r
+            assert_close(out[new], r, "bf16", f"resnet18 bf16 b64 group {label}, 64 images")
+            for n in (0, 21, 42, 63):
+                assert_close(out[new][n], r[n], "bf16", f"resnet18 bf16 b64 group {label}, image {n}")
+    assert seen_kernels == set(whole.values()), set(whole.values()) - seen_kernels
 
 
 # ------------------------------------------------------------------ automatic fusion
@@ -573,7 +632,7 @@ def test_automatically_fused_graphs(dtype):
     got, s = run_hip(spec, data, auto_groups=True)
     assert len(s.plan.describe()["steps"]) < len(run_hip(spec, data)[1].plan.describe()["steps"])
     for vid in spec.outputs:
-        assert_close(got[vid], ref[vid], dtype, f"auto-fused conv tail {dtype}")
+        assert_close(got[vid], ref[vid], dtype, f"auto-fused conv tail {dtype}", budget=None if dtype == "bf16" else (lambda: error_budget(spec, data)[vid]))
     spec, raw, bn = W.resnet18(batch=2, dtype=dtype, image=64, width=16, classes=24)
     from paper_1810_00952_amd import harness
     import torch
@@ -595,7 +654,7 @@ def test_lenet_shaped_graph(dtype, batch):
     spec, data = W.lenet(batch, dtype)
     check_graph(spec, data, f"lenet {dtype} b{batch}")
     # every op in a group of its own gives the same values up to the rounding of the stored intermediates
-    check_graph(spec.ungrouped(), data, f"lenet ungrouped {dtype} b{batch}", atol_scale=2.0 if dtype == "bf16" else 1.0)
+    check_graph(spec.ungrouped(), data, f"lenet ungrouped {dtype} b{batch}")
 
 
 # ------------------------------------------------------------------ LSTM
@@ -634,8 +693,8 @@ def test_lstm_recurrent(fused, dtype, T, B, I, H):
     hs_ref, c_ref = O.lstm_sequence(O.widen(d["x"], dtype), O.widen(d["w"], dtype), O.widen(d["b"], "f32"),
                                     np.zeros((B, H)), np.zeros((B, H)), h_dtype=dtype)
     hs, c = _lstm_hip(T, B, I, H, dtype, fused, d)
-    assert_close(hs, hs_ref, dtype, f"lstm h {dtype} fused={fused}")
-    assert_close(c, c_ref, dtype if dtype == "bf16" else "f32", f"lstm c {dtype} fused={fused}")
+    assert_close(hs, hs_ref, dtype, f"lstm h {dtype} fused={fused}", rms_scaled=True)
+    assert_close(c, c_ref, dtype if dtype == "bf16" else "f32", f"lstm c {dtype} fused={fused}", rms_scaled=True)
 
 
 # Hoisted form (input projection of many steps in one contraction, then one recurrent kernel per step):
@@ -700,12 +759,13 @@ def test_contraction_with_k_split_over_workgroups(case):
     got, _ = run_hip(spec, data)
     ref = OG.run(spec, data)
     v = spec.outputs[0]
-    assert_close(got[v], ref[v], dtype, f"split-K {case}")
+    bud = None if dtype == "bf16" else (lambda: error_budget(spec, data)[v])
+    assert_close(got[v], ref[v], dtype, f"split-K {case}", budget=bud)
     again, _ = run_hip(spec, data)
     np.testing.assert_array_equal(got[v], again[v])               # slices are added in a fixed order
     whole, s1 = run_hip(spec, data, opts={"no_splitk": 1})
     assert not any(st["kernel"].endswith("_splitk") for st in s1.plan.describe()["steps"])
-    assert_close(whole[v], ref[v], dtype, f"unsplit {case}")
+    assert_close(whole[v], ref[v], dtype, f"unsplit {case}", budget=bud)
 
 
 # ---- typed changes of layout -----------------------------------------------------------------------------
@@ -738,7 +798,7 @@ def test_block_between_channel_last_tensors(batch, c, h, w, dtype):
     got, _ = run_hip(spec, data)
     ref = OG.run(spec, data)
     v = spec.outputs[0]
-    assert_close(got[v], ref[v], dtype, "channel-last block")
+    assert_close(got[v], ref[v], dtype, "channel-last block", budget=None if dtype == "bf16" else (lambda: error_budget(spec, data)[v]))
 
 
 @pytest.mark.parametrize("batch,c,h,w,k,s,p,dtype", [(2, 16, 33, 31, 3, 2, 1, "bf16"), (1, 8, 40, 17, 3, 2, 0, "f32"), (2, 64, 112, 112, 3, 2, 1, "bf16"),

@@ -132,3 +132,49 @@ def test_channel_last_block_equals_the_channel_first_block():
     c1 = O.round_to(O.unary("relu", O.bias_add(O.conv2d(x, w1, (1, 1), (1, 1)), b1, 1)), "f32")
     c2 = O.round_to(O.unary("relu", O.binary("add", O.bias_add(O.conv2d(c1, w2, (1, 1), (1, 1)), b2, 1), x)), "f32")
     np.testing.assert_array_equal(y, np.transpose(c2, (0, 2, 3, 1)))
+
+
+def _bits32(a):
+    return np.asarray(a, dtype=np.float64).astype(np.float32).view(np.uint32).ravel()
+
+
+def test_cast_rounds_where_it_stands_and_nothing_else_does_inside_a_group():
+    # The cast expression rounds at once, also in the middle of a fusion group; every other operator's result is
+    # rounded only when it leaves its group.  Expected values are bit patterns worked out by hand:
+    #   x0 = 1 + 2^-8            tie between 1 and 1 + 2^-7          -> bf16 0x3F80 (even)
+    #   x1 = 1 + 3 * 2^-8        tie between 1 + 2^-7 and 1 + 2^-6   -> bf16 0x3F82 (even)
+    #   x2 = 1 + 2^-8 + 2^-12    above the tie                       -> bf16 0x3F81
+    x = np.array([[1 + 2.0 ** -8, 1 + 3 * 2.0 ** -8, 1 + 2.0 ** -8 + 2.0 ** -12]], dtype=np.float32)
+    g = W.GraphSpec("cast_out")
+    xv = g.input("x", "f32", (1, 3))
+    o0, (y,) = g.op("cast", [xv], [("bf16", (1, 3))], to="bf16")
+    g.group([o0]); g.output(y)
+    out = OG.run(g, {"x": x})[y]
+    np.testing.assert_array_equal(_bits32(out) >> 16, [0x3F80, 0x3F82, 0x3F81])
+    np.testing.assert_array_equal(_bits32(out) & 0xFFFF, [0, 0, 0])
+
+    # cast -> sq -> cast back, as one group: the first cast rounds (1 + 2^-7 for x2), the square (1 + 2^-6 + 2^-14) is
+    # *not* rounded to bf16 although its declared type is bf16, the cast to f32 keeps it: 0x3F820200.
+    # (cast as identity would give (1 + 2^-8 + 2^-12)^2; rounding the square to bf16 would give 0x3F820000.)
+    def chain(grouped):
+        g = W.GraphSpec("cast_chain")
+        xv = g.input("x", "f32", (1, 3))
+        o0, (a,) = g.op("cast", [xv], [("bf16", (1, 3))], to="bf16")
+        o1, (b,) = g.op("sq", [a], [("bf16", (1, 3))])
+        o2, (c,) = g.op("cast", [b], [("f32", (1, 3))], to="f32")
+        if grouped:
+            g.group([o0, o1, o2])
+        g.output(c)
+        return g, c
+    g, c = chain(True)
+    np.testing.assert_array_equal(_bits32(OG.run(g, {"x": x})[c]), [0x3F800000, 0x3F840800, 0x3F820200])
+    # the same calls each in a group of its own: the square leaves its group as a bf16 value (1 + 2^-6 for x2;
+    # (1 + 2^-6)^2 = 1 + 2^-5 + 2^-12 -> 1 + 2^-5 for x1)
+    g, c = chain(False)
+    np.testing.assert_array_equal(_bits32(OG.run(g, {"x": x})[c]), [0x3F800000, 0x3F840000, 0x3F820000])
+    # a cast to the type the value already has changes nothing, grouped or not
+    g = W.GraphSpec("cast_same")
+    xv = g.input("x", "f32", (1, 3))
+    o0, (a,) = g.op("cast", [xv], [("f32", (1, 3))], to="f32")
+    g.output(a)
+    np.testing.assert_array_equal(_bits32(OG.run(g, {"x": x})[a]), x.view(np.uint32).ravel())

@@ -245,6 +245,25 @@ def test_folded_batchnorm_equals_explicit():
     assert abs(y[1, 2, 3, 4] - (g[2] * (x[1, 2, 3, 4] - m[2]) / math.sqrt(v[2] + 1e-5) + b[2])) < 1e-14
 
 
+def test_batchnorm_closed_forms():
+    # gamma = sqrt(var + eps), beta = mean  =>  y = x;   x = mean  =>  y = beta  (whatever the other statistics are)
+    x = RNG.standard_normal((3, 4, 5, 2))
+    g, b, m, v = RNG.uniform(.5, 1.5, 4), RNG.uniform(-1, 1, 4), RNG.standard_normal(4), RNG.uniform(.5, 1.5, 4)
+    np.testing.assert_allclose(O.batchnorm(x, np.sqrt(v + 1e-5), m, m, v, 1e-5), x, atol=1e-14)
+    xm = np.broadcast_to(m[None, :, None, None], x.shape)
+    np.testing.assert_array_equal(O.batchnorm(xm, g, b, m, v, 1e-5), np.broadcast_to(b[None, :, None, None], x.shape))
+    # eps sits under the root, next to the variance: numbers worked by hand (all exactly representable).
+    # channel 0: (5 - 1) / sqrt(3.75 + .25) * 1 + 0 = 2;  channel 1: (5 - 2) / sqrt(.75 + .25) * 3 - 1 = 8
+    y = O.batchnorm(np.full((2, 2, 1, 3), 5.0), [1.0, 3.0], [0.0, -1.0], [1.0, 2.0], [3.75, 0.75], 0.25)
+    np.testing.assert_array_equal(y, np.broadcast_to(np.array([2.0, 8.0])[None, :, None, None], (2, 2, 1, 3)))
+    # zero variance: only eps is left in the denominator: 2 * (3 - 1) / sqrt(.25) + .5 = 8.5
+    assert O.batchnorm(np.full((1, 1, 1, 1), 3.0), [2.0], [0.5], [1.0], [0.0], 0.25)[0, 0, 0, 0] == 8.5
+    # the folded form on the same hand numbers: scale = 3 / sqrt(.75 + .25) = 3, w' = 3 w, b' = -1 - 2 * 3 = -7
+    wf, bf = O.fold_batchnorm(np.array([[2.0, 4.0], [1.0, -1.0]]), [3.0, 1.0], [-1.0, 0.0], [2.0, 1.0], [0.75, 3.75], 0.25)
+    np.testing.assert_array_equal(wf, [[6.0, 12.0], [0.5, -0.5]])
+    np.testing.assert_array_equal(bf, [-7.0, -0.5])
+
+
 # ---------------------------------------------------------------- library cross-check
 def test_against_library_float64():
     x, w = RNG.standard_normal((2, 8, 13, 11)), RNG.standard_normal((5, 8, 3, 3))

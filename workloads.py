@@ -312,14 +312,25 @@ def channel_last_block(batch=3, c=64, h=14, w=14, dtype="bf16", config=12):
 # configs 3 and 4: ResNet-18-shaped inference graph with folded batch-norm
 # --------------------------------------------------------------------------
 def resnet18(batch=1, dtype="f32", image=224, width=64, classes=1000, config=3,
-             blocks=(2, 2, 2, 2)):
+             blocks=(2, 2, 2, 2), taps=False):
     """Returns (graph, data, bn) where `data` holds x, the *unfolded* conv
     weights, dense weight/bias, and `bn` maps each conv name to its batch-norm
     statistics (gamma, beta, mean, var).  The graph refers to folded parameters
     "<conv>.wf" / "<conv>.bf"; each consumer folds with its own code and casts
     to the graph dtype.  Random draws never depend on `batch` beyond x, nor on
-    dtype, so the b64/bf16 graph has the b1/f32 graph's weights."""
+    dtype, so the b64/bf16 graph has the b1/f32 graph's weights.
+    taps=True makes the pooled stem tensor and every basic block's result graph outputs as well (behind the
+    logits), each as its channel-last view (a layout_transform, which costs the plan no kernel and leaves every
+    group's kernel what it is without the taps)."""
     rng = rng_for(3)          # configs 3 and 4 share weights by design
+    tapped = []
+
+    def tap(v, c, hw):
+        if taps:
+            o, (t,) = g.op("layout_transform", [v], [(dtype, (batch, hw, hw, c))], perm=(0, 2, 3, 1))
+            g.group([o])
+            tapped.append(t)
+
     xrng = rng_for(3, salt=1)
     g = GraphSpec(f"resnet18_b{batch}_{dtype}")
     raw: Dict[str, np.ndarray] = {}
@@ -355,6 +366,7 @@ def resnet18(batch=1, dtype="f32", image=224, width=64, classes=1000, config=3,
     o, (y,) = g.op("maxpool2d", [y], [(dtype, (batch, width, ho, ho))], kernel=(3, 3), stride=(2, 2), pad=(1, 1))
     g.group([o])
     h = ho
+    tap(y, width, h)
     cin = width
     for stage, nblk in enumerate(blocks):
         cout = width << stage
@@ -367,6 +379,7 @@ def resnet18(batch=1, dtype="f32", image=224, width=64, classes=1000, config=3,
                 skip, _ = conv_bn(name + ".ds", y, cin, cout, 1, s, 0, h, relu=False)
             y, h = conv_bn(name + ".c2", y1, cout, cout, 3, 1, 1, h1, res=skip)
             cin = cout
+            tap(y, cout, h)
     o, (y,) = g.op("global_avgpool", [y], [(dtype, (batch, cin, 1, 1))]); g.group([o])
     o, (y,) = g.op("flatten", [y], [(dtype, (batch, cin))]); g.group([o])
     raw["fc.w"] = as_dtype(kaiming_uniform(rng, (classes, cin), cin), dtype)
@@ -377,6 +390,8 @@ def resnet18(batch=1, dtype="f32", image=224, width=64, classes=1000, config=3,
     o1, (y,) = g.op("bias_add", [y, bv], [(dtype, (batch, classes))], axis=1)
     g.group([o0, o1])
     g.output(y)
+    for t in tapped:
+        g.output(t)
     return g, raw, bn
 
 
