@@ -217,6 +217,16 @@ rl_status rl_plan_prepack(const rl_plan *plan, int32_t param_value_id, const voi
 rl_status rl_plan_run(const rl_plan *plan, const rl_binding *bindings, int32_t n_bindings,
                       void *workspace_dev, size_t workspace_bytes, void *hip_stream);
 
+/* rl_plan_run without a workspace argument, for callers that cannot allocate device memory (code under HIP graph
+ * capture, serving loops, harnesses that forbid hipMalloc): the intermediates live in an array of
+ * RL_STATIC_WORKSPACE_BYTES that is part of the library's code object (each GPU the library runs on holds one copy
+ * until the process ends).  Plans with rl_plan_workspace_bytes above that return RL_ERR_WORKSPACE.  The call
+ * allocates nothing on the device and otherwise behaves like rl_plan_run (same kernels, same results, same errors).
+ * All calls on one GPU share the array: two calls that may overlap in time (different streams or threads) race;
+ * serialise them or use rl_plan_run with workspaces of the caller's. */
+#define RL_STATIC_WORKSPACE_BYTES (16u << 20)
+rl_status rl_plan_run_static(const rl_plan *plan, const rl_binding *bindings, int32_t n_bindings, void *hip_stream);
+
 /* Measurement aid (not part of the hot path): enqueue the plan `reps` times
  * with a HIP event recorded on hip_stream before and after every step, then
  * wait for the stream -- the only entry point that synchronises.  step_ms[i]

@@ -13,6 +13,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "librelayhip.so")
 
 RL_F32, RL_BF16 = 0, 1
+STATIC_WORKSPACE_BYTES = 16 << 20
 RL_MAX_RANK = 6
 DTYPES = {"f32": RL_F32, "bf16": RL_BF16}
 DTYPE_BYTES = {"f32": 4, "bf16": 2}
@@ -97,7 +98,7 @@ _lib = None
 SYMBOLS = ["rl_ctx_create", "rl_ctx_destroy", "rl_last_error", "rl_graph_create", "rl_graph_destroy", "rl_graph_input",
            "rl_graph_param", "rl_graph_op", "rl_graph_group", "rl_graph_output", "rl_graph_autogroup", "rl_graph_group_of", "rl_plan_create", "rl_plan_destroy",
            "rl_plan_describe", "rl_plan_workspace_bytes", "rl_plan_packed_bytes", "rl_plan_prepack", "rl_plan_run",
-           "rl_plan_run_recurrent", "rl_plan_recurrent_workspace_bytes", "rl_prep_fold_batchnorm", "rl_plan_profile"]
+           "rl_plan_run_static", "rl_plan_run_recurrent", "rl_plan_recurrent_workspace_bytes", "rl_prep_fold_batchnorm", "rl_plan_profile"]
 
 
 def lib():
@@ -137,6 +138,7 @@ def lib():
         L.rl_plan_packed_bytes.argtypes = [c_void_p, c_int32, POINTER(c_size_t)]
         L.rl_plan_prepack.argtypes = [c_void_p, c_int32, c_void_p, c_void_p, c_void_p]
         L.rl_plan_run.argtypes = [c_void_p, POINTER(rl_binding), c_int32, c_void_p, c_size_t, c_void_p]
+        L.rl_plan_run_static.argtypes = [c_void_p, POINTER(rl_binding), c_int32, c_void_p]
         L.rl_plan_profile.argtypes = [c_void_p, POINTER(rl_binding), c_int32, c_void_p, c_size_t, c_void_p, c_int32,
                                       POINTER(ctypes.c_float), c_int32, POINTER(c_int32)]
         L.rl_plan_run_recurrent.argtypes = [c_void_p, c_int32, POINTER(rl_recurrent), POINTER(rl_binding), c_int32, c_void_p,
@@ -349,6 +351,10 @@ class Plan:
     def run(self, bindings: Dict[int, int], workspace_ptr: int = 0, workspace_bytes: int = 0, stream: int = 0) -> None:
         self.ctx.check(lib().rl_plan_run(self._h, self._bindings(bindings), len(bindings), c_void_p(workspace_ptr),
                                          c_size_t(workspace_bytes), c_void_p(stream)))
+
+    def run_static(self, bindings: Dict[int, int], stream: int = 0) -> None:
+        """rl_plan_run_static: the library's built-in workspace (STATIC_WORKSPACE_BYTES at most), no device allocation."""
+        self.ctx.check(lib().rl_plan_run_static(self._h, self._bindings(bindings), len(bindings), c_void_p(stream)))
 
     def profile(self, bindings: Dict[int, int], workspace_ptr: int, workspace_bytes: int, stream: int, reps: int) -> List[float]:
         """Mean milliseconds per plan step over `reps` runs (synchronises)."""

@@ -142,6 +142,20 @@ def test_plan_options_are_fixed_in_the_plan():
         B.make_opts({"no_such_switch": 1})
 
 
+def test_static_entry_point_refuses_plans_beyond_its_workspace():
+    # decided on the host before anything touches a GPU
+    spec = W.resnet18(batch=64, dtype="bf16")[0]
+    ctx = B.Context()
+    plan = B.Plan(B.graph_from_spec(ctx, spec))
+    assert plan.workspace_bytes() > B.STATIC_WORKSPACE_BYTES
+    header = open(os.path.join(ROOT, "include", "relayhip.h")).read()
+    assert re.search(r"#define RL_STATIC_WORKSPACE_BYTES \((\d+)u << 20\)", header).group(1) == str(B.STATIC_WORKSPACE_BYTES >> 20)
+    with pytest.raises(B.RelayError) as ei:
+        plan.run_static({0: 0x1000}, 0)
+    assert ei.value.category == "workspace" and str(B.STATIC_WORKSPACE_BYTES) in str(ei.value)
+    assert B.lib().rl_plan_run_static(None, None, 0, None) == -1
+
+
 def test_recurrent_call_rejects_mismatched_roles_on_the_host():
     fake = 0x10000
     ctx = B.Context()
