@@ -20,6 +20,10 @@ configurations and the HBM-bound groups:
   copy      y = -x on 24 Mi f32 elements: a plain copy kernel of known size
             (100.7 MB read, 100.7 MB written, ordinary loads and stores), the
             yardstick for the HBM byte counters
+  mfma_peak a chain of bf16 MFMAs on register operands on every SIMD: what the
+            matrix pipes deliver here, next to the quoted 2.5 PFLOP/s
+The default line also carries that calibration ("peaks") and the HBM-bound groups
+on tensors far larger than the last-level cache ("hbm_bound_groups").
 """
 from __future__ import annotations
 
@@ -65,9 +69,16 @@ def cpu_baseline_graph(spec, data, unit_count: float, unit: str, what: str):
 GRAPH = False     # --graph: time replays of a HIP graph holding one step instead of eager launches
 
 
-def time_steps(run, steps, warmup):
+TIMING = {}       # distribution of the last time_steps call (per-step milliseconds over chunks of the timed region)
+
+
+def time_steps(run, steps, warmup, graph=None):
+    """W untimed steps, then exactly `steps` steps between two events on the launch stream, bracketed by device
+    synchronisation on both sides.  Returns the mean milliseconds per step of that region.  Events every few steps
+    inside the region (at most 20 chunks, so that their own cost stays far below a percent) give median, minimum
+    and 90th percentile of the per-step time over the chunks, left in TIMING."""
     import torch
-    if GRAPH:
+    if GRAPH if graph is None else graph:
         run()
         torch.cuda.synchronize()
         g = torch.cuda.CUDAGraph()
@@ -78,15 +89,25 @@ def time_steps(run, steps, warmup):
     for _ in range(warmup):
         run()
     torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    chunk = max(1, -(-steps // 20))
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(-(-steps // chunk) + 1)]
     t0 = time.perf_counter()
-    e0.record(stream)
-    for _ in range(steps):
+    marks[0].record(stream)
+    for i in range(steps):
         run()
-    e1.record(stream)
+        if (i + 1) % chunk == 0 or i + 1 == steps:
+            marks[(i + chunk) // chunk].record(stream)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
-    ms = e0.elapsed_time(e1) / steps
+    ms = marks[0].elapsed_time(marks[-1]) / steps
+    per = []
+    for j in range(len(marks) - 1):
+        n = min(chunk, steps - j * chunk)
+        per.append(marks[j].elapsed_time(marks[j + 1]) / n)
+    per.sort()
+    TIMING.clear()
+    TIMING.update({"ms_per_step_median": per[len(per) // 2], "ms_per_step_min": per[0], "ms_per_step_p90": per[min(len(per) - 1, int(0.9 * len(per)))],
+                   "chunks": len(per), "steps_per_chunk": chunk})
     return max(ms, wall * 1e3 / steps)          # never report less than the host saw
 
 
@@ -160,21 +181,91 @@ def roofline_of(name, k, peak_tflops):
     return roof
 
 
-def kernels_json(by_kernel):
+def kernels_json(by_kernel, peak_tflops=None):
+    """Per kernel: time, launches, algorithmic TFLOP/s and GB/s, and both as fractions of the quoted peaks (a contraction
+    is held against the MFMA peak of its dtype whatever its arithmetic intensity says)."""
     rate = lambda amount, ms, unit: amount / (ms * 1e-3) / unit if ms > 0 else 0.0
-    return {k: {"ms_per_step": v["ms"], "launches": v["launches"], "tflops": rate(v["flops"], v["ms"], 1e12),
-                "gbs": rate(v["bytes"], v["ms"], 1e9)} for k, v in sorted(by_kernel.items(), key=lambda kv: -kv[1]["ms"])}
+    out = {}
+    for k, v in sorted(by_kernel.items(), key=lambda kv: -kv[1]["ms"]):
+        e = {"ms_per_step": v["ms"], "launches": v["launches"], "tflops": rate(v["flops"], v["ms"], 1e12), "gbs": rate(v["bytes"], v["ms"], 1e9)}
+        e["hbm_frac"] = e["gbs"] / PEAK_HBM_GBS
+        if peak_tflops and k.startswith("igemm"):
+            e["mfma_frac"] = e["tflops"] / peak_tflops
+        out[k] = e
+    return out
+
+
+def measure_peaks():
+    """What this machine delivers next to the quoted peaks: a register-only bf16 MFMA chain on every SIMD, and the
+    fused bias + residual + ReLU group streaming 1.2 GB (two reads and a write per element)."""
+    import torch
+    from paper_1810_00952_amd import binding, harness
+    ctx = binding.Context()
+    wg, iters = 512, 4096
+    scratch = torch.empty(wg * 512, dtype=torch.float32, device="cuda:0")
+    stream = harness.stream_handle()
+    ctx.calibrate_mfma_bf16(scratch.data_ptr(), wg, 64, stream)
+    torch.cuda.synchronize()
+    best = None
+    for _ in range(3):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(torch.cuda.current_stream())
+        flops = ctx.calibrate_mfma_bf16(scratch.data_ptr(), wg, iters, stream)
+        e1.record(torch.cuda.current_stream())
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1)
+        best = ms if best is None else min(best, ms)
+    return {"mfma_bf16_tflops_quoted": PEAK_BF16_TFLOPS, "mfma_bf16_tflops_measured": flops / (best * 1e-3) / 1e12,
+            "mfma_measure": f"{wg} workgroups x 8 waves x {16 * iters} MFMAs 32x32x16 bf16 on register operands, best of 3",
+            "hbm_gbs_quoted": PEAK_HBM_GBS}
+
+
+def hbm_groups(args):
+    """The HBM-bound groups on tensors far larger than the last-level cache, each as a plan of its own: algorithmic
+    bytes per launch / mean launch duration (events on the launch stream) against the quoted 8 TB/s."""
+    import workloads as W
+    from paper_1810_00952_amd import harness
+    import torch
+    res = []
+
+    def one(label, spec, data, nbytes):
+        s = harness.Session(spec)
+        s.load(data)
+        s.alloc()
+        ms = time_steps(s.run, 30, 5, graph=False)
+        res.append({"group": label, "kernel": "+".join(st["kernel"] for st in s.plan.describe()["steps"]), "us": ms * 1e3,
+                    "algorithmic_bytes": nbytes, "gbs": nbytes / (ms * 1e-3) / 1e9, "hbm_frac": nbytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS})
+        del s
+        torch.cuda.empty_cache()
+    for dtype, shape in (("bf16", (256, 64, 112, 112)), ("f32", (128, 64, 112, 112))):
+        spec, make = W.eltwise_bias_res_relu(shape, dtype)
+        n = shape[0] * shape[1] * shape[2] * shape[3]
+        one(f"relu(bias_add(x) + r) {dtype} {'x'.join(map(str, shape))}", spec, make(), 3 * n * (2 if dtype == "bf16" else 4))
+    B, H = 16384, 1024
+    g = W.GraphSpec("gates")
+    z = g.input("z", "f32", (B, 4 * H)); c = g.input("c", "f32", (B, H))
+    o, (c2, h2) = g.op("lstm_gates", [z, c], [("f32", (B, H)), ("bf16", (B, H))])
+    g.output(c2); g.output(h2)
+    rng = W.rng_for(6, salt=2)
+    one(f"lstm_gates z {B}x{4 * H} f32", g, {"z": W.as_dtype(W.normal(rng, (B, 4 * H)), "f32"), "c": W.as_dtype(W.normal(rng, (B, H)), "f32")},
+        B * H * (16 + 4 + 4 + 2))
+    spec, data = W.channel_last_maxpool(64, 64, 112, 112, 3, 2, 1, "bf16")
+    one("maxpool2d 3x3/2 bf16 64x64x112x112 (channel-last)", spec, data, 64 * 64 * (112 * 112 + 56 * 56) * 2)
+    return res
 
 
 def base_json(metric, value, unit, args, ms, dtype, workload, extra_cfg=None):
     cfg = {"workload": workload, "launch": "hip graph replay" if GRAPH else "eager"}
     cfg.update(extra_cfg or {})
-    return {"metric": metric, "value": value, "unit": unit, "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
-            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": dtype, "data": "synthetic", "config": cfg,
-            "paper_figures": "none"}
+    out = {"metric": metric, "value": value, "unit": unit, "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": dtype, "data": "synthetic", "config": cfg,
+           "paper_figures": "none"}
+    out.update(TIMING)
+    return out
 
 
 def bench_resnet(args, batch, dtype):
+    import torch
     import workloads as W
     from paper_1810_00952_amd import harness
     from helpers import fold_resnet_hip
@@ -197,7 +288,19 @@ def bench_resnet(args, batch, dtype):
         per_step = measured_traffic(dom_name, "resnet18_b64_bf16_hbm_traffic.txt")
         out["roofline"]["traffic"] = per_step / dom["launches"] if per_step is not None else None      # bytes per launch
         out["roofline"]["traffic_per_step"] = per_step
-    out["kernels"] = kernels_json(by_kernel)
+    out["kernels"] = kernels_json(by_kernel, peak)
+    if dtype == "bf16" and batch == 64:
+        # the two targets of this path side by side: contractions against the bf16 MFMA peak, HBM-bound groups against 8 TB/s
+        mf = sum(v["flops"] for k, v in by_kernel.items() if k.startswith("igemm"))
+        mt = sum(v["ms"] for k, v in by_kernel.items() if k.startswith("igemm"))
+        out["contractions_mfma_frac"] = mf / (mt * 1e-3) / 1e12 / peak if mt > 0 else None
+        saved = dict(TIMING)
+        del s
+        torch.cuda.empty_cache()
+        if not args.no_extras:
+            out["peaks"] = measure_peaks()
+            out["hbm_bound_groups"] = hbm_groups(args)
+        TIMING.clear(); TIMING.update(saved)
     if not args.no_cpu and dtype == "bf16" and batch == 64:
         out["cpu_baseline"] = cpu_baseline_resnet(args.cpu_images)
     return out
@@ -213,7 +316,7 @@ def bench_graph(args, spec, data, metric, unit, units_per_step, dtype, workload,
     dom_name, dom = max(by_kernel.items(), key=lambda kv: kv[1]["ms"])
     out = base_json(metric, units_per_step / (ms * 1e-3), unit, args, ms, dtype, workload)
     out["roofline"] = roofline_of(dom_name, dom, peak_tflops)
-    out["kernels"] = kernels_json(by_kernel)
+    out["kernels"] = kernels_json(by_kernel, peak_tflops)
     if cpu is not None and not args.no_cpu:
         out["cpu_baseline"] = cpu()
     return out
@@ -243,6 +346,10 @@ def bench_lstm(args):
         s.plan.run_recurrent(T, roles, x.data_ptr(), B * I * 2, h0.data_ptr(), c.data_ptr(), hs.data_ptr(), B * H * 2, params,
                              ws.data_ptr(), ws.numel(), harness.stream_handle())
     ms = time_steps(run, args.steps, args.warmup)
+    timing = dict(TIMING)
+    # the same sequence of launches replayed from a HIP graph (the cell-state reset and every kernel of the sequence)
+    ms_graph = time_steps(run, args.steps, args.warmup, graph=True) if not GRAPH else None
+    TIMING.clear(); TIMING.update(timing)
     desc = s.plan.describe()
     flops = sum(st["flops"] for st in desc["steps"]) * T
     hoisted = ws.numel() > max(256, s.plan.workspace_bytes()) and not args.unfused
@@ -259,6 +366,8 @@ def bench_lstm(args):
                     + ("input projection hoisted, one recurrent kernel per step" if hoisted else
                        "gate math fused into the GEMM epilogue" if not args.unfused else "GEMM group and gate group"))
     out["us_per_step_of_sequence"] = ms * 1e3 / T
+    if ms_graph is not None:
+        out["hip_graph_replay"] = {"ms_per_step": ms_graph, "us_per_step_of_sequence": ms_graph * 1e3 / T, "sequences_per_s": B / (ms_graph * 1e-3)}
     tflops, gbs = flops / (ms * 1e-3) / 1e12, nbytes / (ms * 1e-3) / 1e9
     # a step is a 64-row contraction that must finish before the next can start: bound by memory traffic and latency
     out["roofline"] = {"bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS, "traffic": None,
@@ -282,10 +391,11 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="resnet18",
-                    choices=["resnet18", "resnet18_f32_b1", "eltwise", "eltwise32", "gates", "lstm", "mlp", "lenet", "conv", "copy", "layout", "layout32", "block_nhwc", "maxpool"])
+                    choices=["resnet18", "resnet18_f32_b1", "eltwise", "eltwise32", "gates", "lstm", "mlp", "lenet", "conv", "copy", "layout", "layout32", "block_nhwc", "maxpool", "mfma_peak"])
     ap.add_argument("--batch", type=int, default=64)
     ap.add_argument("--cpu-images", type=int, default=128)
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--no-extras", action="store_true", help="default workload: skip the MFMA calibration and the HBM-bound groups")
     ap.add_argument("--unfused", action="store_true", help="lstm: gate math as a group of its own")
     ap.add_argument("--profile-reps", type=int, default=20)
     ap.add_argument("--graph", action="store_true", help="time replays of a HIP graph that holds one step (same kernels, no host launches)")
@@ -347,6 +457,11 @@ def main():
                           "-> channel-last output, bf16, batch 64", PEAK_BF16_TFLOPS)
     elif wl == "lstm":
         out = bench_lstm(args)
+    elif wl == "mfma_peak":
+        pk = measure_peaks()
+        out = base_json("TFLOP/s bf16 MFMA chain on register operands", pk["mfma_bf16_tflops_measured"], "TFLOP/s", args, 0.0, "bf16", pk["mfma_measure"])
+        out["roofline"] = {"bound": "mfma", "achieved": pk["mfma_bf16_tflops_measured"], "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                           "frac": pk["mfma_bf16_tflops_measured"] / PEAK_BF16_TFLOPS, "traffic": None, "kernel": "mfma_peak_kernel"}
     elif wl == "mlp":
         spec, data = W.mlp(32, 784, 128, 10, "f32")
         out = bench_graph(args, spec, data, "samples/sec MLP 784-128-10 f32 b32", "samples/s", 32, "f32",

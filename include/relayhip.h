@@ -237,6 +237,13 @@ rl_status rl_plan_profile(const rl_plan *plan, const rl_binding *bindings, int32
                           void *workspace_dev, size_t workspace_bytes, void *hip_stream,
                           int32_t reps, float *step_ms, int32_t cap, int32_t *n_steps);
 
+/* Measurement aid (not part of the hot path): enqueue a kernel that does nothing but bf16 MFMAs (32x32x16, fp32
+ * accumulate) on register operands -- `workgroups` workgroups of eight waves, every wave a chain of 16 * iters
+ * MFMAs, i.e. workgroups * 8 * 16 * iters * 32768 flops in all.  Timed by the caller (events on hip_stream), it
+ * gives the rate the matrix pipes deliver on this machine, the yardstick next to the quoted peak.  scratch_dev
+ * receives workgroups * 512 floats (ignore them).  Errors: RL_ERR_NULL, RL_ERR_BINDING (counts < 1), RL_ERR_HIP. */
+rl_status rl_calibrate_mfma_bf16(rl_ctx *ctx, void *scratch_dev, int32_t workgroups, int32_t iters, void *hip_stream);
+
 /* Recurrent execution of a one-step cell plan for `steps` steps: at step t the
  * cell's x input is x_seq_dev + t*x_step_bytes, its h input is h0_dev (t = 0)
  * or the previous step's h output, its c input/output is c_dev (updated in

@@ -98,7 +98,7 @@ _lib = None
 SYMBOLS = ["rl_ctx_create", "rl_ctx_destroy", "rl_last_error", "rl_graph_create", "rl_graph_destroy", "rl_graph_input",
            "rl_graph_param", "rl_graph_op", "rl_graph_group", "rl_graph_output", "rl_graph_autogroup", "rl_graph_group_of", "rl_plan_create", "rl_plan_destroy",
            "rl_plan_describe", "rl_plan_workspace_bytes", "rl_plan_packed_bytes", "rl_plan_prepack", "rl_plan_run",
-           "rl_plan_run_static", "rl_plan_run_recurrent", "rl_plan_recurrent_workspace_bytes", "rl_prep_fold_batchnorm", "rl_plan_profile"]
+           "rl_plan_run_static", "rl_plan_run_recurrent", "rl_plan_recurrent_workspace_bytes", "rl_prep_fold_batchnorm", "rl_plan_profile", "rl_calibrate_mfma_bf16"]
 
 
 def lib():
@@ -144,6 +144,7 @@ def lib():
         L.rl_plan_run_recurrent.argtypes = [c_void_p, c_int32, POINTER(rl_recurrent), POINTER(rl_binding), c_int32, c_void_p,
                                             c_size_t, c_void_p]
         L.rl_prep_fold_batchnorm.argtypes = [c_void_p] + [c_void_p] * 5 + [c_double, c_void_p, c_int32, c_void_p, c_int64, c_int64, c_void_p]
+        L.rl_calibrate_mfma_bf16.argtypes = [c_void_p, c_void_p, c_int32, c_int32, c_void_p]
         for s in SYMBOLS:
             if getattr(L, s).restype is not None and s != "rl_last_error":
                 getattr(L, s).restype = c_int32
@@ -178,6 +179,11 @@ class Context:
         """rl_prep_fold_batchnorm on device pointers (ints)."""
         self.check(lib().rl_prep_fold_batchnorm(self._h, w, gamma, beta, mean, var, c_double(eps), w_out, DTYPES[out_dtype], b_out,
                                                 c_int64(O), c_int64(per_o), c_void_p(stream or 0)))
+
+    def calibrate_mfma_bf16(self, scratch_ptr: int, workgroups: int, iters: int, stream=None) -> float:
+        """rl_calibrate_mfma_bf16; returns the flops the enqueued kernel performs."""
+        self.check(lib().rl_calibrate_mfma_bf16(self._h, c_void_p(scratch_ptr), workgroups, iters, c_void_p(stream or 0)))
+        return float(workgroups) * 8 * 16 * iters * 32768.0
 
     def __del__(self):
         if getattr(self, "_h", None) and _lib is not None:

@@ -494,6 +494,19 @@ rl_status rl_plan_run_recurrent(const rl_plan *cell, int32_t steps, const rl_rec
     });
 }
 
+rl_status rl_calibrate_mfma_bf16(rl_ctx *ctx, void *scratch, int32_t workgroups, int32_t iters, void *stream)
+{
+    if (!ctx) return RL_ERR_NULL;
+    auto &err = ctx->err;
+    return guarded(err, [&]() -> rl_status {
+        if (!scratch) return fail(err, RL_ERR_NULL, "null device pointer");
+        if (workgroups < 1 || iters < 1) return fail(err, RL_ERR_BINDING, "workgroups and iters must be positive");
+        hipError_t er = launch_mfma_peak((float *)scratch, workgroups, iters, (hipStream_t)stream);
+        if (er != hipSuccess) return fail(err, RL_ERR_HIP, std::string("mfma calibration kernel: ") + hipGetErrorString(er));
+        return RL_OK;
+    });
+}
+
 rl_status rl_prep_fold_batchnorm(rl_ctx *ctx, const void *w, const void *gamma, const void *beta, const void *mean, const void *var,
                                  double eps, void *w_out, int32_t out_dtype, void *b_out, int64_t O, int64_t per_o, void *stream)
 {

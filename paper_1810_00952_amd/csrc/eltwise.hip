@@ -12,7 +12,8 @@ namespace rl {
 // fused elementwise chain: y = chain(x, operands...), one 8-element vector per
 // thread (one 16-byte access per bf16 tensor, two per f32 tensor), one pass, no
 // grid-stride loop: many short-lived workgroups with streaming accesses get
-// closest to the HBM rate on this part (four vectors per thread measured slower).
+// closest to the HBM rate on this part.  This kernel interprets any chain; the
+// forms a fused group mostly takes have kernels of their own further down.
 // When a per-channel operand is constant over runs of >= 8 elements (e.g. NCHW
 // planes), a vector's channel comes from a multiply-high division by the run length.
 // ---------------------------------------------------------------------------
@@ -21,50 +22,6 @@ __global__ __launch_bounds__(256) void eltwise_kernel(const EltwiseParams p)
     const Epilogue &e = p.epi;
     const int64_t vi = (int64_t)blockIdx.x * 256 + threadIdx.x;
     const bool nt = p.nt != 0;
-    constexpr int UU = 4;
-    if (p.v2 == UU) {
-        // the common form on large 2-byte tensors: four vectors per thread, 256 vectors apart (every load instruction
-        // still covers 64 consecutive vectors), all loads requested before anything is computed
-        const int64_t va = (int64_t)blockIdx.x * (256 * UU) + threadIdx.x;
-        float v[UU][8], tt[UU][8];
-        float b[UU];
-        bool live[UU];
-#pragma unroll
-        for (int u = 0; u < UU; ++u) {
-            const int64_t vv = va + 256 * u;
-            live[u] = vv < (p.n >> 3);
-            const int64_t i0 = (live[u] ? vv : 0) << 3;
-            if (nt) { load8_nt(p.x, p.x_dtype, i0, v[u]); load8_nt(e.t_ptr, e.t_dtype, i0, tt[u]); }
-            else { load8(p.x, p.x_dtype, i0, v[u]); load8(e.t_ptr, e.t_dtype, i0, tt[u]); }
-            b[u] = 0.0f;
-            if (e.has_bias) {
-                const uint32_t run = p.vec_per_run == 1 ? (uint32_t)vv : (__umulhi((uint32_t)vv, p.run_mul) >> p.run_sh);
-                b[u] = load_as_f32(e.bias_ptr, e.bias_dtype, (int)(run % (uint32_t)p.ch_count));
-            }
-        }
-#pragma unroll
-        for (int u = 0; u < UU; ++u) {
-#pragma unroll
-            for (int k = 0; k < 8; ++k) v[u][k] = binop(e.t_op, v[u][k] + b[u], tt[u][k]);
-            uint64_t codes = e.rest_ops;
-            for (int st = 0; st < e.rest_n; ++st, codes >>= 8) {
-                const int op = (int)(codes & 0xff);
-                if (op == E_RELU) {
-#pragma unroll
-                    for (int k = 0; k < 8; ++k) v[u][k] = v[u][k] > 0.0f ? v[u][k] : 0.0f;
-                } else {
-#pragma unroll
-                    for (int k = 0; k < 8; ++k) v[u][k] = unary_step(op, v[u][k]);
-                }
-            }
-            if (live[u]) {
-                const int64_t i0 = (va + 256 * u) << 3;
-                if (nt) store8_nt(p.y, p.y_dtype, i0, v[u]);
-                else store8(p.y, p.y_dtype, i0, v[u]);
-            }
-        }
-        return;
-    }
     if (vi < (p.n >> 3)) {
         const int64_t i0 = vi << 3;
         int ch_hint = -1;
@@ -113,6 +70,80 @@ __global__ __launch_bounds__(256) void eltwise_kernel(const EltwiseParams p)
     }
 }
 
+// ---------------------------------------------------------------------------
+// The forms fused groups mostly take -- y = [relu]( x [+ bias[channel]] [+ t] ) with x, t, y of one base type and
+// an f32 bias that is constant over runs of whole vectors -- compiled per form: no program to interpret, a dozen
+// registers per lane, so that a SIMD holds enough waves to cover the HBM latency.  One 16-byte vector of each
+// tensor per thread (f32: two), streaming accesses for tensors the caches would not keep anyway.
+// ---------------------------------------------------------------------------
+template <typename T, bool BIAS, bool TADD, bool RELU, bool NT>
+__global__ __launch_bounds__(256) void eltwise_form_kernel(const T *__restrict__ x, const T *__restrict__ t, T *__restrict__ y,
+                                                           const float *__restrict__ bias, int64_t nunit, uint32_t unit_per_run,
+                                                           uint32_t run_mul, uint32_t run_sh, uint32_t ch_count)
+{
+    // a unit: the 16 bytes a lane moves per tensor (8 bf16 / 4 f32); consecutive lanes, consecutive units
+    const int64_t vi = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (vi >= nunit) return;
+    const u32x4 *xp = (const u32x4 *)x + vi;
+    const u32x4 *tp = (const u32x4 *)t + vi;
+    const u32x4 a = NT ? __builtin_nontemporal_load(xp) : *xp;
+    u32x4 b = {0u, 0u, 0u, 0u};
+    if (TADD) b = NT ? __builtin_nontemporal_load(tp) : *tp;
+    float bv = 0.0f;
+    if (BIAS) {
+        const uint32_t run = unit_per_run == 1 ? (uint32_t)vi : (__umulhi((uint32_t)vi, run_mul) >> run_sh);
+        bv = bias[run % ch_count];
+    }
+    u32x4 o;
+    if (sizeof(T) == 2) {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            float lo = __uint_as_float(a[k] << 16) + bv, hi = __uint_as_float(a[k] & 0xffff0000u) + bv;
+            if (TADD) { lo += __uint_as_float(b[k] << 16); hi += __uint_as_float(b[k] & 0xffff0000u); }
+            if (RELU) { lo = lo > 0.0f ? lo : 0.0f; hi = hi > 0.0f ? hi : 0.0f; }
+            o[k] = pack_bf16x2(lo, hi);
+        }
+    } else {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            float v = __uint_as_float(a[k]) + bv;
+            if (TADD) v += __uint_as_float(b[k]);
+            if (RELU) v = v > 0.0f ? v : 0.0f;
+            o[k] = __float_as_uint(v);
+        }
+    }
+    u32x4 *yp = (u32x4 *)y + vi;
+    if (NT) __builtin_nontemporal_store(o, yp);
+    else *yp = o;
+}
+
+struct FormLaunch { int64_t nunit; uint32_t unit_per_run, run_mul, run_sh, ch_count; unsigned blocks; bool nt; };
+
+template <typename T, bool BIAS, bool TADD, bool RELU>
+static void launch_form_nt(const FormLaunch &f, hipStream_t s, const EltwiseParams &p, const Epilogue &e)
+{
+    const T *x = (const T *)p.x, *t = (const T *)e.t_ptr;
+    T *y = (T *)p.y;
+    const float *bias = (const float *)e.bias_ptr;
+    if (f.nt) hipLaunchKernelGGL((eltwise_form_kernel<T, BIAS, TADD, RELU, true>), dim3(f.blocks), dim3(256), 0, s, x, t, y, bias, f.nunit, f.unit_per_run, f.run_mul, f.run_sh, f.ch_count);
+    else hipLaunchKernelGGL((eltwise_form_kernel<T, BIAS, TADD, RELU, false>), dim3(f.blocks), dim3(256), 0, s, x, t, y, bias, f.nunit, f.unit_per_run, f.run_mul, f.run_sh, f.ch_count);
+}
+template <typename T>
+static void launch_form(bool bias, bool tadd, bool relu, const FormLaunch &fl, hipStream_t s, const EltwiseParams &p, const Epilogue &e)
+{
+    const int f = (bias ? 4 : 0) | (tadd ? 2 : 0) | (relu ? 1 : 0);
+    switch (f) {
+    case 0: launch_form_nt<T, false, false, false>(fl, s, p, e); break;
+    case 1: launch_form_nt<T, false, false, true>(fl, s, p, e); break;
+    case 2: launch_form_nt<T, false, true, false>(fl, s, p, e); break;
+    case 3: launch_form_nt<T, false, true, true>(fl, s, p, e); break;
+    case 4: launch_form_nt<T, true, false, false>(fl, s, p, e); break;
+    case 5: launch_form_nt<T, true, false, true>(fl, s, p, e); break;
+    case 6: launch_form_nt<T, true, true, false>(fl, s, p, e); break;
+    default: launch_form_nt<T, true, true, true>(fl, s, p, e); break;
+    }
+}
+
 hipError_t launch_eltwise(const EltwiseParams &p0, hipStream_t s)
 {
     EltwiseParams p = p0;
@@ -125,21 +156,34 @@ hipError_t launch_eltwise(const EltwiseParams &p0, hipStream_t s)
         p.runs = 1;
         make_fast_div((uint32_t)p.vec_per_run, p.run_mul, p.run_sh);
     }
-    // four vectors per thread: large 2-byte tensors in the common form without a ragged tail
-    p.v2 = 0;
-    {
-        Epilogue e = p.epi;
-        finalize_epilogue(e);
-        const bool common = e.simple && e.t_op >= 0 && (p.runs > 0) == (e.has_bias != 0);
-        // measured on 256x64x112x112: bf16 4.3-5.0 TB/s with one vector per thread, 5.4-5.7 with four; f32 is fastest
-        // (5.6 TB/s) with its one 32-byte run per thread
-        if (common && p.x_dtype == DT_BF16 && p.y_dtype == DT_BF16 && e.t_dtype == DT_BF16 && (p.n & 7) == 0 && p.n >= ((int64_t)32 << 20) &&
-            nvec < ((int64_t)1 << 31))
-            p.v2 = 4;
-    }
-    const int64_t blocks = std::max<int64_t>(1, p.v2 ? (nvec + 256 * p.v2 - 1) / (256 * p.v2) : (nvec + 255) / 256);
+    const int64_t blocks = std::max<int64_t>(1, (nvec + 255) / 256);
     if (blocks > 0x7fffffff) return hipErrorInvalidValue;
     p.nt = p.n >= ((int64_t)32 << 20);           // tens of MB per tensor: beyond what the caches would keep for a consumer
+    {
+        // y = [relu](x [+ bias] [+ t]) on whole 16-byte units of one base type: the kernels compiled per form
+        Epilogue e = p.epi;
+        finalize_epilogue(e);
+        const int per = p.x_dtype == DT_BF16 ? 8 : 4;                 // elements per 16 bytes
+        FormLaunch f{};
+        f.nunit = p.n / per; f.unit_per_run = 1; f.ch_count = 1; f.nt = p.nt != 0;
+        bool bias_ok = !e.has_bias;
+        if (e.has_bias && e.bias_dtype == DT_F32 && e.bias_ptr && p.ch_count >= 1 && p.ch_inner >= per && p.ch_inner % per == 0 && p.n % p.ch_inner == 0 &&
+            p.ch_inner / per < ((int64_t)1 << 31)) {
+            bias_ok = true;
+            f.unit_per_run = (uint32_t)(p.ch_inner / per); f.ch_count = (uint32_t)p.ch_count;
+            make_fast_div(f.unit_per_run, f.run_mul, f.run_sh);
+        }
+        const bool t_ok = e.t_op < 0 || (e.t_op == E_ADD && e.t_dtype == p.x_dtype && e.t_ptr);
+        const bool rest_ok = e.rest_n == 0 || e.relu_last;
+        const int64_t fblocks = (f.nunit + 255) / 256;
+        if (e.simple && bias_ok && t_ok && rest_ok && p.x_dtype == p.y_dtype && p.n % per == 0 && f.nunit >= 1 && f.nunit < ((int64_t)1 << 31) &&
+            (((uintptr_t)p.x | (uintptr_t)p.y | (uintptr_t)e.t_ptr) & 15) == 0) {
+            f.blocks = (unsigned)fblocks;
+            if (p.x_dtype == DT_BF16) launch_form<uint16_t>(e.has_bias, e.t_op >= 0, e.relu_last, f, s, p, e);
+            else launch_form<float>(e.has_bias, e.t_op >= 0, e.relu_last, f, s, p, e);
+            return hipGetLastError();
+        }
+    }
     hipLaunchKernelGGL(eltwise_kernel, dim3((unsigned)blocks), dim3(256), 0, s, p);
     return hipGetLastError();
 }
@@ -312,6 +356,53 @@ __global__ __launch_bounds__(256) void gavgpool_nhwc_kernel(const PoolParams p)
 template <template <typename, int> class K>
 struct PoolDispatch;
 
+// The 3x3 window (the pools of the convolutional graphs here) on tensors of fewer than 2^31 vectors: one thread
+// per (pixel, channel vector), its coordinates by multiply-high divisions, the nine loads requested together from
+// clamped coordinates and the taps outside the image discarded afterwards.
+template <typename T, int VEC>
+__global__ __launch_bounds__(256) void maxpool3x3_nhwc_kernel(const PoolParams p)
+{
+    const uint32_t cv = (uint32_t)(p.C / VEC);
+    const uint32_t total = (uint32_t)p.N * p.OH * p.OW * cv;
+    // consecutive workgroup ids go to different XCDs: give each XCD a contiguous run of the output
+    uint32_t bid = blockIdx.x;
+    {
+        const uint32_t per = gridDim.x / 8, main = per * 8;
+        if (bid < main) bid = (bid % 8) * per + bid / 8;
+    }
+    const uint32_t idx = bid * 256 + threadIdx.x;
+    if (idx >= total) return;
+    const uint32_t q1 = cv == 1 ? idx : (__umulhi(idx, p.cv_mul) >> p.cv_sh);
+    const uint32_t c = (idx - q1 * cv) * VEC;
+    const uint32_t q2 = p.OW == 1 ? q1 : (__umulhi(q1, p.ow_mul) >> p.ow_sh);
+    const int ow = (int)(q1 - q2 * p.OW);
+    const uint32_t n = p.OH == 1 ? q2 : (__umulhi(q2, p.oh_mul) >> p.oh_sh);
+    const int oh = (int)(q2 - n * p.OH);
+    const T *x = (const T *)p.x + (int64_t)n * p.H * p.W * p.C + c;
+    float v[9][VEC];
+    bool ok[9];
+#pragma unroll
+    for (int a = 0; a < 3; ++a)
+#pragma unroll
+        for (int b = 0; b < 3; ++b) {
+            const int ih = oh * p.sh - p.ph + a, iw = ow * p.sw - p.pw + b;
+            ok[3 * a + b] = (unsigned)ih < (unsigned)p.H && (unsigned)iw < (unsigned)p.W;
+            const int ihc = ih < 0 ? 0 : (ih >= p.H ? p.H - 1 : ih), iwc = iw < 0 ? 0 : (iw >= p.W ? p.W - 1 : iw);
+            VecIO<T, VEC>::load(x + ((int64_t)ihc * p.W + iwc) * p.C, v[3 * a + b]);
+        }
+    float best[VEC];
+#pragma unroll
+    for (int k = 0; k < VEC; ++k) best[k] = -INFINITY;
+#pragma unroll
+    for (int tp = 0; tp < 9; ++tp)
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) {
+            const float t = ok[tp] ? v[tp][k] : -INFINITY;
+            best[k] = t > best[k] ? t : best[k];
+        }
+    VecIO<T, VEC>::store((T *)p.y + (((int64_t)n * p.OH + oh) * p.OW + ow) * p.C + c, best);
+}
+
 static inline unsigned grid_for(int64_t total)
 {
     int64_t blocks = (total + 255) / 256;
@@ -320,8 +411,20 @@ static inline unsigned grid_for(int64_t total)
     return (unsigned)blocks;
 }
 
-hipError_t launch_maxpool_nhwc(const PoolParams &p, hipStream_t s)
+hipError_t launch_maxpool_nhwc(const PoolParams &p0, hipStream_t s)
 {
+    PoolParams p = p0;
+    const int vec = p.dtype == DT_BF16 ? 8 : 4;
+    if (p.KH == 3 && p.KW == 3 && p.C % vec == 0 && (int64_t)p.N * p.OH * p.OW * (p.C / vec) < ((int64_t)1 << 31) &&
+        (int64_t)p.N * p.H * p.W * p.C < ((int64_t)1 << 40)) {
+        make_fast_div((uint32_t)(p.C / vec), p.cv_mul, p.cv_sh);
+        make_fast_div((uint32_t)p.OW, p.ow_mul, p.ow_sh);
+        make_fast_div((uint32_t)p.OH, p.oh_mul, p.oh_sh);
+        const unsigned grid = (unsigned)(((int64_t)p.N * p.OH * p.OW * (p.C / vec) + 255) / 256);
+        if (p.dtype == DT_BF16) hipLaunchKernelGGL((maxpool3x3_nhwc_kernel<uint16_t, 8>), dim3(grid), dim3(256), 0, s, p);
+        else hipLaunchKernelGGL((maxpool3x3_nhwc_kernel<float, 4>), dim3(grid), dim3(256), 0, s, p);
+        return hipGetLastError();
+    }
     if (p.dtype == DT_BF16) {
         if (p.C % 8 == 0) hipLaunchKernelGGL((maxpool_nhwc_kernel<uint16_t, 8>), dim3(grid_for((int64_t)p.N * p.OH * p.OW * (p.C / 8))), dim3(256), 0, s, p);
         else hipLaunchKernelGGL((maxpool_nhwc_kernel<uint16_t, 1>), dim3(grid_for((int64_t)p.N * p.OH * p.OW * p.C)), dim3(256), 0, s, p);

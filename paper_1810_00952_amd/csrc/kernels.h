@@ -145,7 +145,6 @@ struct EltwiseParams {
     // filled by launch_eltwise.  runs > 0: a per-channel operand is constant over runs of vec_per_run
     // 8-element vectors; the run of vector v is v / vec_per_run by multiply-high (make_fast_div)
     int64_t vec_per_run; int32_t runs; uint32_t run_mul, run_sh; int32_t nt;   // nt: streaming accesses
-    int32_t v2;                         // 4: four vectors per thread, 256 vectors apart (large 2-byte tensors, common form); else 0
 };
 hipError_t launch_eltwise(const EltwiseParams &p, hipStream_t s);
 
@@ -159,6 +158,8 @@ hipError_t launch_lstm_gates(const GatesParams &p, hipStream_t s);
 struct PoolParams {
     const void *x; void *y; int32_t dtype;
     int32_t N, C, H, W, OH, OW, KH, KW, sh, sw, ph, pw;
+    // filled by launch_maxpool_nhwc: multiply-high constants (make_fast_div) for the divisions by C / vector, OW, OH
+    uint32_t cv_mul, cv_sh, ow_mul, ow_sh, oh_mul, oh_sh;
 };
 hipError_t launch_maxpool_nhwc(const PoolParams &p, hipStream_t s);
 hipError_t launch_gavgpool_nhwc(const PoolParams &p, hipStream_t s);   // y: [N, C]
@@ -190,6 +191,8 @@ hipError_t launch_pack_weight(const void *src, void *dst, int32_t dtype, int32_t
 hipError_t launch_stem_pad(const void *src, void *dst, int32_t N, int32_t C, int32_t H, int32_t W, int32_t Hp, int32_t Wp,
                            int32_t ph, int32_t pw, hipStream_t s);
 hipError_t launch_pack_weight_stem(const void *src, void *dst, int32_t O, int32_t C, int32_t KH, int32_t KW, int32_t Kp, hipStream_t s);
+// measurement aid (calibrate.hip): a chain of register-operand bf16 MFMAs per wave; out holds grid * 512 floats
+hipError_t launch_mfma_peak(float *out, int32_t grid, int32_t iters, hipStream_t s);
 hipError_t launch_fold_bn(const float *w, const float *gamma, const float *beta, const float *mean, const float *var,
                           double eps, void *w_out, int32_t out_dtype, float *b_out, int64_t O, int64_t per_o,
                           hipStream_t s);
