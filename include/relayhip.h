@@ -184,6 +184,9 @@ typedef struct rl_plan_opts {
     int32_t no_run;         /* no nine-taps-from-one-copy kernel for 3x3 stride-1 convolutions on short rows */
     int32_t no_run_ks;      /* in that kernel's 128x64 form: do not split K over the waves */
     int32_t no_pair;        /* a stride-2 convolution and the 1x1 projection beside it go out as two launches */
+    int32_t s2_pair;        /* opt in: such a pair as ONE contraction whose centre tap carries the projection (second
+                               accumulators) with the input rows shared in LDS -- correct and tested, but its 64-pixel tiles
+                               lose to the two-contractions-in-one-grid form on every shape measured so far */
     int32_t no_splitk;      /* never split K over several workgroups per tile */
     int32_t no_hoist;       /* rl_plan_run_recurrent: never hoist the input projection out of the step loop */
 } rl_plan_opts;

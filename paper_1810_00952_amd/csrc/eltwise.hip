@@ -660,10 +660,66 @@ __global__ __launch_bounds__(256) void stem_pad_kernel(const uint16_t *__restric
     }
 }
 
+// The same for even W and Wp and 4-byte aligned tensors: one thread per pair of frame pixels (one 16-byte store, so
+// a wave writes a contiguous KB), each plane read as aligned dwords (two when the pair starts on an odd image
+// column) instead of single elements.
+template <int C>
+__global__ __launch_bounds__(256) void stem_pad_pair_kernel(const uint16_t *__restrict__ src, uint16_t *__restrict__ dst, int N, int H, int W,
+                                                            int Hp, int Wp2, int ph, int pw, uint32_t wp2_mul, uint32_t wp2_sh,
+                                                            uint32_t hp_mul, uint32_t hp_sh)
+{
+    const uint32_t total = (uint32_t)N * Hp * Wp2;
+    const uint32_t idx = blockIdx.x * 256 + threadIdx.x;
+    if (idx >= total) return;
+    const uint32_t q = Wp2 == 1 ? idx : (__umulhi(idx, wp2_mul) >> wp2_sh);
+    const int j = (int)(idx - q * Wp2);
+    const uint32_t n = Hp == 1 ? q : (__umulhi(q, hp_mul) >> hp_sh);
+    const int hp = (int)(q - n * Hp);
+    const int h = hp - ph, w = 2 * j - pw;          // image position of the pair's first pixel
+    uint32_t px0[4] = {0u, 0u, 0u, 0u}, px1[4] = {0u, 0u, 0u, 0u};
+    if ((unsigned)h < (unsigned)H && w + 1 >= 0 && w < W) {
+        const bool ok0 = w >= 0, ok1 = w + 1 < W;
+        // aligned dwords: elements (e, e+1) with e = w rounded down to even, and the next pair when w is odd
+        const int e = w & ~1;
+        const int ea = e < 0 ? 0 : e, eb = e + 2 > W - 2 ? W - 2 : e + 2;
+        const uint16_t *row = src + (((int64_t)n * C) * H + h) * W;
+#pragma unroll
+        for (int c = 0; c < C; ++c) {
+            const uint16_t *pr = row + (int64_t)c * H * W;
+            const uint32_t a = *(const uint32_t *)(pr + ea);
+            if (w & 1) {
+                const uint32_t b = *(const uint32_t *)(pr + eb);
+                px0[c] = ok0 ? (a >> 16) : 0u;                     // element e + 1 = w
+                px1[c] = ok1 ? (b & 0xffffu) : 0u;                 // element e + 2 = w + 1
+            } else {
+                px0[c] = ok0 ? (a & 0xffffu) : 0u;
+                px1[c] = ok1 ? (a >> 16) : 0u;
+            }
+        }
+    }
+    u32x4 o = {px0[0] | (px0[1] << 16), px0[2] | (px0[3] << 16), px1[0] | (px1[1] << 16), px1[2] | (px1[3] << 16)};
+    *(u32x4 *)(dst + (size_t)idx * 8) = o;
+}
+
 hipError_t launch_stem_pad(const void *src, void *dst, int32_t N, int32_t C, int32_t H, int32_t W, int32_t Hp, int32_t Wp,
                            int32_t ph, int32_t pw, hipStream_t s)
 {
     if (C < 1 || C > 4) return hipErrorInvalidValue;
+    if (W % 2 == 0 && W >= 2 && Wp % 2 == 0 && (((uintptr_t)src & 3) == 0) && (((uintptr_t)dst & 15) == 0) && (int64_t)N * Hp * (Wp / 2) < ((int64_t)1 << 31)) {
+        uint32_t m1, s1, m2, s2;
+        make_fast_div((uint32_t)(Wp / 2), m1, s1);
+        make_fast_div((uint32_t)Hp, m2, s2);
+        const unsigned grid = (unsigned)(((int64_t)N * Hp * (Wp / 2) + 255) / 256);
+        const uint16_t *sp = (const uint16_t *)src;
+        uint16_t *dp = (uint16_t *)dst;
+        switch (C) {
+        case 1: hipLaunchKernelGGL(stem_pad_pair_kernel<1>, dim3(grid), dim3(256), 0, s, sp, dp, N, H, W, Hp, Wp / 2, ph, pw, m1, s1, m2, s2); break;
+        case 2: hipLaunchKernelGGL(stem_pad_pair_kernel<2>, dim3(grid), dim3(256), 0, s, sp, dp, N, H, W, Hp, Wp / 2, ph, pw, m1, s1, m2, s2); break;
+        case 3: hipLaunchKernelGGL(stem_pad_pair_kernel<3>, dim3(grid), dim3(256), 0, s, sp, dp, N, H, W, Hp, Wp / 2, ph, pw, m1, s1, m2, s2); break;
+        default: hipLaunchKernelGGL(stem_pad_pair_kernel<4>, dim3(grid), dim3(256), 0, s, sp, dp, N, H, W, Hp, Wp / 2, ph, pw, m1, s1, m2, s2); break;
+        }
+        return hipGetLastError();
+    }
     hipLaunchKernelGGL(stem_pad_kernel, dim3(grid_for((int64_t)N * Hp * Wp)), dim3(256), 0, s, (const uint16_t *)src, (uint16_t *)dst, N, C,
                        H, W, Hp, Wp, ph, pw);
     return hipGetLastError();

@@ -105,11 +105,16 @@ struct IgemmLaunch {
     int32_t run;        // 1 (with lp): 3x3 / stride 1 / pad 1, C a multiple of 64, image rows of at most 30 pixels, tile not 64x64 (conv3x3_run.hip);
                         // 2: its 128x64 form with K split over the waves (C a multiple of 128)
     int32_t splits;     // > 1 (with dma, no lp, no gates): K split over that many workgroups per tile (IgemmParams::splits)
+    int32_t s2pair;     // 1 (first step of a pair): the pair runs as one stride-2 contraction with two accumulator sets (conv3x3s2.hip)
 };
 hipError_t launch_igemm(const IgemmParams &p, const IgemmLaunch &l, hipStream_t s);
 // two independent pixel-on-lane contractions that use the same kernel variant, in one launch (igemm_lp.hip)
 bool igemm_lp_can_pair(const IgemmParams &a, const IgemmLaunch &la, const IgemmParams &b, const IgemmLaunch &lb);
 hipError_t launch_igemm_lp_pair(const IgemmParams &a, const IgemmLaunch &la, const IgemmParams &b, const IgemmLaunch &lb, hipStream_t s);
+// a stage's 3x3 / stride 2 convolution (a) and the 1x1 / stride 2 projection of the same input (b) as one contraction with two
+// accumulator sets (conv3x3s2.hip); the planner asks conv3x3s2_pair_ok before any pointer is bound
+bool conv3x3s2_pair_ok(const IgemmParams &a, const IgemmLaunch &la, const IgemmParams &b, const IgemmLaunch &lb);
+hipError_t launch_conv3x3s2_pair(const IgemmParams &a, const IgemmLaunch &la, const IgemmParams &b, const IgemmLaunch &lb, hipStream_t s);
 hipError_t launch_conv3x3_c64(const IgemmParams &p, hipStream_t s);
 hipError_t launch_conv3x3_run(const IgemmParams &p, const IgemmLaunch &l, hipStream_t s);
 

@@ -815,7 +815,10 @@ struct Planner {
             Step &a = plan.steps[si];
             Step &b = plan.steps[si + 1];
             if (a.kind != S_IGEMM || b.kind != S_IGEMM || a.pair || b.pair || a.stem || b.stem) continue;
-            if (!igemm_lp_can_pair(a.ig, a.il, b.ig, b.il)) continue;
+            // a 3x3 / stride 2 convolution and the 1x1 / stride 2 projection of the same tensor: one contraction, the
+            // projection riding on the centre tap; any other two contractions of one kernel variant: one grid
+            const bool fused = plan.opts.s2_pair && a.slot[SL_X] >= 0 && a.slot[SL_X] == b.slot[SL_X] && conv3x3s2_pair_ok(a.ig, a.il, b.ig, b.il);
+            if (!fused && !igemm_lp_can_pair(a.ig, a.il, b.ig, b.il)) continue;
             const int ya = a.slot[SL_Y], yb = b.slot[SL_Y];
             if (ya < 0 || yb < 0 || ya == yb) continue;
             bool dep = false;
@@ -823,6 +826,11 @@ struct Planner {
             for (int s : a.slot) dep |= (s == yb);          // a reads what b writes
             if (dep) continue;
             a.pair = 1; b.pair = 2;
+            if (fused) {
+                a.il.s2pair = 1;
+                a.kernel = "igemm_conv2d_bf16_3x3s2_pair";
+                b.bytes -= (double)plan.bufs[b.slot[SL_X]].bytes;     // the shared input is read once
+            }
             a.flops += b.flops; a.bytes += b.bytes;
             b.flops = 0; b.bytes = 0;
             a.name += " | " + b.name;
@@ -969,7 +977,8 @@ rl_status run_steps(const Plan &plan, void *const *ptrs, hipStream_t stream, std
             };
             if (s.pair == 1) {
                 const Step &t = plan.steps[si];     // si already counts this step: the next one
-                er = launch_igemm_lp_pair(params(s), s.il, params(t), t.il, stream);
+                er = s.il.s2pair ? launch_conv3x3s2_pair(params(s), s.il, params(t), t.il, stream)
+                                 : launch_igemm_lp_pair(params(s), s.il, params(t), t.il, stream);
             } else {
                 er = launch_igemm(params(s), s.il, stream);
             }

@@ -265,6 +265,7 @@ def test_independent_contractions_in_one_launch(case):
     from paper_1810_00952_amd import binding
     desc = binding.Plan(binding.graph_from_spec(binding.Context(), spec)).describe()
     assert sum(st["kernel"] == "(launched with the step before)" for st in desc["steps"]) == 1, [st["kernel"] for st in desc["steps"]]
+    assert not any(st["kernel"].endswith("3x3s2_pair") for st in desc["steps"])
     print(f"paired launch case {case}: {[st['kernel'] for st in desc['steps']]}", flush=True)
     got, _ = check_graph(spec, data, f"paired launch {case}")
     desc = binding.Plan(binding.graph_from_spec(binding.Context(), spec), {"no_pair": 1}).describe()
@@ -272,6 +273,47 @@ def test_independent_contractions_in_one_launch(case):
     two, _ = run_hip(spec, data, opts={"no_pair": 1})
     for vid in spec.outputs:
         np.testing.assert_array_equal(got[vid], two[vid])
+
+
+# The same pair as ONE contraction (the projection's K tile rides on the 3x3 window's centre tap, second accumulators):
+# one, two, three and four 64-channel slices, rows of 3 to 28 output pixels (both run-buffer sizes), images smaller than
+# a tile (so that a tile spans several) and tiles that end inside an image row, ragged M and N tails, a single tile.
+# Both convolutions' own results are compared (tapped as channel-last views), then the block's.
+S2_PAIR_CASES = [
+    # batch cin cout h   w
+    (4, 64, 128, 32, 32),
+    (16, 64, 128, 56, 56),       # the benchmark's first pair at a quarter of its batch: rows of 28, the larger run buffer
+    (8, 128, 256, 28, 28),       # two slices
+    (9, 256, 512, 14, 14),       # four slices, rows of 7: nine images under a tile
+    (3, 192, 72, 12, 20),        # three slices, N tail inside the only channel tile
+    (5, 64, 136, 6, 10),         # N tail in a second channel tile, tiny images
+    (1, 64, 128, 2, 2),          # a single output pixel
+    (7, 128, 264, 10, 38),       # rows of 19, ragged last tile
+]
+
+
+@pytest.mark.parametrize("case", S2_PAIR_CASES, ids=[f"s2pair{i}" for i in range(len(S2_PAIR_CASES))])
+def test_stride2_convolution_and_projection_as_one_contraction(case):
+    b, ci, co, h, w = case
+    spec, data = W.downsample_block(b, ci, co, h, w, "bf16", taps=True)
+    from paper_1810_00952_amd import binding
+    opts = {"s2_pair": 1}                           # opt-in: the planner's own choice is two contractions in one grid
+    desc = binding.Plan(binding.graph_from_spec(binding.Context(), spec), opts).describe()
+    assert sum(st["kernel"] == "igemm_conv2d_bf16_3x3s2_pair" for st in desc["steps"]) == 1, [st["kernel"] for st in desc["steps"]]
+    print(f"stride-2 pair case {case}: {[st['kernel'] for st in desc['steps']]}", flush=True)
+    ref = OG.run(spec, data)
+    got, _ = run_hip(spec, data, opts=opts)
+    y, c1, d = spec.outputs
+    for vid, what in ((c1, "3x3/2"), (d, "1x1/2 projection"), (y, "block")):
+        assert_close(got[vid], ref[vid], "bf16", f"stride-2 pair {case} {what}")
+    # against the two contractions launched as one grid: same products, another summation order
+    lp, s = run_hip(spec, data)
+    assert not any(st["kernel"].endswith("3x3s2_pair") for st in s.plan.describe()["steps"])
+    for vid, what in ((c1, "3x3/2"), (d, "1x1/2 projection")):
+        assert_close(got[vid], lp[vid], "bf16", f"stride-2 pair {case} {what} against the general kernel")
+    again, _ = run_hip(spec, data, opts=opts)
+    for vid in spec.outputs:
+        np.testing.assert_array_equal(got[vid], again[vid])
 
 
 def test_conv_large_tiles_many_blocks():

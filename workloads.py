@@ -214,9 +214,10 @@ def conv_group(batch=1, cin=64, cout=64, h=56, w=56, k=3, stride=1, pad=1, dtype
     return g, data
 
 
-def downsample_block(batch=4, cin=64, cout=128, h=32, w=32, dtype="bf16", config=10):
+def downsample_block(batch=4, cin=64, cout=128, h=32, w=32, dtype="bf16", config=10, taps=False):
     """The first block of a ResNet stage on its own: y = relu(conv3x3(relu(conv3x3/2(x) + b1)) + b3 + (conv1x1/2(x) + b2)).
-    The stride-2 convolution and the 1x1 projection both read x and neither needs the other."""
+    The stride-2 convolution and the 1x1 projection both read x and neither needs the other.
+    taps=True: their two results are graph outputs as well (behind y), as channel-last views."""
     rng = rng_for(config)
     g = GraphSpec("downsample_block")
     data = {}
@@ -244,6 +245,11 @@ def downsample_block(batch=4, cin=64, cout=128, h=32, w=32, dtype="bf16", config
     d = conv("ds", x, cin, 1, 2, 0, relu=False)
     y = conv("c2", c1, cout, 3, 1, 1, extra=d)
     g.output(y)
+    if taps:
+        for v in (c1, d):
+            o, (t,) = g.op("layout_transform", [v], [(dtype, (batch, oh, ow, cout))], perm=(0, 2, 3, 1))
+            g.group([o])
+            g.output(t)
     return g, data
 
 
