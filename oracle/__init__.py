@@ -82,6 +82,50 @@ def conv2d(x, w, stride=(1, 1), pad=(0, 0)):
     return y
 
 
+def dense_grad_x(dy, w):
+    dy, w = _d(dy), _d(w)
+    (M, N), (N2, K) = dy.shape, w.shape
+    assert N == N2
+    dx = np.empty((M, K))
+    lib().oracle_dense_grad_x(_p(dy), _p(w), _p(dx), _i(M), _i(N), _i(K))
+    return dx
+
+
+def dense_grad_w(dy, x):
+    dy, x = _d(dy), _d(x)
+    (M, N), (M2, K) = dy.shape, x.shape
+    assert M == M2
+    dw = np.empty((N, K))
+    lib().oracle_dense_grad_w(_p(dy), _p(x), _p(dw), _i(M), _i(N), _i(K))
+    return dw
+
+
+def conv2d_grad_x(dy, w, x_shape, stride=(1, 1), pad=(0, 0)):
+    dy, w = _d(dy), _d(w)
+    N, C, H, W = x_shape
+    O, C2, KH, KW = w.shape
+    N2, O2, OH, OW = dy.shape
+    assert (N, C, O) == (N2, C2, O2)
+    assert OH == (H + 2 * pad[0] - KH) // stride[0] + 1 and OW == (W + 2 * pad[1] - KW) // stride[1] + 1
+    dx = np.empty((N, C, H, W))
+    lib().oracle_conv2d_grad_x(_p(dy), _p(w), _p(dx), _i(N), _i(C), _i(H), _i(W), _i(O), _i(KH), _i(KW),
+                               _i(stride[0]), _i(stride[1]), _i(pad[0]), _i(pad[1]), _i(OH), _i(OW))
+    return dx
+
+
+def conv2d_grad_w(dy, x, kernel, stride=(1, 1), pad=(0, 0)):
+    dy, x = _d(dy), _d(x)
+    N, C, H, W = x.shape
+    N2, O, OH, OW = dy.shape
+    KH, KW = kernel
+    assert N == N2
+    assert OH == (H + 2 * pad[0] - KH) // stride[0] + 1 and OW == (W + 2 * pad[1] - KW) // stride[1] + 1
+    dw = np.empty((O, C, KH, KW))
+    lib().oracle_conv2d_grad_w(_p(dy), _p(x), _p(dw), _i(N), _i(C), _i(H), _i(W), _i(O), _i(KH), _i(KW),
+                               _i(stride[0]), _i(stride[1]), _i(pad[0]), _i(pad[1]), _i(OH), _i(OW))
+    return dw
+
+
 def bias_add(x, b, axis=1):
     x, b = _d(x), _d(b)
     C = x.shape[axis]

@@ -120,6 +120,60 @@ def infer(kind: str, ins: List[Tuple[str, Tuple[int, ...]]], attrs: Dict) -> Lis
         if sx[2] + 2 * p0 < sw[2] or sx[3] + 2 * p1 < sw[3]:
             raise IllTyped("shape", "kernel larger than padded input")
         return [(_out_dtype(attrs, dx), (sx[0], sw[0], oh, ow))]
+    # partial derivatives of the contractions: the arrow types of the operators a reverse-mode gradient calls
+    if kind == "dense_grad_x":              # (dy[M,N], W[N,K]) -> [M,K]
+        need(2)
+        (dy, sy), (dw, sw) = ins
+        if len(sy) != 2 or len(sw) != 2:
+            raise IllTyped("type", "dense_grad_x wants rank-2 operands")
+        if dy != dw:
+            raise IllTyped("type", "dense_grad_x operands differ in base type")
+        if sy[1] != sw[0]:
+            raise IllTyped("type", f"dense_grad_x: dy has {sy[1]} columns, W {sw[0]} rows")
+        return [(_out_dtype(attrs, dy), (sy[0], sw[1]))]
+    if kind == "dense_grad_w":              # (dy[M,N], x[M,K]) -> [N,K]
+        need(2)
+        (dy, sy), (dx, sx) = ins
+        if len(sy) != 2 or len(sx) != 2:
+            raise IllTyped("type", "dense_grad_w wants rank-2 operands")
+        if dy != dx:
+            raise IllTyped("type", "dense_grad_w operands differ in base type")
+        if sy[0] != sx[0]:
+            raise IllTyped("type", f"dense_grad_w: batch {sy[0]} vs {sx[0]}")
+        return [(_out_dtype(attrs, dy), (sy[1], sx[1]))]
+    if kind in ("conv2d_grad_x", "conv2d_grad_w"):
+        # (dy[N,O,OH,OW], w[O,C,KH,KW]) -> [N,C,H,W]   /   (dy[N,O,OH,OW], x[N,C,H,W]) -> [O,C,KH,KW]
+        # The forward output size floor((H + 2p - KH)/s) + 1 does not determine H (or KH) from the operands: the
+        # declaration states the result's Shape and the forward relation is checked against it.
+        need(2)
+        (dy, sy), (d2, s2) = ins
+        if len(sy) != 4 or len(s2) != 4:
+            raise IllTyped("type", f"{kind} wants rank-4 operands")
+        if dy != d2:
+            raise IllTyped("type", f"{kind} operands differ in base type")
+        (s0, s1), (p0, p1) = _pair(attrs.get("stride", (1, 1)), "stride"), _pair(attrs.get("pad", (0, 0)), "pad")
+        if s0 < 1 or s1 < 1 or p0 < 0 or p1 < 0:
+            raise IllTyped("kind", "bad stride/pad")
+        decl = attrs.get("declared_shape")
+        if decl is None or len(decl) != 4:
+            raise IllTyped("type", f"{kind}: the declared result must be rank 4")
+        if kind == "conv2d_grad_x":
+            n, c, h, w = decl
+            o, c2, kh, kw = s2
+            x_shape = (sy[0], s2[1], h, w)
+            ok = (n, c) == (sy[0], s2[1]) and sy[1] == o
+        else:
+            o, c, kh, kw = decl
+            n, c2, h, w = s2
+            x_shape = s2
+            ok = (o, c) == (sy[1], s2[1]) and sy[0] == n
+        if not ok:
+            raise IllTyped("type", f"{kind}: batch / channel counts of operands and declared result disagree")
+        if h + 2 * p0 < kh or w + 2 * p1 < kw:
+            raise IllTyped("shape", "kernel larger than padded input")
+        if ((h + 2 * p0 - kh) // s0 + 1, (w + 2 * p1 - kw) // s1 + 1) != tuple(sy[2:]):
+            raise IllTyped("type", f"{kind}: the forward convolution of {x_shape} with a {kh}x{kw} kernel does not give dy's {sy[2:]}")
+        return [(_out_dtype(attrs, dy), tuple(decl))]
     if kind == "maxpool2d":
         need(1)
         (dx, sx), = ins
@@ -195,6 +249,8 @@ def check(spec) -> None:
         declared = [(spec.values[v].type.dtype, spec.values[v].type.shape) for v in op.outputs]
         if op.kind == "lstm_gates" and len(declared) == 2:
             attrs["h_dtype"] = declared[1][0]
+        if op.kind in ("conv2d_grad_x", "conv2d_grad_w") and len(declared) == 1:
+            attrs["declared_shape"] = tuple(declared[0][1])
         got = infer(op.kind, ins, attrs)
         if got != declared:
             raise IllTyped("type", f"op {oi} ({op.kind}): declared {declared}, inferred {got}")
@@ -300,6 +356,16 @@ def run(spec, data: Dict[str, np.ndarray], keep_all: bool = False, keep=()) -> D
             out = [O.dense(a[0], a[1])]
         elif k == "conv2d":
             out = [O.conv2d(a[0], a[1], tuple(op.attrs.get("stride", (1, 1))), tuple(op.attrs.get("pad", (0, 0))))]
+        elif k == "dense_grad_x":
+            out = [O.dense_grad_x(a[0], a[1])]
+        elif k == "dense_grad_w":
+            out = [O.dense_grad_w(a[0], a[1])]
+        elif k == "conv2d_grad_x":
+            out = [O.conv2d_grad_x(a[0], a[1], spec.values[op.outputs[0]].type.shape, tuple(op.attrs.get("stride", (1, 1))),
+                                   tuple(op.attrs.get("pad", (0, 0))))]
+        elif k == "conv2d_grad_w":
+            out = [O.conv2d_grad_w(a[0], a[1], spec.values[op.outputs[0]].type.shape[2:], tuple(op.attrs.get("stride", (1, 1))),
+                                   tuple(op.attrs.get("pad", (0, 0))))]
         elif k == "bias_add":
             out = [O.bias_add(a[0], a[1], int(op.attrs.get("axis", 1)))]
         elif k in ("add", "sub", "mul", "div"):

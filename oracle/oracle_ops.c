@@ -61,6 +61,90 @@ void oracle_conv2d(const double *x, const double *w, double *y,
                 }
 }
 
+/* Partial derivatives of the two contractions, each written out as the sum it is by definition of the forward
+ * operator (y = dense / conv2d above, L any scalar function of y, dy = dL/dy):
+ *   dL/dx[m,k] = sum_n dy[m,n] * W[n,k]            dL/dW[n,k] = sum_m dy[m,n] * x[m,k]
+ * These are the operators a reverse-mode gradient of a program (the paper's section "Automatic Differentiation",
+ * node Grad) calls for every dense / conv2d it differentiates through; the paper gives no formula for them. */
+void oracle_dense_grad_x(const double *dy, const double *w, double *dx, int64_t M, int64_t N, int64_t K)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t k = 0; k < K; ++k) {
+            double s = 0.0;
+            for (int64_t n = 0; n < N; ++n)
+                s += dy[m * N + n] * w[n * K + k];
+            dx[m * K + k] = s;
+        }
+}
+
+void oracle_dense_grad_w(const double *dy, const double *x, double *dw, int64_t M, int64_t N, int64_t K)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t n = 0; n < N; ++n)
+        for (int64_t k = 0; k < K; ++k) {
+            double s = 0.0;
+            for (int64_t m = 0; m < M; ++m)
+                s += dy[m * N + n] * x[m * K + k];
+            dw[n * K + k] = s;
+        }
+}
+
+/* dL/dx[n,c,h,w] = sum over every (o, a, b, i, j) whose forward term read x[n,c,h,w], i.e. with
+ * h = i*sh - ph + a and w = j*sw - pw + b, of dy[n,o,i,j] * wt[o,c,a,b].  Written as the scatter it is. */
+void oracle_conv2d_grad_x(const double *dy, const double *wt, double *dx,
+                          int64_t N, int64_t C, int64_t H, int64_t W,
+                          int64_t O, int64_t KH, int64_t KW,
+                          int64_t sh, int64_t sw, int64_t ph, int64_t pw,
+                          int64_t OH, int64_t OW)
+{
+    memset(dx, 0, (size_t)(N * C * H * W) * sizeof(double));
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int64_t n = 0; n < N; ++n)
+        for (int64_t c = 0; c < C; ++c)
+            for (int64_t o = 0; o < O; ++o)
+                for (int64_t i = 0; i < OH; ++i)
+                    for (int64_t j = 0; j < OW; ++j) {
+                        double g = dy[((n * O + o) * OH + i) * OW + j];
+                        for (int64_t a = 0; a < KH; ++a) {
+                            int64_t ih = i * sh - ph + a;
+                            if (ih < 0 || ih >= H) continue;
+                            for (int64_t b = 0; b < KW; ++b) {
+                                int64_t iw = j * sw - pw + b;
+                                if (iw < 0 || iw >= W) continue;
+                                dx[((n * C + c) * H + ih) * W + iw] += g * wt[((o * C + c) * KH + a) * KW + b];
+                            }
+                        }
+                    }
+}
+
+/* dL/dwt[o,c,a,b] = sum_{n,i,j} dy[n,o,i,j] * xpad[n,c,i*sh-ph+a, j*sw-pw+b] */
+void oracle_conv2d_grad_w(const double *dy, const double *x, double *dw,
+                          int64_t N, int64_t C, int64_t H, int64_t W,
+                          int64_t O, int64_t KH, int64_t KW,
+                          int64_t sh, int64_t sw, int64_t ph, int64_t pw,
+                          int64_t OH, int64_t OW)
+{
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int64_t o = 0; o < O; ++o)
+        for (int64_t c = 0; c < C; ++c)
+            for (int64_t a = 0; a < KH; ++a)
+                for (int64_t b = 0; b < KW; ++b) {
+                    double s = 0.0;
+                    for (int64_t n = 0; n < N; ++n)
+                        for (int64_t i = 0; i < OH; ++i) {
+                            int64_t ih = i * sh - ph + a;
+                            if (ih < 0 || ih >= H) continue;
+                            for (int64_t j = 0; j < OW; ++j) {
+                                int64_t iw = j * sw - pw + b;
+                                if (iw < 0 || iw >= W) continue;
+                                s += dy[((n * O + o) * OH + i) * OW + j] * x[((n * C + c) * H + ih) * W + iw];
+                            }
+                        }
+                    dw[((o * C + c) * KH + a) * KW + b] = s;
+                }
+}
+
 /* y[outer, c, inner] = x[outer, c, inner] + b[c] */
 void oracle_bias_add(const double *x, const double *b, double *y, int64_t outer, int64_t C, int64_t inner)
 {

@@ -264,6 +264,144 @@ def test_batchnorm_closed_forms():
     np.testing.assert_array_equal(bf, [-7.0, -0.5])
 
 
+# ---------------------------------------------------------------- partial derivatives of the contractions
+GRAD_GEOMS = [
+    # n  c  h  w  o  k  s  p
+    (2, 3, 5, 4, 2, 3, 1, 1),
+    (1, 2, 7, 6, 3, 3, 2, 1),          # (H + 2p - K) % s = 0 for H, 1 for W: the last input column gets no gradient from some taps
+    (2, 2, 6, 6, 2, 1, 2, 0),          # the 1x1 / stride 2 projection: odd rows and columns get none at all
+    (1, 1, 8, 5, 2, 5, 1, 2),
+    (1, 2, 6, 7, 2, 2, 3, 0),          # stride larger than the kernel: gaps
+]
+
+
+def _brute_conv_grads(dy, x, w, s, p):
+    """Gather formulation, pure Python: each result element collects the forward terms that contain it."""
+    N, C, H, W = x.shape
+    O, _, KH, KW = w.shape
+    _, _, OH, OW = dy.shape
+    dx = np.zeros(x.shape); dw = np.zeros(w.shape)
+    for n in range(N):
+        for c in range(C):
+            for h in range(H):
+                for ww in range(W):
+                    acc = 0.0
+                    for o in range(O):
+                        for a in range(KH):
+                            for b in range(KW):
+                                ti, tj = h + p - a, ww + p - b
+                                if ti % s or tj % s:
+                                    continue
+                                i, j = ti // s, tj // s
+                                if 0 <= i < OH and 0 <= j < OW:
+                                    acc += dy[n, o, i, j] * w[o, c, a, b]
+                    dx[n, c, h, ww] = acc
+    for o in range(O):
+        for c in range(C):
+            for a in range(KH):
+                for b in range(KW):
+                    acc = 0.0
+                    for n in range(N):
+                        for i in range(OH):
+                            for j in range(OW):
+                                ih, iw = i * s - p + a, j * s - p + b
+                                if 0 <= ih < H and 0 <= iw < W:
+                                    acc += dy[n, o, i, j] * x[n, c, ih, iw]
+                    dw[o, c, a, b] = acc
+    return dx, dw
+
+
+@pytest.mark.parametrize("geom", GRAD_GEOMS, ids=[f"g{i}" for i in range(len(GRAD_GEOMS))])
+def test_conv_gradients_brute_force_and_adjoint(geom):
+    n, c, h, w_, o, k, s, p = geom
+    x = RNG.integers(-3, 4, (n, c, h, w_)).astype(np.float64)
+    w = RNG.integers(-3, 4, (o, c, k, k)).astype(np.float64)
+    y = O.conv2d(x, w, (s, s), (p, p))
+    dy = RNG.integers(-3, 4, y.shape).astype(np.float64)
+    dx = O.conv2d_grad_x(dy, w, x.shape, (s, s), (p, p))
+    dw = O.conv2d_grad_w(dy, x, (k, k), (s, s), (p, p))
+    bx, bw = _brute_conv_grads(dy, x, w, s, p)
+    np.testing.assert_array_equal(dx, bx)          # integer-valued: exact
+    np.testing.assert_array_equal(dw, bw)
+    # the convolution is linear in x and in w, and the gradients are its adjoints: <conv(x; w), dy> = <x, dx> = <w, dw>
+    lhs = float((y * dy).sum())
+    assert lhs == float((x * dx).sum()) == float((w * dw).sum())
+
+
+def test_conv_gradients_by_finite_differences():
+    # L = <conv(x; w), g> is linear in x and in w, so a central difference gives its partial derivatives up to rounding
+    n, c, h, w_, o, k, s, p = 1, 2, 5, 6, 2, 3, 2, 1
+    x, w = RNG.standard_normal((n, c, h, w_)), RNG.standard_normal((o, c, k, k))
+    L = lambda xx, ww: float((O.conv2d(xx, ww, (s, s), (p, p)) * g).sum())
+    g = RNG.standard_normal(O.conv2d(x, w, (s, s), (p, p)).shape)
+    dx = O.conv2d_grad_x(g, w, x.shape, (s, s), (p, p))
+    dw = O.conv2d_grad_w(g, x, (k, k), (s, s), (p, p))
+    eps = 0.5
+    for idx in [(0, 0, 0, 0), (0, 1, 4, 5), (0, 0, 2, 3), (0, 1, 3, 0)]:
+        e = np.zeros_like(x); e[idx] = eps
+        assert abs((L(x + e, w) - L(x - e, w)) / (2 * eps) - dx[idx]) < 1e-12
+    for idx in [(0, 0, 0, 0), (1, 1, 2, 2), (0, 1, 1, 2), (1, 0, 2, 0)]:
+        e = np.zeros_like(w); e[idx] = eps
+        assert abs((L(x, w + e) - L(x, w - e)) / (2 * eps) - dw[idx]) < 1e-12
+
+
+def test_conv_gradient_closed_forms():
+    # all-ones dy and weights, 3x3 / stride 1 / pad 1: dx counts the outputs whose window holds the pixel, times O:
+    # 9 O inside, 6 O on an edge, 4 O in a corner; all-ones dy and x: dw counts the window positions inside the image
+    dy, w = np.ones((1, 5, 6, 7)), np.ones((5, 2, 3, 3))
+    dx = O.conv2d_grad_x(dy, w, (1, 2, 6, 7), (1, 1), (1, 1))
+    assert dx[0, 0, 3, 3] == 45 and dx[0, 1, 0, 3] == 30 and dx[0, 0, 5, 6] == 20 and dx[0, 1, 2, 0] == 30
+    dw = O.conv2d_grad_w(dy, np.ones((1, 2, 6, 7)), (3, 3), (1, 1), (1, 1))
+    assert dw[0, 0, 1, 1] == 42 and dw[4, 1, 0, 1] == 35 and dw[2, 0, 0, 0] == 30 and dw[0, 1, 1, 2] == 36
+    # a one-hot dy puts the (unflipped) kernel into dx at the window's place, and the window of x into dw
+    w = RNG.standard_normal((1, 1, 3, 3)); x = RNG.standard_normal((1, 1, 6, 6))
+    dy = np.zeros((1, 1, 2, 2)); dy[0, 0, 1, 0] = 1.0            # stride 2, pad 0: window rows 2..4, columns 0..2
+    dx = O.conv2d_grad_x(dy, w, x.shape, (2, 2), (0, 0))
+    np.testing.assert_array_equal(dx[0, 0, 2:5, 0:3], w[0, 0])
+    assert abs(dx.sum() - w.sum()) < 1e-12 and np.count_nonzero(dx) == 9
+    np.testing.assert_array_equal(O.conv2d_grad_w(dy, x, (3, 3), (2, 2), (0, 0))[0, 0], x[0, 0, 2:5, 0:3])
+
+
+def test_dense_gradients():
+    dy, w, x = RNG.integers(-3, 4, (4, 3)).astype(float), RNG.integers(-3, 4, (3, 5)).astype(float), RNG.integers(-3, 4, (4, 5)).astype(float)
+    dx, dw = O.dense_grad_x(dy, w), O.dense_grad_w(dy, x)
+    for m in range(4):
+        for k in range(5):
+            assert dx[m, k] == sum(dy[m, n] * w[n, k] for n in range(3))
+    for n in range(3):
+        for k in range(5):
+            assert dw[n, k] == sum(dy[m, n] * x[m, k] for m in range(4))
+    # adjoints of y = dense(x, W): <y, dy> = <x, dx> = <W, dW>; a one-hot dy picks a row of W / a row of x
+    y = O.dense(x, w)
+    assert float((y * dy).sum()) == float((x * dx).sum()) == float((w * dw).sum())
+    e = np.zeros((4, 3)); e[2, 1] = 1.0
+    np.testing.assert_array_equal(O.dense_grad_x(e, w)[2], w[1])
+    np.testing.assert_array_equal(O.dense_grad_w(e, x)[1], x[2])
+    # the 1x1 convolution's gradients are the dense ones on the [N*H*W, C] view
+    xc, wc = RNG.standard_normal((2, 5, 4, 3)), RNG.standard_normal((6, 5, 1, 1))
+    g = RNG.standard_normal((2, 6, 4, 3))
+    gm, xm = g.transpose(0, 2, 3, 1).reshape(-1, 6), xc.transpose(0, 2, 3, 1).reshape(-1, 5)
+    np.testing.assert_allclose(O.conv2d_grad_x(g, wc, xc.shape), O.dense_grad_x(gm, wc.reshape(6, 5)).reshape(2, 4, 3, 5).transpose(0, 3, 1, 2), atol=1e-13)
+    np.testing.assert_allclose(O.conv2d_grad_w(g, xc, (1, 1)).reshape(6, 5), O.dense_grad_w(gm, xm), atol=1e-13)
+
+
+def test_gradients_against_library_autograd_float64():
+    for (n, c, h, w_, o, k, s, p) in [(2, 3, 9, 8, 4, 3, 1, 1), (1, 4, 11, 10, 3, 3, 2, 1), (2, 2, 8, 8, 3, 1, 2, 0), (1, 3, 12, 12, 2, 7, 2, 3)]:
+        x = torch.from_numpy(RNG.standard_normal((n, c, h, w_))).requires_grad_(True)
+        w = torch.from_numpy(RNG.standard_normal((o, c, k, k))).requires_grad_(True)
+        y = torch.nn.functional.conv2d(x, w, stride=s, padding=p)
+        g = torch.from_numpy(RNG.standard_normal(tuple(y.shape)))
+        gx, gw = torch.autograd.grad(y, (x, w), g)
+        np.testing.assert_allclose(O.conv2d_grad_x(g.numpy(), w.detach().numpy(), x.shape, (s, s), (p, p)), gx.numpy(), atol=1e-12)
+        np.testing.assert_allclose(O.conv2d_grad_w(g.numpy(), x.detach().numpy(), (k, k), (s, s), (p, p)), gw.numpy(), atol=1e-12)
+    a = torch.from_numpy(RNG.standard_normal((7, 33))).requires_grad_(True)
+    b = torch.from_numpy(RNG.standard_normal((9, 33))).requires_grad_(True)
+    g = torch.from_numpy(RNG.standard_normal((7, 9)))
+    ga, gb = torch.autograd.grad(a @ b.T, (a, b), g)
+    np.testing.assert_allclose(O.dense_grad_x(g.numpy(), b.detach().numpy()), ga.numpy(), atol=1e-12)
+    np.testing.assert_allclose(O.dense_grad_w(g.numpy(), a.detach().numpy()), gb.numpy(), atol=1e-12)
+
+
 # ---------------------------------------------------------------- library cross-check
 def test_against_library_float64():
     x, w = RNG.standard_normal((2, 8, 13, 11)), RNG.standard_normal((5, 8, 3, 3))
