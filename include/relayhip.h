@@ -101,7 +101,16 @@ enum {
                                     Always a group of its own.  On rank-4 tensors the two channel-first <-> channel-last
                                     permutations (0,2,3,1) and (0,3,1,2) cost nothing when the other side of the value is
                                     a convolution, pool or elementwise group: those run channel-last internally. */
-    RL_OP_KIND_COUNT = 19
+    /* Partial derivatives of the two contractions: the operators a reverse-mode gradient of a program (the paper's section
+     * "Automatic Differentiation", node Grad) calls for every dense / conv2d it differentiates through.  Each is a group of
+     * its own.  dy is the derivative with respect to the forward operator's result. */
+    RL_OP_DENSE_GRAD_X = 19,  /* (dy[M,N], W[N,K]) -> [M,K]: sum_n dy[m,n] W[n,k]; attrs rl_attr_contract (may be NULL) */
+    RL_OP_DENSE_GRAD_W = 20,  /* (dy[M,N], x[M,K]) -> [N,K]: sum_m dy[m,n] x[m,k]; attrs rl_attr_contract (may be NULL) */
+    RL_OP_CONV2D_GRAD_X = 21, /* (dy[N,O,OH,OW], w[O,C,KH,KW]) -> [N,C,H,W]; attrs rl_attr_conv2d of the forward convolution.  The
+                                 forward output size does not determine H and W: the declared result states them, and
+                                 OH = floor((H + 2 pad - KH)/stride) + 1 is checked (else RL_ERR_TYPE) */
+    RL_OP_CONV2D_GRAD_W = 22, /* (dy[N,O,OH,OW], x[N,C,H,W]) -> [O,C,KH,KW]; attrs as above; the declared result states KH and KW */
+    RL_OP_KIND_COUNT = 23
 };
 
 typedef struct rl_attr_contract { int32_t out_dtype; /* operand dtype, or RL_F32 */ } rl_attr_contract;

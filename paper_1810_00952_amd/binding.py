@@ -20,7 +20,7 @@ DTYPE_BYTES = {"f32": 4, "bf16": 2}
 
 OPS = {"dense": 0, "conv2d": 1, "bias_add": 2, "add": 3, "sub": 4, "mul": 5, "div": 6, "neg": 7, "sq": 8, "relu": 9,
        "sigmoid": 10, "tanh": 11, "maxpool2d": 12, "global_avgpool": 13, "flatten": 14, "lstm_gates": 15, "cast": 16,
-       "concat": 17, "layout_transform": 18}
+       "concat": 17, "layout_transform": 18, "dense_grad_x": 19, "dense_grad_w": 20, "conv2d_grad_x": 21, "conv2d_grad_w": 22}
 
 STATUS = {0: "ok", -1: "null", -2: "kind", -3: "shape", -4: "type", -5: "group", -6: "binding", -7: "workspace",
           -8: "align", -9: "unsupported", -10: "hip"}
@@ -193,9 +193,9 @@ class Context:
 
 def _attrs_for(kind: str, attrs: Dict):
     od = attrs.get("out_dtype")
-    if kind == "dense":
+    if kind in ("dense", "dense_grad_x", "dense_grad_w"):
         return rl_attr_contract(DTYPES[od]) if od is not None else None
-    if kind == "conv2d":
+    if kind in ("conv2d", "conv2d_grad_x", "conv2d_grad_w"):
         s, p = attrs.get("stride", (1, 1)), attrs.get("pad", (0, 0))
         d = attrs.get("dilation", (1, 1))
         return rl_attr_conv2d(s[0], s[1], p[0], p[1], d[0], d[1], attrs.get("groups", 1), DTYPES[od] if od is not None else -1)

@@ -635,6 +635,33 @@ hipError_t launch_pack_weight(const void *src, void *dst, int32_t dtype, int32_t
     return hipGetLastError();
 }
 
+template <typename T>
+__global__ __launch_bounds__(256) void pack_gather_kernel(const T *__restrict__ src, T *__restrict__ dst, const GatherPack g)
+{
+    const int64_t total = (int64_t)g.R * g.Kp;
+    const int Kreal = g.T * g.Cq;
+    for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += (int64_t)gridDim.x * blockDim.x) {
+        const int k = (int)(idx % g.Kp);
+        const int64_t r = idx / g.Kp;
+        T v = 0;
+        if (k < Kreal) {
+            const int tap = k / g.Cq, c = k - tap * g.Cq;
+            const int ti = tap / g.TW, tj = tap - ti * g.TW;
+            v = src[g.base + r * g.s_row + (int64_t)c * g.s_c + (int64_t)ti * g.s_ti + (int64_t)tj * g.s_tj];
+        }
+        dst[idx] = v;
+    }
+}
+
+hipError_t launch_pack_gather(const void *src, void *dst, const GatherPack &g, hipStream_t s)
+{
+    if (g.R < 1 || g.Kp < 1 || g.T < 1 || g.Cq < 1 || g.TW < 1 || g.T % g.TW != 0 || (int64_t)g.T * g.Cq > g.Kp) return hipErrorInvalidValue;
+    const unsigned grid = grid_for((int64_t)g.R * g.Kp);
+    if (g.dtype == DT_BF16) hipLaunchKernelGGL(pack_gather_kernel<uint16_t>, dim3(grid), dim3(256), 0, s, (const uint16_t *)src, (uint16_t *)dst, g);
+    else hipLaunchKernelGGL(pack_gather_kernel<float>, dim3(grid), dim3(256), 0, s, (const float *)src, (float *)dst, g);
+    return hipGetLastError();
+}
+
 // ---------------------------------------------------------------------------
 // stem convolutions: zero-padded 4-channel channel-last frame and matching weights (bf16)
 // ---------------------------------------------------------------------------

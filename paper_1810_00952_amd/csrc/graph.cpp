@@ -10,7 +10,8 @@ namespace rl {
 
 static const char *kOpNames[RL_OP_KIND_COUNT] = {
     "dense", "conv2d", "bias_add", "add", "sub", "mul", "div", "neg", "sq", "relu", "sigmoid", "tanh",
-    "maxpool2d", "global_avgpool", "flatten", "lstm_gates", "cast", "concat", "layout_transform"};
+    "maxpool2d", "global_avgpool", "flatten", "lstm_gates", "cast", "concat", "layout_transform",
+    "dense_grad_x", "dense_grad_w", "conv2d_grad_x", "conv2d_grad_w"};
 
 const char *op_name(int kind) { return (kind >= 0 && kind < RL_OP_KIND_COUNT) ? kOpNames[kind] : "?"; }
 bool is_anchor(int kind) { return kind == RL_OP_DENSE || kind == RL_OP_CONV2D; }
@@ -68,12 +69,12 @@ rl_status parse_attrs(int kind, const void *attrs, size_t size, Attrs &a, std::s
         return true;
     };
     switch (kind) {
-    case RL_OP_DENSE:
+    case RL_OP_DENSE: case RL_OP_DENSE_GRAD_X: case RL_OP_DENSE_GRAD_W:
         if (!want(sizeof(rl_attr_contract))) return RL_ERR_KIND;
         if (attrs) a.out_dtype = ((const rl_attr_contract *)attrs)->out_dtype;
         break;
-    case RL_OP_CONV2D: {
-        if (!attrs) { msg = "conv2d needs rl_attr_conv2d"; return RL_ERR_KIND; }
+    case RL_OP_CONV2D: case RL_OP_CONV2D_GRAD_X: case RL_OP_CONV2D_GRAD_W: {
+        if (!attrs) { msg = std::string(op_name(kind)) + " needs rl_attr_conv2d"; return RL_ERR_KIND; }
         if (!want(sizeof(rl_attr_conv2d))) return RL_ERR_KIND;
         const rl_attr_conv2d *c = (const rl_attr_conv2d *)attrs;
         a.stride[0] = c->stride_h; a.stride[1] = c->stride_w; a.pad[0] = c->pad_h; a.pad[1] = c->pad_w;
@@ -186,6 +187,51 @@ rl_status infer_type(int kind, const std::vector<rl_type> &in, const Attrs &a, c
         int64_t oh = (x.dims[2] + 2 * a.pad[0] - w.dims[2]) / a.stride[0] + 1;
         int64_t ow = (x.dims[3] + 2 * a.pad[1] - w.dims[3]) / a.stride[1] + 1;
         out.push_back(make_type(od, {x.dims[0], w.dims[0], oh, ow}));
+        return RL_OK;
+    }
+    case RL_OP_DENSE_GRAD_X: case RL_OP_DENSE_GRAD_W: {
+        if (!arity(2)) return RL_ERR_TYPE;
+        const rl_type &dy = in[0], &b = in[1];
+        if (dy.rank != 2 || b.rank != 2) { msg = std::string(op_name(kind)) + " wants rank-2 operands"; return RL_ERR_TYPE; }
+        if (dy.dtype != b.dtype) { msg = std::string(op_name(kind)) + " operands differ in base type"; return RL_ERR_TYPE; }
+        int od;
+        if (!out_dtype(dy.dtype, od)) return RL_ERR_TYPE;
+        if (kind == RL_OP_DENSE_GRAD_X) {
+            if (dy.dims[1] != b.dims[0]) { msg = "dense_grad_x: dy's columns and W's rows differ"; return RL_ERR_TYPE; }
+            out.push_back(make_type(od, {dy.dims[0], b.dims[1]}));
+        } else {
+            if (dy.dims[0] != b.dims[0]) { msg = "dense_grad_w: dy and x differ in their first dimension"; return RL_ERR_TYPE; }
+            out.push_back(make_type(od, {dy.dims[1], b.dims[1]}));
+        }
+        return RL_OK;
+    }
+    case RL_OP_CONV2D_GRAD_X: case RL_OP_CONV2D_GRAD_W: {
+        if (!arity(2)) return RL_ERR_TYPE;
+        const rl_type &dy = in[0], &b = in[1];
+        if (dy.rank != 4 || b.rank != 4) { msg = std::string(op_name(kind)) + " wants rank-4 operands"; return RL_ERR_TYPE; }
+        if (dy.dtype != b.dtype) { msg = std::string(op_name(kind)) + " operands differ in base type"; return RL_ERR_TYPE; }
+        if (declared.size() != 1 || declared[0].rank != 4) { msg = std::string(op_name(kind)) + ": the declared result must be rank 4"; return RL_ERR_TYPE; }
+        const rl_type &d = declared[0];
+        int64_t H, W, KH, KW;
+        bool ok;
+        if (kind == RL_OP_CONV2D_GRAD_X) {       // b = w[O,C,KH,KW], d = [N,C,H,W]
+            H = d.dims[2]; W = d.dims[3]; KH = b.dims[2]; KW = b.dims[3];
+            ok = d.dims[0] == dy.dims[0] && d.dims[1] == b.dims[1] && dy.dims[1] == b.dims[0];
+        } else {                                 // b = x[N,C,H,W], d = [O,C,KH,KW]
+            H = b.dims[2]; W = b.dims[3]; KH = d.dims[2]; KW = d.dims[3];
+            ok = d.dims[0] == dy.dims[1] && d.dims[1] == b.dims[1] && dy.dims[0] == b.dims[0];
+        }
+        if (!ok) { msg = std::string(op_name(kind)) + ": batch / channel counts of operands and declared result disagree"; return RL_ERR_TYPE; }
+        if (H + 2 * a.pad[0] < KH || W + 2 * a.pad[1] < KW) { msg = "kernel larger than padded input"; return RL_ERR_SHAPE; }
+        if ((H + 2 * a.pad[0] - KH) / a.stride[0] + 1 != dy.dims[2] || (W + 2 * a.pad[1] - KW) / a.stride[1] + 1 != dy.dims[3]) {
+            msg = std::string(op_name(kind)) + ": the forward convolution of the declared geometry does not give dy's size";
+            return RL_ERR_TYPE;
+        }
+        int od;
+        if (!out_dtype(dy.dtype, od)) return RL_ERR_TYPE;
+        rl_type t = d;
+        t.dtype = od;
+        out.push_back(t);
         return RL_OK;
     }
     case RL_OP_MAXPOOL2D: {

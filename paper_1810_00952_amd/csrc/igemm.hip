@@ -132,8 +132,15 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmParams p)
                             int c = k - tap * p.C;
                             int kh = tap / p.KW;
                             int kw = tap - kh * p.KW;
-                            int ih = a_ih0[i] + kh, iw = a_iw0[i] + kw;
-                            if ((unsigned)ih < (unsigned)p.H && (unsigned)iw < (unsigned)p.W)
+                            int ih = a_ih0[i] + kh * (p.tap_dil_m1 + 1), iw = a_iw0[i] + kw * (p.tap_dil_m1 + 1);
+                            bool on = true;
+                            if (p.in_dil_m1 > 0) {           // only every (in_dil_m1 + 1)-th position of the virtual input holds a pixel
+                                const int d = p.in_dil_m1 + 1;
+                                on = ih >= 0 && iw >= 0 && ih % d == 0 && iw % d == 0;
+                                ih = on ? ih / d : -1;
+                                iw = on ? iw / d : -1;
+                            }
+                            if (on && (unsigned)ih < (unsigned)p.H && (unsigned)iw < (unsigned)p.W)
                                 val = x[(int64_t)a_img[i] * p.xs_n + (int64_t)c * p.xs_c + (int64_t)ih * p.xs_h + (int64_t)iw * p.xs_w];
                         } else {
                             val = x2[(int64_t)a_img[i] * p.x2s_n + (k - p.K1)];

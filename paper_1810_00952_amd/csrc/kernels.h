@@ -86,6 +86,9 @@ struct IgemmParams {
     // K split over `splits` workgroups per tile (direct-load variant only; 0 or 1: no split): workgroup (tile, z)
     // multiplies K tiles [z*per, (z+1)*per) and writes its fp32 sums to partial[z][M][N]; a second kernel adds the
     // slices in order z = 0, 1, ... and applies the epilogue
+    // element-gather variant only (both zero: an ordinary convolution): filter taps tap_dil_m1 + 1 input pixels apart;
+    // the input taken as if in_dil_m1 zeros stood between its pixels in both directions (H, W: the real extent)
+    int32_t tap_dil_m1, in_dil_m1;
     int32_t nmajor;                        // conv3x3_run_ks_kernel: 1: tiles in channel-tile-major order
     int32_t splits, split_tiles;           // split_tiles: K tiles per slice
     float *partial;
@@ -195,6 +198,15 @@ hipError_t launch_pack_weight(const void *src, void *dst, int32_t dtype, int32_t
 // dst[o][((t*2 + seg)*8 + px)*4 + c] = src[o][c][2t+seg][px], zero outside the filter.
 hipError_t launch_stem_pad(const void *src, void *dst, int32_t N, int32_t C, int32_t H, int32_t W, int32_t Hp, int32_t Wp,
                            int32_t ph, int32_t pw, hipStream_t s);
+// Operand of a contraction gathered into the K-contiguous rows the kernels read: for row r < R and k < Kp,
+// dst[r][k] = k < T*Cq ? src[base + r*s_row + (k % Cq)*s_c + (k / Cq / TW)*s_ti + (k / Cq % TW)*s_tj] : 0
+// (element strides, possibly negative).  Serves the transposed, flipped and re-ordered operands of the gradient operators,
+// at prepack time for params and as a step of the plan for activations.
+struct GatherPack {
+    int32_t dtype, R, Kp, T, Cq, TW;
+    int64_t base, s_row, s_c, s_ti, s_tj;
+};
+hipError_t launch_pack_gather(const void *src, void *dst, const GatherPack &g, hipStream_t s);
 hipError_t launch_pack_weight_stem(const void *src, void *dst, int32_t O, int32_t C, int32_t KH, int32_t KW, int32_t Kp, hipStream_t s);
 // measurement aid (calibrate.hip): a chain of register-operand bf16 MFMAs per wave; out holds grid * 512 floats
 hipError_t launch_mfma_peak(float *out, int32_t grid, int32_t iters, hipStream_t s);

@@ -651,6 +651,124 @@ struct Planner {
         return RL_OK;
     }
 
+    // ---- partial derivatives of the contractions --------------------------------
+    // Each is again a contraction C[m, n] = sum_k A[m, k] Wp[n, k] once its operands are looked at the right way round:
+    //   dense_grad_x   m = batch row,       n = input feature k',  k = output feature:   A = dy,            Wp[k'][n] = W[n][k']
+    //   dense_grad_w   m = output feature,  n = input feature,     k = batch row:        A[n][m] = dy[m][n], Wp[k'][m] = x[m][k']
+    //   conv2d_grad_x  m = input pixel,     n = input channel,     k = (tap, out chan.): A = dy with stride-1 zeros between its
+    //                  pixels and a border of K-1-pad, Wp = w with taps reversed and channel roles exchanged
+    //   conv2d_grad_w  m = (in chan., tap), n = output channel,    k = (out pixel, image): A = x read with channel and image
+    //                  exchanged and taps `stride` apart, Wp[o][(i, j), n] = dy[n][o][i][j]
+    // A is read in place through the element-gather kernel's strides; Wp is gathered once into K-contiguous rows: at
+    // prepack time when it comes from a param, by a step of the plan when it comes from an activation.
+    rl_status plan_grad(int gi, int oi)
+    {
+        const OpNode &o = g.ops[oi];
+        const int va = o.in[0], vb = o.in[1], vy = o.out[0];
+        const rl_type &ta = T(va), &tb = T(vb), &ty = T(vy);
+        const int dt = ta.dtype;
+        const int KV = kv_of(dt);
+        IgemmParams p{};
+        GatherPack gp{};
+        p.in_dtype = dt; p.y_dtype = ty.dtype;
+        gp.dtype = dt;
+        if (numel(ta) >= ((int64_t)1 << 31) || numel(tb) >= ((int64_t)1 << 31) || numel(ty) >= ((int64_t)1 << 31))
+            return fail(RL_ERR_UNSUPPORTED, std::string(op_name(o.kind)) + ": tensor too large");
+        p.C = 1; p.H = p.W = p.KH = p.KW = p.OH = p.OW = p.OHW = 1; p.sh = p.sw = 1;
+        if (o.kind == RL_OP_DENSE_GRAD_X) {
+            const int M = (int)ta.dims[0], N = (int)ta.dims[1], K = (int)tb.dims[1];
+            p.M = M; p.N = K; p.K = N; p.C = N;
+            p.xs_n = N; p.xs_c = 1;
+            gp.R = K; gp.T = 1; gp.TW = 1; gp.Cq = N; gp.s_row = 1; gp.s_c = K;
+        } else if (o.kind == RL_OP_DENSE_GRAD_W) {
+            const int M = (int)ta.dims[0], N = (int)ta.dims[1], K = (int)tb.dims[1];
+            p.M = N; p.N = K; p.K = M; p.C = M;
+            p.xs_n = 1; p.xs_c = N;
+            gp.R = K; gp.T = 1; gp.TW = 1; gp.Cq = M; gp.s_row = 1; gp.s_c = K;
+        } else if (o.kind == RL_OP_CONV2D_GRAD_X) {
+            // dy[N,O,OH,OW], w[O,C,KH,KW] -> dx[N,C,H,W]
+            const int Nb = (int)ta.dims[0], O = (int)ta.dims[1], OH = (int)ta.dims[2], OW = (int)ta.dims[3];
+            const int C = (int)tb.dims[1], KH = (int)tb.dims[2], KW = (int)tb.dims[3], H = (int)ty.dims[2], W = (int)ty.dims[3];
+            if (o.attrs.stride[0] != o.attrs.stride[1]) return fail(RL_ERR_UNSUPPORTED, "conv2d_grad_x: strides must agree");
+            if (o.attrs.pad[0] > KH - 1 || o.attrs.pad[1] > KW - 1) return fail(RL_ERR_UNSUPPORTED, "conv2d_grad_x: padding larger than the kernel");
+            if ((int64_t)Nb * H * W > 0x7fffffff) return fail(RL_ERR_UNSUPPORTED, "conv2d_grad_x too large");
+            p.M = Nb * H * W; p.N = C; p.K = O * KH * KW; p.C = O;
+            p.H = OH; p.W = OW; p.KH = KH; p.KW = KW; p.OH = H; p.OW = W; p.OHW = H * W;
+            p.sh = p.sw = 1; p.ph = KH - 1 - o.attrs.pad[0]; p.pw = KW - 1 - o.attrs.pad[1];
+            p.in_dil_m1 = o.attrs.stride[0] - 1;
+            p.xs_n = (int64_t)O * OH * OW; p.xs_c = (int64_t)OH * OW; p.xs_h = OW; p.xs_w = 1;
+            p.ys_n = (int64_t)C * H * W; p.ys_p = 1; p.ys_c = (int64_t)H * W;
+            // Wp[c][(a', b'), o] = w[o][c][KH-1-a'][KW-1-b']
+            gp.R = C; gp.T = KH * KW; gp.TW = KW; gp.Cq = O;
+            gp.s_row = (int64_t)KH * KW; gp.s_c = (int64_t)C * KH * KW; gp.s_ti = -KW; gp.s_tj = -1; gp.base = (int64_t)KH * KW - 1;
+        } else {
+            // dy[N,O,OH,OW], x[N,C,H,W] -> dw[O,C,KH,KW]
+            const int Nb = (int)ta.dims[0], O = (int)ta.dims[1], OH = (int)ta.dims[2], OW = (int)ta.dims[3];
+            const int C = (int)tb.dims[1], H = (int)tb.dims[2], W = (int)tb.dims[3], KH = (int)ty.dims[2], KW = (int)ty.dims[3];
+            if (o.attrs.stride[0] != o.attrs.stride[1]) return fail(RL_ERR_UNSUPPORTED, "conv2d_grad_w: strides must agree");
+            if ((int64_t)Nb * OH * OW > 0x7ffffff0) return fail(RL_ERR_UNSUPPORTED, "conv2d_grad_w too large");
+            p.M = C * KH * KW; p.N = O; p.K = Nb * OH * OW; p.C = Nb;
+            p.H = H; p.W = W; p.KH = OH; p.KW = OW; p.OH = KH; p.OW = KW; p.OHW = KH * KW;
+            p.sh = p.sw = 1; p.ph = o.attrs.pad[0]; p.pw = o.attrs.pad[1];
+            p.tap_dil_m1 = o.attrs.stride[0] - 1;
+            p.xs_n = (int64_t)H * W; p.xs_c = (int64_t)C * H * W; p.xs_h = W; p.xs_w = 1;      // "image" = channel c, "channel" = image n
+            p.ys_n = (int64_t)KH * KW; p.ys_p = 1; p.ys_c = (int64_t)C * KH * KW;               // dw[o][c][a][b] at n*ys_c + m
+            // Wp[o][(i, j), n] = dy[n][o][i][j]
+            gp.R = O; gp.T = OH * OW; gp.TW = OW; gp.Cq = Nb;
+            gp.s_row = (int64_t)OH * OW; gp.s_c = (int64_t)O * OH * OW; gp.s_ti = OW; gp.s_tj = 1;
+        }
+        if (o.kind == RL_OP_DENSE_GRAD_X || o.kind == RL_OP_DENSE_GRAD_W) { p.ys_n = p.N; p.ys_p = p.N; p.ys_c = 1; }
+        p.K1 = p.K;
+        p.Kp = (int)round_up(p.K, KV);
+        gp.Kp = p.Kp;
+        p.ts_h = p.xs_h; p.ts_w = p.xs_w; p.seg_stride = 64;
+        make_fast_div((uint32_t)p.OHW, p.div_ohw_mul, p.div_ohw_sh);
+        make_fast_div((uint32_t)p.OW, p.div_ow_mul, p.div_ow_sh);
+        const size_t lim = (size_t)1 << 31;
+        const size_t wbytes = (size_t)gp.R * gp.Kp * dtype_size(dt);
+        if (wbytes >= lim) return fail(RL_ERR_UNSUPPORTED, std::string(op_name(o.kind)) + ": operand too large");
+        p.x_bytes = (uint32_t)std::min(bytes_of(va), lim - 1);
+        p.w_bytes = (uint32_t)wbytes;
+        p.y_bytes = (uint32_t)std::min(bytes_of(vy), lim - 1);
+
+        int abuf, wbuf;
+        rl_status st;
+        // which of the two operands is A and which is gathered into Wp: dy is A except for conv2d_grad_w, where x is
+        int a_val = va, w_val = vb;
+        if (o.kind == RL_OP_CONV2D_GRAD_W) { a_val = vb; w_val = va; }
+        st = need(a_val, L_NATIVE, abuf);
+        if (st != RL_OK) return st;
+        if (g.values[w_val].role == ROLE_PARAM && consumers[w_val].size() == 1) {     // a param with other uses keeps its own layout for them
+            PackSpec pack;
+            pack.dtype = dt; pack.gather = 1; pack.gp = gp; pack.bytes = wbytes; pack.Kp = gp.Kp; pack.perm_block = -3;
+            auto it = plan.packs.find(w_val);
+            if (it != plan.packs.end()) return fail(RL_ERR_UNSUPPORTED, "one param needs two different kernel-native layouts");
+            plan.packs[w_val] = pack;
+            wbuf = bound(w_val);
+        } else {
+            int src;
+            st = need(w_val, L_NATIVE, src);
+            if (st != RL_OK) return st;
+            wbuf = new_ws(wbytes);
+            Step &ps = add_step(S_PACK, std::string(op_name(o.kind)) + "#" + std::to_string(oi) + ".operand", "pack_gather");
+            ps.group = gi;
+            ps.gp = gp;
+            ps.slot[SL_X] = src; ps.slot[SL_Y] = wbuf;
+            ps.bytes = (double)bytes_of(w_val) + (double)wbytes;
+        }
+        const int ybuf = out_buf(vy, L_NATIVE);
+        IgemmLaunch il{};
+        il.tile = TILE_64x64;                         // element gather: any strides, any counts
+        Step &s = add_step(S_IGEMM, std::string(op_name(o.kind)) + "#" + std::to_string(oi),
+                           std::string("igemm_") + op_name(o.kind) + (dt == RL_BF16 ? "_bf16" : "_f32") + "_64x64_gather");
+        s.group = gi;
+        s.ig = p; s.il = il;
+        s.slot[SL_X] = abuf; s.slot[SL_W] = wbuf; s.slot[SL_Y] = ybuf;
+        s.flops = 2.0 * p.M * (double)p.N * p.K / (double)((p.in_dil_m1 + 1) * (p.in_dil_m1 + 1));     // the zeros between dy's pixels are no work
+        s.bytes = (double)bytes_of(va) + (double)bytes_of(vb) + (double)bytes_of(vy);
+        return RL_OK;
+    }
+
     rl_status plan_group(int gi, std::vector<int> ops)
     {
         std::sort(ops.begin(), ops.end());
@@ -665,6 +783,7 @@ struct Planner {
             if (k0 == RL_OP_FLATTEN) return plan_flatten(ops[0]);
             if (k0 == RL_OP_LSTM_GATES) return plan_gates(gi, ops[0]);
             if (k0 == RL_OP_LAYOUT_TRANSFORM) return plan_layout(gi, ops[0]);
+            if (k0 >= RL_OP_DENSE_GRAD_X && k0 <= RL_OP_CONV2D_GRAD_W) return plan_grad(gi, ops[0]);
             if (k0 == RL_OP_CONCAT) return fail(RL_ERR_UNSUPPORTED, "concat is only implemented as the operand of a dense in its group");
         }
         return plan_eltwise(gi, ops);
@@ -1029,6 +1148,9 @@ rl_status run_steps(const Plan &plan, void *const *ptrs, hipStream_t stream, std
             er = launch_permute(p, stream);
             break;
         }
+        case S_PACK:
+            er = launch_pack_gather(P(s, SL_X), P(s, SL_Y), s.gp, stream);
+            break;
         case S_STEM_PAD:
             er = launch_stem_pad(P(s, SL_X), P(s, SL_Y), s.t_N, s.t_C, s.st_H, s.st_W, s.st_Hp, s.st_Wp, s.st_ph, s.st_pw, stream);
             break;

@@ -10,7 +10,7 @@
 
 namespace rl {
 
-enum StepKind { S_IGEMM = 0, S_ELTWISE, S_GATES, S_MAXPOOL, S_GAVG, S_TO_NHWC, S_TO_NCHW, S_STEM_PAD, S_STEM_POOL, S_PERMUTE };
+enum StepKind { S_IGEMM = 0, S_ELTWISE, S_GATES, S_MAXPOOL, S_GAVG, S_TO_NHWC, S_TO_NCHW, S_STEM_PAD, S_STEM_POOL, S_PERMUTE, S_PACK };
 enum Slot { SL_X = 0, SL_X2, SL_W, SL_Y, SL_E0, SL_E1, SL_E2, SL_E3, SL_E4, SL_E5, SL_CIN, SL_COUT, SL_HOUT, SL_PART, SL_COUNT };
 
 struct BufDesc {
@@ -30,6 +30,7 @@ struct Step {
     GatesParams ga{};
     PoolParams po{};
     PermuteParams pe{};
+    GatherPack gp{};                    // S_PACK: an activation gathered into the K-contiguous rows a contraction reads
     int t_dtype = 0, t_N = 0, t_C = 0, t_P = 0;
     int st_H = 0, st_W = 0, st_Hp = 0, st_Wp = 0, st_ph = 0, st_pw = 0;   // S_STEM_PAD geometry (t_N, t_C: batch, channels)
     int stem = 0;                       // S_IGEMM: the few-channel stem form (padded 4-channel frame, regrouped taps)
@@ -45,6 +46,7 @@ struct Step {
 struct PackSpec {
     int dtype = 0, O = 0, C = 0, T = 0, Kp = 0, perm_block = 0;   // perm_block -1: matrix, then the 64x64x3x3 fragment-order copy
     int stem = 0, KH = 0, KW = 0;      // stem = 1: few-channel stem layout (launch_pack_weight_stem)
+    int gather = 0; GatherPack gp{};   // gather = 1: launch_pack_gather (operands of the gradient operators)
     size_t bytes = 0;
 };
 

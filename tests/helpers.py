@@ -88,6 +88,16 @@ def error_budget(spec, data):
             st, pd = tuple(op.attrs.get("stride", (1, 1))), tuple(op.attrs.get("pad", (0, 0)))
             K = a[1].shape[1] * a[1].shape[2] * a[1].shape[3]
             out = O.conv2d(ea[0], a[1], st, pd) + O.conv2d(a[0], ea[1], st, pd) + (K + 1) * U32 * O.conv2d(a[0], a[1], st, pd)
+        elif k in ("dense_grad_x", "dense_grad_w", "conv2d_grad_x", "conv2d_grad_w"):
+            st, pd = tuple(op.attrs.get("stride", (1, 1))), tuple(op.attrs.get("pad", (0, 0)))
+            oshape = spec.values[op.outputs[0]].type.shape
+            f = {"dense_grad_x": lambda p, q: O.dense_grad_x(p, q), "dense_grad_w": lambda p, q: O.dense_grad_w(p, q),
+                 "conv2d_grad_x": lambda p, q: O.conv2d_grad_x(p, q, oshape, st, pd),
+                 "conv2d_grad_w": lambda p, q: O.conv2d_grad_w(p, q, oshape[2:], st, pd)}[k]
+            terms = {"dense_grad_x": a[0].shape[1], "dense_grad_w": a[0].shape[0],
+                     "conv2d_grad_x": a[0].shape[1] * a[1].shape[2] * a[1].shape[3] if k == "conv2d_grad_x" else 0,
+                     "conv2d_grad_w": a[0].shape[0] * a[0].shape[2] * a[0].shape[3] if k == "conv2d_grad_w" else 0}[k]
+            out = f(ea[0], a[1]) + f(a[0], ea[1]) + (terms + 1) * U32 * f(a[0], a[1])
         elif k == "bias_add":
             out = O.bias_add(ea[0], ea[1], int(op.attrs.get("axis", 1))) + U32 * y
         elif k in ("add", "sub"):

@@ -810,6 +810,71 @@ def test_contraction_with_k_split_over_workgroups(case):
     assert_close(whole[v], ref[v], dtype, f"unsplit {case}", budget=bud)
 
 
+# ---- partial derivatives of the contractions ---------------------------------------------------------------
+GRAD_CASES = [
+    # kind             dims                      stride pad  second operand a param?
+    ("dense_grad_x", (32, 10, 128), 1, 0, True),          # the MLP's second layer
+    ("dense_grad_x", (70, 136, 200), 1, 0, False),
+    ("dense_grad_x", (5, 7, 30), 1, 0, True),             # nothing a multiple of anything
+    ("dense_grad_w", (32, 128, 784), 1, 0, False),        # the MLP's first layer
+    ("dense_grad_w", (9, 6, 16), 1, 0, False),
+    ("dense_grad_w", (300, 72, 40), 1, 0, False),
+    ("conv2d_grad_x", (2, 16, 12, 12, 24, 3), 1, 1, True),
+    ("conv2d_grad_x", (3, 8, 15, 14, 16, 3), 2, 1, True),     # stride 2: (H + 2p - K) % s = 0 for H and 1 for W
+    ("conv2d_grad_x", (2, 32, 14, 14, 64, 1), 2, 0, True),    # the 1x1 / stride 2 projection: three of four pixels get no gradient
+    ("conv2d_grad_x", (1, 3, 33, 33, 16, 7), 2, 3, False),    # the stem's geometry, small; weights as an activation
+    ("conv2d_grad_x", (2, 5, 9, 10, 7, 3), 1, 0, True),
+    ("conv2d_grad_w", (2, 16, 12, 12, 24, 3), 1, 1, False),
+    ("conv2d_grad_w", (3, 8, 15, 14, 16, 3), 2, 1, False),
+    ("conv2d_grad_w", (2, 32, 14, 14, 64, 1), 2, 0, False),
+    ("conv2d_grad_w", (1, 3, 33, 33, 16, 7), 2, 3, False),
+    ("conv2d_grad_w", (4, 64, 14, 14, 64, 3), 1, 1, False),   # a ResNet block's shape, small batch
+]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("case", GRAD_CASES, ids=[f"{c[0]}-{i}" for i, c in enumerate(GRAD_CASES)])
+def test_gradient_operators(dtype, case):
+    kind, dims, stride, pad, is_param = case
+    spec, data = W.grad_case(kind, dims, dtype, stride, pad, second_is_param=is_param)
+    print(f"gradient case {dtype} {case}", flush=True)
+    check_graph(spec, data, f"{kind} {dtype} {dims} s{stride} p{pad}")
+    kernels = [st["kernel"] for st in s_plan_steps(spec)]
+    assert any(k.startswith(f"igemm_{kind}_") for k in kernels), kernels
+    assert ("pack_gather" in kernels) == (not is_param), kernels          # a param's operand form is made at prepack time
+    if dtype == "bf16":
+        # fp32 results from bf16 operands (what an optimizer would accumulate into): no rounding of the sum at all
+        spec32, _ = W.grad_case(kind, dims, dtype, stride, pad, second_is_param=is_param, out_dtype="f32")
+        ref = OG.run(spec32, data)
+        out, _ = run_hip(spec32, data)
+        v = spec32.outputs[0]
+        assert_close(out[v], ref[v], "f32", f"{kind} bf16->f32 {dims}", budget=lambda: error_budget(spec32, data)[v])
+
+
+def s_plan_steps(spec):
+    from paper_1810_00952_amd import binding
+    return binding.Plan(binding.graph_from_spec(binding.Context(), spec)).describe()["steps"]
+
+
+def test_gradients_inside_a_graph():
+    # forward dense + bias + relu, then the two gradients of the dense for a given dy: the weight is read by the forward
+    # contraction in its own layout and by dense_grad_x through a gather step; x feeds dense_grad_w
+    for dtype in ("f32", "bf16"):
+        g = W.GraphSpec("train_step")
+        M, K, N = 24, 40, 16
+        x = g.input("x", dtype, (M, K)); w = g.param("w", dtype, (N, K)); b = g.param("b", "f32", (N,)); dy = g.input("dy", dtype, (M, N))
+        o0, (y,) = g.op("dense", [x, w], [(dtype, (M, N))])
+        o1, (y,) = g.op("bias_add", [y, b], [(dtype, (M, N))], axis=1)
+        g.group([o0, o1])
+        o2, (dx,) = g.op("dense_grad_x", [dy, w], [(dtype, (M, K))]); g.group([o2])
+        o3, (dw,) = g.op("dense_grad_w", [dy, x], [(dtype, (N, K))]); g.group([o3])
+        g.output(y); g.output(dx); g.output(dw)
+        rng = W.rng_for(16)
+        data = {"x": W.as_dtype(W.normal(rng, (M, K)), dtype), "w": W.as_dtype(W.normal(rng, (N, K)) * 0.2, dtype),
+                "b": W.as_dtype(W.uniform(rng, (N,), -0.1, 0.1), "f32"), "dy": W.as_dtype(W.normal(rng, (M, N)), dtype)}
+        check_graph(g, data, f"forward and gradients in one graph {dtype}")
+
+
 # ---- typed changes of layout -----------------------------------------------------------------------------
 LAYOUT_CASES = [
     ((3, 5, 7, 4), (0, 2, 3, 1), "f32"), ((3, 5, 7, 4), (0, 3, 1, 2), "bf16"), ((37, 70), (1, 0), "bf16"), ((2, 3, 33, 65), (0, 1, 3, 2), "f32"),

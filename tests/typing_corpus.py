@@ -223,6 +223,49 @@ def _group_gates_skip_the_bias():               # the gate operator reads the co
     g.group([o0, o1, o2]); g.output(c2); g.output(h2); return g
 
 
+def _dense_grad_ok():
+    return W.grad_case("dense_grad_x", (4, 6, 8))[0]
+
+
+def _dense_grad_w_ok_f32_from_bf16():
+    return W.grad_case("dense_grad_w", (4, 6, 8), "bf16", out_dtype="f32")[0]
+
+
+def _dense_grad_x_inner_mismatch():          # dy's columns are W's rows
+    g = GraphSpec("t"); dy = g.input("dy", "f32", (4, 6)); w = g.param("w", "f32", (5, 8))
+    o, (y,) = g.op("dense_grad_x", [dy, w], [("f32", (4, 8))]); g.output(y); return g
+
+
+def _dense_grad_w_wrong_declared():          # the gradient has the weight's Shape [N, K], not its transpose
+    g = GraphSpec("t"); dy = g.input("dy", "f32", (4, 6)); x = g.input("x", "f32", (4, 8))
+    o, (y,) = g.op("dense_grad_w", [dy, x], [("f32", (8, 6))]); g.output(y); return g
+
+
+def _conv_grad_x_ok_stride2():                # 7 -> floor((7 + 2 - 3)/2) + 1 = 4; and so does 8: the declaration decides
+    return W.grad_case("conv2d_grad_x", (2, 3, 8, 7, 4, 3), stride=2, pad=1)[0]
+
+
+def _conv_grad_x_declared_size_not_a_preimage():
+    g = GraphSpec("t"); dy = g.input("dy", "f32", (1, 4, 4, 4)); w = g.param("w", "f32", (4, 3, 3, 3))
+    o, (y,) = g.op("conv2d_grad_x", [dy, w], [("f32", (1, 3, 9, 8))], stride=(2, 2), pad=(1, 1)); g.output(y); return g
+
+
+def _conv_grad_w_ok():
+    return W.grad_case("conv2d_grad_w", (2, 3, 6, 6, 4, 3), stride=1, pad=1, second_is_param=False)[0]
+
+
+def _conv_grad_w_channel_mismatch():
+    g = GraphSpec("t"); dy = g.input("dy", "f32", (2, 4, 6, 6)); x = g.input("x", "f32", (2, 3, 6, 6))
+    o, (y,) = g.op("conv2d_grad_w", [dy, x], [("f32", (4, 5, 3, 3))], stride=(1, 1), pad=(1, 1)); g.output(y); return g
+
+
+def _group_grad_fused():                      # a gradient operator is neither a contraction that opens a group nor injective
+    g = GraphSpec("t"); dy = g.input("dy", "f32", (4, 6)); w = g.param("w", "f32", (6, 8))
+    o0, (y,) = g.op("dense_grad_x", [dy, w], [("f32", (4, 8))])
+    o1, (y,) = g.op("relu", [y], [("f32", (4, 8))])
+    g.group([o0, o1]); g.output(y); return g
+
+
 def _cast_ok():
     g = GraphSpec("t"); x = g.input("x", "f32", (2, 4))
     o, (y,) = g.op("cast", [x], [("bf16", (2, 4))], to="bf16"); g.output(y); return g
@@ -362,6 +405,15 @@ CASES = [
     ("group_gates_behind_injective_chain", _group_gates_behind_injective_chain, "group"),
     ("gates_behind_injective_chain_ungrouped_ok", _gates_behind_injective_chain_ungrouped_ok, None),
     ("group_gates_skip_the_bias", _group_gates_skip_the_bias, "group"),
+    ("dense_grad_ok", _dense_grad_ok, None),
+    ("dense_grad_w_ok_f32_from_bf16", _dense_grad_w_ok_f32_from_bf16, None),
+    ("dense_grad_x_inner_mismatch", _dense_grad_x_inner_mismatch, "type"),
+    ("dense_grad_w_wrong_declared", _dense_grad_w_wrong_declared, "type"),
+    ("conv_grad_x_ok_stride2", _conv_grad_x_ok_stride2, None),
+    ("conv_grad_x_declared_size_not_a_preimage", _conv_grad_x_declared_size_not_a_preimage, "type"),
+    ("conv_grad_w_ok", _conv_grad_w_ok, None),
+    ("conv_grad_w_channel_mismatch", _conv_grad_w_channel_mismatch, "type"),
+    ("group_grad_fused", _group_grad_fused, "group"),
     ("cast_ok", _cast_ok, None),
     ("cast_wrong_declared", _cast_wrong_declared, "type"),
     ("layout_ok", _layout_ok, None),

@@ -253,6 +253,34 @@ def downsample_block(batch=4, cin=64, cout=128, h=32, w=32, dtype="bf16", config
     return g, data
 
 
+def grad_case(kind, dims, dtype="f32", stride=1, pad=0, second_is_param=True, out_dtype=None, config=15):
+    """One partial-derivative operator on its own.  dims: dense kinds (M, N, K); conv kinds (n, c, h, w, o, k).
+    dy ~ N(0,1); the second operand (W or x) is a param or an input as asked."""
+    rng = rng_for(config, salt=sum((i + 1) * int(d) for i, d in enumerate(dims)) + 7 * stride + pad)
+    g = GraphSpec(kind)
+    od = out_dtype or dtype
+    attrs = {"out_dtype": out_dtype} if out_dtype else {}
+    second = g.param if second_is_param else g.input
+    if kind in ("dense_grad_x", "dense_grad_w"):
+        M, N, K = dims
+        dy = g.input("dy", dtype, (M, N))
+        b_shape, out_shape = ((N, K), (M, K)) if kind == "dense_grad_x" else ((M, K), (N, K))
+        scale = 1.0 / np.sqrt(N if kind == "dense_grad_x" else M)
+    else:
+        n, c, h, w, o, k = dims
+        oh, ow = conv_out(h, k, stride, pad), conv_out(w, k, stride, pad)
+        dy = g.input("dy", dtype, (n, o, oh, ow))
+        b_shape, out_shape = (((o, c, k, k), (n, c, h, w)) if kind == "conv2d_grad_x" else ((n, c, h, w), (o, c, k, k)))
+        attrs.update(stride=(stride, stride), pad=(pad, pad))
+        scale = 1.0 / np.sqrt(o * k * k if kind == "conv2d_grad_x" else n * oh * ow)
+    b = second("b", dtype, b_shape)
+    o_, (y,) = g.op(kind, [dy, b], [(od, out_shape)], **attrs)
+    g.group([o_])
+    g.output(y)
+    data = {"dy": as_dtype(normal(rng, g.values[dy].type.shape), dtype), "b": as_dtype(normal(rng, b_shape) * scale, dtype)}
+    return g, data
+
+
 def layout_case(shape=(3, 5, 7, 4), perm=(0, 2, 3, 1), dtype="f32", config=11):
     """One change of layout on its own: y = layout_transform(x; perm), y's Shape is x's Shape permuted."""
     rng = rng_for(config, salt=len(shape) * 100 + sum((i + 1) * p for i, p in enumerate(perm)))
