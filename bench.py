@@ -20,6 +20,7 @@ configurations and the HBM-bound groups:
   copy      y = -x on 24 Mi f32 elements: a plain copy kernel of known size
             (100.7 MB read, 100.7 MB written, ordinary loads and stores), the
             yardstick for the HBM byte counters
+  grads     the gradient operators of dense / conv2d at the benchmark graph's shapes
   mfma_peak a chain of bf16 MFMAs on register operands on every SIMD: what the
             matrix pipes deliver here, next to the quoted 2.5 PFLOP/s
 The default line also carries that calibration ("peaks") and the HBM-bound groups
@@ -385,13 +386,44 @@ def bench_lstm(args):
     return out
 
 
+def bench_grads(args):
+    """The four gradient operators of the contractions at the shapes of the benchmark graph's second stage (batch 64,
+    128 channels, 28x28) and of its dense head, bf16 operands; each a plan of its own."""
+    import torch
+    import workloads as W
+    from paper_1810_00952_amd import harness
+    cases = [("conv2d_grad_x", (64, 128, 28, 28, 128, 3), 1, 1, True), ("conv2d_grad_w", (64, 128, 28, 28, 128, 3), 1, 1, False),
+             ("conv2d_grad_x", (64, 64, 56, 56, 128, 3), 2, 1, True), ("conv2d_grad_w", (64, 64, 56, 56, 128, 3), 2, 1, False),
+             ("dense_grad_x", (64, 1000, 512), 1, 0, True), ("dense_grad_w", (64, 1000, 512), 1, 0, False)]
+    rows, tot_ms, tot_flops = [], 0.0, 0.0
+    for kind, dims, stride, pad, is_param in cases:
+        spec, data = W.grad_case(kind, dims, "bf16", stride, pad, second_is_param=is_param)
+        s = harness.Session(spec)
+        s.load(data)
+        s.alloc()
+        ms = time_steps(s.run, args.steps, args.warmup, graph=False)
+        steps = s.plan.describe()["steps"]
+        flops = sum(st["flops"] for st in steps)
+        rows.append({"op": kind, "dims": list(dims), "stride": stride, "pad": pad, "kernels": [st["kernel"] for st in steps], "us": ms * 1e3,
+                     "tflops": flops / (ms * 1e-3) / 1e12, "mfma_frac": flops / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS})
+        tot_ms += ms; tot_flops += flops
+        del s
+        torch.cuda.empty_cache()
+    out = base_json("TFLOP/s gradient operators of dense / conv2d, bf16", tot_flops / (tot_ms * 1e-3) / 1e12, "TFLOP/s", args, tot_ms, "bf16",
+                    "dense_grad_x/_w on 64x1000x512 and conv2d_grad_x/_w on 64x128x28x28 (3x3/1) and 64x64x56x56 -> 128 (3x3/2), bf16, N(0,1) operands")
+    out["roofline"] = {"bound": "mfma", "achieved": out["value"], "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": out["value"] / PEAK_BF16_TFLOPS,
+                       "traffic": None, "kernel": "igemm_kernel (element gather) + pack_gather + splitk_reduce"}
+    out["operators"] = rows
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="resnet18",
-                    choices=["resnet18", "resnet18_f32_b1", "eltwise", "eltwise32", "gates", "lstm", "mlp", "lenet", "conv", "copy", "layout", "layout32", "block_nhwc", "maxpool", "mfma_peak"])
+                    choices=["resnet18", "resnet18_f32_b1", "eltwise", "eltwise32", "gates", "lstm", "mlp", "lenet", "conv", "copy", "layout", "layout32", "block_nhwc", "maxpool", "mfma_peak", "grads"])
     ap.add_argument("--batch", type=int, default=64)
     ap.add_argument("--cpu-images", type=int, default=128)
     ap.add_argument("--no-cpu", action="store_true")
@@ -457,6 +489,8 @@ def main():
                           "-> channel-last output, bf16, batch 64", PEAK_BF16_TFLOPS)
     elif wl == "lstm":
         out = bench_lstm(args)
+    elif wl == "grads":
+        out = bench_grads(args)
     elif wl == "mfma_peak":
         pk = measure_peaks()
         out = base_json("TFLOP/s bf16 MFMA chain on register operands", pk["mfma_bf16_tflops_measured"], "TFLOP/s", args, 0.0, "bf16", pk["mfma_measure"])

@@ -82,7 +82,13 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmParams p)
             a_iw0[i] = 0;
         }
     }
-    int kc = lchunk * KV;                 // k of this thread's chunk in the current tile
+    // K split over gridDim.y workgroups per tile (p.splits > 1): this one multiplies K tiles [kt0, kt0 + nk) and leaves
+    // its bare fp32 sums in partial[blockIdx.y][M][N]; splitk_reduce_kernel adds the slices in order and finishes
+    const int nk_all = (p.Kp + BKE - 1) / BKE;
+    const int split = p.splits > 1 ? (int)blockIdx.y : 0;
+    const int kt0 = p.splits > 1 ? split * p.split_tiles : 0;
+    const int nk = p.splits > 1 ? max(0, min(nk_all - kt0, p.split_tiles)) : nk_all;
+    int kc = kt0 * BKE + lchunk * KV;     // k of this thread's chunk in the current tile
     int c_cur = 0, kh_cur = 0, kw_cur = 0;
     if (AVEC) {
         int tap = kc / p.C;
@@ -186,10 +192,11 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmParams p)
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
 
-    const int nk = (p.Kp + BKE - 1) / BKE;
-    fetch();
-    advance();
-    park(0);
+    if (nk > 0) {
+        fetch();
+        advance();
+        park(0);
+    }
     __syncthreads();
 
     const int frow = lane & 31, fhalf = lane >> 5;
@@ -215,6 +222,21 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmParams p)
         __syncthreads();
     }
 
+    if (!GATES && p.splits > 1) {
+        float *dst = p.partial + (int64_t)split * p.M * p.N;
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const int n = n0 + wn * WTN + j * 32 + (lane & 31);
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int m = m0 + wm * WTM + i * 32 + 8 * (r >> 2) + 4 * fhalf + (r & 3);
+                    if (m < p.M && n < p.N) dst[(int64_t)m * p.N + n] = acc[i][j][r];
+                }
+            }
+        return;
+    }
     // ---- epilogue: chain applied to the accumulators in registers
     const Epilogue &e = p.epi;
     const bool rowmajor = (p.ys_n == (int64_t)p.OHW * p.ys_p);
@@ -315,6 +337,8 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmParams p)
     }
 }
 
+hipError_t launch_splitk_reduce(const IgemmParams &p, hipStream_t s);     // igemm_dma.hip
+
 template <typename T, int BM, int BN, bool AVEC, bool GATES>
 static hipError_t launch_one(const IgemmParams &p0, hipStream_t s)
 {
@@ -335,6 +359,17 @@ static hipError_t launch_one(const IgemmParams &p0, hipStream_t s)
     }
     int64_t nblk = (int64_t)p.nblk_m * p.nblk_n;
     if (nblk <= 0 || nblk > 0x7fffffff) return hipErrorInvalidValue;
+    if (p.splits > 1) {
+        constexpr int BKE = CHUNKS * Elem<T>::KV;
+        const int nk = (p.Kp + BKE - 1) / BKE;
+        if (GATES || AVEC || !p.partial || p.splits > 64 || (int64_t)p.M * p.N * p.splits >= (int64_t)1 << 31 || p.split_tiles < 1 ||
+            (int64_t)p.splits * p.split_tiles < nk || p.x2)
+            return hipErrorInvalidValue;
+        hipLaunchKernelGGL(kern, dim3((unsigned)nblk, (unsigned)p.splits), dim3(256), lds, s, p);
+        hipError_t er = hipGetLastError();
+        if (er != hipSuccess) return er;
+        return launch_splitk_reduce(p, s);
+    }
     hipLaunchKernelGGL(kern, dim3((unsigned)nblk), dim3(256), lds, s, p);
     return hipGetLastError();
 }

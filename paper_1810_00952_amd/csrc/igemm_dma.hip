@@ -347,6 +347,14 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const IgemmParams p)
     }
 }
 
+hipError_t launch_splitk_reduce(const IgemmParams &p, hipStream_t s)
+{
+    const int64_t total = (int64_t)p.M * p.N;
+    if (total < 1 || total * p.splits >= (int64_t)1 << 31 || !p.partial) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)std::min<int64_t>((total + 255) / 256, 256 * 16)), dim3(256), 0, s, p);
+    return hipGetLastError();
+}
+
 // explicit instantiations (the host-side launch stubs of a kernel template with function-local
 // __shared__ arrays are not emitted implicitly)
 #define RL_INST(T, BM, BN, G) template __global__ void igemm_dma_kernel<T, BM, BN, G>(const IgemmParams);
@@ -377,9 +385,7 @@ static hipError_t launch_dma(const IgemmParams &p0, hipStream_t s)
         hipLaunchKernelGGL((igemm_dma_kernel<T, BM, BN, GATES>), dim3((unsigned)nblk, (unsigned)p.splits), dim3(256), 0, s, p);
         hipError_t er = hipGetLastError();
         if (er != hipSuccess) return er;
-        const int64_t total = (int64_t)p.M * p.N;
-        hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)std::min<int64_t>((total + 255) / 256, 256 * 16)), dim3(256), 0, s, p);
-        return hipGetLastError();
+        return launch_splitk_reduce(p, s);
     }
     hipLaunchKernelGGL((igemm_dma_kernel<T, BM, BN, GATES>), dim3((unsigned)nblk), dim3(256), 0, s, p);
     return hipGetLastError();

@@ -759,11 +759,25 @@ struct Planner {
         const int ybuf = out_buf(vy, L_NATIVE);
         IgemmLaunch il{};
         il.tile = TILE_64x64;                         // element gather: any strides, any counts
+        // few tiles and a long K (a weight gradient contracts over every pixel of the batch): K split over workgroups
+        int part_buf = -1;
+        if (!plan.opts.no_splitk) {
+            const int64_t tiles = (int64_t)((p.M + 63) / 64) * ((p.N + 63) / 64);
+            const int nk = (p.Kp + 8 * KV - 1) / (8 * KV);
+            const int want = (int)std::min<int64_t>(std::min<int64_t>(64, 512 / std::max<int64_t>(tiles, 1)), nk / 4);
+            if (tiles <= 128 && want >= 2 && (int64_t)want * p.M * p.N * 4 < (int64_t)1 << 28) {
+                const int per = (nk + want - 1) / want;
+                il.splits = (nk + per - 1) / per;
+                p.splits = il.splits; p.split_tiles = per;
+                part_buf = new_ws((size_t)il.splits * p.M * p.N * 4);
+            }
+        }
         Step &s = add_step(S_IGEMM, std::string(op_name(o.kind)) + "#" + std::to_string(oi),
                            std::string("igemm_") + op_name(o.kind) + (dt == RL_BF16 ? "_bf16" : "_f32") + "_64x64_gather");
         s.group = gi;
         s.ig = p; s.il = il;
-        s.slot[SL_X] = abuf; s.slot[SL_W] = wbuf; s.slot[SL_Y] = ybuf;
+        s.slot[SL_X] = abuf; s.slot[SL_W] = wbuf; s.slot[SL_Y] = ybuf; s.slot[SL_PART] = part_buf;
+        if (il.splits > 1) s.kernel += "_splitk";
         s.flops = 2.0 * p.M * (double)p.N * p.K / (double)((p.in_dil_m1 + 1) * (p.in_dil_m1 + 1));     // the zeros between dy's pixels are no work
         s.bytes = (double)bytes_of(va) + (double)bytes_of(vb) + (double)bytes_of(vy);
         return RL_OK;
