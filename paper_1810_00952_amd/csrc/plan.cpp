@@ -199,7 +199,15 @@ struct Planner {
     }
 
     // ---- contraction groups ------------------------------------------------
-    rl_status plan_anchor(int gi, const std::vector<int> &ops)
+    // A contraction seen through other eyes than its op's: the gradient with respect to the first operand of a dense
+    // or of a stride-1 conv2d is a dense / a stride-1 conv2d of dy with re-ordered weights, and runs on the same kernels.
+    struct AnchorView {
+        int kind;                         // RL_OP_DENSE or RL_OP_CONV2D
+        int N, KH, KW, ph, pw;            // output channels (features), taps, padding; stride 1; contraction channels come from x
+        GatherPack gp;                    // where the rows of the K-contiguous weight matrix come from
+    };
+
+    rl_status plan_anchor(int gi, const std::vector<int> &ops, const AnchorView *ov = nullptr)
     {
         std::set<int> gset(ops.begin(), ops.end());
         size_t ai = 0;
@@ -212,6 +220,7 @@ struct Planner {
             x2 = cc.in[1];
         }
         const OpNode &an = g.ops[ops[ai]];
+        const int akind = ov ? ov->kind : an.kind;
         if (x < 0) x = an.in[0];
         const int wv = an.in[1];
         if (g.values[wv].role != ROLE_PARAM) return fail(RL_ERR_UNSUPPORTED, "contraction weights must be a param");
@@ -251,14 +260,16 @@ struct Planner {
         bool stem = false;
         const size_t lim = (size_t)1 << 31;
 
-        if (an.kind == RL_OP_CONV2D) {
+        if (akind == RL_OP_CONV2D) {
             const rl_type &xt = T(x), &wt = T(wv);
             p.C = (int)xt.dims[1]; p.H = (int)xt.dims[2]; p.W = (int)xt.dims[3];
             p.KH = (int)wt.dims[2]; p.KW = (int)wt.dims[3];
             p.OH = (int)ot.dims[2]; p.OW = (int)ot.dims[3]; p.OHW = p.OH * p.OW;
             p.sh = an.attrs.stride[0]; p.sw = an.attrs.stride[1]; p.ph = an.attrs.pad[0]; p.pw = an.attrs.pad[1];
+            p.N = (int)wt.dims[0];
+            if (ov) { p.N = ov->N; p.KH = ov->KH; p.KW = ov->KW; p.sh = p.sw = 1; p.ph = ov->ph; p.pw = ov->pw; }
             if (xt.dims[0] * (int64_t)p.OHW > 0x7fffffff) return fail(RL_ERR_UNSUPPORTED, "conv2d too large");
-            p.M = (int)(xt.dims[0] * p.OHW); p.N = (int)wt.dims[0]; p.K = p.C * p.KH * p.KW; p.K1 = p.K;
+            p.M = (int)(xt.dims[0] * p.OHW); p.K = p.C * p.KH * p.KW; p.K1 = p.K;
             p.Kp = (int)round_up(p.K, KV);
             out_layout = (vout >= 0 && out_set.count(vout)) ? L_NATIVE : L_NHWC;
             if (out_layout == L_NHWC) { p.ys_n = (int64_t)p.OHW * p.N; p.ys_p = p.N; p.ys_c = 1; }
@@ -271,7 +282,7 @@ struct Planner {
             const int64_t Hp = (int64_t)(p.OH - 1) * p.sh + 2 * KH2, Wp = (int64_t)(p.OW - 1) * p.sw + 8;
             const size_t frame = (size_t)xt.dims[0] * Hp * Wp * 8;
             stem = in_dt == RL_BF16 && p.C <= 4 && p.KW <= 8 && p.sw % 2 == 0 && KH2 <= 32 && epi_lp && vout >= 0 && T(vout).dtype == RL_BF16 &&
-                   out_layout == L_NHWC && p.N % 8 == 0 && bytes_of(vout) < lim && frame < lim && phys[L_NATIVE][x] >= 0 && !plan.opts.no_stem;
+                   out_layout == L_NHWC && p.N % 8 == 0 && bytes_of(vout) < lim && frame < lim && phys[L_NATIVE][x] >= 0 && !plan.opts.no_stem && !ov;
             if (stem) {
                 int xnat;
                 st = need(x, L_NATIVE, xnat);
@@ -302,15 +313,15 @@ struct Planner {
                 if (xl == L_NHWC) { p.xs_n = (int64_t)p.H * p.W * p.C; p.xs_h = (int64_t)p.W * p.C; p.xs_w = p.C; p.xs_c = 1; }
                 else { p.xs_n = (int64_t)p.C * p.H * p.W; p.xs_c = (int64_t)p.H * p.W; p.xs_h = p.W; p.xs_w = 1; }
                 p.ts_h = p.xs_h; p.ts_w = p.xs_w; p.seg_stride = 64;
-                need_pack = !(p.KH * p.KW == 1 && p.C % KV == 0);
+                need_pack = !(p.KH * p.KW == 1 && p.C % KV == 0) || ov;
                 pack.dtype = in_dt; pack.O = p.N; pack.C = p.C; pack.T = p.KH * p.KW; pack.Kp = p.Kp; pack.perm_block = 0;
                 x_extent = bytes_of(x);
             }
         } else {
             const rl_type &wt = T(wv);
-            const int64_t K = wt.dims[1];
-            if (ot.dims[0] > 0x7fffffff || K > 0x7ffffff0 || wt.dims[0] > 0x7fffffff) return fail(RL_ERR_UNSUPPORTED, "dense too large");
-            p.M = (int)ot.dims[0]; p.N = (int)wt.dims[0]; p.K = (int)K; p.Kp = (int)round_up(K, KV);
+            const int64_t K = ov ? T(x).dims[1] : wt.dims[1], Nf = ov ? ov->N : wt.dims[0];
+            if (ot.dims[0] > 0x7fffffff || K > 0x7ffffff0 || Nf > 0x7fffffff) return fail(RL_ERR_UNSUPPORTED, "dense too large");
+            p.M = (int)ot.dims[0]; p.N = (int)Nf; p.K = (int)K; p.Kp = (int)round_up(K, KV);
             p.C = p.K; p.H = p.W = p.KH = p.KW = p.OH = p.OW = p.OHW = 1; p.sh = p.sw = 1;
             p.K1 = x2 >= 0 ? (int)T(x).dims[1] : p.K;
             const int K2 = p.K - p.K1;
@@ -322,13 +333,13 @@ struct Planner {
             p.ts_h = 0; p.ts_w = 0; p.seg_stride = 64;
             flops = 2.0 * p.M * (double)p.N * p.K;
             x_extent = bytes_of(x);
-            need_pack = (p.K % KV != 0) || gates;
+            need_pack = (p.K % KV != 0) || gates || ov;
             pack.dtype = in_dt; pack.O = p.N; pack.C = p.K; pack.T = 1; pack.Kp = p.Kp; pack.perm_block = gates ? 64 : 0;
             p.ys_n = p.N; p.ys_p = p.N; p.ys_c = 1;
         }
         // 3x3 bf16 weights from 64 to 64 channels carry, behind the matrix, a second copy in the fragment order of the
         // kernel that keeps them in registers (whichever kernel a step ends up with, so that every user agrees)
-        const bool dual = an.kind == RL_OP_CONV2D && !stem && in_dt == RL_BF16 && p.N == 64 && p.C == 64 && p.KH == 3 && p.KW == 3 && p.Kp == p.K;
+        const bool dual = !ov && akind == RL_OP_CONV2D && !stem && in_dt == RL_BF16 && p.N == 64 && p.C == 64 && p.KH == 3 && p.KW == 3 && p.Kp == p.K;
         if (dual) pack.perm_block = -1;
         pack.bytes = (size_t)pack.O * pack.Kp * dtype_size(in_dt);
         // the vector-load kernel addresses its operands with 32-bit byte offsets and wants a K tile
@@ -347,7 +358,7 @@ struct Planner {
                      (x2 < 0 || p.K1 % bke == 0) && x_extent + halo < lim && !plan.opts.no_dma;
             // a dense contraction whose K is a multiple of the vector but not of the K tile: the weights are packed
             // with zeros up to whole tiles and the kernel requests the activation chunks past K out of range
-            if (!il.dma && an.kind == RL_OP_DENSE && !stem && !gates && x2 < 0 && il.avec && p.K % bke != 0 && p.K / bke >= 2 &&
+            if (!il.dma && akind == RL_OP_DENSE && !stem && !gates && x2 < 0 && il.avec && p.K % bke != 0 && p.K / bke >= 2 &&
                 x_extent < lim && (size_t)p.N * round_up(p.K, bke) * dtype_size(in_dt) < lim && !plan.opts.no_dma) {
                 il.dma = 1;
                 p.Kp = (int)round_up(p.K, bke);
@@ -366,7 +377,7 @@ struct Planner {
             il.ws = il.lp && p.N <= 64 && (p.K / bke <= 5 || (p.K / bke <= 9 && plan.opts.ws_all)) && !plan.opts.no_ws;
             // 3x3 / stride 1 / pad 1 from 64 to 64 channels on rows of at most 63 pixels: weights in registers, every
             // input pixel fetched once per region
-            il.c64 = il.lp && !stem && an.kind == RL_OP_CONV2D && p.C == 64 && p.N == 64 && p.KH == 3 && p.KW == 3 && p.sh == 1 && p.sw == 1 &&
+            il.c64 = il.lp && !stem && akind == RL_OP_CONV2D && p.C == 64 && p.N == 64 && p.KH == 3 && p.KW == 3 && p.sh == 1 && p.sw == 1 &&
                      p.ph == 1 && p.pw == 1 && p.OH == p.H && p.OW == p.W && p.W <= 63 && p.Kp == p.K && p.ys_p == 64 && !plan.opts.no_c64;
             il.c64 = il.c64 && dual;
             if (il.c64) { il.ws = 0; p.w_bytes = (uint32_t)pack.bytes; }
@@ -377,9 +388,10 @@ struct Planner {
             if (p.KH * p.KW <= 32)
                 for (int kh = 0; kh < p.KH; ++kh) p.tap_rep |= 1u << (kh * p.KW);
         }
+        if (ov) { pack.gather = 1; pack.gp = ov->gp; pack.gp.Kp = pack.Kp; pack.perm_block = -3; }
         if (need_pack) {
             auto it = plan.packs.find(wv);
-            if (it != plan.packs.end() && (it->second.perm_block != pack.perm_block || it->second.Kp != pack.Kp))
+            if (it != plan.packs.end() && (ov || it->second.perm_block != pack.perm_block || it->second.Kp != pack.Kp))
                 return fail(RL_ERR_UNSUPPORTED, "one param needs two different kernel-native layouts");
             plan.packs[wv] = pack;
         } else if (plan.packs.count(wv)) {
@@ -409,7 +421,7 @@ struct Planner {
 
         // 3x3 / stride 1 / pad 1 on short image rows with whole 64-channel slices: the nine taps of a slice are read
         // from one copy of the input rows (needs one of the larger tiles)
-        il.run = il.lp && !il.c64 && !il.ws && !stem && an.kind == RL_OP_CONV2D && p.KH == 3 && p.KW == 3 && p.sh == 1 && p.sw == 1 && p.ph == 1 &&
+        il.run = il.lp && !il.c64 && !il.ws && !stem && akind == RL_OP_CONV2D && p.KH == 3 && p.KW == 3 && p.sh == 1 && p.sw == 1 && p.ph == 1 &&
                  p.pw == 1 && p.OH == p.H && p.OW == p.W && p.W <= 30 && p.C % 64 == 0 && p.Kp == p.K && il.tile != TILE_64x64 &&
                  !plan.opts.no_run;
         if (il.run && il.tile == TILE_128x64 && p.C % 128 == 0 && !plan.opts.no_run_ks) {
@@ -458,7 +470,7 @@ struct Planner {
             }
         }
         static const char *tile_names[] = {"128x128", "128x64", "64x64", "256x128"};
-        std::string kname = std::string(an.kind == RL_OP_CONV2D ? "igemm_conv2d_" : "igemm_dense_") + (in_dt == RL_BF16 ? "bf16_" : "f32_") +
+        std::string kname = (ov ? std::string("igemm_") + op_name(an.kind) + "_" : std::string(akind == RL_OP_CONV2D ? "igemm_conv2d_" : "igemm_dense_")) + (in_dt == RL_BF16 ? "bf16_" : "f32_") +
                             (il.c64 ? "3x3_c64" : il.ws ? "128x64_ws" : tile_names[il.tile]) + (il.c64 || il.ws ? "" : il.run ? "_run" : il.lp ? "_lp" : il.avec ? (il.dma ? "_dma" : "") : "_gather") + (gates ? "_gates" : "") +
                             (il.splits > 1 ? "_splitk" : "");
         Step &s = add_step(S_IGEMM, std::string(op_name(an.kind)) + "#" + std::to_string(ops[ai]), kname);
@@ -674,6 +686,26 @@ struct Planner {
         gp.dtype = dt;
         if (numel(ta) >= ((int64_t)1 << 31) || numel(tb) >= ((int64_t)1 << 31) || numel(ty) >= ((int64_t)1 << 31))
             return fail(RL_ERR_UNSUPPORTED, std::string(op_name(o.kind)) + ": tensor too large");
+        // With respect to the first operand, through weights that are a param of their own: a dense, or a stride-1 conv2d
+        // with reversed taps and exchanged channel roles, of dy; planned like the forward operator, onto its kernels.
+        if (g.values[vb].role == ROLE_PARAM && consumers[vb].size() == 1 && !plan.packs.count(vb) && !plan.opts.no_grad_fwd) {
+            AnchorView ov{};
+            ov.gp.dtype = dt;
+            if (o.kind == RL_OP_DENSE_GRAD_X) {
+                const int N = (int)ta.dims[1], K = (int)tb.dims[1];
+                ov.kind = RL_OP_DENSE; ov.N = K; ov.KH = ov.KW = 1;
+                ov.gp.R = K; ov.gp.T = 1; ov.gp.TW = 1; ov.gp.Cq = N; ov.gp.s_row = 1; ov.gp.s_c = K;
+                return plan_anchor(gi, std::vector<int>{oi}, &ov);
+            }
+            if (o.kind == RL_OP_CONV2D_GRAD_X && o.attrs.stride[0] == 1 && o.attrs.stride[1] == 1) {
+                const int O = (int)ta.dims[1], C = (int)tb.dims[1], KH = (int)tb.dims[2], KW = (int)tb.dims[3];
+                if (o.attrs.pad[0] > KH - 1 || o.attrs.pad[1] > KW - 1) return fail(RL_ERR_UNSUPPORTED, "conv2d_grad_x: padding larger than the kernel");
+                ov.kind = RL_OP_CONV2D; ov.N = C; ov.KH = KH; ov.KW = KW; ov.ph = KH - 1 - o.attrs.pad[0]; ov.pw = KW - 1 - o.attrs.pad[1];
+                ov.gp.R = C; ov.gp.T = KH * KW; ov.gp.TW = KW; ov.gp.Cq = O;
+                ov.gp.s_row = (int64_t)KH * KW; ov.gp.s_c = (int64_t)C * KH * KW; ov.gp.s_ti = -KW; ov.gp.s_tj = -1; ov.gp.base = (int64_t)KH * KW - 1;
+                return plan_anchor(gi, std::vector<int>{oi}, &ov);
+            }
+        }
         p.C = 1; p.H = p.W = p.KH = p.KW = p.OH = p.OW = p.OHW = 1; p.sh = p.sw = 1;
         if (o.kind == RL_OP_DENSE_GRAD_X) {
             const int M = (int)ta.dims[0], N = (int)ta.dims[1], K = (int)tb.dims[1];

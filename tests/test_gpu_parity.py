@@ -829,6 +829,12 @@ GRAD_CASES = [
     ("conv2d_grad_w", (2, 32, 14, 14, 64, 1), 2, 0, False),
     ("conv2d_grad_w", (1, 3, 33, 33, 16, 7), 2, 3, False),
     ("conv2d_grad_w", (4, 64, 14, 14, 64, 3), 1, 1, False),   # a ResNet block's shape, small batch
+    # through a param at stride 1: planned as the forward operator on re-ordered weights (its fast kernels in bf16)
+    ("conv2d_grad_x", (4, 64, 28, 28, 128, 3), 1, 1, True),
+    ("conv2d_grad_x", (2, 256, 14, 14, 256, 3), 1, 1, True),
+    ("conv2d_grad_x", (3, 64, 20, 20, 64, 3), 1, 1, True),
+    ("conv2d_grad_x", (2, 128, 14, 14, 256, 1), 1, 0, True),
+    ("dense_grad_x", (64, 1000, 512), 1, 0, True),        # ResNet-18's logits layer
 ]
 
 
@@ -842,6 +848,12 @@ def test_gradient_operators(dtype, case):
     kernels = [st["kernel"] for st in s_plan_steps(spec)]
     assert any(k.startswith(f"igemm_{kind}_") for k in kernels), kernels
     assert ("pack_gather" in kernels) == (not is_param), kernels          # a param's operand form is made at prepack time
+    as_forward = is_param and (kind == "dense_grad_x" or (kind == "conv2d_grad_x" and stride == 1))
+    if as_forward:
+        # the same operator on the element-gather kernel, as the other gradients run
+        check_graph(spec, data, f"{kind} {dtype} {dims} s{stride} p{pad} gather", opts={"no_grad_fwd": 1})
+        kernels = [st["kernel"] for st in s_plan_steps(spec, {"no_grad_fwd": 1})]
+        assert any(k.startswith(f"igemm_{kind}_") and "_gather" in k for k in kernels), kernels
     if dtype == "bf16":
         # fp32 results from bf16 operands (what an optimizer would accumulate into): no rounding of the sum at all
         spec32, _ = W.grad_case(kind, dims, dtype, stride, pad, second_is_param=is_param, out_dtype="f32")
@@ -851,9 +863,21 @@ def test_gradient_operators(dtype, case):
         assert_close(out[v], ref[v], "f32", f"{kind} bf16->f32 {dims}", budget=lambda: error_budget(spec32, data)[v])
 
 
-def s_plan_steps(spec):
+def s_plan_steps(spec, opts=None):
     from paper_1810_00952_amd import binding
-    return binding.Plan(binding.graph_from_spec(binding.Context(), spec)).describe()["steps"]
+    return binding.Plan(binding.graph_from_spec(binding.Context(), spec), opts).describe()["steps"]
+
+
+def test_gradient_chain_through_two_convolutions():
+    # dy pushed back through two stacked 3x3 convolutions: the first gradient's result stays channel-last inside the
+    # plan, so it runs on the forward operator's bf16 kernels (nine taps from one copy of the rows)
+    for dtype, N, C, H in (("bf16", 32, 128, 28), ("bf16", 4, 256, 14), ("f32", 2, 64, 12)):
+        g, data = W.grad_chain(N, C, H, 2, dtype)
+        check_graph(g, data, f"two conv2d_grad_x in a row {dtype} {N}x{C}x{H}x{H}")
+        kernels = [st["kernel"] for st in s_plan_steps(g)]
+        print("gradient chain kernels", kernels, flush=True)
+        if dtype == "bf16":
+            assert any(k.startswith("igemm_conv2d_grad_x_bf16") and k.endswith("_run" if N == 32 else "_lp") for k in kernels), kernels
 
 
 def test_gradients_inside_a_graph():

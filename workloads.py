@@ -281,6 +281,23 @@ def grad_case(kind, dims, dtype="f32", stride=1, pad=0, second_is_param=True, ou
     return g, data
 
 
+def grad_chain(n, c, h, depth=2, dtype="bf16", config=23):
+    """dy pushed back through `depth` stacked 3x3 / stride 1 / pad 1 convolutions of c channels: conv2d_grad_x applied
+    `depth` times, each through a param of its own (He-scaled), each a group of its own."""
+    g = GraphSpec("conv_backward_chain")
+    d = g.input("dy", dtype, (n, c, h, h))
+    rng = rng_for(config, salt=n + 3 * c + 5 * h + 7 * depth)
+    data = {"dy": as_dtype(normal(rng, (n, c, h, h)), dtype)}
+    sc = (2.0 / (9 * c)) ** 0.5
+    for i in reversed(range(depth)):
+        w = g.param(f"w{i}", dtype, (c, c, 3, 3))
+        data[f"w{i}"] = as_dtype(normal(rng, (c, c, 3, 3)) * sc, dtype)
+        o, (d,) = g.op("conv2d_grad_x", [d, w], [(dtype, (n, c, h, h))], stride=(1, 1), pad=(1, 1))
+        g.group([o])
+    g.output(d)
+    return g, data
+
+
 def layout_case(shape=(3, 5, 7, 4), perm=(0, 2, 3, 1), dtype="f32", config=11):
     """One change of layout on its own: y = layout_transform(x; perm), y's Shape is x's Shape permuted."""
     rng = rng_for(config, salt=len(shape) * 100 + sum((i + 1) * p for i, p in enumerate(perm)))
