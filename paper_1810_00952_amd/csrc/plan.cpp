@@ -373,7 +373,7 @@ struct Planner {
             il.lp = stem || (il.avec && in_dt == RL_BF16 && p.C % bke == 0 && p.K % bke == 0 && p.KH * p.KW <= 32 && x2 < 0 && !gates &&
                              x_extent + halo < lim && epi_lp && y_ok && !plan.opts.no_lp);
             // weights-stationary persistent variant: pays off when the weights leave LDS for a deep ring (K <= 320);
-            // RELAYHIP_WS_ALL=1 also takes it up to K = 576, where its shallower ring is latency-bound
+            // the plan option ws_all also takes it up to K = 576, where its shallower ring is latency-bound
             il.ws = il.lp && p.N <= 64 && (p.K / bke <= 5 || (p.K / bke <= 9 && plan.opts.ws_all)) && !plan.opts.no_ws;
             // 3x3 / stride 1 / pad 1 from 64 to 64 channels on rows of at most 63 pixels: weights in registers, every
             // input pixel fetched once per region
