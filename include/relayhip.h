@@ -203,8 +203,9 @@ typedef struct rl_plan_opts {
 } rl_plan_opts;
 
 /* rl_plan_create re-checks the whole graph (Type-Call on every call, group legality, outputs reachable), picks
- * one kernel per fusion group, tiles and private layouts, and sizes the workspace -- the paper's evaluator
- * "producing a type-specialised operator per call" (section "Runtime System"), done once ahead of the runs.
+ * one kernel per fusion group, tiles and private layouts, and sizes the workspace -- the role the paper gives
+ * its evaluator's just-in-time operator compiler (section "Runtime System": one operator specialised to the types of
+ * each call), done once ahead of the runs.
  * It needs no GPU.  opts may be NULL.  The graph may be destroyed afterwards.  Errors: RL_ERR_NULL, RL_ERR_KIND
  * (opts->struct_size larger than the library knows), RL_ERR_TYPE / RL_ERR_GROUP (graph), RL_ERR_UNSUPPORTED. */
 rl_status rl_plan_create(rl_graph *g, const rl_plan_opts *opts, rl_plan **out);
@@ -215,12 +216,18 @@ rl_status rl_plan_describe(const rl_plan *plan, char *buf, size_t cap, size_t *n
 rl_status rl_plan_workspace_bytes(const rl_plan *plan, size_t *bytes);
 /* Bytes of the kernel-native copy of a param, or 0 when the param is bound as is. */
 rl_status rl_plan_packed_bytes(const rl_plan *plan, int32_t param_value_id, size_t *bytes);
-/* Enqueue the re-layout of one param: src_dev holds it in boundary layout,
- * dst_dev (rl_plan_packed_bytes bytes) receives the kernel-native copy, which
- * is what rl_plan_run must then be given for that value id. */
+/* Enqueue the re-layout of one param: src_dev holds it in boundary layout (dense row-major in the order of its
+ * Shape), dst_dev (rl_plan_packed_bytes bytes, caller-owned) receives the kernel-native copy, which is what
+ * rl_plan_run must then be given for that value id.  This is the "layout change" of the paper's list of high-level
+ * optimisations (section "Background") applied to constants, once, outside the runs; the typed graph never sees it
+ * (the paper's types carry no layout: section on future extensions).  Asynchronous on hip_stream; src and dst must not
+ * overlap.  Errors: RL_ERR_NULL, RL_ERR_BINDING (not a param of this plan, or one that is bound as is), RL_ERR_HIP. */
 rl_status rl_plan_prepack(const rl_plan *plan, int32_t param_value_id, const void *src_dev, void *dst_dev,
                           void *hip_stream);
-/* Enqueue every step of the plan.  bindings must cover every input, param
+/* Execute the typed graph: every fusion group's type-specialised kernel in dependency order -- what the paper's
+ * run time does with a checked program (section "Runtime System"), with the fusion and memory reuse its section
+ * "Background" lists among the optimisations below the graph decided beforehand by rl_plan_create.
+ * Enqueues every step of the plan.  bindings must cover every input, param
  * (packed copy where rl_plan_packed_bytes > 0) and output value id exactly
  * once; intermediates live in workspace_dev (>= rl_plan_workspace_bytes).
  * Inputs and params are read only; outputs and workspace are overwritten.
@@ -258,7 +265,9 @@ rl_status rl_plan_profile(const rl_plan *plan, const rl_binding *bindings, int32
  * receives workgroups * 512 floats (ignore them).  Errors: RL_ERR_NULL, RL_ERR_BINDING (counts < 1), RL_ERR_HIP. */
 rl_status rl_calibrate_mfma_bf16(rl_ctx *ctx, void *scratch_dev, int32_t workgroups, int32_t iters, void *hip_stream);
 
-/* Recurrent execution of a one-step cell plan for `steps` steps: at step t the
+/* Recurrent execution of a one-step cell plan for `steps` steps.  The paper's language expresses a recurrent model as
+ * a recursive function over its time steps (section "Grammar and Design": recursion and conditionals are part of the
+ * language; its evaluator would call the cell's operators once per step); this call is that loop for a cell whose types are checked once: at step t the
  * cell's x input is x_seq_dev + t*x_step_bytes, its h input is h0_dev (t = 0)
  * or the previous step's h output, its c input/output is c_dev (updated in
  * place; the caller initialises it), and its h output is written to
@@ -285,7 +294,9 @@ rl_status rl_plan_run_recurrent(const rl_plan *cell, int32_t steps, const rl_rec
                                 void *workspace_dev, size_t workspace_bytes, void *hip_stream);
 
 /* ---- one-time weight preparation (device side, asynchronous) ------------- */
-/* Fold an inference batch-norm into the preceding convolution:
+/* Fold an inference batch-norm into the preceding convolution -- a rewrite of constants of the kind the paper leaves to
+ * optimisation passes over the typed program (section "Optimizations"; the paper prints no formula, this is the
+ * textbook one):
  * scale[o] = gamma[o]/sqrt(var[o]+eps); w_out[o,:] = w[o,:]*scale[o];
  * b_out[o] = beta[o] - mean[o]*scale[o], evaluated in float64 and rounded to
  * f32 (then to out_dtype for w_out).  w: f32 [O, per_o]; gamma..var, b_out:
