@@ -326,6 +326,7 @@ rl_status rl_plan_prepack(const rl_plan *plan, int32_t v, const void *src, void 
         if (((uintptr_t)src & 15) || ((uintptr_t)dst & 15)) return fail(err, RL_ERR_ALIGN, "device pointer is not 16-byte aligned");
         const PackSpec &k = it->second;
         hipError_t er = k.gather ? launch_pack_gather(src, dst, k.gp, (hipStream_t)stream)
+                      : k.stem == 2 ? launch_pack_weight_stem_direct(src, dst, k.O, k.C, k.KH, k.KW, k.pw, (hipStream_t)stream)
                       : k.stem ? launch_pack_weight_stem(src, dst, k.O, k.C, k.KH, k.KW, k.Kp, (hipStream_t)stream)
                                : launch_pack_weight(src, dst, k.dtype, k.O, k.C, k.T, k.Kp, k.perm_block, (hipStream_t)stream);
         if (er != hipSuccess) return fail(err, RL_ERR_HIP, std::string("pack_weight: ") + hipGetErrorString(er));

@@ -772,6 +772,31 @@ hipError_t launch_pack_weight_stem(const void *src, void *dst, int32_t O, int32_
     return hipGetLastError();
 }
 
+// weights of the stem kernel that reads the channel-first input: contraction index 16 (c ceil(KH/2) + kh/2) + 8 (kh & 1) + j,
+// window column j = kw + (pw & 1); zeros where the filter does not reach and past the last plane
+__global__ __launch_bounds__(256) void pack_weight_stem_direct_kernel(const uint16_t *__restrict__ src, uint16_t *__restrict__ dst, int O, int C,
+                                                                      int KH, int KW, int e)
+{
+    const int total = O * STEM_DIRECT_KP;
+    for (int idx = blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += gridDim.x * blockDim.x) {
+        const int k = idx % STEM_DIRECT_KP, o = idx / STEM_DIRECT_KP;
+        const int khh = (KH + 1) >> 1;
+        const int ks = k >> 4, kw = (k & 7) - e;
+        const int c = ks / khh, kh = 2 * (ks - c * khh) + ((k >> 3) & 1);
+        uint16_t v = 0;
+        if (c < C && kh < KH && kw >= 0 && kw < KW) v = src[(((int64_t)o * C + c) * KH + kh) * KW + kw];
+        dst[idx] = v;
+    }
+}
+
+hipError_t launch_pack_weight_stem_direct(const void *src, void *dst, int32_t O, int32_t C, int32_t KH, int32_t KW, int32_t pw, hipStream_t s)
+{
+    if (O < 1 || O > (1 << 20) || C < 1 || KH < 1 || KW < 1 || C * ((KH + 1) / 2) * 16 > STEM_DIRECT_KP || KW + (pw & 1) > 8) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(pack_weight_stem_direct_kernel, dim3(grid_for((int64_t)O * STEM_DIRECT_KP)), dim3(256), 0, s, (const uint16_t *)src,
+                       (uint16_t *)dst, O, C, KH, KW, pw & 1);
+    return hipGetLastError();
+}
+
 // ---------------------------------------------------------------------------
 // batch-norm folding, float64 arithmetic
 // ---------------------------------------------------------------------------

@@ -130,6 +130,20 @@ struct StemPoolParams {
 };
 hipError_t launch_stem_pool(const StemPoolParams &q, hipStream_t s);
 
+// ---- the same fusion reading the channel-first input itself (stem_direct.hip) ----
+constexpr int STEM_DIRECT_KP = 192;     // contraction length of its packed weights: 12 k-steps of 16 = (plane, pair of filter rows) x 2 rows x 8 columns
+struct StemDirectParams {
+    const void *x; uint32_t x_bytes;    // [n_img, C, H, W] bf16, 4-byte aligned
+    const void *w; uint32_t w_bytes;    // [64][STEM_DIRECT_KP] bf16 (launch_pack_weight_stem_direct)
+    Epilogue epi;                       // [f32 bias] [relu]
+    void *yp; uint32_t yp_bytes;        // pooled output [n_img, PH, PW, 64] bf16
+    int32_t n_img, C, H, W, KH, KW, ph, pw, OH, OW, PH, PW;
+};
+bool stem_direct_ok(int32_t C, int32_t H, int32_t W, int32_t KH, int32_t KW, int32_t ph, int32_t pw);
+hipError_t launch_stem_pool_direct(const StemDirectParams &q, hipStream_t s);
+// weights [64, C, KH, KW] -> [64][STEM_DIRECT_KP]: index 16 (c ceil(KH/2) + kh/2) + 8 (kh & 1) + kw + (pw & 1), zeros elsewhere
+hipError_t launch_pack_weight_stem_direct(const void *src, void *dst, int32_t O, int32_t C, int32_t KH, int32_t KW, int32_t pw, hipStream_t s);
+
 // ---- one LSTM step on a precomputed input projection (lstm_step.hip) ------
 struct LstmStepParams {
     const void *h_prev;                 // [B, H] bf16

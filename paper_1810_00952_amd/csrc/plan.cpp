@@ -954,19 +954,50 @@ struct Planner {
             const PoolParams &po = m.po;
             Epilogue e = g.epi;                 // wanted: [f32 bias] [relu] and nothing else
             finalize_epilogue(e);
-            if (other_use || g.sh != 2 || g.sw != 2 || g.N != 64 || g.K != 256 || g.Kp != 256 || g.KH != 4 || g.y_dtype != DT_BF16 || po.dtype != DT_BF16 || po.C != 64 ||
+            if (other_use || g.sh != 2 || g.sw != 2 || g.N != 64 || g.y_dtype != DT_BF16 || po.dtype != DT_BF16 || po.C != 64 ||
                 po.KH != 3 || po.KW != 3 || po.sh != 2 || po.sw != 2 || po.ph != 1 || po.pw != 1 || po.H != g.OH || po.W != g.OW ||
                 po.OH != (g.OH - 1) / 2 + 1 || po.OW != (g.OW - 1) / 2 + 1 || !e.simple || e.t_op >= 0 ||
                 (e.has_bias && e.bias_dtype != DT_F32) || (e.rest_n != 0 && !e.relu_last) ||
                 (uint64_t)po.N * po.OH * po.OW * 64 * 2 >= ((uint64_t)1 << 31))
                 continue;
+            // Two forms of the fused kernel.  One fetches its patches from the channel-first planes themselves: the frame
+            // copy in front of this step (the step before, whose result only this step reads) then goes, and the weights
+            // are packed for that kernel's contraction order instead.  The other reads the frame (exactly four K tiles).
+            bool direct = false;
+            if (si > 0 && !plan.opts.no_stem_direct) {
+                const Step &pd = plan.steps[si - 1];
+                const int wbuf = c.slot[SL_W];
+                const int wv = wbuf >= 0 ? plan.bufs[wbuf].bound_value : -1;
+                auto pk = wv >= 0 ? plan.packs.find(wv) : plan.packs.end();
+                bool frame_private = pd.kind == S_STEM_PAD && pd.slot[SL_Y] == c.slot[SL_X];
+                for (size_t sj = 0; frame_private && sj < plan.steps.size(); ++sj)
+                    if (sj != si && sj != si - 1)
+                        for (int b : plan.steps[sj].slot) frame_private &= (b != pd.slot[SL_Y]);
+                direct = frame_private && pk != plan.packs.end() && pk->second.stem == 1 && consumers[wv].size() == 1 &&
+                         stem_direct_ok(pd.t_C, pd.st_H, pd.st_W, pk->second.KH, pk->second.KW, pd.st_ph, pd.st_pw) &&
+                         (uint64_t)pd.t_N * pd.t_C * pd.st_H * pd.st_W * 2 < ((uint64_t)1 << 31);
+                if (direct) {
+                    c.stem_direct = 1;
+                    c.t_N = pd.t_N; c.t_C = pd.t_C; c.st_H = pd.st_H; c.st_W = pd.st_W; c.st_ph = pd.st_ph; c.st_pw = pd.st_pw;
+                    c.stem_kh = pk->second.KH; c.stem_kw = pk->second.KW;
+                    c.bytes += (double)plan.bufs[pd.slot[SL_X]].bytes - (double)plan.bufs[pd.slot[SL_Y]].bytes;
+                    c.slot[SL_X] = pd.slot[SL_X];
+                    PackSpec &ps = pk->second;
+                    ps.stem = 2; ps.pw = pd.st_pw; ps.Kp = STEM_DIRECT_KP; ps.bytes = (size_t)ps.O * STEM_DIRECT_KP * 2;
+                }
+            }
+            if (!direct && (g.K != 256 || g.Kp != 256 || g.KH != 4)) continue;
             c.kind = S_STEM_POOL;
             c.sp_N = po.N; c.sp_PH = po.OH; c.sp_PW = po.OW;
             c.slot[SL_Y] = m.slot[SL_Y];
             c.name += "+" + m.name;
-            c.kernel = "igemm_conv2d_bf16_stem_maxpool";
+            c.kernel = direct ? "igemm_conv2d_bf16_stem_maxpool_direct" : "igemm_conv2d_bf16_stem_maxpool";
             c.bytes = c.bytes - (double)plan.bufs[mid].bytes + (double)plan.bufs[m.slot[SL_Y]].bytes;
             plan.steps.erase(plan.steps.begin() + (long)si + 1);
+            if (direct) {
+                plan.steps.erase(plan.steps.begin() + (long)si - 1);
+                --si;
+            }
         }
     }
 
@@ -1176,6 +1207,21 @@ rl_status run_steps(const Plan &plan, void *const *ptrs, hipStream_t stream, std
             er = launch_nhwc_to_nchw(P(s, SL_X), P(s, SL_Y), s.t_dtype, s.t_N, s.t_C, s.t_P, stream);
             break;
         case S_STEM_POOL: {
+            if (s.stem_direct) {
+                StemDirectParams q{};
+                q.x = P(s, SL_X); q.w = P(s, SL_W);
+                q.x_bytes = (uint32_t)((uint64_t)s.t_N * s.t_C * s.st_H * s.st_W * 2);
+                q.w_bytes = (uint32_t)(64 * STEM_DIRECT_KP * 2);
+                q.epi = s.ig.epi;
+                for (int i = 0; i < RL_EPI_MAX_PTRS; ++i) q.epi.ptr[i] = P(s, SL_E0 + i);
+                finalize_epilogue(q.epi);
+                q.yp = P(s, SL_Y);
+                q.yp_bytes = (uint32_t)((uint64_t)s.sp_N * s.sp_PH * s.sp_PW * 64 * 2);
+                q.n_img = s.sp_N; q.C = s.t_C; q.H = s.st_H; q.W = s.st_W; q.KH = s.stem_kh; q.KW = s.stem_kw; q.ph = s.st_ph; q.pw = s.st_pw;
+                q.OH = s.ig.OH; q.OW = s.ig.OW; q.PH = s.sp_PH; q.PW = s.sp_PW;
+                er = launch_stem_pool_direct(q, stream);
+                break;
+            }
             StemPoolParams q{};
             q.g = s.ig;
             q.g.x = P(s, SL_X); q.g.w = P(s, SL_W); q.g.y = nullptr;

@@ -36,6 +36,7 @@ struct Step {
     int stem = 0;                       // S_IGEMM: the few-channel stem form (padded 4-channel frame, regrouped taps)
     int sp_N = 0, sp_PH = 0, sp_PW = 0; // S_STEM_POOL: images and pooled size (ig: the stem contraction)
     int stem_kh = 0;                    // stem contractions: the filter's own height (ig.KH counts pairs of frame rows)
+    int stem_direct = 0, stem_kw = 0;   // S_STEM_POOL reading the channel-first input itself (st_* and t_C: its geometry; stem_kw: filter width)
     int pair = 0;                       // S_IGEMM: 1: launched together with the next step (an independent contraction of the
                                         // same tile shape); 2: that next step, which launches nothing itself
     int slot[SL_COUNT];
@@ -45,7 +46,8 @@ struct Step {
 
 struct PackSpec {
     int dtype = 0, O = 0, C = 0, T = 0, Kp = 0, perm_block = 0;   // perm_block -1: matrix, then the 64x64x3x3 fragment-order copy
-    int stem = 0, KH = 0, KW = 0;      // stem = 1: few-channel stem layout (launch_pack_weight_stem)
+    int stem = 0, KH = 0, KW = 0;      // stem = 1: few-channel stem layout (launch_pack_weight_stem); 2: launch_pack_weight_stem_direct
+    int pw = 0;                         // stem = 2: the convolution's left padding (its parity shifts the filter inside the 8-pixel window)
     int gather = 0; GatherPack gp{};   // gather = 1: launch_pack_gather (operands of the gradient operators)
     size_t bytes = 0;
 };

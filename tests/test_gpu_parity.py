@@ -158,6 +158,9 @@ STEM_POOL_CASES = [
     (9, 4, 61, 127, 8, 2, 3, True, True),
     (1, 3, 7, 250, 7, 2, 3, False, True),
     (64, 3, 224, 224, 7, 2, 3, True, True),          # the benchmark's stem at full size: 12 544 regions streaming through 512 workgroups
+    (4, 2, 30, 46, 5, 2, 2, False, True),            # two planes, 5x5 with even padding (the window starts at the filter)
+    (3, 3, 40, 38, 8, 2, 4, True, False),            # 8x8 filter, even padding: every window column and both rows of the last pair used
+    (2, 3, 9, 12, 3, 2, 1, True, True),              # 3x3: two row pairs per plane, half of the second one zero weights
 ]
 
 
@@ -166,11 +169,19 @@ def test_stem_conv_with_maxpool_in_one_kernel(case):
     b, ci, h, w, k, s_, p, relu, tail = case
     spec, data = W.conv_pool(b, ci, 64, h, w, k, s_, p, "bf16", relu=relu, tail=tail)
     from paper_1810_00952_amd import binding
-    desc = binding.Plan(binding.graph_from_spec(binding.Context(), spec)).describe()
-    assert any(st["kernel"] == "igemm_conv2d_bf16_stem_maxpool" for st in desc["steps"]), [st["kernel"] for st in desc["steps"]]
+    kernels = [st["kernel"] for st in binding.Plan(binding.graph_from_spec(binding.Context(), spec)).describe()["steps"]]
+    # up to three planes of even width, and a filter that fits the 8-pixel window: patches fetched from the channel-first
+    # input itself, no frame copy; everything else through the padded 4-channel frame
+    direct = ci <= 3 and w % 2 == 0 and k + (p & 1) <= 8
+    assert ("igemm_conv2d_bf16_stem_maxpool_direct" in kernels) == direct and ("stem_pad_nhwc4" in kernels) == (not direct), kernels
+    assert any(kn.startswith("igemm_conv2d_bf16_stem_maxpool") for kn in kernels), kernels
     print(f"stem+pool case {case}", flush=True)
-    got, _ = check_graph(spec, data, f"stem+pool {case}")
-    # the two-kernel form of the same plan gives the same bits: max commutes with bias, ReLU and the rounding
+    check_graph(spec, data, f"stem+pool {case}")
+    # the frame form of the fused kernel (filters 7 or 8 rows high; its own contraction order) ...
+    kernels = [st["kernel"] for st in binding.Plan(binding.graph_from_spec(binding.Context(), spec), {"no_stem_direct": 1}).describe()["steps"]]
+    assert ("igemm_conv2d_bf16_stem_maxpool" in kernels) == (k >= 7) and "stem_pad_nhwc4" in kernels, kernels
+    got, _ = check_graph(spec, data, f"stem+pool {case} from the frame", opts={"no_stem_direct": 1})
+    # ... gives the same bits as the two-kernel form of the same plan: max commutes with bias, ReLU and the rounding
     desc = binding.Plan(binding.graph_from_spec(binding.Context(), spec), {"no_stem_pool": 1}).describe()
     assert any(st["kernel"] == "maxpool_nhwc" for st in desc["steps"])
     two, _ = run_hip(spec, data, opts={"no_stem_pool": 1})

@@ -84,7 +84,10 @@ def test_resnet18_plan_structure():
     assert sum(" | " in s["name"] for s in d["steps"]) == 3
     assert sum(k.startswith("igemm_dense") for k in kernels) == 1
     # the stem group and the max-pool group behind it run as one kernel; the pool kernel is gone from the plan
-    assert kernels.count("igemm_conv2d_bf16_stem_maxpool") == 1 and kernels.count("maxpool_nhwc") == 0
+    # (and it reads the channel-first input itself: no frame copy in front of it)
+    assert kernels.count("igemm_conv2d_bf16_stem_maxpool_direct") == 1 and kernels.count("maxpool_nhwc") == 0 and kernels.count("stem_pad_nhwc4") == 0
+    k2 = [s["kernel"] for s in B.Plan(B.graph_from_spec(ctx, spec), {"no_stem_direct": 1}).describe()["steps"]]
+    assert k2.count("igemm_conv2d_bf16_stem_maxpool") == 1 and k2.count("stem_pad_nhwc4") == 1 and len(k2) == len(kernels) + 1
     assert kernels.count("gavgpool_nhwc") == 1
     flops = sum(s["flops"] for s in d["steps"] if s["kernel"].startswith("igemm"))
     assert flops == 2 * 64 * (1813561344 + 512000)
