@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "librelayhip.so")
-SOURCES = ["api.cpp", "graph.cpp", "plan.cpp", "igemm.hip", "igemm_fast.hip", "igemm_dma.hip", "igemm_lp.hip", "igemm_ws.hip", "lstm_step.hip", "stem_pool.hip", "conv3x3_c64.hip", "conv3x3_run.hip", "conv3x3s2.hip", "eltwise.hip", "static_ws.hip", "calibrate.hip", "stem_direct.hip"]
+SOURCES = ["api.cpp", "graph.cpp", "plan.cpp", "igemm.hip", "igemm_fast.hip", "igemm_dma.hip", "igemm_lp.hip", "igemm_ws.hip", "lstm_step.hip", "stem_pool.hip", "conv3x3_c64.hip", "conv3x3_run.hip", "conv3x3s2.hip", "eltwise.hip", "static_ws.hip", "calibrate.hip", "stem_direct.hip", "conv_wgrad.hip"]
 HEADERS = ["graph.h", "plan.h", "handles.h", "kernels.h", "device_utils.h", "igemm_epilogue.h", os.path.join("..", "..", "include", "relayhip.h")]
 FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -738,6 +738,9 @@ struct Planner {
             const int Nb = (int)ta.dims[0], O = (int)ta.dims[1], OH = (int)ta.dims[2], OW = (int)ta.dims[3];
             const int C = (int)tb.dims[1], H = (int)tb.dims[2], W = (int)tb.dims[3], KH = (int)ty.dims[2], KW = (int)ty.dims[3];
             if (o.attrs.stride[0] != o.attrs.stride[1]) return fail(RL_ERR_UNSUPPORTED, "conv2d_grad_w: strides must agree");
+            if (dt == RL_BF16 && conv_wgrad_ok(Nb, O, C, KH, KW, o.attrs.stride[0]) && o.attrs.pad[0] < KH && o.attrs.pad[1] < KW &&
+                bytes_of(va) < ((size_t)1 << 31) && bytes_of(vb) < ((size_t)1 << 31) && !plan.opts.no_wgrad)
+                return plan_wgrad(gi, oi);
             if ((int64_t)Nb * OH * OW > 0x7ffffff0) return fail(RL_ERR_UNSUPPORTED, "conv2d_grad_w too large");
             p.M = C * KH * KW; p.N = O; p.K = Nb * OH * OW; p.C = Nb;
             p.H = H; p.W = W; p.KH = OH; p.KW = OW; p.OH = KH; p.OW = KW; p.OHW = KH * KW;
@@ -812,6 +815,67 @@ struct Planner {
         if (il.splits > 1) s.kernel += "_splitk";
         s.flops = 2.0 * p.M * (double)p.N * p.K / (double)((p.in_dil_m1 + 1) * (p.in_dil_m1 + 1));     // the zeros between dy's pixels are no work
         s.bytes = (double)bytes_of(va) + (double)bytes_of(vb) + (double)bytes_of(vy);
+        return RL_OK;
+    }
+
+    // conv2d_grad_w on bf16 batches of 64: both operands transposed so that the images are the fastest axis (two steps),
+    // the contraction per output pixel and filter tap (conv_wgrad.hip), the row segments' sums added in order (a step).
+    rl_status plan_wgrad(int gi, int oi)
+    {
+        const OpNode &o = g.ops[oi];
+        const int vdy = o.in[0], vx = o.in[1], vy = o.out[0];
+        const rl_type &ta = T(vdy), &tb = T(vx), &ty = T(vy);
+        const int Nb = (int)ta.dims[0], O = (int)ta.dims[1], OH = (int)ta.dims[2], OW = (int)ta.dims[3];
+        const int C = (int)tb.dims[1], H = (int)tb.dims[2], W = (int)tb.dims[3], KH = (int)ty.dims[2], KW = (int)ty.dims[3];
+        WgradParams w{};
+        w.O = O; w.C = C; w.H = H; w.W = W; w.OH = OH; w.OW = OW; w.KH = KH; w.KW = KW;
+        w.s = o.attrs.stride[0]; w.ph = o.attrs.pad[0]; w.pw = o.attrs.pad[1];
+        // an operand as the plan holds it (channel-last if some group already wrote or asked for that, else as declared),
+        // viewed as a matrix [images][everything else] and transposed
+        auto batch_last = [&](int v, int Cc, int P, int64_t &s_pix, int64_t &s_ch, int &tbuf) -> rl_status {
+            int src;
+            const bool cl = phys[L_NHWC][v] >= 0;
+            rl_status st = need(v, cl ? L_NHWC : L_NATIVE, src);
+            if (st != RL_OK) return st;
+            if (cl) { s_pix = (int64_t)Cc * Nb; s_ch = Nb; }
+            else { s_pix = Nb; s_ch = (int64_t)P * Nb; }
+            tbuf = new_ws(bytes_of(v));
+            Step &ts = add_step(S_TO_NHWC, std::string(op_name(o.kind)) + "#" + std::to_string(oi) + ".images_last", "transpose_images_last");
+            ts.group = gi;
+            ts.t_dtype = T(v).dtype; ts.t_N = 1; ts.t_C = Nb; ts.t_P = Cc * P;
+            ts.slot[SL_X] = src; ts.slot[SL_Y] = tbuf;
+            ts.bytes = 2.0 * bytes_of(v);
+            return RL_OK;
+        };
+        int dyT, xT;
+        rl_status st = batch_last(vdy, O, OH * OW, w.ys_pix, w.ys_o, dyT);
+        if (st != RL_OK) return st;
+        st = batch_last(vx, C, H * W, w.xs_pix, w.xs_c, xT);
+        if (st != RL_OK) return st;
+        w.n_ot = O % 128 == 0 ? O / 128 : O / 64;
+        w.n_ct = C / 64;
+        // one workgroup per CU (its LDS is full): as many row segments as keep the grid within one round
+        const int tiles = OH * w.n_ot * w.n_ct;
+        int nseg = std::max(1, std::min(OW, 256 / std::max(tiles, 1)));
+        w.L = (OW + nseg - 1) / nseg;
+        w.nseg = (OW + w.L - 1) / w.L;
+        const int chunks = OH * w.nseg, Tt = KH * KW;
+        const size_t part_bytes = (size_t)chunks * Tt * O * C * 4;
+        if (part_bytes >= ((size_t)1 << 32)) return fail(RL_ERR_UNSUPPORTED, "conv2d_grad_w: partial sums too large");
+        const int part = new_ws(part_bytes);
+        Step &s = add_step(S_WGRAD, std::string(op_name(o.kind)) + "#" + std::to_string(oi), std::string("conv2d_grad_w_bf16_") + (O % 128 == 0 ? "128x64" : "64x64") + "_images_last");
+        s.group = gi;
+        s.wg = w;
+        s.slot[SL_X] = xT; s.slot[SL_X2] = dyT; s.slot[SL_PART] = part;
+        s.flops = 2.0 * Nb * OH * OW * (double)O * C * Tt;
+        s.bytes = (double)bytes_of(vdy) + (double)bytes_of(vx) + (double)part_bytes;
+        const int ybuf = out_buf(vy, L_NATIVE);
+        Step &r = add_step(S_WGRAD_REDUCE, std::string(op_name(o.kind)) + "#" + std::to_string(oi) + ".segments", "wgrad_reduce");
+        r.group = gi;
+        r.wg = w;
+        r.t_dtype = ty.dtype; r.t_N = chunks; r.t_C = Tt;
+        r.slot[SL_X] = part; r.slot[SL_Y] = ybuf;
+        r.bytes = (double)part_bytes + (double)bytes_of(vy);
         return RL_OK;
     }
 
@@ -1242,6 +1306,17 @@ rl_status run_steps(const Plan &plan, void *const *ptrs, hipStream_t stream, std
         }
         case S_PACK:
             er = launch_pack_gather(P(s, SL_X), P(s, SL_Y), s.gp, stream);
+            break;
+        case S_WGRAD: {
+            WgradParams q = s.wg;
+            q.xT = P(s, SL_X); q.dyT = P(s, SL_X2); q.part = (float *)P(s, SL_PART);
+            q.dy_bytes = (uint32_t)((uint64_t)q.OH * q.OW * q.O * 64 * 2);
+            q.x_bytes = (uint32_t)((uint64_t)q.H * q.W * q.C * 64 * 2);
+            er = launch_conv_wgrad(q, stream);
+            break;
+        }
+        case S_WGRAD_REDUCE:
+            er = launch_wgrad_reduce((const float *)P(s, SL_X), P(s, SL_Y), s.t_dtype, s.t_N, s.t_C, s.wg.O, s.wg.C, stream);
             break;
         case S_STEM_PAD:
             er = launch_stem_pad(P(s, SL_X), P(s, SL_Y), s.t_N, s.t_C, s.st_H, s.st_W, s.st_Hp, s.st_Wp, s.st_ph, s.st_pw, stream);

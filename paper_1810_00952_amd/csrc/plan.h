@@ -10,7 +10,7 @@
 
 namespace rl {
 
-enum StepKind { S_IGEMM = 0, S_ELTWISE, S_GATES, S_MAXPOOL, S_GAVG, S_TO_NHWC, S_TO_NCHW, S_STEM_PAD, S_STEM_POOL, S_PERMUTE, S_PACK };
+enum StepKind { S_IGEMM = 0, S_ELTWISE, S_GATES, S_MAXPOOL, S_GAVG, S_TO_NHWC, S_TO_NCHW, S_STEM_PAD, S_STEM_POOL, S_PERMUTE, S_PACK, S_WGRAD, S_WGRAD_REDUCE };
 enum Slot { SL_X = 0, SL_X2, SL_W, SL_Y, SL_E0, SL_E1, SL_E2, SL_E3, SL_E4, SL_E5, SL_CIN, SL_COUT, SL_HOUT, SL_PART, SL_COUNT };
 
 struct BufDesc {
@@ -30,6 +30,7 @@ struct Step {
     GatesParams ga{};
     PoolParams po{};
     PermuteParams pe{};
+    WgradParams wg{};                   // S_WGRAD (and the counts S_WGRAD_REDUCE adds up)
     GatherPack gp{};                    // S_PACK: an activation gathered into the K-contiguous rows a contraction reads
     int t_dtype = 0, t_N = 0, t_C = 0, t_P = 0;
     int st_H = 0, st_W = 0, st_Hp = 0, st_Wp = 0, st_ph = 0, st_pw = 0;   // S_STEM_PAD geometry (t_N, t_C: batch, channels)

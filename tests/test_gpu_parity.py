@@ -879,6 +879,42 @@ def s_plan_steps(spec, opts=None):
     return binding.Plan(binding.graph_from_spec(binding.Context(), spec), opts).describe()["steps"]
 
 
+# conv2d_grad_w on bf16 batches of 64: both operands transposed to images-last, one contraction per output pixel and tap.
+WGRAD_CASES = [
+    # n   c    h   w   o   k  s  p
+    (64, 64, 6, 6, 64, 3, 1, 1),          # 64-channel blocks (four waves), one segment per row
+    (64, 128, 7, 9, 128, 3, 1, 1),        # 128 output channels (eight waves), two blocks of input channels, ragged segments
+    (64, 64, 9, 8, 128, 3, 2, 1),         # stride 2: two new window columns per pixel; (H + 2p - K) % s = 0 for H and 1 for W
+    (64, 64, 8, 8, 128, 1, 2, 0),         # the 1x1 / stride 2 projection
+    (64, 64, 5, 5, 64, 3, 1, 0),          # no padding: every tap inside the image
+    (64, 128, 10, 6, 64, 3, 2, 1),
+    (64, 64, 30, 3, 64, 3, 1, 1),         # more rows than columns: one pixel per segment
+    (64, 192, 4, 33, 192, 3, 1, 1),       # 192 = 3 x 64 channels on both sides (64-wide output blocks), long rows
+]
+
+
+@pytest.mark.parametrize("case", WGRAD_CASES, ids=[f"wgrad{i}" for i in range(len(WGRAD_CASES))])
+def test_conv2d_grad_w_images_last(case):
+    n, c, h, w, o, k, stride, pad = case
+    for out_dtype in (None, "f32"):
+        spec, data = W.grad_case("conv2d_grad_w", (n, c, h, w, o, k), "bf16", stride, pad, second_is_param=False, out_dtype=out_dtype)
+        kernels = [st["kernel"] for st in s_plan_steps(spec)]
+        assert kernels.count("transpose_images_last") == 2 and "wgrad_reduce" in kernels and any(kn.startswith("conv2d_grad_w_bf16_") for kn in kernels), kernels
+        print(f"wgrad case {case} {out_dtype}", flush=True)
+        v = spec.outputs[0]
+        if out_dtype == "f32":
+            ref = OG.run(spec, data)
+            out, _ = run_hip(spec, data)
+            assert_close(out[v], ref[v], "f32", f"conv2d_grad_w images-last bf16->f32 {case}", budget=lambda: error_budget(spec, data)[v])
+        else:
+            check_graph(spec, data, f"conv2d_grad_w images-last {case}")
+    # the element-gather form of the same operator
+    spec, data = W.grad_case("conv2d_grad_w", (n, c, h, w, o, k), "bf16", stride, pad, second_is_param=False)
+    kernels = [st["kernel"] for st in s_plan_steps(spec, {"no_wgrad": 1})]
+    assert any(kn.startswith("igemm_conv2d_grad_w_") for kn in kernels), kernels
+    check_graph(spec, data, f"conv2d_grad_w gather {case}", opts={"no_wgrad": 1})
+
+
 def test_gradient_chain_through_two_convolutions():
     # dy pushed back through two stacked 3x3 convolutions: the first gradient's result stays channel-last inside the
     # plan, so it runs on the forward operator's bf16 kernels (nine taps from one copy of the rows)
