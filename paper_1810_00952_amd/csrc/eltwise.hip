@@ -663,6 +663,41 @@ hipError_t launch_pack_gather(const void *src, void *dst, const GatherPack &g, h
 }
 
 // ---------------------------------------------------------------------------
+// A channel-last tensor spread out with zeros: dst[n][s i][s j][:] = src[n][i][j][:], everything else 0 (dst is Hd x Wd
+// pixels, at least (OH-1) s + 1 by (OW-1) s + 1).  What the gradient of a strided convolution with respect to its input
+// convolves at stride 1.  One 16-byte vector per thread.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void dilate_nhwc_kernel(const u32x4 *__restrict__ src, u32x4 *__restrict__ dst, int64_t total, int OH, int OW,
+                                                          int Hd, int Wd, int CV, int s)
+{
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= total) return;
+    const int cv = (int)(idx % CV);
+    const int64_t pix = idx / CV;
+    const int wd = (int)(pix % Wd);
+    const int64_t r = pix / Wd;
+    const int hd = (int)(r % Hd);
+    const int64_t n = r / Hd;
+    u32x4 v = {0u, 0u, 0u, 0u};
+    const int i = hd / s, j = wd / s;
+    if (i * s == hd && j * s == wd && i < OH && j < OW) v = src[((n * OH + i) * OW + j) * CV + cv];
+    dst[idx] = v;
+}
+
+hipError_t launch_dilate_nhwc(const void *src, void *dst, int32_t N, int32_t OH, int32_t OW, int32_t Hd, int32_t Wd, int32_t pixel_bytes, int32_t stride,
+                              hipStream_t s)
+{
+    if (N < 1 || OH < 1 || OW < 1 || stride < 1 || pixel_bytes < 16 || pixel_bytes % 16 != 0 || Hd < (OH - 1) * stride + 1 || Wd < (OW - 1) * stride + 1 ||
+        ((uintptr_t)src & 15) || ((uintptr_t)dst & 15))
+        return hipErrorInvalidValue;
+    const int64_t total = (int64_t)N * Hd * Wd * (pixel_bytes / 16);
+    if (total > ((int64_t)1 << 40)) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(dilate_nhwc_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, (const u32x4 *)src, (u32x4 *)dst, total, OH, OW, Hd, Wd,
+                       pixel_bytes / 16, stride);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
 // stem convolutions: zero-padded 4-channel channel-last frame and matching weights (bf16)
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void stem_pad_kernel(const uint16_t *__restrict__ src, uint16_t *__restrict__ dst, int N, int C, int H,

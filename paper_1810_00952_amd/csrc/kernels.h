@@ -224,6 +224,8 @@ hipError_t launch_pack_weight(const void *src, void *dst, int32_t dtype, int32_t
 // (h + ph, w + pw); a run of 8 pixels then is 64 contiguous bytes and a K tile holds filter rows
 // 2t and 2t+1 (8 pixels x 4 channels each).  The weights are packed to match:
 // dst[o][((t*2 + seg)*8 + px)*4 + c] = src[o][c][2t+seg][px], zero outside the filter.
+hipError_t launch_dilate_nhwc(const void *src, void *dst, int32_t N, int32_t OH, int32_t OW, int32_t Hd, int32_t Wd, int32_t pixel_bytes, int32_t stride,
+                              hipStream_t s);
 hipError_t launch_stem_pad(const void *src, void *dst, int32_t N, int32_t C, int32_t H, int32_t W, int32_t Hp, int32_t Wp,
                            int32_t ph, int32_t pw, hipStream_t s);
 // Operand of a contraction gathered into the K-contiguous rows the kernels read: for row r < R and k < Kp,

@@ -205,6 +205,8 @@ struct Planner {
         int kind;                         // RL_OP_DENSE or RL_OP_CONV2D
         int N, KH, KW, ph, pw;            // output channels (features), taps, padding; stride 1; contraction channels come from x
         GatherPack gp;                    // where the rows of the K-contiguous weight matrix come from
+        int xbuf = -1;                    // >= 0: the activations are this channel-last buffer [xN][xH][xW][C] instead of x's own
+        int xH = 0, xW = 0;
     };
 
     rl_status plan_anchor(int gi, const std::vector<int> &ops, const AnchorView *ov = nullptr)
@@ -263,6 +265,9 @@ struct Planner {
         if (akind == RL_OP_CONV2D) {
             const rl_type &xt = T(x), &wt = T(wv);
             p.C = (int)xt.dims[1]; p.H = (int)xt.dims[2]; p.W = (int)xt.dims[3];
+            const bool xov = ov && ov->xbuf >= 0;
+            if (xov) { p.H = ov->xH; p.W = ov->xW; }
+            const size_t x_own = xov ? (size_t)xt.dims[0] * p.H * p.W * p.C * dtype_size(in_dt) : bytes_of(x);
             p.KH = (int)wt.dims[2]; p.KW = (int)wt.dims[3];
             p.OH = (int)ot.dims[2]; p.OW = (int)ot.dims[3]; p.OHW = p.OH * p.OW;
             p.sh = an.attrs.stride[0]; p.sw = an.attrs.stride[1]; p.ph = an.attrs.pad[0]; p.pw = an.attrs.pad[1];
@@ -306,16 +311,17 @@ struct Planner {
             } else {
                 il.avec = (p.C % KV == 0);
                 int xl;
-                if (il.avec) xl = L_NHWC;
+                if (il.avec || xov) xl = L_NHWC;
                 else xl = phys[L_NATIVE][x] >= 0 ? L_NATIVE : L_NHWC;
-                st = need(x, xl, xbuf);
+                if (xov) xbuf = ov->xbuf;
+                else st = need(x, xl, xbuf);
                 if (st != RL_OK) return st;
                 if (xl == L_NHWC) { p.xs_n = (int64_t)p.H * p.W * p.C; p.xs_h = (int64_t)p.W * p.C; p.xs_w = p.C; p.xs_c = 1; }
                 else { p.xs_n = (int64_t)p.C * p.H * p.W; p.xs_c = (int64_t)p.H * p.W; p.xs_h = p.W; p.xs_w = 1; }
                 p.ts_h = p.xs_h; p.ts_w = p.xs_w; p.seg_stride = 64;
                 need_pack = !(p.KH * p.KW == 1 && p.C % KV == 0) || ov;
                 pack.dtype = in_dt; pack.O = p.N; pack.C = p.C; pack.T = p.KH * p.KW; pack.Kp = p.Kp; pack.perm_block = 0;
-                x_extent = bytes_of(x);
+                x_extent = x_own;
             }
         } else {
             const rl_type &wt = T(wv);
@@ -704,6 +710,37 @@ struct Planner {
                 ov.gp.R = C; ov.gp.T = KH * KW; ov.gp.TW = KW; ov.gp.Cq = O;
                 ov.gp.s_row = (int64_t)KH * KW; ov.gp.s_c = (int64_t)C * KH * KW; ov.gp.s_ti = -KW; ov.gp.s_tj = -1; ov.gp.base = (int64_t)KH * KW - 1;
                 return plan_anchor(gi, std::vector<int>{oi}, &ov);
+            }
+            // At a stride: the same stride-1 convolution of dy spread out with zeros (a step of its own writes that
+            // tensor; three of four products are with zeros, on kernels that are many times faster than the gather).
+            if (o.kind == RL_OP_CONV2D_GRAD_X && o.attrs.stride[0] == o.attrs.stride[1] && o.attrs.stride[0] > 1 &&
+                (ta.dims[1] * (int64_t)dtype_size(dt)) % 16 == 0) {
+                const int Nb = (int)ta.dims[0], O = (int)ta.dims[1], OH = (int)ta.dims[2], OW = (int)ta.dims[3];
+                const int C = (int)tb.dims[1], KH = (int)tb.dims[2], KW = (int)tb.dims[3], H = (int)ty.dims[2], W = (int)ty.dims[3];
+                const int sd = o.attrs.stride[0];
+                if (o.attrs.pad[0] > KH - 1 || o.attrs.pad[1] > KW - 1) return fail(RL_ERR_UNSUPPORTED, "conv2d_grad_x: padding larger than the kernel");
+                const int Hd = H + 2 * o.attrs.pad[0] - KH + 1, Wd = W + 2 * o.attrs.pad[1] - KW + 1;
+                const size_t dbytes = (size_t)Nb * Hd * Wd * O * dtype_size(dt);
+                if (Hd >= (OH - 1) * sd + 1 && Wd >= (OW - 1) * sd + 1 && dbytes < ((size_t)1 << 31)) {
+                    int src;
+                    rl_status st = need(va, L_NHWC, src);
+                    if (st != RL_OK) return st;
+                    const int dil = new_ws(dbytes);
+                    Step &ds = add_step(S_DILATE, std::string(op_name(o.kind)) + "#" + std::to_string(oi) + ".spread", "dilate_nhwc");
+                    ds.group = gi;
+                    ds.t_N = Nb; ds.t_C = (int)(O * dtype_size(dt)); ds.st_H = OH; ds.st_W = OW; ds.st_Hp = Hd; ds.st_Wp = Wd; ds.st_ph = sd;
+                    ds.slot[SL_X] = src; ds.slot[SL_Y] = dil;
+                    ds.bytes = (double)bytes_of(va) + (double)dbytes;
+                    ov.kind = RL_OP_CONV2D; ov.N = C; ov.KH = KH; ov.KW = KW; ov.ph = KH - 1 - o.attrs.pad[0]; ov.pw = KW - 1 - o.attrs.pad[1];
+                    ov.gp.R = C; ov.gp.T = KH * KW; ov.gp.TW = KW; ov.gp.Cq = O;
+                    ov.gp.s_row = (int64_t)KH * KW; ov.gp.s_c = (int64_t)C * KH * KW; ov.gp.s_ti = -KW; ov.gp.s_tj = -1; ov.gp.base = (int64_t)KH * KW - 1;
+                    ov.xbuf = dil; ov.xH = Hd; ov.xW = Wd;
+                    st = plan_anchor(gi, std::vector<int>{oi}, &ov);
+                    if (st != RL_OK) return st;
+                    for (size_t k = plan.steps.size(); k-- > 0;)
+                        if (plan.steps[k].kind == S_IGEMM) { plan.steps[k].flops /= (double)(sd * sd); break; }     // the zeros are no work
+                    return RL_OK;
+                }
             }
         }
         p.C = 1; p.H = p.W = p.KH = p.KW = p.OH = p.OW = p.OHW = 1; p.sh = p.sw = 1;
@@ -1315,6 +1352,9 @@ rl_status run_steps(const Plan &plan, void *const *ptrs, hipStream_t stream, std
             er = launch_conv_wgrad(q, stream);
             break;
         }
+        case S_DILATE:
+            er = launch_dilate_nhwc(P(s, SL_X), P(s, SL_Y), s.t_N, s.st_H, s.st_W, s.st_Hp, s.st_Wp, s.t_C, s.st_ph, stream);
+            break;
         case S_WGRAD_REDUCE:
             er = launch_wgrad_reduce((const float *)P(s, SL_X), P(s, SL_Y), s.t_dtype, s.t_N, s.t_C, s.wg.O, s.wg.C, stream);
             break;

@@ -10,7 +10,7 @@
 
 namespace rl {
 
-enum StepKind { S_IGEMM = 0, S_ELTWISE, S_GATES, S_MAXPOOL, S_GAVG, S_TO_NHWC, S_TO_NCHW, S_STEM_PAD, S_STEM_POOL, S_PERMUTE, S_PACK, S_WGRAD, S_WGRAD_REDUCE };
+enum StepKind { S_IGEMM = 0, S_ELTWISE, S_GATES, S_MAXPOOL, S_GAVG, S_TO_NHWC, S_TO_NCHW, S_STEM_PAD, S_STEM_POOL, S_PERMUTE, S_PACK, S_WGRAD, S_WGRAD_REDUCE, S_DILATE };
 enum Slot { SL_X = 0, SL_X2, SL_W, SL_Y, SL_E0, SL_E1, SL_E2, SL_E3, SL_E4, SL_E5, SL_CIN, SL_COUT, SL_HOUT, SL_PART, SL_COUNT };
 
 struct BufDesc {

@@ -859,7 +859,10 @@ def test_gradient_operators(dtype, case):
     kernels = [st["kernel"] for st in s_plan_steps(spec)]
     assert any(k.startswith(f"igemm_{kind}_") for k in kernels), kernels
     assert ("pack_gather" in kernels) == (not is_param), kernels          # a param's operand form is made at prepack time
-    as_forward = is_param and (kind == "dense_grad_x" or (kind == "conv2d_grad_x" and stride == 1))
+    # through a param, the gradient with respect to the first operand is planned as the forward operator (at a stride: on
+    # dy spread out with zeros by a step of its own)
+    as_forward = is_param and kind in ("dense_grad_x", "conv2d_grad_x")
+    assert ("dilate_nhwc" in kernels) == (as_forward and kind == "conv2d_grad_x" and stride > 1), kernels
     if as_forward:
         # the same operator on the element-gather kernel, as the other gradients run
         check_graph(spec, data, f"{kind} {dtype} {dims} s{stride} p{pad} gather", opts={"no_grad_fwd": 1})
