@@ -101,7 +101,9 @@ def test_resnet18_plan_structure():
 def test_workspace_reuse_is_liveness_safe():
     # two workspace buffers that hold live data at the same step never overlap, and all lie inside the workspace
     for spec in (W.resnet18(batch=2, dtype="f32", image=64)[0], W.resnet18(batch=64, dtype="bf16")[0], W.resnet18(batch=1, dtype="f32")[0],
-                 W.lenet(5, "bf16")[0], W.mlp()[0], W.lstm_unrolled_graph(4, 8, 64, 64, "bf16", fused=False)):
+                 W.lenet(5, "bf16")[0], W.mlp()[0], W.lstm_unrolled_graph(4, 8, 64, 64, "bf16", fused=False),
+                 W.grad_case("conv2d_grad_w", (64, 128, 28, 28, 128, 3), "bf16", 1, 1, second_is_param=False)[0],
+                 W.grad_case("conv2d_grad_x", (64, 64, 56, 56, 128, 3), "bf16", 2, 1)[0], W.grad_chain(8, 128, 28, 3, "bf16")[0]):
         plan = B.Plan(B.graph_from_spec(B.Context(), spec))
         d = plan.describe()
         bufs = d["buffers"]
@@ -120,6 +122,31 @@ def test_workspace_reuse_is_liveness_safe():
                 n_shared += overlap
         if len(bufs) > 3:
             assert n_shared > 0 and ws < sum(b["bytes"] for b in bufs), spec.name        # reuse happened
+
+
+def test_gradient_operators_plan_onto_the_fast_kernels():
+    ctx = B.Context()
+    k = lambda spec, opts=None: [s["kernel"] for s in B.Plan(B.graph_from_spec(ctx, spec), opts).describe()["steps"]]
+    # with respect to the input, through a param: the forward operator on re-ordered weights ...
+    spec = W.grad_case("conv2d_grad_x", (64, 128, 28, 28, 128, 3), "bf16", 1, 1)[0]
+    assert k(spec) == ["nchw_to_nhwc", "igemm_conv2d_grad_x_bf16_128x128_dma"]
+    assert k(spec, {"no_grad_fwd": 1}) == ["igemm_conv2d_grad_x_bf16_64x64_gather"]
+    # ... inside a chain on the nine-taps-from-one-copy kernel, like the forward pass
+    assert k(W.grad_chain(64, 128, 28, 3, "bf16")[0]) == ["nchw_to_nhwc", "igemm_conv2d_grad_x_bf16_256x128_run", "igemm_conv2d_grad_x_bf16_256x128_run",
+                                                         "igemm_conv2d_grad_x_bf16_128x128_dma"]
+    # ... at a stride on dy spread out with zeros
+    spec = W.grad_case("conv2d_grad_x", (64, 64, 56, 56, 128, 3), "bf16", 2, 1)[0]
+    assert k(spec) == ["nchw_to_nhwc", "dilate_nhwc", "igemm_conv2d_grad_x_bf16_128x64_dma"]
+    # through weights that are an activation: the element gather, its operand gathered by a step of the plan
+    spec = W.grad_case("conv2d_grad_x", (64, 64, 56, 56, 128, 3), "bf16", 2, 1, second_is_param=False)[0]
+    assert k(spec) == ["pack_gather", "igemm_conv2d_grad_x_bf16_64x64_gather"]
+    # with respect to the weights, bf16 batches of 64: images-last operands, contraction, ordered reduction
+    spec = W.grad_case("conv2d_grad_w", (64, 128, 28, 28, 128, 3), "bf16", 1, 1, second_is_param=False)[0]
+    assert k(spec) == ["transpose_images_last", "transpose_images_last", "conv2d_grad_w_bf16_128x64_images_last", "wgrad_reduce"]
+    assert k(spec, {"no_wgrad": 1}) == ["pack_gather", "igemm_conv2d_grad_w_bf16_64x64_gather_splitk"]
+    for dims, dtype in (((32, 128, 28, 28, 128, 3), "bf16"), ((64, 128, 28, 28, 128, 3), "f32"), ((64, 96, 28, 28, 128, 3), "bf16"), ((64, 128, 28, 28, 128, 5), "bf16")):
+        pad = dims[5] // 2
+        assert "wgrad_reduce" not in k(W.grad_case("conv2d_grad_w", dims, dtype, 1, pad, second_is_param=False)[0])     # other batches, dtypes, channel counts, filters
 
 
 def test_plan_options_are_fixed_in_the_plan():
