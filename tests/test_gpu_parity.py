@@ -893,6 +893,9 @@ WGRAD_CASES = [
     (64, 128, 10, 6, 64, 3, 2, 1),
     (64, 64, 30, 3, 64, 3, 1, 1),         # more rows than columns: one pixel per segment
     (64, 192, 4, 33, 192, 3, 1, 1),       # 192 = 3 x 64 channels on both sides (64-wide output blocks), long rows
+    (64, 128, 9, 9, 64, 1, 1, 0),         # 1x1 at stride 1: one tap, one new column per pixel
+    (64, 64, 6, 7, 64, 3, 1, 2),          # padding 2: the result is larger than the input, whole windows outside it
+    (64, 64, 11, 11, 64, 3, 2, 0),        # stride 2 without padding
 ]
 
 
