@@ -200,7 +200,7 @@ typedef struct rl_plan_opts {
     int32_t no_hoist;       /* rl_plan_run_recurrent: never hoist the input projection out of the step loop */
     int32_t no_stem_direct; /* the fused stem + max-pool kernel reads a padded channel-last copy of the input (written by a step
                                of its own) even where it could fetch its patches from the channel-first input directly */
-    int32_t no_wgrad;       /* conv2d_grad_w on bf16 batches of 64: no images-last contraction kernel; the element-gather kernel */
+    int32_t no_wgrad;       /* conv2d_grad_w on bf16 batches that are multiples of 64: no images-last contraction kernel; the element-gather kernel */
     int32_t no_grad_fwd;    /* dense_grad_x and stride-1 conv2d_grad_x through a param: do not plan them as the forward
                                operator on re-ordered weights; take the element-gather kernel like the other gradients */
 } rl_plan_opts;

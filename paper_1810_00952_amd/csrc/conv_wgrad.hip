@@ -1,4 +1,5 @@
-// Gradient of a convolution with respect to its weights, bf16 in / fp32 accumulate, for batches of 64 images:
+// Gradient of a convolution with respect to its weights, bf16 in / fp32 accumulate, for batches of 64 images (or a
+// multiple of 64: a workgroup then walks its row segment once per 64 images):
 //   dw[o][c][a][b] = sum over (n, i, j) of dy[n][o][i][j] * x[n][c][s*i + a - ph][s*j + b - pw]
 //
 // The contraction runs over pixels and images, which are the SLOW axes of both operands as a plan stores them, while an
@@ -111,8 +112,9 @@ __global__ __launch_bounds__(WO * 2 * 64) void conv_wgrad_kernel(const WgradPara
         const int r = (wave * XI + d) * 8 + (lane >> 3);
         x_voff[d] = (uint32_t)(((int64_t)(ct * WG_CT + r) * p.xs_c) * 2) + (uint32_t)(((lane & 7) ^ ((r >> 1) & 7)) * 16);
     }
+    uint32_t noff = 0;                              // byte offset of the current 64 images inside a row
     auto issue_dy = [&](int j, int buf) {
-        const uint32_t soff = (uint32_t)(((int64_t)(i * p.OW + j) * p.ys_pix) * 2);
+        const uint32_t soff = (uint32_t)(((int64_t)(i * p.OW + j) * p.ys_pix) * 2) + noff;
 #pragma unroll
         for (int d = 0; d < 2; ++d) dma16(ddy, lds_a + buf * DY_BYTES + (wave * 2 + d) * 1024, dy_voff[d], soff);
     };
@@ -125,17 +127,13 @@ __global__ __launch_bounds__(WO * 2 * 64) void conv_wgrad_kernel(const WgradPara
         for (int a = 0; a < KH; ++a) {
             const int h = i * s + a - p.ph;
             if (h < 0 || h >= p.H) continue;
-            const uint32_t soff = (uint32_t)(((int64_t)(h * p.W + w) * p.xs_pix) * 2);
+            const uint32_t soff = (uint32_t)(((int64_t)(h * p.W + w) * p.xs_pix) * 2) + noff;
 #pragma unroll
             for (int d = 0; d < XI; ++d) dma16(ddx, lds_a + X_OFF + (a * RING_COLS + cs) * XT_BYTES + (wave * XI + d) * 1024, x_voff[d], soff);
         }
     };
 
-    // ---- prologue: the first pixel's tiles
     if (t < 32) *(uint32_t *)(lds + ZERO_OFF + t * 4) = 0u;
-    issue_dy(j0, 0);
-#pragma unroll
-    for (int b = 0; b < KW; ++b) issue_col(j0 * s + b - p.pw);
 
     // fragment addresses inside a tile: row (wave's 32 rows) x chunk 2 ks + fhalf, swizzled
     uint32_t fa_dy[4], fa_x[4];
@@ -152,6 +150,14 @@ __global__ __launch_bounds__(WO * 2 * 64) void conv_wgrad_kernel(const WgradPara
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[tp][v] = 0.0f;
 
+#pragma unroll 1
+    for (int nc = 0; nc < p.nck; ++nc) {
+    // ---- the first pixel's tiles of this group of 64 images (every wave has left the last group's tiles: the barrier
+    // that ended its last pixel)
+    noff = (uint32_t)nc * 128u;
+    issue_dy(j0, 0);
+#pragma unroll
+    for (int b = 0; b < KW; ++b) issue_col(j0 * s + b - p.pw);
     RL_WAIT_VM(0);
     wg_barrier();
 
@@ -200,6 +206,7 @@ __global__ __launch_bounds__(WO * 2 * 64) void conv_wgrad_kernel(const WgradPara
         }
         RL_WAIT_VM(0);                              // the next pixel's tiles have landed
         wg_barrier();                               // ... for every wave; and every wave has left this pixel's tiles
+    }
     }
 
     // ---- this workgroup's sums: part[chunk][tap][o][c], accumulator register 4g + k of lane l: o = 8g + 4 (l >> 5) + k, c = l & 31
@@ -251,23 +258,24 @@ __global__ __launch_bounds__(64 * RED_WAVES) void wgrad_reduce_kernel(const floa
 
 bool conv_wgrad_ok(int32_t NB, int32_t O, int32_t C, int32_t KH, int32_t KW, int32_t s)
 {
-    return NB == WG_NB && O >= 64 && O % 64 == 0 && C >= 64 && C % 64 == 0 && ((KH == 3 && KW == 3) || (KH == 1 && KW == 1)) && (s == 1 || s == 2);
+    return NB >= WG_NB && NB % WG_NB == 0 && O >= 64 && O % 64 == 0 && C >= 64 && C % 64 == 0 && ((KH == 3 && KW == 3) || (KH == 1 && KW == 1)) && (s == 1 || s == 2);
 }
 
 hipError_t launch_conv_wgrad(const WgradParams &p, hipStream_t s)
 {
-    if (!conv_wgrad_ok(WG_NB, p.O, p.C, p.KH, p.KW, p.s) || !p.dyT || !p.xT || !p.part || ((uintptr_t)p.dyT & 15) || ((uintptr_t)p.xT & 15) ||
+    const int64_t NB = (int64_t)p.nck * WG_NB;
+    if (p.nck < 1 || p.nck > 64 || !conv_wgrad_ok((int32_t)NB, p.O, p.C, p.KH, p.KW, p.s) || !p.dyT || !p.xT || !p.part || ((uintptr_t)p.dyT & 15) || ((uintptr_t)p.xT & 15) ||
         ((uintptr_t)p.part & 3) || p.H < 1 || p.W < 1 || p.OH < 1 || p.OW < 1 || p.ph < 0 || p.pw < 0 || p.ph >= p.KH || p.pw >= p.KW ||
         p.OH != (p.H + 2 * p.ph - p.KH) / p.s + 1 || p.OW != (p.W + 2 * p.pw - p.KW) / p.s + 1 ||
         p.n_ct != p.C / WG_CT || (p.n_ot != p.O / 128 && p.n_ot != p.O / 64) || p.L < 1 || p.nseg != (p.OW + p.L - 1) / p.L ||
-        p.ys_o < WG_NB || p.ys_o % 8 != 0 || p.ys_pix % 8 != 0 || p.xs_c < WG_NB || p.xs_c % 8 != 0 || p.xs_pix % 8 != 0 ||
-        (uint64_t)p.dy_bytes != (uint64_t)p.OH * p.OW * p.O * WG_NB * 2 || (uint64_t)p.x_bytes != (uint64_t)p.H * p.W * p.C * WG_NB * 2 ||
+        p.ys_o < NB || p.ys_o % 8 != 0 || p.ys_pix % 8 != 0 || p.xs_c < NB || p.xs_c % 8 != 0 || p.xs_pix % 8 != 0 ||
+        (uint64_t)p.dy_bytes != (uint64_t)p.OH * p.OW * p.O * NB * 2 || (uint64_t)p.x_bytes != (uint64_t)p.H * p.W * p.C * NB * 2 ||
         p.dy_bytes >= 0x7fffffffu || p.x_bytes >= 0x7fffffffu)
         return hipErrorInvalidValue;
     // every tile a workgroup requests lies inside its tensor: row (pixel, channel) starts at pixel*pix_stride + channel*ch_stride
     // and is 64 elements long; the largest such start over the tensor must leave room for the row
-    const int64_t dy_last = (int64_t)(p.OH * p.OW - 1) * p.ys_pix + (int64_t)(p.O - 1) * p.ys_o + WG_NB;
-    const int64_t x_last = (int64_t)(p.H * p.W - 1) * p.xs_pix + (int64_t)(p.C - 1) * p.xs_c + WG_NB;
+    const int64_t dy_last = (int64_t)(p.OH * p.OW - 1) * p.ys_pix + (int64_t)(p.O - 1) * p.ys_o + NB;
+    const int64_t x_last = (int64_t)(p.H * p.W - 1) * p.xs_pix + (int64_t)(p.C - 1) * p.xs_c + NB;
     if (dy_last * 2 > (int64_t)p.dy_bytes || x_last * 2 > (int64_t)p.x_bytes) return hipErrorInvalidValue;
     const int64_t grid = (int64_t)p.OH * p.nseg * p.n_ot * p.n_ct;
     if (grid < 1 || grid > 0x7fffffff) return hipErrorInvalidValue;

@@ -691,7 +691,7 @@ hipError_t launch_dilate_nhwc(const void *src, void *dst, int32_t N, int32_t OH,
         ((uintptr_t)src & 15) || ((uintptr_t)dst & 15))
         return hipErrorInvalidValue;
     const int64_t total = (int64_t)N * Hd * Wd * (pixel_bytes / 16);
-    if (total > ((int64_t)1 << 40)) return hipErrorInvalidValue;
+    if (total >= ((int64_t)1 << 38)) return hipErrorInvalidValue;              // the grid stays below 2^30 workgroups
     hipLaunchKernelGGL(dilate_nhwc_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, (const u32x4 *)src, (u32x4 *)dst, total, OH, OW, Hd, Wd,
                        pixel_bytes / 16, stride);
     return hipGetLastError();

@@ -144,15 +144,16 @@ hipError_t launch_stem_pool_direct(const StemDirectParams &q, hipStream_t s);
 // weights [64, C, KH, KW] -> [64][STEM_DIRECT_KP]: index 16 (c ceil(KH/2) + kh/2) + 8 (kh & 1) + kw + (pw & 1), zeros elsewhere
 hipError_t launch_pack_weight_stem_direct(const void *src, void *dst, int32_t O, int32_t C, int32_t KH, int32_t KW, int32_t pw, hipStream_t s);
 
-// ---- gradient of a convolution with respect to its weights, batches of 64 (conv_wgrad.hip) ----
+// ---- gradient of a convolution with respect to its weights, batches that are multiples of 64 (conv_wgrad.hip) ----
 struct WgradParams {
-    const void *dyT; uint32_t dy_bytes;     // dy with the 64 images as the fastest axis: element (pixel, o, n) at pixel*ys_pix + o*ys_o + n
+    const void *dyT; uint32_t dy_bytes;     // dy with the images as the fastest axis: element (pixel, o, n) at pixel*ys_pix + o*ys_o + n
     const void *xT; uint32_t x_bytes;       // x likewise: (pixel, c, n) at pixel*xs_pix + c*xs_c + n
     float *part;                            // [OH * nseg][KH*KW][O][C] fp32: the sums of the row segments
     int32_t O, C, H, W, OH, OW, KH, KW, s, ph, pw;
     int64_t ys_pix, ys_o, xs_pix, xs_c;     // in elements, multiples of 8
     int32_t nseg, L;                        // segments per output row, output pixels per segment
     int32_t n_ot, n_ct;                     // blocks of output channels (of 128, or of 64) and of input channels (of 64)
+    int32_t nck;                            // groups of 64 images (the batch is 64 * nck)
 };
 bool conv_wgrad_ok(int32_t NB, int32_t O, int32_t C, int32_t KH, int32_t KW, int32_t s);
 hipError_t launch_conv_wgrad(const WgradParams &p, hipStream_t s);

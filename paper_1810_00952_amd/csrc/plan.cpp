@@ -889,6 +889,7 @@ struct Planner {
         if (st != RL_OK) return st;
         st = batch_last(vx, C, H * W, w.xs_pix, w.xs_c, xT);
         if (st != RL_OK) return st;
+        w.nck = Nb / 64;
         w.n_ot = O % 128 == 0 ? O / 128 : O / 64;
         w.n_ct = C / 64;
         // one workgroup per CU (its LDS is full): as many row segments as keep the grid within one round
@@ -1347,8 +1348,8 @@ rl_status run_steps(const Plan &plan, void *const *ptrs, hipStream_t stream, std
         case S_WGRAD: {
             WgradParams q = s.wg;
             q.xT = P(s, SL_X); q.dyT = P(s, SL_X2); q.part = (float *)P(s, SL_PART);
-            q.dy_bytes = (uint32_t)((uint64_t)q.OH * q.OW * q.O * 64 * 2);
-            q.x_bytes = (uint32_t)((uint64_t)q.H * q.W * q.C * 64 * 2);
+            q.dy_bytes = (uint32_t)((uint64_t)q.OH * q.OW * q.O * 64 * q.nck * 2);
+            q.x_bytes = (uint32_t)((uint64_t)q.H * q.W * q.C * 64 * q.nck * 2);
             er = launch_conv_wgrad(q, stream);
             break;
         }

@@ -882,7 +882,8 @@ def s_plan_steps(spec, opts=None):
     return binding.Plan(binding.graph_from_spec(binding.Context(), spec), opts).describe()["steps"]
 
 
-# conv2d_grad_w on bf16 batches of 64: both operands transposed to images-last, one contraction per output pixel and tap.
+# conv2d_grad_w on bf16 batches that are multiples of 64: both operands transposed to images-last, one contraction per output
+# pixel, filter tap and group of 64 images.
 WGRAD_CASES = [
     # n   c    h   w   o   k  s  p
     (64, 64, 6, 6, 64, 3, 1, 1),          # 64-channel blocks (four waves), one segment per row
@@ -896,6 +897,8 @@ WGRAD_CASES = [
     (64, 128, 9, 9, 64, 1, 1, 0),         # 1x1 at stride 1: one tap, one new column per pixel
     (64, 64, 6, 7, 64, 3, 1, 2),          # padding 2: the result is larger than the input, whole windows outside it
     (64, 64, 11, 11, 64, 3, 2, 0),        # stride 2 without padding
+    (128, 64, 5, 6, 64, 3, 1, 1),         # two groups of 64 images: the segment is walked twice
+    (192, 64, 4, 4, 128, 3, 2, 1),        # three groups, stride 2
 ]
 
 
