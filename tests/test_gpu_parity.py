@@ -882,6 +882,54 @@ def s_plan_steps(spec, opts=None):
     return binding.Plan(binding.graph_from_spec(binding.Context(), spec), opts).describe()["steps"]
 
 
+# A seeded sweep over conv groups nobody picked by hand: whatever kernel the planner chooses for the shape, the result
+# must match the oracle (shapes small enough for the oracle, wide enough to reach the gather, vector, direct-load,
+# pixel-on-lane, weights-stationary, stem and split-K forms and every epilogue).
+def _random_conv_cases(n, seed=1810):
+    rng = np.random.default_rng(seed)
+    cases = []
+    while len(cases) < n:
+        k = int(rng.choice([1, 1, 2, 3, 3, 3, 5, 7]))
+        stride = int(rng.choice([1, 1, 1, 2, 2, 3]))
+        pad = int(rng.integers(0, k))
+        h, w = int(rng.integers(1, 24)), int(rng.integers(1, 24))
+        if h + 2 * pad < k or w + 2 * pad < k:
+            continue
+        cases.append((int(rng.integers(1, 6)), int(rng.choice([1, 3, 4, 8, 16, 24, 64, 72, 128, 192])), int(rng.choice([3, 8, 16, 24, 64, 72, 128, 200])), h, w, k, stride, pad,
+                      str(rng.choice(["f32", "bf16", "bf16"])), bool(rng.integers(0, 2)), bool(rng.integers(0, 2)), bool(rng.integers(0, 2)), bool(rng.integers(0, 2))))
+    return cases
+
+
+RANDOM_CONV_CASES = _random_conv_cases(60)
+
+
+@pytest.mark.parametrize("case", RANDOM_CONV_CASES, ids=[f"rc{i}" for i in range(len(RANDOM_CONV_CASES))])
+def test_random_conv_groups(case):
+    b, ci, co, h, w, k, stride, pad, dtype, bias, res, relu, tail = case
+    spec, data = W.conv_group(b, ci, co, h, w, k, stride, pad, dtype, residual=res, relu=relu, tail=tail, bias=bias)
+    print(f"random conv case {case}: {[st['kernel'] for st in s_plan_steps(spec)]}", flush=True)
+    check_graph(spec, data, f"random conv {case}")
+
+
+def _random_mlp_cases(n, seed=952):
+    rng = np.random.default_rng(seed)
+    dims = [1, 2, 7, 8, 10, 16, 31, 32, 64, 65, 100, 128, 200, 256, 513, 784, 1000, 1024]
+    return [(int(rng.integers(1, 140)), int(rng.choice(dims)), int(rng.choice(dims)), int(rng.choice(dims)), str(rng.choice(["f32", "bf16"]))) for _ in range(n)]
+
+
+RANDOM_MLP_CASES = _random_mlp_cases(30)
+
+
+@pytest.mark.parametrize("case", RANDOM_MLP_CASES, ids=[f"rm{i}" for i in range(len(RANDOM_MLP_CASES))])
+def test_random_dense_groups(case):
+    # two dense groups in a row (bias + ReLU fused into the first, bias into the second) on sizes nobody picked by hand:
+    # odd and partial K tiles, single rows, K split over workgroups, element gather
+    b, d_in, d_h, d_out, dtype = case
+    spec, data = W.mlp(b, d_in, d_h, d_out, dtype)
+    print(f"random dense case {case}: {[st['kernel'] for st in s_plan_steps(spec)]}", flush=True)
+    check_graph(spec, data, f"random dense {case}")
+
+
 # conv2d_grad_w on bf16 batches that are multiples of 64: both operands transposed to images-last, one contraction per output
 # pixel, filter tap and group of 64 images.
 WGRAD_CASES = [
