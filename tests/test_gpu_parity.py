@@ -930,6 +930,40 @@ def test_random_dense_groups(case):
     check_graph(spec, data, f"random dense {case}")
 
 
+def _random_grad_cases(n, seed=4952):
+    rng = np.random.default_rng(seed)
+    cases = []
+    while len(cases) < n:
+        kind = str(rng.choice(["dense_grad_x", "dense_grad_w", "conv2d_grad_x", "conv2d_grad_x", "conv2d_grad_w", "conv2d_grad_w"]))
+        dtype, is_param = str(rng.choice(["f32", "bf16"])), bool(rng.integers(0, 2))
+        if kind.startswith("dense"):
+            cases.append((kind, (int(rng.integers(1, 100)), int(rng.choice([1, 5, 8, 16, 40, 64, 100, 128])), int(rng.choice([1, 7, 8, 16, 30, 64, 128, 200]))), 1, 0, dtype, is_param))
+            continue
+        k = int(rng.choice([1, 2, 3, 3, 5])); stride = int(rng.choice([1, 1, 2, 2, 3])); pad = int(rng.integers(0, k))
+        h, w = int(rng.integers(1, 18)), int(rng.integers(1, 18))
+        if h + 2 * pad < k or w + 2 * pad < k:
+            continue
+        nb = int(rng.choice([1, 2, 3, 5, 64]))
+        c, o = int(rng.choice([1, 3, 8, 16, 24, 64])), int(rng.choice([4, 8, 16, 24, 64, 128]))
+        if nb == 64:
+            h, w = min(h, 7), min(w, 7)
+            if h + 2 * pad < k or w + 2 * pad < k:
+                continue
+        cases.append((kind, (nb, c, h, w, o, k), stride, pad, dtype, is_param))
+    return cases
+
+
+RANDOM_GRAD_CASES = _random_grad_cases(60)
+
+
+@pytest.mark.parametrize("case", RANDOM_GRAD_CASES, ids=[f"rg{i}" for i in range(len(RANDOM_GRAD_CASES))])
+def test_random_gradient_operators(case):
+    kind, dims, stride, pad, dtype, is_param = case
+    spec, data = W.grad_case(kind, dims, dtype, stride, pad, second_is_param=is_param)
+    print(f"random gradient case {case}: {[st['kernel'] for st in s_plan_steps(spec)]}", flush=True)
+    check_graph(spec, data, f"random gradient {case}")
+
+
 # conv2d_grad_w on bf16 batches that are multiples of 64: both operands transposed to images-last, one contraction per output
 # pixel, filter tap and group of 64 images.
 WGRAD_CASES = [
