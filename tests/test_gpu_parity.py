@@ -930,6 +930,25 @@ def test_random_dense_groups(case):
     check_graph(spec, data, f"random dense {case}")
 
 
+BENCH_GRAD_CASES = [("conv2d_grad_x", (64, 128, 28, 28, 128, 3), 1, 1, True), ("conv2d_grad_w", (64, 128, 28, 28, 128, 3), 1, 1, False),
+                    ("conv2d_grad_x", (64, 64, 56, 56, 128, 3), 2, 1, True), ("conv2d_grad_w", (64, 64, 56, 56, 128, 3), 2, 1, False),
+                    ("dense_grad_x", (64, 1000, 512), 1, 0, True), ("dense_grad_w", (64, 1000, 512), 1, 0, False)]
+
+
+@pytest.mark.parametrize("case", BENCH_GRAD_CASES, ids=[f"{c[0]}-s{c[2]}" for c in BENCH_GRAD_CASES])
+def test_gradient_operators_at_the_sizes_the_bench_times(case):
+    # every element, at full size, in the plans `bench.py --workload grads` times
+    kind, dims, stride, pad, is_param = case
+    spec, data = W.grad_case(kind, dims, "bf16", stride, pad, second_is_param=is_param)
+    print(f"bench-size gradient case {case}: {[st['kernel'] for st in s_plan_steps(spec)]}", flush=True)
+    check_graph(spec, data, f"bench-size {kind} {dims} s{stride}")
+
+
+def test_gradient_chain_at_the_size_the_bench_times():
+    spec, data = W.grad_chain(64, 128, 28, 3, "bf16")
+    check_graph(spec, data, "bench-size chain of three conv2d_grad_x")
+
+
 def _random_grad_cases(n, seed=4952):
     rng = np.random.default_rng(seed)
     cases = []
