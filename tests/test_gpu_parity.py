@@ -266,6 +266,11 @@ PAIR_CASES = [
     (16, 64, 128, 56, 56),       # 128x64, four stages
     (17, 64, 136, 55, 57),       # 128x128, odd image, N tail
     (64, 64, 128, 56, 56),       # 256x128
+    (8, 128, 256, 28, 28),       # the projection reads 128 channels: two K tiles
+    (64, 128, 256, 28, 28),      # the benchmark's second pair
+    (3, 128, 384, 9, 11),        # six channel chunks, ragged pixel tiles
+    (2, 64, 256, 5, 7),          # fewer pixel tiles than waves
+    (9, 256, 512, 14, 14),       # 256 input channels: four K tiles
 ]
 
 
