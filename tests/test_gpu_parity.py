@@ -563,7 +563,8 @@ def test_resnet_small_end_to_end_and_per_group(dtype):
                          budget=None if dtype == "bf16" else (lambda: error_budget(sub, sd)[vid]))
 
 
-@pytest.mark.parametrize("which", ["resnet_small_f32", "resnet_small_bf16", "conv_bf16", "mlp_f32", "splitk_f32", "channel_last_bf16"])
+@pytest.mark.parametrize("which", ["resnet_small_f32", "resnet_small_bf16", "conv_bf16", "mlp_f32", "splitk_f32", "channel_last_bf16", "grad_w_bf16", "grad_x_stride2_bf16",
+                                   "stem_pool_bf16"])
 def test_plan_replays_from_a_hip_graph(which):
     # one rl_plan_run captured into a HIP graph, then replayed with fresh inputs, with eager work and
     # synchronisation between the replays; every replay must reproduce the eager run bit for bit
@@ -581,6 +582,18 @@ def test_plan_replays_from_a_hip_graph(which):
         spec, data = W.conv_group(1, 256, 256, 14, 14, 3, 1, 1, "f32", residual=True, relu=True)
         s = harness.Session(spec); s.load(data)
         assert any(st["kernel"].endswith("_splitk") for st in s.plan.describe()["steps"])
+    elif which == "grad_w_bf16":                    # two transpositions, the contraction, the ordered reduction of its row segments
+        spec, data = W.grad_case("conv2d_grad_w", (64, 64, 9, 8, 128, 3), "bf16", 2, 1, second_is_param=False)
+        s = harness.Session(spec); s.load(data)
+        assert any(st["kernel"] == "wgrad_reduce" for st in s.plan.describe()["steps"])
+    elif which == "grad_x_stride2_bf16":            # dy spread out with zeros by a step of its own, then the forward kernels
+        spec, data = W.grad_case("conv2d_grad_x", (3, 8, 15, 14, 16, 3), "bf16", 2, 1)
+        s = harness.Session(spec); s.load(data)
+        assert any(st["kernel"] == "dilate_nhwc" for st in s.plan.describe()["steps"])
+    elif which == "stem_pool_bf16":                 # the fused stem + pool kernel reading the channel-first input
+        spec, data = W.conv_pool(3, 3, 64, 40, 48, 7, 2, 3, "bf16", relu=True, tail=True)
+        s = harness.Session(spec); s.load(data)
+        assert any(st["kernel"].endswith("stem_maxpool_direct") for st in s.plan.describe()["steps"])
     elif which == "channel_last_bf16":              # typed views: the first group reads the caller's buffer, the last writes the output
         spec, data = W.channel_last_block(3, 64, 14, 14, "bf16")
         s = harness.Session(spec); s.load(data)
