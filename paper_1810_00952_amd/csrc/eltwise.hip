@@ -191,14 +191,20 @@ hipError_t launch_eltwise(const EltwiseParams &p0, hipStream_t s)
 // ---------------------------------------------------------------------------
 // stand-alone LSTM gate group: z[B, 4H] in (i | f | g | o) blocks
 // ---------------------------------------------------------------------------
-template <typename V> __device__ __forceinline__ V ld_maybe_nt(const V *p, bool nt) { return nt ? __builtin_nontemporal_load(p) : *p; }
+template <typename V> __device__ __forceinline__ V ld_maybe_nt(const V *p, bool nt)
+{
+    if (nt) return __builtin_nontemporal_load(p);
+    return *p;
+}
 template <typename V> __device__ __forceinline__ void st_maybe_nt(V *p, V v, bool nt) { if (nt) __builtin_nontemporal_store(v, p); else *p = v; }
 
-// one thread per four hidden units (16-byte accesses), one pass
+// one thread per four hidden units (16-byte accesses), one pass.  NT: streaming accesses (a compile-time choice: selected at
+// run time, the two kinds of access fold into the plain one)
+template <bool NT>
 __global__ __launch_bounds__(256) void lstm_gates_kernel(const GatesParams p)
 {
     const int64_t total = (int64_t)p.B * p.H;
-    const bool nt = p.nt != 0;
+    constexpr bool nt = NT;
     if ((p.H & 3) == 0) {
         const int64_t q = (int64_t)blockIdx.x * 256 + threadIdx.x;
         if (q < (total >> 2)) {
@@ -245,7 +251,8 @@ hipError_t launch_lstm_gates(const GatesParams &p0, hipStream_t s)
     const int64_t blocks = std::max<int64_t>(1, (work + 255) / 256);
     if (blocks > 0x7fffffff) return hipErrorInvalidValue;
     p.nt = total >= ((int64_t)8 << 20);
-    hipLaunchKernelGGL(lstm_gates_kernel, dim3((unsigned)blocks), dim3(256), 0, s, p);
+    if (p.nt) hipLaunchKernelGGL(lstm_gates_kernel<true>, dim3((unsigned)blocks), dim3(256), 0, s, p);
+    else hipLaunchKernelGGL(lstm_gates_kernel<false>, dim3((unsigned)blocks), dim3(256), 0, s, p);
     return hipGetLastError();
 }
 
@@ -486,7 +493,7 @@ __global__ __launch_bounds__(256) void transpose_kernel(const T *__restrict__ sr
 // LDS: a lane reads a VEC x VEC block as VEC row vectors, transposes it in registers and writes VEC column
 // vectors.  A wave covers 8 x 8 such blocks; eight lanes read 128 contiguous bytes of a row, and eight lanes
 // write 128 contiguous bytes of a result row.
-template <typename T>
+template <typename T, bool NT>
 __global__ __launch_bounds__(256) void transpose_vec_kernel(const T *__restrict__ src, T *__restrict__ dst, int R, int Q, int tiles_r, int tiles_q,
                                                             int64_t total_tiles)
 {
@@ -504,7 +511,7 @@ __global__ __launch_bounds__(256) void transpose_vec_kernel(const T *__restrict_
         const T *sp = src + (n * R + r0) * Q + q0;
         u32x4 in[VEC];
 #pragma unroll
-        for (int i = 0; i < VEC; ++i) in[i] = *(const u32x4 *)(sp + (int64_t)i * Q);
+        for (int i = 0; i < VEC; ++i) in[i] = NT ? __builtin_nontemporal_load((const u32x4 *)(sp + (int64_t)i * Q)) : *(const u32x4 *)(sp + (int64_t)i * Q);
         T *dp = dst + (n * Q + q0) * R + r0;
 #pragma unroll
         for (int j = 0; j < VEC; ++j) {
@@ -520,7 +527,8 @@ __global__ __launch_bounds__(256) void transpose_vec_kernel(const T *__restrict_
                     o[k] = (j & 1) ? ((a >> 16) | (b & 0xffff0000u)) : ((a & 0xffffu) | (b << 16));
                 }
             }
-            *(u32x4 *)(dp + (int64_t)j * R) = o;
+            if (NT) __builtin_nontemporal_store(o, (u32x4 *)(dp + (int64_t)j * R));
+            else *(u32x4 *)(dp + (int64_t)j * R) = o;
         }
     }
 }
@@ -533,8 +541,12 @@ static hipError_t launch_transpose(const void *src, void *dst, int dtype, int N,
         const int tiles_r = (R + ts - 1) / ts, tiles_q = (Q + ts - 1) / ts;
         const int64_t total = (int64_t)N * tiles_r * tiles_q;
         const unsigned grid = (unsigned)std::min<int64_t>((total + 3) / 4, 256 * 64);
-        if (dtype == DT_BF16) hipLaunchKernelGGL(transpose_vec_kernel<uint16_t>, dim3(grid), dim3(256), 0, s, (const uint16_t *)src, (uint16_t *)dst, R, Q, tiles_r, tiles_q, total);
-        else hipLaunchKernelGGL(transpose_vec_kernel<float>, dim3(grid), dim3(256), 0, s, (const float *)src, (float *)dst, R, Q, tiles_r, tiles_q, total);
+        // tensors larger than the last-level cache: streaming accesses (bf16 256x64x112x112: 140 us against 154)
+        const bool nt = (int64_t)N * R * Q * (dtype == DT_BF16 ? 2 : 4) >= ((int64_t)1 << 28);
+        if (dtype == DT_BF16 && nt) hipLaunchKernelGGL((transpose_vec_kernel<uint16_t, true>), dim3(grid), dim3(256), 0, s, (const uint16_t *)src, (uint16_t *)dst, R, Q, tiles_r, tiles_q, total);
+        else if (dtype == DT_BF16) hipLaunchKernelGGL((transpose_vec_kernel<uint16_t, false>), dim3(grid), dim3(256), 0, s, (const uint16_t *)src, (uint16_t *)dst, R, Q, tiles_r, tiles_q, total);
+        else if (nt) hipLaunchKernelGGL((transpose_vec_kernel<float, true>), dim3(grid), dim3(256), 0, s, (const float *)src, (float *)dst, R, Q, tiles_r, tiles_q, total);
+        else hipLaunchKernelGGL((transpose_vec_kernel<float, false>), dim3(grid), dim3(256), 0, s, (const float *)src, (float *)dst, R, Q, tiles_r, tiles_q, total);
         return hipGetLastError();
     }
     dim3 grid((Q + 31) / 32, (R + 31) / 32, N);
