@@ -191,44 +191,51 @@ hipError_t launch_eltwise(const EltwiseParams &p0, hipStream_t s)
 // ---------------------------------------------------------------------------
 // stand-alone LSTM gate group: z[B, 4H] in (i | f | g | o) blocks
 // ---------------------------------------------------------------------------
-template <typename V> __device__ __forceinline__ V ld_maybe_nt(const V *p, bool nt)
+// streaming or plain access, chosen at compile time.  (With the choice as a run-time argument the two branches hold the
+// same access twice, the optimiser merges them into one before inlining, and the merged access keeps no streaming hint.)
+template <bool NT, typename V> __device__ __forceinline__ V ld_maybe_nt(const V *p)
 {
-    if (nt) return __builtin_nontemporal_load(p);
-    return *p;
+    if constexpr (NT) return __builtin_nontemporal_load(p);
+    else return *p;
 }
-template <typename V> __device__ __forceinline__ void st_maybe_nt(V *p, V v, bool nt) { if (nt) __builtin_nontemporal_store(v, p); else *p = v; }
+template <bool NT, typename V> __device__ __forceinline__ void st_maybe_nt(V *p, V v)
+{
+    if constexpr (NT) __builtin_nontemporal_store(v, p);
+    else *p = v;
+}
 
-// one thread per four hidden units (16-byte accesses), one pass.  NT: streaming accesses (a compile-time choice: selected at
-// run time, the two kinds of access fold into the plain one)
+// one thread per four hidden units (16-byte accesses), one pass.  NT: streaming loads for tensors beyond the last-level cache
+// (measured at 16384 rows of 1024 hidden units: 78.5 us plain, 68.1 us with streaming loads, 69.4-69.9 us with streaming stores as well, so
+// the stores stay plain)
 template <bool NT>
 __global__ __launch_bounds__(256) void lstm_gates_kernel(const GatesParams p)
 {
     const int64_t total = (int64_t)p.B * p.H;
-    constexpr bool nt = NT;
+    constexpr bool NTS = false;
     if ((p.H & 3) == 0) {
         const int64_t q = (int64_t)blockIdx.x * 256 + threadIdx.x;
         if (q < (total >> 2)) {
             int64_t idx = q << 2;
             int b = (int)(idx / p.H), u = (int)(idx - (int64_t)b * p.H);
             const float *zr = p.z + (int64_t)b * 4 * p.H + u;
-            f32x4 zi = ld_maybe_nt((const f32x4 *)zr, nt), zf = ld_maybe_nt((const f32x4 *)(zr + p.H), nt);
-            f32x4 zg = ld_maybe_nt((const f32x4 *)(zr + 2 * p.H), nt), zo = ld_maybe_nt((const f32x4 *)(zr + 3 * p.H), nt);
-            f32x4 c = ld_maybe_nt((const f32x4 *)(p.c_in + idx), nt), cn;
+            f32x4 zi = ld_maybe_nt<NT>((const f32x4 *)zr), zf = ld_maybe_nt<NT>((const f32x4 *)(zr + p.H));
+            f32x4 zg = ld_maybe_nt<NT>((const f32x4 *)(zr + 2 * p.H)), zo = ld_maybe_nt<NT>((const f32x4 *)(zr + 3 * p.H));
+            f32x4 c = ld_maybe_nt<NT>((const f32x4 *)(p.c_in + idx)), cn;
             float hn[4];
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
                 cn[k] = sigmoidf_(zf[k]) * c[k] + sigmoidf_(zi[k]) * tanhf_(zg[k]);
                 hn[k] = sigmoidf_(zo[k]) * tanhf_(cn[k]);
             }
-            st_maybe_nt((f32x4 *)(p.c_out + idx), cn, nt);
+            st_maybe_nt<NTS>((f32x4 *)(p.c_out + idx), cn);
             if (p.h_dtype == DT_BF16) {
                 u32x2 r;
                 r[0] = f32_to_bf16_bits(hn[0]) | (f32_to_bf16_bits(hn[1]) << 16);
                 r[1] = f32_to_bf16_bits(hn[2]) | (f32_to_bf16_bits(hn[3]) << 16);
-                st_maybe_nt((u32x2 *)((uint16_t *)p.h_out + idx), r, nt);
+                st_maybe_nt<NTS>((u32x2 *)((uint16_t *)p.h_out + idx), r);
             } else {
                 f32x4 hv = {hn[0], hn[1], hn[2], hn[3]};
-                st_maybe_nt((f32x4 *)((float *)p.h_out + idx), hv, nt);
+                st_maybe_nt<NTS>((f32x4 *)((float *)p.h_out + idx), hv);
             }
         }
     } else {
