@@ -52,7 +52,7 @@ def _p(a: np.ndarray):
 
 
 def _d(a) -> np.ndarray:
-    return np.ascontiguousarray(a, dtype=np.float64)
+    return np.asarray(a, dtype=np.float64, order="C")          # (unlike ascontiguousarray, keeps a rank-0 array rank 0)
 
 
 def _i(v):
@@ -218,9 +218,9 @@ def widen(a: np.ndarray, dtype: str) -> np.ndarray:
     """Exact widening of stored tensor data (float32 array, or uint16 bf16 bit
     patterns) to float64."""
     if dtype == "bf16":
-        a = np.ascontiguousarray(a, dtype=np.uint16)
+        a = np.asarray(a, dtype=np.uint16, order="C")
         return (a.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
-    return np.ascontiguousarray(a, dtype=np.float32).astype(np.float64)
+    return np.asarray(a, dtype=np.float32, order="C").astype(np.float64)
 
 
 def lstm_sequence(x_seq, w, b, h0, c0, h_dtype="bf16"):

@@ -16,9 +16,9 @@ _TORCH_DT = {"f32": torch.float32, "bf16": torch.bfloat16}
 def to_device(a: np.ndarray, dtype: str, device="cuda:0") -> torch.Tensor:
     """float32 array, or uint16 bf16 bit patterns, to a device tensor (bit-exact)."""
     if dtype == "bf16":
-        t = torch.from_numpy(np.ascontiguousarray(a, dtype=np.uint16).view(np.int16)).to(device)
+        t = torch.from_numpy(np.asarray(a, dtype=np.uint16, order="C").view(np.int16)).to(device)
         return t.view(torch.bfloat16)
-    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(device)
+    return torch.from_numpy(np.asarray(a, dtype=np.float32, order="C")).to(device)
 
 
 def to_host(t: torch.Tensor) -> np.ndarray:

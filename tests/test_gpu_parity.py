@@ -378,7 +378,7 @@ def test_run_twice_is_bitwise_identical():
 
 # ------------------------------------------------------------------ elementwise groups
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-@pytest.mark.parametrize("shape", [(7, 5, 33), (4096,), (3, 1000, 9), (1,), (2, 3, 4, 5, 6)])
+@pytest.mark.parametrize("shape", [(7, 5, 33), (4096,), (3, 1000, 9), (1,), (2, 3, 4, 5, 6), ()])
 def test_eltwise_chain_all_ops(dtype, shape):
     spec, data = W.eltwise_chain(shape, dtype)
     check_graph(spec, data, f"eltwise chain {dtype} {shape}")

@@ -72,6 +72,32 @@ def test_failed_op_leaves_graph_unchanged():
     assert (o, y) == (0, 2)          # ids continue as if the failed call never happened
 
 
+def test_degenerate_tensor_types():
+    """A dimension is a positive constant (an empty tensor has no type here), a scalar is a rank-0 tensor, the rank and
+    the base type are bounded: the degenerate declarations are errors of their own category, and leave the graph as it was."""
+    ctx = B.Context()
+    g = B.Graph(ctx)
+    for shape in [(0, 3), (2, 0), (-1, 3)]:
+        with pytest.raises(B.RelayError) as ei:
+            g.input("f32", shape)
+        assert ei.value.category == "shape" and "positive" in str(ei.value)
+    with pytest.raises(B.RelayError) as ei:
+        g.input("f32", (1,) * 9)
+    assert ei.value.category == "kind" and "rank" in str(ei.value)
+    with pytest.raises(B.RelayError) as ei:
+        g.input("f16", (2, 2))
+    assert ei.value.category == "kind"
+    a = g.input("f32", ())                       # rank 0
+    assert a == 0                                # none of the failed declarations took an id
+    o, (y,) = g.op("tanh", [a], [("f32", ())])
+    with pytest.raises(B.RelayError) as ei:      # a scalar is not a rank-1 tensor of one element
+        g.op("relu", [y], [("f32", (1,))])
+    assert ei.value.category == "type"
+    g.group([o]); g.output(y)
+    d = B.Plan(g).describe()
+    assert [s["kernel"] for s in d["steps"]] == ["eltwise_chain"]
+
+
 def test_resnet18_plan_structure():
     spec, raw, bn = W.resnet18(batch=64, dtype="bf16")
     ctx = B.Context()

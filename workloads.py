@@ -108,14 +108,15 @@ def rng_for(config: int, salt: int = 0) -> np.random.Generator:
 
 def f32_to_bf16_bits(a: np.ndarray) -> np.ndarray:
     """float32 -> bf16 bit patterns (uint16), round to nearest, ties to even."""
+    shape = np.shape(a)
     u = np.ascontiguousarray(a, dtype=np.float32).view(np.uint32)
     lsb = (u >> np.uint32(16)) & np.uint32(1)
     r = u + np.uint32(0x7FFF) + lsb
-    return (r >> np.uint32(16)).astype(np.uint16)
+    return (r >> np.uint32(16)).astype(np.uint16).reshape(shape)          # (a rank-0 array stays rank 0)
 
 
 def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
-    return (np.ascontiguousarray(b, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
+    return (np.ascontiguousarray(b, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32).reshape(np.shape(b))
 
 
 def as_dtype(a: np.ndarray, dtype: str) -> np.ndarray:
