@@ -623,6 +623,51 @@ def test_plan_replays_from_a_hip_graph(which):
         assert all(bool(torch.isfinite(a.float()).all()) for a in got)
 
 
+@pytest.mark.parametrize("which", ["resnet_bf16", "resnet_f32", "grad_w_bf16"])
+def test_two_sessions_on_two_streams_do_not_disturb_each_other(which):
+    # Independent steps may overlap on the GPU (a caller's second stream, or the two-stream figure of the benchmark):
+    # two sessions with buffers of their own and different inputs, launched alternately on two streams without any
+    # synchronisation in between, must each give the bits they give when run alone.
+    import torch
+    from paper_1810_00952_amd import harness
+    sess = []
+    for k in range(2):
+        if which.startswith("resnet"):
+            dtype = which.split("_")[1]
+            spec, raw, bn = W.resnet18(batch=4, dtype=dtype, image=96, width=64, classes=40)
+            s = harness.Session(spec)
+            fold_resnet_hip(s, raw, bn, dtype)
+        else:                                       # a plan with scratch tensors in its workspace
+            spec, data = W.grad_case("conv2d_grad_w", (64, 64, 9, 8, 128, 3), "bf16", 2, 1, second_is_param=False)
+            s = harness.Session(spec); s.load(data)
+        s.alloc()
+        sess.append(s)
+    gen = torch.Generator(device="cuda:0"); gen.manual_seed(11)
+    xin = [vid for vid, v in enumerate(spec.values) if v.role == "input"]
+    for s in sess:                                  # different inputs in the two sessions
+        for vid in xin:
+            t = s.tensors[vid]
+            t.copy_(torch.randn(t.shape, generator=gen, device="cuda:0", dtype=torch.float32).to(t.dtype))
+    alone = []
+    for s in sess:
+        s.run()
+        torch.cuda.synchronize()
+        alone.append([s.tensors[vid].clone() for vid in spec.outputs])
+        for vid in spec.outputs:
+            s.tensors[vid].zero_()
+    assert not torch.equal(alone[0][0], alone[1][0])
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    for rep in range(6):
+        for k in (0, 1):
+            with torch.cuda.stream(streams[k]):
+                sess[k].run()
+    torch.cuda.synchronize()
+    for k in (0, 1):
+        for a, vid in zip(alone[k], spec.outputs):
+            assert torch.equal(a.view(torch.uint8), sess[k].tensors[vid].view(torch.uint8)), f"{which}: session {k} differs when overlapped with the other"
+
+
 def test_resnet18_f32_batch1():
     spec, raw, bn = W.resnet18(batch=1, dtype="f32")
     ref = OG.run(spec, fold_resnet_oracle(raw, bn, "f32"))[spec.outputs[0]]
