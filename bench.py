@@ -381,6 +381,21 @@ def bench_lstm(args):
                              ws.data_ptr(), ws.numel(), harness.stream_handle())
     ms = time_steps(run, args.steps, args.warmup)
     timing = dict(TIMING)
+    ms_two = None
+    if not args.no_extras:
+        # two independent batches of sequences on two streams (second cell state, outputs and workspace; x, h_0 and
+        # the weights are only read): one stream's step kernel runs between two dependent launches of the other
+        c2, hs2, ws2 = torch.zeros_like(c), torch.empty_like(hs), torch.empty_like(ws)
+
+        def run2():
+            c2.zero_()
+            s.plan.run_recurrent(T, roles, x.data_ptr(), B * I * 2, h0.data_ptr(), c2.data_ptr(), hs2.data_ptr(), B * H * 2, params,
+                                 ws2.data_ptr(), ws2.numel(), harness.stream_handle())
+
+        class _R:
+            def __init__(self, f): self.run = f
+        ms_two = time_steps_on_streams([_R(run), _R(run2)], args.steps, args.warmup)
+        assert bool(torch.equal(hs, hs2)), "the two streams' sequences differ"
     # the same sequence of launches replayed from a HIP graph (the cell-state reset and every kernel of the sequence)
     ms_graph = time_steps(run, args.steps, args.warmup, graph=True) if not GRAPH else None
     TIMING.clear(); TIMING.update(timing)
@@ -400,6 +415,9 @@ def bench_lstm(args):
                     + ("input projection hoisted, one recurrent kernel per step" if hoisted else
                        "gate math fused into the GEMM epilogue" if not args.unfused else "GEMM group and gate group"))
     out["us_per_step_of_sequence"] = ms * 1e3 / T
+    if ms_two is not None:
+        out["two_streams"] = {"value": B / (ms_two * 1e-3), "unit": "sequences/s", "ms_per_step": ms_two, "streams": 2,
+                              "note": "independent batches of sequences dealt alternately to two streams; host clock, device synchronisation on both sides"}
     if ms_graph is not None:
         out["hip_graph_replay"] = {"ms_per_step": ms_graph, "us_per_step_of_sequence": ms_graph * 1e3 / T, "sequences_per_s": B / (ms_graph * 1e-3)}
     tflops, gbs = flops / (ms * 1e-3) / 1e12, nbytes / (ms * 1e-3) / 1e9
