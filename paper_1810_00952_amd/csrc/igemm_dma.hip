@@ -355,6 +355,54 @@ hipError_t launch_splitk_reduce(const IgemmParams &p, hipStream_t s)
     return hipGetLastError();
 }
 
+// The adding launch of a split dense contraction together with the small dense layer that consumes its result: one
+// workgroup per row.  Threads add the slices of their columns in slice order and apply the first group's epilogue
+// (and the rounding to the dtype the tensor between the groups has), the row meets in LDS, then every wave takes
+// output columns in turn: lanes multiply a strided share of the row, the 64 shares are added in a fixed tree.
+__global__ __launch_bounds__(256) void reduce_dense_kernel(const ReduceDenseParams p)
+{
+    __shared__ float hs[REDUCE_DENSE_MAX_N1];
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const int m = blockIdx.x;
+    const int64_t slice = (int64_t)p.M * p.N1;
+    for (int n = t; n < p.N1; n += 256) {
+        const float *src = p.partial + (int64_t)m * p.N1 + n;
+        float val = 0.0f;
+        for (int z0 = 0; z0 < p.splits; z0 += 8) {
+            float v[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) v[j] = z0 + j < p.splits ? src[(int64_t)(z0 + j) * slice] : 0.0f;
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                if (z0 + j < p.splits) val = z0 + j == 0 ? v[j] : val + v[j];
+        }
+        const int64_t off = (int64_t)m * p.hs_n + (int64_t)n * p.hs_c;
+        for (int s = 0; s < p.epi1.n_ops; ++s) val = epi_step(p.epi1, s, val, off, n);
+        hs[n] = p.h_dtype == DT_BF16 ? round_bf16(val) : val;
+    }
+    __syncthreads();
+    for (int j = wave; j < p.N2; j += 4) {
+        float acc = 0.0f;
+        for (int n = lane; n < p.N1; n += 64) acc += hs[n] * load_as_f32(p.w2, p.w_dtype, (int64_t)j * p.Kp2 + n);
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) acc += __shfl_xor(acc, d, 64);
+        if (lane == 0) {
+            const int64_t off = (int64_t)m * p.ys_n + (int64_t)j * p.ys_c;
+            for (int s = 0; s < p.epi2.n_ops; ++s) acc = epi_step(p.epi2, s, acc, off, j);
+            store_from_f32(p.y, p.y_dtype, off, acc);
+        }
+    }
+}
+
+hipError_t launch_reduce_dense(const ReduceDenseParams &p, hipStream_t s)
+{
+    if (!p.partial || !p.w2 || !p.y || p.splits < 2 || p.splits > 64 || p.M < 1 || p.M > 65535 || p.N1 < 1 || p.N1 > REDUCE_DENSE_MAX_N1 ||
+        p.N2 < 1 || p.N2 > REDUCE_DENSE_MAX_N2 || p.Kp2 < p.N1 || (int64_t)p.M * p.N1 * p.splits >= (int64_t)1 << 31)
+        return hipErrorInvalidValue;
+    hipLaunchKernelGGL(reduce_dense_kernel, dim3((unsigned)p.M), dim3(256), 0, s, p);
+    return hipGetLastError();
+}
+
 // explicit instantiations (the host-side launch stubs of a kernel template with function-local
 // __shared__ arrays are not emitted implicitly)
 #define RL_INST(T, BM, BN, G) template __global__ void igemm_dma_kernel<T, BM, BN, G>(const IgemmParams);
@@ -384,7 +432,7 @@ static hipError_t launch_dma(const IgemmParams &p0, hipStream_t s)
             return hipErrorInvalidValue;
         hipLaunchKernelGGL((igemm_dma_kernel<T, BM, BN, GATES>), dim3((unsigned)nblk, (unsigned)p.splits), dim3(256), 0, s, p);
         hipError_t er = hipGetLastError();
-        if (er != hipSuccess) return er;
+        if (er != hipSuccess || p.skip_reduce) return er;
         return launch_splitk_reduce(p, s);
     }
     hipLaunchKernelGGL((igemm_dma_kernel<T, BM, BN, GATES>), dim3((unsigned)nblk), dim3(256), 0, s, p);

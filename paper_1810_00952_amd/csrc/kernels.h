@@ -92,6 +92,7 @@ struct IgemmParams {
     int32_t nmajor;                        // conv3x3_run_ks_kernel: 1: tiles in channel-tile-major order
     int32_t splits, split_tiles;           // split_tiles: K tiles per slice
     float *partial;
+    int32_t skip_reduce;                   // direct-load variant, splits > 1: the slices are added by the caller's next launch
 };
 // q = n / d for n < 2^31:  d == 1 ? n : (mulhi(n, mul) >> sh)
 void make_fast_div(uint32_t d, uint32_t &mul, uint32_t &sh);
@@ -111,6 +112,26 @@ struct IgemmLaunch {
     int32_t s2pair;     // 1 (first step of a pair): the pair runs as one stride-2 contraction with two accumulator sets (conv3x3s2.hip)
 };
 hipError_t launch_igemm(const IgemmParams &p, const IgemmLaunch &l, hipStream_t s);
+
+// The adding launch of a split dense contraction, and the small dense layer behind it, in one kernel: row m of
+//   h = epi1(partial[0][m][:] + partial[1][m][:] + ...)         (slices in order; rounded to h_dtype as the tensor between
+//   y[m][j] = epi2(sum_n h[n] * w2[j][n])                         the two groups would be)
+// by one workgroup, h staying in LDS.  N1 <= 2048, N2 <= 64; w2 row-major with rows Kp2 elements apart.
+struct ReduceDenseParams {
+    const float *partial;
+    int32_t splits, M, N1;
+    Epilogue epi1;
+    int64_t hs_n, hs_c;          // strides of h as the operands of epi1 are laid out
+    int32_t h_dtype;
+    const void *w2;
+    int32_t w_dtype, N2, Kp2;
+    Epilogue epi2;
+    void *y;
+    int32_t y_dtype;
+    int64_t ys_n, ys_c;
+};
+constexpr int REDUCE_DENSE_MAX_N1 = 2048, REDUCE_DENSE_MAX_N2 = 64;
+hipError_t launch_reduce_dense(const ReduceDenseParams &p, hipStream_t s);
 // two independent pixel-on-lane contractions that use the same kernel variant, in one launch (igemm_lp.hip)
 bool igemm_lp_can_pair(const IgemmParams &a, const IgemmLaunch &la, const IgemmParams &b, const IgemmLaunch &lb);
 hipError_t launch_igemm_lp_pair(const IgemmParams &a, const IgemmLaunch &la, const IgemmParams &b, const IgemmLaunch &lb, hipStream_t s);

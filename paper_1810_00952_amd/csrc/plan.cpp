@@ -1031,6 +1031,7 @@ struct Planner {
         }
         fuse_stem_pool();
         pair_contractions();
+        chain_small_dense();
         assign_workspace();
         return RL_OK;
     }
@@ -1132,6 +1133,42 @@ struct Planner {
             a.flops += b.flops; a.bytes += b.bytes;
             b.flops = 0; b.bytes = 0;
             a.name += " | " + b.name;
+            b.kernel = "(launched with the step before)";
+            ++si;
+        }
+    }
+
+    // A dense contraction whose K is split over workgroups ends in a launch that adds the slices.  When its result feeds
+    // nothing but a small dense layer right behind it (an MLP's output layer), that launch computes the small layer as
+    // well, a row per workgroup, and the tensor between the two groups never leaves LDS: a launch fewer on graphs
+    // whose time is the number of their launches.
+    void chain_small_dense()
+    {
+        if (plan.opts.no_dense_chain) return;
+        for (size_t si = 0; si + 1 < plan.steps.size(); ++si) {
+            Step &a = plan.steps[si];
+            Step &b = plan.steps[si + 1];
+            if (a.kind != S_IGEMM || b.kind != S_IGEMM || a.pair || b.pair || a.chain || b.chain || a.stem || b.stem) continue;
+            const IgemmParams &pa = a.ig, &pb = b.ig;
+            if (a.il.splits < 2 || !a.il.avec || !a.il.dma || a.il.lp || a.il.gates || b.il.gates) continue;
+            if (pa.OHW != 1 || pb.OHW != 1 || pa.KH * pa.KW != 1 || pb.KH * pb.KW != 1) continue;                       // two dense layers
+            if (pa.ys_c != 1 || pa.ys_n != pa.N || pa.N > REDUCE_DENSE_MAX_N1 || pa.M > 65535) continue;
+            if (pb.M != pa.M || pb.K != pa.N || pb.K1 != pb.K || pb.N > REDUCE_DENSE_MAX_N2 || pb.xs_c != 1 || pb.xs_n != pa.N) continue;
+            if (b.slot[SL_X2] >= 0 || pb.in_dtype != pa.y_dtype) continue;
+            const int h = a.slot[SL_Y];
+            if (h < 0 || plan.bufs[h].bound_value >= 0 || b.slot[SL_X] != h) continue;                               // the result is the plan's own
+            bool other = false;                                                                                        // ... and nobody else's
+            for (size_t sj = 0; sj < plan.steps.size(); ++sj)
+                for (int q = 0; q < SL_COUNT; ++q)
+                    if (plan.steps[sj].slot[q] == h && !((sj == si && q == SL_Y) || (sj == si + 1 && q == SL_X))) other = true;
+            if (other) continue;
+            a.chain = 1; b.chain = 2;
+            b.slot[SL_PART] = -1;                       // the small layer's own K split, if it had one, is not used
+            b.il.splits = 1; b.ig.splits = 0; b.ig.split_tiles = 0;
+            a.kernel += "+dense";
+            a.name += " > " + b.name;
+            a.flops += b.flops; a.bytes += b.bytes - 2.0 * plan.bufs[h].bytes;      // the tensor between them is neither written nor read
+            b.flops = 0; b.bytes = 0;
             b.kernel = "(launched with the step before)";
             ++si;
         }
@@ -1263,7 +1300,7 @@ rl_status run_steps(const Plan &plan, void *const *ptrs, hipStream_t stream, std
         ++si;
         if (er == hipSuccess) switch (s.kind) {
         case S_IGEMM: {
-            if (s.pair == 2) break;                 // went out with the step before
+            if (s.pair == 2 || s.chain == 2) break; // went out with the step before
             auto params = [&](const Step &t) {
                 IgemmParams p = t.ig;
                 p.x = P(t, SL_X); p.x2 = P(t, SL_X2); p.w = P(t, SL_W); p.y = P(t, SL_Y);
@@ -1273,7 +1310,20 @@ rl_status run_steps(const Plan &plan, void *const *ptrs, hipStream_t stream, std
                 p.partial = (float *)P(t, SL_PART);
                 return p;
             };
-            if (s.pair == 1) {
+            if (s.chain == 1) {
+                const Step &t = plan.steps[si];     // si already counts this step: the next one
+                IgemmParams pa = params(s), pb = params(t);
+                pa.skip_reduce = 1;
+                er = launch_igemm(pa, s.il, stream);
+                if (er == hipSuccess) {
+                    ReduceDenseParams r{};
+                    r.partial = pa.partial; r.splits = pa.splits; r.M = pa.M; r.N1 = pa.N;
+                    r.epi1 = pa.epi; r.hs_n = pa.ys_n; r.hs_c = pa.ys_c; r.h_dtype = pa.y_dtype;
+                    r.w2 = pb.w; r.w_dtype = pb.in_dtype; r.N2 = pb.N; r.Kp2 = pb.Kp;
+                    r.epi2 = pb.epi; r.y = pb.y; r.y_dtype = pb.y_dtype; r.ys_n = pb.ys_n; r.ys_c = pb.ys_c;
+                    er = launch_reduce_dense(r, stream);
+                }
+            } else if (s.pair == 1) {
                 const Step &t = plan.steps[si];     // si already counts this step: the next one
                 er = s.il.s2pair ? launch_conv3x3s2_pair(params(s), s.il, params(t), t.il, stream)
                                  : launch_igemm_lp_pair(params(s), s.il, params(t), t.il, stream);

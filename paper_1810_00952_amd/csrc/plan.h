@@ -40,6 +40,8 @@ struct Step {
     int stem_direct = 0, stem_kw = 0;   // S_STEM_POOL reading the channel-first input itself (st_* and t_C: its geometry; stem_kw: filter width)
     int pair = 0;                       // S_IGEMM: 1: launched together with the next step (an independent contraction of the
                                         // same tile shape); 2: that next step, which launches nothing itself
+    int chain = 0;                      // S_IGEMM: 1: a split dense contraction whose adding launch also runs the next step (a
+                                        // small dense layer on its result); 2: that next step, which launches nothing itself
     int slot[SL_COUNT];
     double flops = 0, bytes = 0;
     Step() { for (int &s : slot) s = -1; }

@@ -33,6 +33,36 @@ def test_mlp(dtype, batch, d_in, d_hidden, d_out):
     check_graph(spec, data, f"mlp {dtype} {batch}x{d_in}x{d_hidden}x{d_out}")
 
 
+DENSE_CHAIN_CASES = [(32, 784, 128, 10, "f32"), (32, 784, 128, 10, "bf16"), (1, 800, 500, 10, "f32"), (64, 800, 500, 10, "f32"), (7, 2048, 2048, 64, "f32"),
+                     (130, 1024, 136, 3, "f32"), (5, 516, 100, 1, "f32"), (33, 1000, 72, 24, "bf16")]
+
+
+@pytest.mark.parametrize("case", DENSE_CHAIN_CASES, ids=[f"b{c[0]}-{c[1]}-{c[2]}-{c[3]}-{c[4]}" for c in DENSE_CHAIN_CASES])
+def test_small_dense_layer_behind_a_split_contraction_rides_on_its_adding_launch(case):
+    # two launches (split contraction; its slices added, epilogue, the small layer) against three or four, the tensor
+    # between the groups never stored: against the oracle like every other plan, and the same plan without the chain
+    # beside it (the small layer's sums run in another order there, so the two agree to rounding, not to the bit)
+    b, d_in, d_h, d_out, dtype = case
+    spec, data = W.mlp(b, d_in, d_h, d_out, dtype)
+    ks = [st["kernel"] for st in s_plan_steps(spec)]
+    assert ks[-2].endswith("_splitk+dense") and ks[-1] == "(launched with the step before)", ks
+    assert not any(k.endswith("+dense") for k in [st["kernel"] for st in s_plan_steps(spec, {"no_dense_chain": 1})])
+    got, ref = check_graph(spec, data, f"dense chain {case}")
+    got2, _ = check_graph(spec, data, f"dense chain {case} as separate steps", opts={"no_dense_chain": 1})
+    for vid in spec.outputs:
+        assert_close(got[vid], got2[vid], dtype, f"dense chain {case}: chained against separate")
+
+
+def test_dense_chain_is_not_planned_where_the_tensor_between_is_needed():
+    # the hidden tensor as a graph output, or read by a third group: the plan keeps the steps apart
+    spec, data = W.mlp(32, 784, 128, 10, "f32")
+    spec.output(spec.ops[2].outputs[0])             # the first group's result is an output too
+    assert not any(st["kernel"].endswith("+dense") for st in s_plan_steps(spec))
+    check_graph(spec, data, "mlp with its hidden layer as an output")
+    spec, data = W.mlp(32, 784, 128, 100, "f32")    # a second layer wider than the chain takes
+    assert not any(st["kernel"].endswith("+dense") for st in s_plan_steps(spec))
+
+
 def test_dense_gather_path_odd_k():
     # K not a multiple of the 16-byte vector: weights are re-laid-out with zero padding, A rows are gathered
     for dtype, k in (("f32", 30), ("bf16", 30), ("f32", 5), ("bf16", 77)):

@@ -424,4 +424,8 @@ def test_split_k_is_planned_for_few_tiles_and_long_k():
     assert not any(x.endswith("_splitk") for x in kernels(W.conv_group(16, 64, 64, 56, 56, 3, 1, 1, "f32")[0])[0])
     assert not any(x.endswith("_splitk") for x in kernels(W.resnet18(64, "bf16")[0])[0])
     # a dense contraction with a partial last K tile (784 = 24.5 x 32) takes the direct-load kernel
-    assert kernels(W.mlp(32, 784, 128, 10, "f32")[0])[0][0] == "igemm_dense_f32_64x64_dma_splitk"
+    assert kernels(W.mlp(32, 784, 128, 10, "f32")[0], {"no_dense_chain": 1})[0] == ["igemm_dense_f32_64x64_dma_splitk", "igemm_dense_f32_64x64_dma"]
+    # ... and, by default, its adding launch also runs the 128 -> 10 layer behind it
+    d = B.Plan(B.graph_from_spec(B.Context(), W.mlp(32, 784, 128, 10, "f32")[0])).describe()
+    assert [s["kernel"] for s in d["steps"]] == ["igemm_dense_f32_64x64_dma_splitk+dense", "(launched with the step before)"]
+    assert d["steps"][1]["flops"] == 0 and d["steps"][0]["flops"] == 2.0 * 32 * (784 * 128 + 128 * 10)
