@@ -466,8 +466,9 @@ struct Planner {
             static const int tbm[] = {128, 128, 64, 256}, tbn[] = {128, 64, 64, 128};
             const int64_t tiles = nblk(tbm[il.tile], tbn[il.tile]);
             const int nk = (p.K + 8 * KV - 1) / (8 * KV);
-            int want = (int)std::min<int64_t>(std::min<int64_t>(16, 256 / std::max<int64_t>(tiles, 1)), nk / 4);
-            if (tiles <= 64 && want >= 2 && (int64_t)want * p.M * p.N * 4 < (int64_t)1 << 28) {
+            // from 8 K tiles on (fewer: the adding launch costs more than the serial K loop); slices of at least two K tiles
+            int want = (int)std::min<int64_t>(std::min<int64_t>(16, 256 / std::max<int64_t>(tiles, 1)), nk / 2);
+            if (tiles <= 64 && nk >= 8 && want >= 2 && (int64_t)want * p.M * p.N * 4 < (int64_t)1 << 28) {
                 const int per = (nk + want - 1) / want;
                 il.splits = (nk + per - 1) / per;
                 p.splits = il.splits; p.split_tiles = per;
