@@ -113,8 +113,14 @@ __global__ __launch_bounds__(256) void igemm_fast_kernel(const IgemmParams p)
         if (n > p.N - 1) n = p.N - 1;          // rows past N are computed on valid memory and never stored
         b_off[i] = (int)((int64_t)n * p.Kp * ES);
     }
-    int ktile0 = 0;                            // first k of the tile being fetched (uniform)
-    int kc = lchunk * KV;                      // k of this thread's chunk in that tile
+    // K split over workgroups (splits > 1): workgroup (tile, z = blockIdx.y) multiplies K tiles [z*per, (z+1)*per) and
+    // leaves its bare fp32 sums in partial[z][M][N]; splitk_reduce_kernel adds the slices in order and finishes
+    const int nk_all = (p.Kp + BKE - 1) / BKE;
+    const int split = p.splits > 1 ? (int)blockIdx.y : 0;
+    const int kt_begin = p.splits > 1 ? split * p.split_tiles : 0;
+    const int kt_end = p.splits > 1 ? min(nk_all, kt_begin + p.split_tiles) : nk_all;
+    int ktile0 = kt_begin * BKE;               // first k of the tile being fetched (uniform)
+    int kc = ktile0 + lchunk * KV;             // k of this thread's chunk in that tile
     int c_cur, kh_cur, kw_cur;
     {
         int tap = kc / p.C;
@@ -193,7 +199,7 @@ __global__ __launch_bounds__(256) void igemm_fast_kernel(const IgemmParams p)
     // ---- K loop: register set 0 / 1 hold the tiles one and two ahead of the
     // MFMAs.  Fetches past the last tile return zeros, so the loop body has one
     // shape; an odd tile count is finished after the loop.
-    const int nk = (p.Kp + BKE - 1) / BKE;
+    const int nk = kt_end - kt_begin;
     u32x4 ra0[APASS], rb0[BPASS], ra1[APASS], rb1[BPASS];
     fetch(ra0, rb0);                 // tile 0
     fetch(ra1, rb1);                 // tile 1
@@ -231,6 +237,16 @@ __global__ __launch_bounds__(256) void igemm_fast_kernel(const IgemmParams p)
             }
     __syncthreads();
 
+    if (!GATES && p.splits > 1) {
+        float *dst = p.partial + (int64_t)split * p.M * p.N;
+        for (int idx = t; idx < BM * BN; idx += 256) {
+            const int row = idx / BN, col = idx - row * BN;
+            const int m = m0 + row, n = n0 + col;
+            if (m < p.M && n < p.N) dst[(int64_t)m * p.N + n] = sC[row * LDC + col];
+        }
+        return;
+    }
+
     // ---- 32-row passes over the staged tile; the residual rows of the next pass are in flight
     // while this pass is stored
     using TE = TileEpilogue<BN>;
@@ -255,6 +271,8 @@ __global__ __launch_bounds__(256) void igemm_fast_kernel(const IgemmParams p)
     }
 }
 
+hipError_t launch_splitk_reduce(const IgemmParams &p, hipStream_t s);     // igemm_dma.hip
+
 template <typename T, int BM, int BN, bool GATES>
 static hipError_t launch_fast(const IgemmParams &p0, hipStream_t s)
 {
@@ -273,6 +291,18 @@ static hipError_t launch_fast(const IgemmParams &p0, hipStream_t s)
     }
     int64_t nblk = (int64_t)p.nblk_m * p.nblk_n;
     if (nblk <= 0 || nblk > 0x7fffffff) return hipErrorInvalidValue;
+    if (p.splits > 1) {
+        constexpr int BKE = CHUNKS * Elem<T>::KV;
+        const int nk = (p.Kp + BKE - 1) / BKE;
+        // every slice holds at least one K tile and the slices cover K exactly once
+        if (GATES || !p.partial || p.splits > 64 || (int64_t)p.M * p.N * p.splits >= (int64_t)1 << 31 || p.split_tiles < 1 ||
+            (int64_t)(p.splits - 1) * p.split_tiles >= nk || (int64_t)p.splits * p.split_tiles < nk || p.x2)
+            return hipErrorInvalidValue;
+        hipLaunchKernelGGL(kern, dim3((unsigned)nblk, (unsigned)p.splits), dim3(256), lds, s, p);
+        hipError_t er = hipGetLastError();
+        if (er != hipSuccess) return er;
+        return launch_splitk_reduce(p, s);
+    }
     hipLaunchKernelGGL(kern, dim3((unsigned)nblk), dim3(256), lds, s, p);
     return hipGetLastError();
 }

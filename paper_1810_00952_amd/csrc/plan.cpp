@@ -462,7 +462,7 @@ struct Planner {
         // Few tiles and a long K (small batches, late stages): K is split over several workgroups per tile, whose fp32
         // sums meet in a scratch tensor [splits][M][N] that a second kernel adds up in order before the epilogue.
         int part_buf = -1;
-        if (il.avec && il.dma && !il.lp && !gates && x2 < 0 && !stem && !plan.opts.no_splitk) {
+        if (il.avec && !il.lp && !gates && x2 < 0 && !stem && !plan.opts.no_splitk) {
             static const int tbm[] = {128, 128, 64, 256}, tbn[] = {128, 64, 64, 128};
             const int64_t tiles = nblk(tbm[il.tile], tbn[il.tile]);
             const int nk = (p.K + 8 * KV - 1) / (8 * KV);

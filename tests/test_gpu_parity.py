@@ -892,6 +892,11 @@ SPLITK_CASES = [
     (2, 64, 72, 9, 11, 3, 1, 1, True, False, "f32", False),        # ragged M and N, 18 K tiles: 4 slices of 5, 5, 5, 3
     (1, 512, 40, 5, 5, 1, 1, 0, False, False, "f32", False),       # 1x1: one tap, 16 K tiles
     (3, 128, 136, 7, 7, 3, 1, 1, True, True, "bf16", False),       # bf16 through the same kernel (result in Shape order)
+    # channel counts that are no multiple of the K tile: the kernel that fetches through registers, K tiles across taps
+    (64, 20, 50, 12, 12, 5, 1, 0, False, False, "f32", False),     # the LeNet shape's second convolution: 64 tiles, 16 K tiles
+    (1, 20, 50, 12, 12, 5, 1, 0, False, True, "f32", True),        # one tile, 8 slices of 2
+    (3, 36, 24, 9, 7, 3, 2, 1, True, True, "f32", False),          # stride 2, ragged last K tile (324 = 10.1 x 32), residual
+    (2, 40, 40, 8, 8, 5, 1, 2, False, True, "bf16", True),         # bf16: 1000 = 15.6 K tiles of 64, result kept channel-last
 ]
 
 
