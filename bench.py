@@ -340,6 +340,14 @@ def bench_resnet(args, batch, dtype):
     return out
 
 
+def harness_session_run(spec, data):
+    from paper_1810_00952_amd import harness
+    s = harness.Session(spec)
+    s.load(data)
+    s.alloc()
+    return s.run
+
+
 def bench_graph(args, spec, data, metric, unit, units_per_step, dtype, workload, peak_tflops, cpu=None):
     from paper_1810_00952_amd import harness
     s = harness.Session(spec)
@@ -479,7 +487,7 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="resnet18",
-                    choices=["resnet18", "resnet18_f32_b1", "eltwise", "eltwise32", "gates", "lstm", "mlp", "lenet", "conv", "copy", "layout", "layout32", "block_nhwc", "maxpool", "mfma_peak", "grads"])
+                    choices=["resnet18", "resnet18_f32_b1", "eltwise", "eltwise32", "gates", "lstm", "mlp", "lenet", "conv", "copy", "layout", "layout32", "block_nhwc", "maxpool", "mfma_peak", "grads", "launch_pitch"])
     ap.add_argument("--batch", type=int, default=64)
     ap.add_argument("--cpu-images", type=int, default=128)
     ap.add_argument("--no-cpu", action="store_true")
@@ -528,6 +536,22 @@ def main():
         data = {"x": W.as_dtype(W.normal(W.rng_for(6, salt=3), (n,)), "f32")}
         out = bench_graph(args, g, data, "elements/sec y = -x f32", "elements/s", n, "f32",
                           f"y = -x on {n} f32 elements (reads {4 * n} bytes, writes {4 * n} bytes)", PEAK_F32_TFLOPS)
+    elif wl == "launch_pitch":
+        # a chain of 16 dependent groups of y = -x on 1024 elements: nothing but the distance between two dependent
+        # launches on one stream (the figure behind the launch-boundary share of every step here)
+        n, depth = 1024, 16
+        g = W.GraphSpec("launch_pitch")
+        v = g.input("x", "f32", (n,))
+        for _ in range(depth):
+            o, (v,) = g.op("neg", [v], [("f32", (n,))])
+            g.group([o])
+        g.output(v)
+        data = {"x": W.as_dtype(W.normal(W.rng_for(6, salt=4), (n,)), "f32")}
+        out = bench_graph(args, g, data, "dependent launches/sec on one stream", "launches/s", depth, "f32",
+                          f"{depth} dependent groups of y = -x on {n} f32 elements, one launch each", PEAK_F32_TFLOPS)
+        out["us_per_dependent_launch"] = out["ms_per_step"] * 1e3 / depth
+        ms_graph = time_steps(harness_session_run(g, data), args.steps, args.warmup, graph=True)
+        out["hip_graph_replay"] = {"us_per_dependent_launch": ms_graph * 1e3 / depth}
     elif wl in ("layout", "layout32"):
         dtype, shape = ("bf16", (256, 64, 112, 112)) if wl == "layout" else ("f32", (128, 64, 112, 112))
         spec, data = W.layout_case(shape, (0, 2, 3, 1), dtype)
