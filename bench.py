@@ -490,6 +490,7 @@ def main():
                     choices=["resnet18", "resnet18_f32_b1", "eltwise", "eltwise32", "gates", "lstm", "mlp", "lenet", "conv", "copy", "layout", "layout32", "block_nhwc", "maxpool", "mfma_peak", "grads", "launch_pitch"])
     ap.add_argument("--batch", type=int, default=64)
     ap.add_argument("--cpu-images", type=int, default=128)
+    ap.add_argument("--elements", type=int, default=0, help="copy: number of f32 elements (default 24 Mi)")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="default workload: skip the MFMA calibration and the HBM-bound groups")
     ap.add_argument("--unfused", action="store_true", help="lstm: gate math as a group of its own")
@@ -528,7 +529,7 @@ def main():
         out = bench_graph(args, g, data, "hidden units/sec LSTM gate group", "units/s", B * H, "f32",
                           f"lstm_gates on z {B}x{4 * H} f32, c {B}x{H} f32 -> c' f32, h' bf16", PEAK_F32_TFLOPS)
     elif wl == "copy":
-        n = 24 << 20
+        n = args.elements or (24 << 20)
         g = W.GraphSpec("copy")
         x = g.input("x", "f32", (n,))
         o, (y,) = g.op("neg", [x], [("f32", (n,))])
