@@ -71,15 +71,16 @@ __global__ __launch_bounds__(256) void eltwise_kernel(const EltwiseParams p)
 }
 
 // ---------------------------------------------------------------------------
-// The forms fused groups mostly take -- y = [relu]( x [+ bias[channel]] [+ t] ) with x, t, y of one base type and
-// an f32 bias that is constant over runs of whole vectors -- compiled per form: no program to interpret, a dozen
+// The forms fused groups mostly take -- y = steps( x [+ bias[channel]] [+ t] ) with x, t, y of one base type, an f32
+// bias that is constant over runs of whole vectors and operand-free steps behind (none, one ReLU, or any) -- compiled per form: no program to interpret, a dozen
 // registers per lane, so that a SIMD holds enough waves to cover the HBM latency.  One 16-byte vector of each
 // tensor per thread (f32: two), streaming accesses for tensors the caches would not keep anyway.
 // ---------------------------------------------------------------------------
-template <typename T, bool BIAS, bool TADD, bool RELU, bool NT>
+// REST: the operand-free steps behind them: 0 none, 1 one ReLU, 2 up to eight steps of any kind, their codes in rest_ops
+template <typename T, bool BIAS, bool TADD, int REST, bool NT>
 __global__ __launch_bounds__(256) void eltwise_form_kernel(const T *__restrict__ x, const T *__restrict__ t, T *__restrict__ y,
                                                            const float *__restrict__ bias, int64_t nunit, uint32_t unit_per_run,
-                                                           uint32_t run_mul, uint32_t run_sh, uint32_t ch_count)
+                                                           uint32_t run_mul, uint32_t run_sh, uint32_t ch_count, int rest_n, uint64_t rest_ops)
 {
     // a unit: the 16 bytes a lane moves per tensor (8 bf16 / 4 f32); consecutive lanes, consecutive units
     const int64_t vi = (int64_t)blockIdx.x * 256 + threadIdx.x;
@@ -94,23 +95,40 @@ __global__ __launch_bounds__(256) void eltwise_form_kernel(const T *__restrict__
         const uint32_t run = unit_per_run == 1 ? (uint32_t)vi : (__umulhi((uint32_t)vi, run_mul) >> run_sh);
         bv = bias[run % ch_count];
     }
-    u32x4 o;
+    constexpr int NE = 16 / (int)sizeof(T);
+    float v[NE];
     if (sizeof(T) == 2) {
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
-            float lo = __uint_as_float(a[k] << 16) + bv, hi = __uint_as_float(a[k] & 0xffff0000u) + bv;
-            if (TADD) { lo += __uint_as_float(b[k] << 16); hi += __uint_as_float(b[k] & 0xffff0000u); }
-            if (RELU) { lo = lo > 0.0f ? lo : 0.0f; hi = hi > 0.0f ? hi : 0.0f; }
-            o[k] = pack_bf16x2(lo, hi);
+            v[2 * k] = __uint_as_float(a[k] << 16) + bv;
+            v[2 * k + 1] = __uint_as_float(a[k] & 0xffff0000u) + bv;
+            if (TADD) { v[2 * k] += __uint_as_float(b[k] << 16); v[2 * k + 1] += __uint_as_float(b[k] & 0xffff0000u); }
         }
     } else {
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
-            float v = __uint_as_float(a[k]) + bv;
-            if (TADD) v += __uint_as_float(b[k]);
-            if (RELU) v = v > 0.0f ? v : 0.0f;
-            o[k] = __float_as_uint(v);
+            v[k] = __uint_as_float(a[k]) + bv;
+            if (TADD) v[k] += __uint_as_float(b[k]);
         }
+    }
+    if (REST == 1) {
+#pragma unroll
+        for (int k = 0; k < NE; ++k) v[k] = v[k] > 0.0f ? v[k] : 0.0f;
+    } else if (REST == 2) {
+        uint64_t codes = rest_ops;
+        for (int st = 0; st < rest_n; ++st, codes >>= 8) {
+            const int op = (int)(codes & 0xff);
+#pragma unroll
+            for (int k = 0; k < NE; ++k) v[k] = unary_step(op, v[k]);
+        }
+    }
+    u32x4 o;
+    if (sizeof(T) == 2) {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) o[k] = pack_bf16x2(v[2 * k], v[2 * k + 1]);
+    } else {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) o[k] = __float_as_uint(v[k]);
     }
     u32x4 *yp = (u32x4 *)y + vi;
     if (NT) __builtin_nontemporal_store(o, yp);
@@ -119,29 +137,32 @@ __global__ __launch_bounds__(256) void eltwise_form_kernel(const T *__restrict__
 
 struct FormLaunch { int64_t nunit; uint32_t unit_per_run, run_mul, run_sh, ch_count; unsigned blocks; bool nt; };
 
-template <typename T, bool BIAS, bool TADD, bool RELU>
+template <typename T, bool BIAS, bool TADD, int REST>
 static void launch_form_nt(const FormLaunch &f, hipStream_t s, const EltwiseParams &p, const Epilogue &e)
 {
     const T *x = (const T *)p.x, *t = (const T *)e.t_ptr;
     T *y = (T *)p.y;
     const float *bias = (const float *)e.bias_ptr;
-    if (f.nt) hipLaunchKernelGGL((eltwise_form_kernel<T, BIAS, TADD, RELU, true>), dim3(f.blocks), dim3(256), 0, s, x, t, y, bias, f.nunit, f.unit_per_run, f.run_mul, f.run_sh, f.ch_count);
-    else hipLaunchKernelGGL((eltwise_form_kernel<T, BIAS, TADD, RELU, false>), dim3(f.blocks), dim3(256), 0, s, x, t, y, bias, f.nunit, f.unit_per_run, f.run_mul, f.run_sh, f.ch_count);
+    if (f.nt) hipLaunchKernelGGL((eltwise_form_kernel<T, BIAS, TADD, REST, true>), dim3(f.blocks), dim3(256), 0, s, x, t, y, bias, f.nunit, f.unit_per_run, f.run_mul, f.run_sh, f.ch_count, (int)e.rest_n, (uint64_t)e.rest_ops);
+    else hipLaunchKernelGGL((eltwise_form_kernel<T, BIAS, TADD, REST, false>), dim3(f.blocks), dim3(256), 0, s, x, t, y, bias, f.nunit, f.unit_per_run, f.run_mul, f.run_sh, f.ch_count, (int)e.rest_n, (uint64_t)e.rest_ops);
+}
+template <typename T, int REST>
+static void launch_form_rest(bool bias, bool tadd, const FormLaunch &fl, hipStream_t s, const EltwiseParams &p, const Epilogue &e)
+{
+    const int f = (bias ? 2 : 0) | (tadd ? 1 : 0);
+    switch (f) {
+    case 0: launch_form_nt<T, false, false, REST>(fl, s, p, e); break;
+    case 1: launch_form_nt<T, false, true, REST>(fl, s, p, e); break;
+    case 2: launch_form_nt<T, true, false, REST>(fl, s, p, e); break;
+    default: launch_form_nt<T, true, true, REST>(fl, s, p, e); break;
+    }
 }
 template <typename T>
-static void launch_form(bool bias, bool tadd, bool relu, const FormLaunch &fl, hipStream_t s, const EltwiseParams &p, const Epilogue &e)
+static void launch_form(bool bias, bool tadd, int rest, const FormLaunch &fl, hipStream_t s, const EltwiseParams &p, const Epilogue &e)
 {
-    const int f = (bias ? 4 : 0) | (tadd ? 2 : 0) | (relu ? 1 : 0);
-    switch (f) {
-    case 0: launch_form_nt<T, false, false, false>(fl, s, p, e); break;
-    case 1: launch_form_nt<T, false, false, true>(fl, s, p, e); break;
-    case 2: launch_form_nt<T, false, true, false>(fl, s, p, e); break;
-    case 3: launch_form_nt<T, false, true, true>(fl, s, p, e); break;
-    case 4: launch_form_nt<T, true, false, false>(fl, s, p, e); break;
-    case 5: launch_form_nt<T, true, false, true>(fl, s, p, e); break;
-    case 6: launch_form_nt<T, true, true, false>(fl, s, p, e); break;
-    default: launch_form_nt<T, true, true, true>(fl, s, p, e); break;
-    }
+    if (rest == 0) launch_form_rest<T, 0>(bias, tadd, fl, s, p, e);
+    else if (rest == 1) launch_form_rest<T, 1>(bias, tadd, fl, s, p, e);
+    else launch_form_rest<T, 2>(bias, tadd, fl, s, p, e);
 }
 
 hipError_t launch_eltwise(const EltwiseParams &p0, hipStream_t s)
@@ -174,16 +195,19 @@ hipError_t launch_eltwise(const EltwiseParams &p0, hipStream_t s)
             make_fast_div(f.unit_per_run, f.run_mul, f.run_sh);
         }
         const bool t_ok = e.t_op < 0 || (e.t_op == E_ADD && e.t_dtype == p.x_dtype && e.t_ptr);
-        const bool rest_ok = e.rest_n == 0 || e.relu_last;
+        const int rest = e.rest_n == 0 ? 0 : e.relu_last ? 1 : 2;
         const int64_t fblocks = (f.nunit + 255) / 256;
-        if (e.simple && bias_ok && t_ok && rest_ok && p.x_dtype == p.y_dtype && p.n % per == 0 && f.nunit >= 1 && f.nunit < ((int64_t)1 << 31) &&
+        if (e.simple && bias_ok && t_ok && p.x_dtype == p.y_dtype && p.n % per == 0 && f.nunit >= 1 && f.nunit < ((int64_t)1 << 31) &&
             (((uintptr_t)p.x | (uintptr_t)p.y | (uintptr_t)e.t_ptr) & 15) == 0) {
             f.blocks = (unsigned)fblocks;
-            if (p.x_dtype == DT_BF16) launch_form<uint16_t>(e.has_bias, e.t_op >= 0, e.relu_last, f, s, p, e);
-            else launch_form<float>(e.has_bias, e.t_op >= 0, e.relu_last, f, s, p, e);
+            if (p.x_dtype == DT_BF16) launch_form<uint16_t>(e.has_bias, e.t_op >= 0, rest, f, s, p, e);
+            else launch_form<float>(e.has_bias, e.t_op >= 0, rest, f, s, p, e);
             return hipGetLastError();
         }
     }
+    // the interpreting kernel moves two vectors per f32 tensor and thread and is faster with plain accesses whatever the
+    // size (f32, 1 GB: 182 us plain, 199 us streaming; bf16: no difference)
+    p.nt = 0;
     hipLaunchKernelGGL(eltwise_kernel, dim3((unsigned)blocks), dim3(256), 0, s, p);
     return hipGetLastError();
 }
