@@ -414,6 +414,37 @@ def test_eltwise_chain_all_ops(dtype, shape):
     check_graph(spec, data, f"eltwise chain {dtype} {shape}")
 
 
+UNARY_CHAINS = [("neg",), ("sq",), ("relu",), ("sigmoid",), ("tanh",), ("tanh", "neg", "sq"), ("sigmoid", "tanh", "relu", "neg", "sq", "tanh", "neg", "relu"),
+                ("relu", "relu"), ("neg", "relu")]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("shape", [(4096,), (3, 5, 7), (2, 24, 10, 10), (1,), (37, 8)])
+def test_groups_of_unary_operators(dtype, shape):
+    # operand-free chains of every length up to eight behind nothing, behind a bias and behind bias + residual: whole
+    # 16-byte units take the kernels compiled per form, ragged sizes the interpreting kernel; same values either way
+    for chain in UNARY_CHAINS:
+        for lead in ("", "bias", "bias+add", "add"):
+            if lead.startswith("bias") and len(shape) < 2:
+                continue
+            rng = W.rng_for(9, salt=len(chain) * 7 + len(lead))
+            g = W.GraphSpec("unary")
+            t = (dtype, shape)
+            x = g.input("x", dtype, shape)
+            data = {"x": W.as_dtype(W.normal(rng, shape), dtype)}
+            ops, y = [], x
+            if lead.startswith("bias"):
+                b = g.param("b", "f32", (shape[1],)); data["b"] = W.as_dtype(W.normal(rng, (shape[1],)), "f32")
+                o, (y,) = g.op("bias_add", [y, b], [t], axis=1); ops.append(o)
+            if lead.endswith("add"):
+                r = g.input("r", dtype, shape); data["r"] = W.as_dtype(W.normal(rng, shape), dtype)
+                o, (y,) = g.op("add", [y, r], [t]); ops.append(o)
+            for k in chain:
+                o, (y,) = g.op(k, [y], [t]); ops.append(o)
+            g.group(ops); g.output(y)
+            check_graph(g, data, f"unary chain {lead} {chain} {dtype} {shape}")
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("shape", [(2, 16, 8, 8), (3, 5, 7, 9), (1, 64, 56, 56), (2, 3, 1, 1), (4, 8, 2, 4)])
 def test_eltwise_bias_residual_relu(dtype, shape):
