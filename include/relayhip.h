@@ -203,6 +203,8 @@ typedef struct rl_plan_opts {
     int32_t no_wgrad;       /* conv2d_grad_w on bf16 batches that are multiples of 64: no images-last contraction kernel; the element-gather kernel */
     int32_t no_grad_fwd;    /* dense_grad_x and stride-1 conv2d_grad_x through a param: do not plan them as the forward
                                operator on re-ordered weights; take the element-gather kernel like the other gradients */
+    int32_t no_out_transpose; /* a large bf16 convolution whose result is a graph output: store it in Shape order from the
+                               direct-load kernel, instead of channel-last from the pixel-on-lane kernels plus a transposition */
     int32_t no_dense_chain; /* a split dense contraction followed by a small dense layer on its result alone: keep them two
                                steps (contraction, adding launch, small layer) instead of letting the adding launch run
                                the small layer too */

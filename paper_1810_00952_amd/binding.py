@@ -65,7 +65,7 @@ class rl_recurrent(ctypes.Structure):
 
 
 PLAN_OPT_FIELDS = ("no_lp", "no_lp_256", "no_ws", "ws_all", "no_stem", "no_stem_pool", "no_dma", "no_c64", "no_run", "no_run_ks",
-                   "no_pair", "s2_pair", "no_splitk", "no_hoist", "no_stem_direct", "no_wgrad", "no_grad_fwd", "no_dense_chain")
+                   "no_pair", "s2_pair", "no_splitk", "no_hoist", "no_stem_direct", "no_wgrad", "no_grad_fwd", "no_out_transpose", "no_dense_chain")
 
 
 class rl_plan_opts(ctypes.Structure):

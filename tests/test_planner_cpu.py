@@ -155,14 +155,17 @@ def test_gradient_operators_plan_onto_the_fast_kernels():
     k = lambda spec, opts=None: [s["kernel"] for s in B.Plan(B.graph_from_spec(ctx, spec), opts).describe()["steps"]]
     # with respect to the input, through a param: the forward operator on re-ordered weights ...
     spec = W.grad_case("conv2d_grad_x", (64, 128, 28, 28, 128, 3), "bf16", 1, 1)[0]
-    assert k(spec) == ["nchw_to_nhwc", "igemm_conv2d_grad_x_bf16_128x128_dma"]
+    # (its result, a graph output in Shape order, written channel-last by the nine-taps-from-one-copy kernel and transposed)
+    assert k(spec) == ["nchw_to_nhwc", "igemm_conv2d_grad_x_bf16_256x128_run", "nhwc_to_nchw"]
+    assert k(spec, {"no_out_transpose": 1}) == ["nchw_to_nhwc", "igemm_conv2d_grad_x_bf16_128x128_dma"]
     assert k(spec, {"no_grad_fwd": 1}) == ["igemm_conv2d_grad_x_bf16_64x64_gather"]
     # ... inside a chain on the nine-taps-from-one-copy kernel, like the forward pass
     assert k(W.grad_chain(64, 128, 28, 3, "bf16")[0]) == ["nchw_to_nhwc", "igemm_conv2d_grad_x_bf16_256x128_run", "igemm_conv2d_grad_x_bf16_256x128_run",
-                                                         "igemm_conv2d_grad_x_bf16_128x128_dma"]
+                                                         "igemm_conv2d_grad_x_bf16_256x128_run", "nhwc_to_nchw"]
     # ... at a stride on dy spread out with zeros
     spec = W.grad_case("conv2d_grad_x", (64, 64, 56, 56, 128, 3), "bf16", 2, 1)[0]
-    assert k(spec) == ["nchw_to_nhwc", "dilate_nhwc", "igemm_conv2d_grad_x_bf16_128x64_dma"]
+    assert k(spec) == ["nchw_to_nhwc", "dilate_nhwc", "igemm_conv2d_grad_x_bf16_128x64_lp", "nhwc_to_nchw"]
+    assert k(spec, {"no_out_transpose": 1}) == ["nchw_to_nhwc", "dilate_nhwc", "igemm_conv2d_grad_x_bf16_128x64_dma"]
     # through weights that are an activation: the element gather, its operand gathered by a step of the plan
     spec = W.grad_case("conv2d_grad_x", (64, 64, 56, 56, 128, 3), "bf16", 2, 1, second_is_param=False)[0]
     assert k(spec) == ["pack_gather", "igemm_conv2d_grad_x_bf16_64x64_gather"]
