@@ -279,11 +279,12 @@ struct Planner {
             out_layout = (vout >= 0 && out_set.count(vout)) ? L_NATIVE : L_NHWC;
             flops = 2.0 * p.M * (double)p.N * p.K;
             // A bf16 result that is a graph output (Shape order): only the slower direct-load kernel stores in that order
-            // itself.  From a gigaflop on, the pixel-on-lane kernels writing channel-last into the workspace plus a
-            // transposition (one launch more) are faster (64x128x28x28 through 3x3: 20 + 9 us against 56).  Chains with a
-            // full-shape operand stay as they are (the operand would want a transposition of its own).
+            // itself.  From 0.4 GFLOP on, the pixel-on-lane kernels writing channel-last into the workspace plus a
+            // transposition (one launch more, and one more for a channel-first residual) are faster: 64x128x28x28 through
+            // 3x3 20 + 9 us against 56, with a residual 43 against 166; at 0.46 GFLOP 14.3 against 16.9; below, the
+            // direct-load kernel with its K split is level or ahead (0.23 GFLOP: 16.4 against 14.6).
             if (out_layout == L_NATIVE && vout >= 0 && !plan.opts.no_out_transpose && !plan.opts.no_lp && in_dt == RL_BF16 && T(vout).dtype == RL_BF16 &&
-                p.C % 64 == 0 && p.N % 8 == 0 && p.KH * p.KW <= 32 && x2 < 0 && !gates && epi_lp && cls.t_op < 0 && flops >= 1e9 &&
+                p.C % 64 == 0 && p.N % 8 == 0 && p.KH * p.KW <= 32 && x2 < 0 && !gates && epi_lp && flops >= 4e8 &&
                 channel_last_output_of(vout) < 0)
                 out_layout = L_NHWC;
             if (out_layout == L_NHWC) { p.ys_n = (int64_t)p.OHW * p.N; p.ys_p = p.N; p.ys_c = 1; }

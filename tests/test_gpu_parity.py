@@ -914,6 +914,31 @@ def test_lstm_full_configuration():
     assert_close(c, c_ref, "bf16", "lstm full c")
 
 
+# ---- a convolution group whose result is a graph output in Shape order (channel-first) ------------------
+OUT_ORDER_CASES = [
+    # batch cin cout h  w  k s p residual relu
+    (16, 128, 128, 28, 28, 3, 1, 1, True, True),       # nine-taps-from-one-copy kernel, channel-first residual transposed too
+    (16, 128, 128, 28, 28, 3, 1, 1, False, True),
+    (9, 64, 64, 56, 56, 3, 1, 1, True, True),          # weights-in-registers kernel
+    (24, 64, 128, 30, 26, 3, 2, 1, False, True),       # stride 2: the general pixel-on-lane kernel
+    (33, 256, 136, 14, 14, 1, 1, 0, True, False),      # 1x1, ragged channel tile, no ReLU
+]
+
+
+@pytest.mark.parametrize("case", OUT_ORDER_CASES, ids=[f"oo{i}" for i in range(len(OUT_ORDER_CASES))])
+def test_convolution_result_as_channel_first_output(case):
+    # the fast kernels write channel-last into the workspace and a transposition fills the output; the plan option
+    # keeps the kernel that stores channel-first itself.  Both against the oracle.
+    b, ci, co, h, w, k, s, p, res, relu = case
+    spec, data = W.conv_group(b, ci, co, h, w, k, s, p, "bf16", residual=res, relu=relu)
+    ks = [st["kernel"] for st in s_plan_steps(spec)]
+    assert ks[-1] == "nhwc_to_nchw" and not ks[-2].endswith("_dma") and ks.count("nchw_to_nhwc") == (2 if res else 1), ks
+    ks1 = [st["kernel"] for st in s_plan_steps(spec, {"no_out_transpose": 1})]
+    assert "_dma" in ks1[-1] and "nhwc_to_nchw" not in ks1, ks1
+    check_graph(spec, data, f"conv to channel-first output {case}")
+    check_graph(spec, data, f"conv storing channel-first itself {case}", opts={"no_out_transpose": 1})
+
+
 # ---- K split over several workgroups per tile (few tiles, long K) --------------------------------------
 SPLITK_CASES = [
     # batch cin cout h  w  k s p residual relu dtype tail
