@@ -395,7 +395,8 @@ static bool s2_epilogue_ok(const Epilogue &e0)
 // Pointers are not looked at (the planner asks before any are bound); the launcher compares them itself.
 bool conv3x3s2_pair_ok(const IgemmParams &a, const IgemmLaunch &la, const IgemmParams &b, const IgemmLaunch &lb)
 {
-    if (!la.lp || !lb.lp || la.ws || lb.ws || la.c64 || lb.c64 || la.run || lb.run || la.gates || lb.gates || la.splits > 1 || lb.splits > 1) return false;
+    if (!la.lp || !lb.lp || la.ws || lb.ws || la.c64 || lb.c64 || la.run || lb.run || la.gates || lb.gates || la.splits > 1 || lb.splits > 1 ||
+        la.anyact || lb.anyact) return false;
     if (a.in_dtype != DT_BF16 || b.in_dtype != DT_BF16 || a.y_dtype != DT_BF16 || b.y_dtype != DT_BF16) return false;
     if (a.KH != 3 || a.KW != 3 || a.sh != 2 || a.sw != 2 || a.ph != 1 || a.pw != 1) return false;
     if (b.KH != 1 || b.KW != 1 || b.sh != 2 || b.sw != 2 || b.ph != 0 || b.pw != 0) return false;

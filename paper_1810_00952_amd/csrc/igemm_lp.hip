@@ -93,7 +93,8 @@ constexpr uint32_t OOB = 0x80000000u;
 }  // namespace
 
 // The workgroup's work: tile number bid_in of the contraction p.  YF32: the output is fp32 (no residual then).
-template <int BM, int BN, int WGM, int WGN, int STAGES, bool YF32 = false>
+// ANYACT: the operand-free steps behind bias and residual are any (up to eight, codes in the epilogue), not just one ReLU.
+template <int BM, int BN, int WGM, int WGN, int STAGES, bool YF32 = false, bool ANYACT = false>
 __device__ __forceinline__ void igemm_lp_body(const IgemmParams &p, const int bid_in)
 {
 #if defined(__HIP_DEVICE_COMPILE__)   // the host pass only needs the launch stub; the body uses gfx950-only builtins
@@ -394,7 +395,7 @@ __device__ __forceinline__ void igemm_lp_body(const IgemmParams &p, const int bi
             }
     wave_lds_exchange();
     const rsrc_t ry = make_rsrc(p.y, y_bytes);
-    const float lo = e.relu_last ? 0.0f : -INFINITY;
+    const float lo = (!ANYACT && e.relu_last) ? 0.0f : -INFINITY;
 #pragma unroll
     for (int q = 0; q < NPASS; ++q) {
         const int row = q * RPP + rr;
@@ -408,6 +409,14 @@ __device__ __forceinline__ void igemm_lp_body(const IgemmParams &p, const int bi
         for (int k = 0; k < 4; ++k) {
             v[2 * k] += __uint_as_float(r[k] << 16);
             v[2 * k + 1] += __uint_as_float(r[k] & 0xffff0000u);
+        }
+        if (ANYACT) {
+            uint64_t codes = e.rest_ops;
+            for (int st = 0; st < e.rest_n; ++st, codes >>= 8) {
+                const int op = (int)(codes & 0xff);
+#pragma unroll
+                for (int k = 0; k < 8; ++k) v[k] = unary_step(op, v[k]);
+            }
         }
         u32x4 o;
 #pragma unroll
@@ -429,6 +438,13 @@ template <int BM, int BN, int WGM, int WGN, int STAGES>
 __global__ __launch_bounds__(WGM * WGN * 64) void igemm_lp_kernel(const IgemmParams p)
 {
     igemm_lp_body<BM, BN, WGM, WGN, STAGES>(p, (int)blockIdx.x);
+}
+
+// any operand-free steps behind bias and residual (tanh, sigmoid, a chain of them) instead of at most one ReLU
+template <int BM, int BN, int WGM, int WGN, int STAGES>
+__global__ __launch_bounds__(WGM * WGN * 64) void igemm_lp_anyact_kernel(const IgemmParams p)
+{
+    igemm_lp_body<BM, BN, WGM, WGN, STAGES, false, true>(p, (int)blockIdx.x);
 }
 
 // fp32 output (a projection whose result feeds further fp32 arithmetic: the recurrent executor's hoisted x . Wx^T)
@@ -454,14 +470,15 @@ RL_INST(128, 128, 2, 4, 4) RL_INST(256, 128, 4, 2, 3) RL_INST(128, 64, 4, 1, 3) 
 #undef RL_INST
 
 template <int BM, int BN, int WGM, int WGN, int STAGES>
-static hipError_t launch_lp(const IgemmParams &p0, hipStream_t s)
+static hipError_t launch_lp(const IgemmParams &p0, hipStream_t s, bool anyact)
 {
     IgemmParams p = p0;
     p.nblk_m = (p.M + BM - 1) / BM;
     p.nblk_n = (p.N + BN - 1) / BN;
     int64_t nblk = (int64_t)p.nblk_m * p.nblk_n;
     if (nblk <= 0 || nblk > 0x7fffffff) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((igemm_lp_kernel<BM, BN, WGM, WGN, STAGES>), dim3((unsigned)nblk), dim3(WGM * WGN * 64), 0, s, p);
+    if (anyact) hipLaunchKernelGGL((igemm_lp_anyact_kernel<BM, BN, WGM, WGN, STAGES>), dim3((unsigned)nblk), dim3(WGM * WGN * 64), 0, s, p);
+    else hipLaunchKernelGGL((igemm_lp_kernel<BM, BN, WGM, WGN, STAGES>), dim3((unsigned)nblk), dim3(WGM * WGN * 64), 0, s, p);
     return hipGetLastError();
 }
 
@@ -491,6 +508,7 @@ static int lp_variant(const IgemmParams &p, const IgemmLaunch &l)
 bool igemm_lp_can_pair(const IgemmParams &a, const IgemmLaunch &la, const IgemmParams &b, const IgemmLaunch &lb)
 {
     return la.lp && lb.lp && !la.ws && !lb.ws && !la.c64 && !lb.c64 && !la.run && !lb.run && !la.gates && !lb.gates && !a.x2 && !b.x2 &&
+           !la.anyact && !lb.anyact &&
            a.in_dtype == DT_BF16 && b.in_dtype == DT_BF16 && a.y_dtype == DT_BF16 && b.y_dtype == DT_BF16 && lp_variant(a, la) == lp_variant(b, lb);
 }
 
@@ -532,20 +550,23 @@ hipError_t launch_igemm_lp(const IgemmParams &p, const IgemmLaunch &l, hipStream
         return hipErrorInvalidValue;
     }
     if (p.in_dtype != DT_BF16 || p.y_dtype != DT_BF16 || l.gates || p.x2) return hipErrorInvalidValue;
+    // the planner's flag and the chain must agree: one ReLU at most without it, other operand-free steps with it
+    const bool anyact = l.anyact != 0;
+    if (anyact != (p.epi.rest_n > 0 && !p.epi.relu_last)) return hipErrorInvalidValue;
     switch (l.tile) {
     case TILE_128x128:
         // eight waves of 64 pixels x 32 channels, two per SIMD: one wave's fragment reads and request stalls are
         // covered by the other's MFMAs (measured 4% faster than four waves of 64 x 64 on the ResNet shapes)
-        return launch_lp<128, 128, 2, 4, 4>(p, s);
+        return launch_lp<128, 128, 2, 4, 4>(p, s, anyact);
     case TILE_256x128:
         // eight waves of 64 x 64, two per SIMD, three stages of 48 KB
-        return launch_lp<256, 128, 4, 2, 3>(p, s);
+        return launch_lp<256, 128, 4, 2, 3>(p, s, anyact);
     case TILE_128x64:
         // few workgroups (at most one per CU anyway): four stages, so fragments are prefetched across the barrier;
         // many: three stages, so two workgroups share a CU and cover each other's barriers and epilogues
-        if ((int64_t)((p.M + 127) / 128) * ((p.N + 63) / 64) <= 320) return launch_lp<128, 64, 4, 1, 4>(p, s);
-        return launch_lp<128, 64, 4, 1, 3>(p, s);
-    default: return launch_lp<64, 64, 2, 2, 4>(p, s);
+        if ((int64_t)((p.M + 127) / 128) * ((p.N + 63) / 64) <= 320) return launch_lp<128, 64, 4, 1, 4>(p, s, anyact);
+        return launch_lp<128, 64, 4, 1, 3>(p, s, anyact);
+    default: return launch_lp<64, 64, 2, 2, 4>(p, s, anyact);
     }
 }
 

@@ -110,6 +110,7 @@ struct IgemmLaunch {
                         // 2: its 128x64 form with K split over the waves (C a multiple of 128)
     int32_t splits;     // > 1 (with dma, no lp, no gates): K split over that many workgroups per tile (IgemmParams::splits)
     int32_t s2pair;     // 1 (first step of a pair): the pair runs as one stride-2 contraction with two accumulator sets (conv3x3s2.hip)
+    int32_t anyact;     // 1 (with lp, no ws / c64 / run / pair): operand-free steps other than one ReLU behind bias and residual
 };
 hipError_t launch_igemm(const IgemmParams &p, const IgemmLaunch &l, hipStream_t s);
 

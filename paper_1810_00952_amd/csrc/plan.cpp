@@ -257,8 +257,9 @@ struct Planner {
         // form of the injective chain, needed before the kernel variant is chosen
         Epilogue cls = chain.epi;
         finalize_epilogue(cls);
-        const bool epi_lp = cls.simple && (!cls.has_bias || cls.bias_dtype == DT_F32) && (cls.t_op < 0 || (cls.t_op == E_ADD && cls.t_dtype == DT_BF16)) &&
-                            (cls.rest_n == 0 || cls.relu_last);
+        const bool epi_any = cls.simple && (!cls.has_bias || cls.bias_dtype == DT_F32) && (cls.t_op < 0 || (cls.t_op == E_ADD && cls.t_dtype == DT_BF16));
+        const bool relu_form = cls.rest_n == 0 || cls.relu_last;     // at most one ReLU behind them: every pixel-on-lane kernel; anything else: the general one
+        const bool epi_lp = epi_any && relu_form;
         bool stem = false;
         const size_t lim = (size_t)1 << 31;
 
@@ -284,7 +285,7 @@ struct Planner {
             // 3x3 20 + 9 us against 56, with a residual 43 against 166; at 0.46 GFLOP 14.3 against 16.9; below, the
             // direct-load kernel with its K split is level or ahead (0.23 GFLOP: 16.4 against 14.6).
             if (out_layout == L_NATIVE && vout >= 0 && !plan.opts.no_out_transpose && !plan.opts.no_lp && in_dt == RL_BF16 && T(vout).dtype == RL_BF16 &&
-                p.C % 64 == 0 && p.N % 8 == 0 && p.KH * p.KW <= 32 && x2 < 0 && !gates && epi_lp && flops >= 4e8 &&
+                p.C % 64 == 0 && p.N % 8 == 0 && p.KH * p.KW <= 32 && x2 < 0 && !gates && epi_any && flops >= 4e8 &&
                 channel_last_output_of(vout) < 0)
                 out_layout = L_NHWC;
             if (out_layout == L_NHWC) { p.ys_n = (int64_t)p.OHW * p.N; p.ys_p = p.N; p.ys_c = 1; }
@@ -387,13 +388,14 @@ struct Planner {
             bool y_ok = vout >= 0 && T(vout).dtype == RL_BF16 && p.ys_c == 1 && p.ys_n == (int64_t)p.OHW * p.ys_p && p.N % 8 == 0 &&
                         bytes_of(vout) < lim;
             il.lp = stem || (il.avec && in_dt == RL_BF16 && p.C % bke == 0 && p.K % bke == 0 && p.KH * p.KW <= 32 && x2 < 0 && !gates &&
-                             x_extent + halo < lim && epi_lp && y_ok && !plan.opts.no_lp);
+                             x_extent + halo < lim && epi_any && y_ok && !plan.opts.no_lp);
+            il.anyact = il.lp && !stem && !relu_form;
             // weights-stationary persistent variant: pays off when the weights leave LDS for a deep ring (K <= 320);
             // the plan option ws_all also takes it up to K = 576, where its shallower ring is latency-bound
-            il.ws = il.lp && p.N <= 64 && (p.K / bke <= 5 || (p.K / bke <= 9 && plan.opts.ws_all)) && !plan.opts.no_ws;
+            il.ws = il.lp && !il.anyact && p.N <= 64 && (p.K / bke <= 5 || (p.K / bke <= 9 && plan.opts.ws_all)) && !plan.opts.no_ws;
             // 3x3 / stride 1 / pad 1 from 64 to 64 channels on rows of at most 63 pixels: weights in registers, every
             // input pixel fetched once per region
-            il.c64 = il.lp && !stem && akind == RL_OP_CONV2D && p.C == 64 && p.N == 64 && p.KH == 3 && p.KW == 3 && p.sh == 1 && p.sw == 1 &&
+            il.c64 = il.lp && !il.anyact && !stem && akind == RL_OP_CONV2D && p.C == 64 && p.N == 64 && p.KH == 3 && p.KW == 3 && p.sh == 1 && p.sw == 1 &&
                      p.ph == 1 && p.pw == 1 && p.OH == p.H && p.OW == p.W && p.W <= 63 && p.Kp == p.K && p.ys_p == 64 && !plan.opts.no_c64;
             il.c64 = il.c64 && dual;
             if (il.c64) { il.ws = 0; p.w_bytes = (uint32_t)pack.bytes; }
@@ -437,7 +439,7 @@ struct Planner {
 
         // 3x3 / stride 1 / pad 1 on short image rows with whole 64-channel slices: the nine taps of a slice are read
         // from one copy of the input rows (needs one of the larger tiles)
-        il.run = il.lp && !il.c64 && !il.ws && !stem && akind == RL_OP_CONV2D && p.KH == 3 && p.KW == 3 && p.sh == 1 && p.sw == 1 && p.ph == 1 &&
+        il.run = il.lp && !il.anyact && !il.c64 && !il.ws && !stem && akind == RL_OP_CONV2D && p.KH == 3 && p.KW == 3 && p.sh == 1 && p.sw == 1 && p.ph == 1 &&
                  p.pw == 1 && p.OH == p.H && p.OW == p.W && p.W <= 30 && p.C % 64 == 0 && p.Kp == p.K && il.tile != TILE_64x64 &&
                  !plan.opts.no_run;
         if (il.run && il.tile == TILE_128x64 && p.C % 128 == 0 && !plan.opts.no_run_ks) {

@@ -939,6 +939,39 @@ def test_convolution_result_as_channel_first_output(case):
     check_graph(spec, data, f"conv storing channel-first itself {case}", opts={"no_out_transpose": 1})
 
 
+# ---- bf16 contractions with operand-free steps other than one ReLU in their group -----------------------
+ANYACT_CASES = [
+    # batch cin cout h  w  k s p residual relu acts
+    (16, 128, 128, 28, 28, 3, 1, 1, False, False, ("tanh",)),
+    (5, 64, 64, 56, 56, 3, 1, 1, True, False, ("sigmoid", "sq")),          # shapes the register-weight kernel would take with a ReLU
+    (9, 128, 136, 14, 15, 3, 2, 1, True, True, ("tanh", "neg")),            # ReLU first, then more; stride 2, ragged channel tile
+    (70, 256, 72, 7, 7, 1, 1, 0, False, False, ("neg",)),
+    (3, 64, 64, 28, 28, 3, 1, 1, False, False, ("sigmoid", "tanh", "relu", "neg", "sq", "tanh", "neg", "relu")),   # eight steps
+]
+
+
+@pytest.mark.parametrize("case", ANYACT_CASES, ids=[f"aa{i}" for i in range(len(ANYACT_CASES))])
+def test_bf16_contraction_with_any_operand_free_steps(case):
+    # the general pixel-on-lane kernel interprets the steps behind bias and residual in its epilogue; without it
+    # (plan option no_lp) the direct-load kernel does.  Both against the oracle.
+    b, ci, co, h, w, k, s, p, res, relu, acts = case
+    spec, data = W.conv_group(b, ci, co, h, w, k, s, p, "bf16", residual=res, relu=relu, acts=acts, tail=True)
+    ks = [st["kernel"] for st in s_plan_steps(spec)]
+    assert any(x.endswith("_lp") for x in ks) and not any(x.endswith(("_run", "_c64", "_ws")) for x in ks), ks
+    check_graph(spec, data, f"any activation {case}")
+    check_graph(spec, data, f"any activation {case} without the pixel-on-lane kernels", opts={"no_lp": 1})
+    # a dense layer with tanh, as the LeNet shape has them
+    spec, data = W.mlp(70, 512, 256, 72, "bf16")
+    g = W.GraphSpec("dense_tanh")
+    x = g.input("x", "bf16", (70, 512)); wv = g.param("w1", "bf16", (256, 512)); bv = g.param("b1", "f32", (256,))
+    o0, (y,) = g.op("dense", [x, wv], [("bf16", (70, 256))])
+    o1, (y,) = g.op("bias_add", [y, bv], [("bf16", (70, 256))], axis=1)
+    o2, (y,) = g.op("tanh", [y], [("bf16", (70, 256))])
+    g.group([o0, o1, o2]); g.output(y)
+    assert [st["kernel"] for st in s_plan_steps(g)] == ["igemm_dense_bf16_64x64_lp"]
+    check_graph(g, {k_: data[k_] for k_ in ("x", "w1", "b1")}, "dense + bias + tanh bf16")
+
+
 # ---- K split over several workgroups per tile (few tiles, long K) --------------------------------------
 SPLITK_CASES = [
     # batch cin cout h  w  k s p residual relu dtype tail

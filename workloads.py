@@ -179,11 +179,11 @@ def mlp(batch=32, d_in=784, d_hidden=128, d_out=10, dtype="f32", config=1):
 # config 2: one fused conv2d group
 # --------------------------------------------------------------------------
 def conv_group(batch=1, cin=64, cout=64, h=56, w=56, k=3, stride=1, pad=1, dtype="f32",
-               residual=False, relu=True, config=2, tail=False, make_x=True, bias=True):
+               residual=False, relu=True, config=2, tail=False, make_x=True, bias=True, acts=()):
     """One fused conv2d group.  tail=True appends a second group (neg) so that the
     conv group's result is an intermediate the plan keeps in its private layout.
     make_x=False leaves x out of the data (the caller supplies it); weights and bias then
-    do not depend on the batch."""
+    do not depend on the batch.  acts: unary operators appended to the group (after the ReLU, if any)."""
     rng = rng_for(config)
     g = GraphSpec("conv_group")
     data = {}
@@ -207,6 +207,8 @@ def conv_group(batch=1, cin=64, cout=64, h=56, w=56, k=3, stride=1, pad=1, dtype
         o, (y,) = g.op("add", [y, r], [ot]); ids.append(o)
     if relu:
         o, (y,) = g.op("relu", [y], [ot]); ids.append(o)
+    for kind in acts:
+        o, (y,) = g.op(kind, [y], [ot]); ids.append(o)
     g.group(ids)
     if tail:
         o, (y,) = g.op("neg", [y], [ot])
