@@ -80,7 +80,7 @@ __global__ __launch_bounds__(256) void eltwise_kernel(const EltwiseParams p)
 template <typename T, bool BIAS, bool TADD, int REST, bool NT>
 __global__ __launch_bounds__(256) void eltwise_form_kernel(const T *__restrict__ x, const T *__restrict__ t, T *__restrict__ y,
                                                            const float *__restrict__ bias, int64_t nunit, uint32_t unit_per_run,
-                                                           uint32_t run_mul, uint32_t run_sh, uint32_t ch_count, int rest_n, uint64_t rest_ops)
+                                                           uint32_t run_mul, uint32_t run_sh, uint32_t ch_count, int rest_n, uint64_t rest_ops, int t_op)
 {
     // a unit: the 16 bytes a lane moves per tensor (8 bf16 / 4 f32); consecutive lanes, consecutive units
     const int64_t vi = (int64_t)blockIdx.x * 256 + threadIdx.x;
@@ -102,13 +102,17 @@ __global__ __launch_bounds__(256) void eltwise_form_kernel(const T *__restrict__
         for (int k = 0; k < 4; ++k) {
             v[2 * k] = __uint_as_float(a[k] << 16) + bv;
             v[2 * k + 1] = __uint_as_float(a[k] & 0xffff0000u) + bv;
-            if (TADD) { v[2 * k] += __uint_as_float(b[k] << 16); v[2 * k + 1] += __uint_as_float(b[k] & 0xffff0000u); }
+            if (TADD) {
+                // the full-shape operand: an addition in the forms with at most a ReLU behind, any of the six steps otherwise
+                if (REST != 2) { v[2 * k] += __uint_as_float(b[k] << 16); v[2 * k + 1] += __uint_as_float(b[k] & 0xffff0000u); }
+                else { v[2 * k] = binop(t_op, v[2 * k], __uint_as_float(b[k] << 16)); v[2 * k + 1] = binop(t_op, v[2 * k + 1], __uint_as_float(b[k] & 0xffff0000u)); }
+            }
         }
     } else {
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
             v[k] = __uint_as_float(a[k]) + bv;
-            if (TADD) v[k] += __uint_as_float(b[k]);
+            if (TADD) v[k] = REST != 2 ? v[k] + __uint_as_float(b[k]) : binop(t_op, v[k], __uint_as_float(b[k]));
         }
     }
     if (REST == 1) {
@@ -143,8 +147,8 @@ static void launch_form_nt(const FormLaunch &f, hipStream_t s, const EltwisePara
     const T *x = (const T *)p.x, *t = (const T *)e.t_ptr;
     T *y = (T *)p.y;
     const float *bias = (const float *)e.bias_ptr;
-    if (f.nt) hipLaunchKernelGGL((eltwise_form_kernel<T, BIAS, TADD, REST, true>), dim3(f.blocks), dim3(256), 0, s, x, t, y, bias, f.nunit, f.unit_per_run, f.run_mul, f.run_sh, f.ch_count, (int)e.rest_n, (uint64_t)e.rest_ops);
-    else hipLaunchKernelGGL((eltwise_form_kernel<T, BIAS, TADD, REST, false>), dim3(f.blocks), dim3(256), 0, s, x, t, y, bias, f.nunit, f.unit_per_run, f.run_mul, f.run_sh, f.ch_count, (int)e.rest_n, (uint64_t)e.rest_ops);
+    if (f.nt) hipLaunchKernelGGL((eltwise_form_kernel<T, BIAS, TADD, REST, true>), dim3(f.blocks), dim3(256), 0, s, x, t, y, bias, f.nunit, f.unit_per_run, f.run_mul, f.run_sh, f.ch_count, (int)e.rest_n, (uint64_t)e.rest_ops, (int)e.t_op);
+    else hipLaunchKernelGGL((eltwise_form_kernel<T, BIAS, TADD, REST, false>), dim3(f.blocks), dim3(256), 0, s, x, t, y, bias, f.nunit, f.unit_per_run, f.run_mul, f.run_sh, f.ch_count, (int)e.rest_n, (uint64_t)e.rest_ops, (int)e.t_op);
 }
 template <typename T, int REST>
 static void launch_form_rest(bool bias, bool tadd, const FormLaunch &fl, hipStream_t s, const EltwiseParams &p, const Epilogue &e)
@@ -194,8 +198,9 @@ hipError_t launch_eltwise(const EltwiseParams &p0, hipStream_t s)
             f.unit_per_run = (uint32_t)(p.ch_inner / per); f.ch_count = (uint32_t)p.ch_count;
             make_fast_div(f.unit_per_run, f.run_mul, f.run_sh);
         }
-        const bool t_ok = e.t_op < 0 || (e.t_op == E_ADD && e.t_dtype == p.x_dtype && e.t_ptr);
-        const int rest = e.rest_n == 0 ? 0 : e.relu_last ? 1 : 2;
+        const bool t_ok = e.t_op < 0 || (e.t_dtype == p.x_dtype && e.t_ptr);
+        // an operand that is not added takes the form with generic steps (which applies the operand's own step too)
+        const int rest = (e.t_op >= 0 && e.t_op != E_ADD) ? 2 : e.rest_n == 0 ? 0 : e.relu_last ? 1 : 2;
         const int64_t fblocks = (f.nunit + 255) / 256;
         if (e.simple && bias_ok && t_ok && p.x_dtype == p.y_dtype && p.n % per == 0 && f.nunit >= 1 && f.nunit < ((int64_t)1 << 31) &&
             (((uintptr_t)p.x | (uintptr_t)p.y | (uintptr_t)e.t_ptr) & 15) == 0) {

@@ -421,10 +421,11 @@ UNARY_CHAINS = [("neg",), ("sq",), ("relu",), ("sigmoid",), ("tanh",), ("tanh", 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("shape", [(4096,), (3, 5, 7), (2, 24, 10, 10), (1,), (37, 8)])
 def test_groups_of_unary_operators(dtype, shape):
-    # operand-free chains of every length up to eight behind nothing, behind a bias and behind bias + residual: whole
-    # 16-byte units take the kernels compiled per form, ragged sizes the interpreting kernel; same values either way
+    # operand-free chains of every length up to eight behind nothing, behind a bias, behind one tensor operand (added,
+    # multiplied, subtracted, divided) and behind both: whole 16-byte units take the kernels compiled per form, ragged
+    # sizes the interpreting kernel; same values either way
     for chain in UNARY_CHAINS:
-        for lead in ("", "bias", "bias+add", "add"):
+        for lead in ("", "bias", "bias+add", "add", "mul", "bias+sub", "div"):
             if lead.startswith("bias") and len(shape) < 2:
                 continue
             rng = W.rng_for(9, salt=len(chain) * 7 + len(lead))
@@ -436,9 +437,10 @@ def test_groups_of_unary_operators(dtype, shape):
             if lead.startswith("bias"):
                 b = g.param("b", "f32", (shape[1],)); data["b"] = W.as_dtype(W.normal(rng, (shape[1],)), "f32")
                 o, (y,) = g.op("bias_add", [y, b], [t], axis=1); ops.append(o)
-            if lead.endswith("add"):
-                r = g.input("r", dtype, shape); data["r"] = W.as_dtype(W.normal(rng, shape), dtype)
-                o, (y,) = g.op("add", [y, r], [t]); ops.append(o)
+            if lead.endswith(("add", "mul", "sub", "div")):
+                r = g.input("r", dtype, shape)
+                data["r"] = W.as_dtype(W.uniform(rng, shape, 1.0, 2.0) if lead.endswith("div") else W.normal(rng, shape), dtype)
+                o, (y,) = g.op(lead[-3:], [y, r], [t]); ops.append(o)
             for k in chain:
                 o, (y,) = g.op(k, [y], [t]); ops.append(o)
             g.group(ops); g.output(y)
