@@ -487,7 +487,7 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="resnet18",
-                    choices=["resnet18", "resnet18_f32_b1", "eltwise", "eltwise32", "gates", "lstm", "mlp", "lenet", "conv", "copy", "layout", "layout32", "block_nhwc", "maxpool", "mfma_peak", "grads", "launch_pitch"])
+                    choices=["resnet18", "resnet18_f32_b1", "eltwise", "eltwise32", "gates", "lstm", "mlp", "lenet", "conv", "copy", "layout", "layout32", "block_nhwc", "maxpool", "mfma_peak", "grads", "launch_pitch", "gemm"])
     ap.add_argument("--batch", type=int, default=64)
     ap.add_argument("--cpu-images", type=int, default=128)
     ap.add_argument("--elements", type=int, default=0, help="copy: number of f32 elements (default 24 Mi)")
@@ -537,6 +537,21 @@ def main():
         data = {"x": W.as_dtype(W.normal(W.rng_for(6, salt=3), (n,)), "f32")}
         out = bench_graph(args, g, data, "elements/sec y = -x f32", "elements/s", n, "f32",
                           f"y = -x on {n} f32 elements (reads {4 * n} bytes, writes {4 * n} bytes)", PEAK_F32_TFLOPS)
+    elif wl == "gemm":
+        # a dense group at matrix-multiplication scale: relu(x W^T + b), 4096 x 4096 x 4096, bf16
+        import numpy as np
+        M = N = K = 4096
+        g = W.GraphSpec("gemm")
+        x = g.input("x", "bf16", (M, K)); w = g.param("w", "bf16", (N, K)); b = g.param("b", "f32", (N,))
+        o0, (y,) = g.op("dense", [x, w], [("bf16", (M, N))])
+        o1, (y,) = g.op("bias_add", [y, b], [("bf16", (M, N))], axis=1)
+        o2, (y,) = g.op("relu", [y], [("bf16", (M, N))])
+        g.group([o0, o1, o2]); g.output(y)
+        rng = W.rng_for(6, salt=5)
+        data = {"x": W.as_dtype(W.normal(rng, (M, K)), "bf16"), "w": W.as_dtype(W.kaiming_uniform(rng, (N, K), K), "bf16"),
+                "b": W.as_dtype(W.uniform(rng, (N,), -0.1, 0.1), "f32")}
+        out = bench_graph(args, g, data, "TFLOP/s dense + bias + ReLU 4096x4096x4096 bf16", "TFLOP/s", 2.0 * M * N * K / 1e12, "bf16",
+                          "one dense group relu(x W^T + b), x 4096x4096, W 4096x4096, bf16 in, fp32 accumulate, N(0,1) / Kaiming inputs", PEAK_BF16_TFLOPS)
     elif wl == "launch_pitch":
         # a chain of 16 dependent groups of y = -x on 1024 elements: nothing but the distance between two dependent
         # launches on one stream (the figure behind the launch-boundary share of every step here)
